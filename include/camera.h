@@ -1,0 +1,202 @@
+/*
+ * camera.h -- C ABI of the MI355X (gfx950) CAMERA micro-expert scoring library.
+ *
+ * The library computes, for one MoE layer, what the paper's Algorithm 1
+ * ("CAMERA -- Micro-Experts Ranking") computes, and the two decisions that
+ * Algorithms 2 and 3 take from its ranking.  A micro-expert (e, c) is gate row
+ * c, up row c and down column c of expert e (Section "From Expert to
+ * Micro-Expert", Eq. 3); its global index in every per-layer vector is
+ * e * d_ff + c (0-based).
+ *
+ * Conventions for every entry point
+ *   - Pointers are DEVICE pointers unless the comment says HOST.  All tensors
+ *     are row-major.  The caller owns every buffer and the stream; the library
+ *     keeps nothing of the caller's beyond the stream work it enqueues.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue their kernels on it and return without waiting.  A context
+ *     must not be used from two streams at the same time: its workspace is
+ *     shared by consecutive calls and ordered only by the stream.
+ *   - Return value: CAMERA_OK (0) or a negative camera_status.  All argument
+ *     checks run on the host before any GPU call; camera_last_error() then
+ *     names the offending argument.  No exception or abort crosses this ABI.
+ *   - The context owns a grow-only device workspace (hipMalloc on first use and
+ *     on growth, which synchronises the device).
+ *   - NaN / Inf in the inputs: results unspecified (not checked).
+ *   - Device data pointers must be 16-byte aligned; for CAMERA_BF16 d_model and
+ *     ldx must be multiples of 8, for CAMERA_F32 multiples of 4.
+ */
+#ifndef CAMERA_H_
+#define CAMERA_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct camera_ctx camera_ctx; /* opaque, library-owned */
+
+enum camera_status {
+  CAMERA_OK = 0,
+  CAMERA_EINVAL = -1,       /* NULL pointer, value out of range */
+  CAMERA_ESHAPE = -2,       /* size / stride / alignment not accepted */
+  CAMERA_EDTYPE = -3,       /* unknown dtype code */
+  CAMERA_EWORKSPACE = -4,   /* workspace allocation failed */
+  CAMERA_EHIP = -5,         /* a HIP runtime call failed (text in camera_last_error) */
+  CAMERA_EUNSUPPORTED = -6  /* valid request outside the built limits */
+};
+
+enum camera_dtype { CAMERA_F32 = 0, CAMERA_BF16 = 1 };
+
+enum camera_flags {
+  CAMERA_ACCUMULATE = 1, /* phi2 / phi_inf already hold earlier token chunks: merge into them */
+  CAMERA_NO_FINALIZE = 2 /* more chunks follow: leave omega2 and energy untouched */
+};
+
+/* Limits of this build. */
+#define CAMERA_MAX_EXPERTS 256   /* routed experts per call */
+#define CAMERA_MAX_SEGMENTS 512  /* expert segments in select / alloc */
+#define CAMERA_MAX_LEVELS 8      /* precision classes in camera_alloc_bits */
+
+/* Kernel groups for camera_profile_read. */
+enum camera_kernel_id {
+  CAMERA_K_ROUTE = 0,
+  CAMERA_K_BUCKET = 1,
+  CAMERA_K_GEMM = 2,     /* grouped gate/up contraction + fused epilogue */
+  CAMERA_K_DOWN_NORM = 3,
+  CAMERA_K_FINALIZE = 4,
+  CAMERA_K_RANK = 5,
+  CAMERA_K_COUNT = 6
+};
+
+/* Create / destroy a context bound to HIP device `device`.  Creation touches no
+ * GPU; device resources are made on the first compute call. */
+int camera_create(camera_ctx** out, int device);
+int camera_destroy(camera_ctx* ctx);
+
+/* HOST string describing the last error of this context (valid until its next
+ * call); with ctx == NULL, the last error of a failed camera_create. */
+const char* camera_last_error(const camera_ctx* ctx);
+
+/* Library ABI version (currently 1). */
+int camera_version(void);
+
+/*
+ * A = Top&Norm(R X)  -- Algorithm 1, line 2; router weights A_i(x) of Eq. 2.
+ *
+ *   X        [n x d_model], row stride ldx elements, `dtype`
+ *   W_r      [n_experts x d_model], row stride ldr, `dtype`  (router R)
+ *   bias     [n_experts] float32 added to the logits, or NULL
+ *   topk_idx [n x top_k] int32 out: the top_k experts with the largest logits,
+ *            largest first, equal logits to the lower expert index
+ *   topk_w   [n x top_k] float32 out: softmax probability (over all n_experts)
+ *            of each kept expert; with renorm != 0 divided by the sum of the
+ *            kept probabilities ("Norm"), so each row sums to 1
+ * Logits are accumulated in float32.  1 <= top_k <= n_experts <= CAMERA_MAX_EXPERTS.
+ * n == 0 is accepted and does nothing.
+ */
+int camera_route_topk(camera_ctx* ctx, void* stream,
+                      const void* X, int dtype, int64_t n, int64_t d_model, int64_t ldx,
+                      const void* W_r, int64_t ldr, const float* bias,
+                      int n_experts, int top_k, int renorm,
+                      int32_t* topk_idx, float* topk_w);
+
+/*
+ * Algorithm 1, lines 3-10 for one group of experts: per micro-expert
+ *   phi2    = sum_j Lambda[j,c]^2            (line 7)
+ *   phi_inf = (max_j |Lambda[j,c]|)^2        (line 8)
+ *   omega2  = sum_r W_down[r,c]^2            (line 5)
+ *   energy  = [(1-alpha) phi2 + alpha phi_inf] * omega2     (line 10, energy with
+ *             the balance coefficient alpha)
+ * with Lambda[j,c] = a_j * silu(<w_gate_c, x_j>) * <w_up_c, x_j>  (line 6, Eq. 4)
+ * taken over the tokens j routed to the expert.  Lambda is never stored.
+ *
+ *   X         [n x d_model], row stride ldx, `dtype`
+ *   topk_idx  [n x top_k] int32 and topk_w [n x top_k] float32 as written by
+ *             camera_route_topk.  Entries outside [0, n_experts) are ignored.
+ *             Both NULL (top_k ignored): every expert sees every token with
+ *             weight 1 -- a shared expert or a dense FFN.
+ *   W_gate, W_up  [n_experts][d_ff][d_model] `dtype`, expert stride stride_gu
+ *             elements (>= d_ff*d_model), rows contiguous
+ *   W_down    [n_experts][d_model][d_ff] `dtype`, expert stride stride_down
+ *             elements; column c belongs to micro-expert c
+ *   alpha     in [0, 1]
+ *   flags     0: one call covers all tokens.  CAMERA_ACCUMULATE: phi2 / phi_inf
+ *             are in-out and this chunk of tokens is merged into them (sum /
+ *             max).  CAMERA_NO_FINALIZE: omega2 and energy are not written (may
+ *             be NULL).
+ *   phi2, phi_inf, omega2, energy   float32 [n_experts * d_ff] out
+ * Contractions run on bf16 MFMA with float32 accumulation (CAMERA_BF16) or in
+ * float32 FMA (CAMERA_F32); the result does not depend on launch order (no
+ * floating-point atomics).  n == 0 gives phi2 = phi_inf = 0 (or leaves them
+ * unchanged under CAMERA_ACCUMULATE).
+ */
+int camera_score_layer(camera_ctx* ctx, void* stream,
+                       const void* X, int dtype, int64_t n, int64_t d_model, int64_t ldx,
+                       const int32_t* topk_idx, const float* topk_w, int top_k,
+                       int n_experts, int64_t d_ff,
+                       const void* W_gate, const void* W_up, int64_t stride_gu,
+                       const void* W_down, int64_t stride_down,
+                       float alpha, int flags,
+                       float* phi2, float* phi_inf, float* omega2, float* energy);
+
+/*
+ * S = TopSelect(R, 1 - lambda)  -- Algorithm 2 (CAMERA-P), line 9, on the
+ * ranking of Algorithm 1 line 11.  The order is the stable ascending order of
+ * (energy, index); the first n_prune = floor(ratio * n_micro + 1e-6)
+ * micro-experts are removed, the rest kept.  -0.0 counts as +0.0.
+ *
+ *   energy          float32 [n_micro]
+ *   seg_offsets     HOST int64 [n_seg + 1], rising from 0 to n_micro: expert
+ *                   boundaries (n_seg <= CAMERA_MAX_SEGMENTS)
+ *   ratio           lambda in [0, 1]
+ *   keep_mask       uint8 [n_micro] out: 1 kept, 0 pruned
+ *   kept_per_expert int32 [n_seg] out: kept micro-experts of every segment
+ *   kept_idx        int32 [n_micro - n_prune] out or NULL: kept global indices,
+ *                   ascending (so grouped by expert)
+ *   rank            uint32 [n_micro] out or NULL: position of every micro-expert
+ *                   in the ascending order (0 = most redundant)
+ */
+int camera_select_prune(camera_ctx* ctx, void* stream,
+                        const float* energy, int64_t n_micro,
+                        const int64_t* seg_offsets, int n_seg, double ratio,
+                        uint8_t* keep_mask, int32_t* kept_per_expert,
+                        int32_t* kept_idx, uint32_t* rank);
+
+/*
+ * S_1..S_L = ListSplitByRatio(R, r_1..r_L) and the per-expert GetSubIndex --
+ * Algorithm 3 (CAMERA-Q), lines 5-8; precision levels and proportions as in the
+ * appendix "Mixed-precision Settings".  Class 0 is the fraction ratios[0] with
+ * the highest energy and gets bits[0]; boundaries are the cumulative floors
+ * cut_m = floor((r_1+..+r_m) * n_micro + 1e-6) counted from the most important
+ * end, on the same order as camera_select_prune.
+ *
+ *   bits, ratios   HOST arrays [n_levels]; ratios >= 0 and sum to 1 (1e-9)
+ *   bit_of         uint8 [n_micro] out: bit width of every micro-expert
+ *   level_count    int32 [n_seg x n_levels] out: class sizes per expert
+ *   perm           int32 [n_micro] out or NULL: inside every expert's range,
+ *                  the members of class 0 first, then class 1, ..., each in
+ *                  ascending index order (the reordering that colocates equal
+ *                  precision inside an expert, Section "Mixed-precision
+ *                  Strategy CAMERA-Q")
+ */
+int camera_alloc_bits(camera_ctx* ctx, void* stream,
+                      const float* energy, int64_t n_micro,
+                      const int64_t* seg_offsets, int n_seg,
+                      int n_levels, const int* bits, const double* ratios,
+                      uint8_t* bit_of, int32_t* level_count, int32_t* perm);
+
+/*
+ * Per-kernel-group timing for benchmarks.  With profiling on, every launch
+ * group is bracketed by HIP events on the caller's stream.
+ * camera_profile_read waits for the recorded events, returns the summed
+ * milliseconds and the number of launch groups since the last reset, and
+ * resets that group's record.
+ */
+int camera_profile_enable(camera_ctx* ctx, int on);
+int camera_profile_read(camera_ctx* ctx, int kernel_id, double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAMERA_H_ */

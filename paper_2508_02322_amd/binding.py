@@ -1,0 +1,168 @@
+"""Thin ctypes binding over libcamera_hip.so (include/camera.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels
+behind the C ABI.  torch is used for device memory and the current stream.
+There is no CPU fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libcamera_hip.so")
+
+F32, BF16 = 0, 1
+ACCUMULATE, NO_FINALIZE = 1, 2
+K_ROUTE, K_BUCKET, K_GEMM, K_DOWN_NORM, K_FINALIZE, K_RANK = range(6)
+KERNEL_NAMES = ["route", "bucket", "gemm", "down_norm", "finalize", "rank"]
+
+EXPORTS = ["camera_create", "camera_destroy", "camera_last_error", "camera_version", "camera_route_topk",
+           "camera_score_layer", "camera_select_prune", "camera_alloc_bits", "camera_profile_enable",
+           "camera_profile_read"]
+
+_c = ctypes
+_vp, _i, _i64, _f, _d = _c.c_void_p, _c.c_int, _c.c_int64, _c.c_float, _c.c_double
+
+
+class CameraError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"camera status {code}: {message}")
+        self.code = code
+        self.message = message
+
+
+def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} is missing: build it with `python -m paper_2508_02322_amd.build` (there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    lib.camera_create.argtypes = [_c.POINTER(_vp), _i]
+    lib.camera_destroy.argtypes = [_vp]
+    lib.camera_last_error.argtypes = [_vp]
+    lib.camera_last_error.restype = _c.c_char_p
+    lib.camera_version.argtypes = []
+    lib.camera_route_topk.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _i64, _vp, _i, _i, _i, _vp, _vp]
+    lib.camera_score_layer.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _vp, _i, _i, _i64, _vp, _vp, _i64,
+                                       _vp, _i64, _f, _i, _vp, _vp, _vp, _vp]
+    lib.camera_select_prune.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _d, _vp, _vp, _vp, _vp]
+    lib.camera_alloc_bits.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _i, _c.POINTER(_i),
+                                      _c.POINTER(_d), _vp, _vp, _vp]
+    lib.camera_profile_enable.argtypes = [_vp, _i]
+    lib.camera_profile_read.argtypes = [_vp, _i, _c.POINTER(_d), _c.POINTER(_i64)]
+    for name in EXPORTS:
+        if name != "camera_last_error":
+            getattr(lib, name).restype = _i
+    return lib
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else _vp(t.data_ptr())
+
+
+def _stream_handle(device) -> _vp:
+    return _vp(torch.cuda.current_stream(device).cuda_stream)
+
+
+class Camera:
+    """One library context on one GPU.  Methods mirror the C entry points and
+    allocate their outputs with torch on the context's device."""
+
+    def __init__(self, device: int = 0, lib_path: str = LIB_PATH):
+        self.lib = load_library(lib_path)
+        self.device = torch.device("cuda", device)
+        self._ctx = _vp()
+        rc = self.lib.camera_create(_c.byref(self._ctx), device)
+        if rc != 0:
+            raise CameraError(rc, self.lib.camera_last_error(None).decode())
+
+    def close(self):
+        if getattr(self, "_ctx", None) is not None and self._ctx.value:
+            self.lib.camera_destroy(self._ctx)
+            self._ctx = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != 0:
+            raise CameraError(rc, self.lib.camera_last_error(self._ctx).decode())
+
+    # ---- entry points ------------------------------------------------------
+    def route_topk(self, X, W_r, bias, top_k: int, renorm: bool = True):
+        n, d = X.shape
+        n_experts = W_r.shape[0]
+        idx = torch.empty((n, top_k), dtype=torch.int32, device=self.device)
+        w = torch.empty((n, top_k), dtype=torch.float32, device=self.device)
+        self._check(self.lib.camera_route_topk(
+            self._ctx, _stream_handle(self.device), _ptr(X), _dtype_code(X), n, d, X.stride(0), _ptr(W_r),
+            W_r.stride(0), _ptr(bias), n_experts, top_k, int(renorm), _ptr(idx), _ptr(w)))
+        return idx, w
+
+    def score_layer(self, X, topk_idx, topk_w, W_gate, W_up, W_down, alpha: float, flags: int = 0, out=None):
+        """W_gate / W_up [N_E, d_ff, d_model], W_down [N_E, d_model, d_ff] (None with NO_FINALIZE).
+        Returns dict(phi2, phi_inf, omega2, energy); pass `out` to reuse / accumulate into buffers."""
+        n, d = X.shape
+        n_experts, d_ff, _ = W_gate.shape
+        n_micro = n_experts * d_ff
+        if out is None:
+            out = {k: torch.empty(n_micro, dtype=torch.float32, device=self.device)
+                   for k in ("phi2", "phi_inf", "omega2", "energy")}
+        top_k = 0 if topk_idx is None else topk_idx.shape[1]
+        self._check(self.lib.camera_score_layer(
+            self._ctx, _stream_handle(self.device), _ptr(X), _dtype_code(X), n, d, X.stride(0), _ptr(topk_idx),
+            _ptr(topk_w), top_k, n_experts, d_ff, _ptr(W_gate), _ptr(W_up), W_gate.stride(0), _ptr(W_down),
+            0 if W_down is None else W_down.stride(0), float(alpha), flags, _ptr(out["phi2"]), _ptr(out["phi_inf"]),
+            _ptr(out.get("omega2")), _ptr(out.get("energy"))))
+        return out
+
+    def select_prune(self, energy, seg_offsets: Sequence[int], ratio: float, want_idx=False, want_rank=False):
+        n_micro = energy.numel()
+        n_seg = len(seg_offsets) - 1
+        seg = (_i64 * (n_seg + 1))(*seg_offsets)
+        keep = torch.empty(n_micro, dtype=torch.uint8, device=self.device)
+        per_expert = torch.empty(n_seg, dtype=torch.int32, device=self.device)
+        # kept_idx is sized for the worst case; the caller trims it with per_expert.sum()
+        kept_idx = torch.empty(n_micro, dtype=torch.int32, device=self.device) if want_idx else None
+        rank = torch.empty(n_micro, dtype=torch.int32, device=self.device) if want_rank else None
+        self._check(self.lib.camera_select_prune(
+            self._ctx, _stream_handle(self.device), _ptr(energy), n_micro, seg, n_seg, float(ratio), _ptr(keep),
+            _ptr(per_expert), _ptr(kept_idx), _ptr(rank)))
+        return keep, per_expert, kept_idx, rank
+
+    def alloc_bits(self, energy, seg_offsets: Sequence[int], bits: Sequence[int], ratios: Sequence[float],
+                   want_perm=False):
+        n_micro = energy.numel()
+        n_seg = len(seg_offsets) - 1
+        n_levels = len(bits)
+        seg = (_i64 * (n_seg + 1))(*seg_offsets)
+        bit_of = torch.empty(n_micro, dtype=torch.uint8, device=self.device)
+        level_count = torch.empty((n_seg, n_levels), dtype=torch.int32, device=self.device)
+        perm = torch.empty(n_micro, dtype=torch.int32, device=self.device) if want_perm else None
+        self._check(self.lib.camera_alloc_bits(
+            self._ctx, _stream_handle(self.device), _ptr(energy), n_micro, seg, n_seg, n_levels,
+            (_i * n_levels)(*bits), (_d * len(ratios))(*ratios), _ptr(bit_of), _ptr(level_count), _ptr(perm)))
+        return bit_of, level_count, perm
+
+    # ---- profiling ---------------------------------------------------------
+    def profile_enable(self, on: bool):
+        self._check(self.lib.camera_profile_enable(self._ctx, int(on)))
+
+    def profile_read(self, kernel_id: int):
+        ms, count = _d(), _i64()
+        self._check(self.lib.camera_profile_read(self._ctx, kernel_id, _c.byref(ms), _c.byref(count)))
+        return ms.value, count.value

@@ -1,0 +1,435 @@
+// C ABI of libcamera_hip: argument checks on the host, workspace carving and
+// the launch sequence of each entry point.  Declarations and the meaning of
+// every argument are in include/camera.h.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "camera_internal.h"
+
+struct camera_ctx {
+  int device = 0;
+  char err[512] = {0};
+  void* ws = nullptr;
+  size_t ws_bytes = 0;
+  bool profiling = false;
+  struct Span {
+    hipEvent_t begin, end;
+  };
+  std::vector<Span> spans[CAMERA_K_COUNT];       // recorded, not yet read
+  std::vector<Span> free_spans;                  // reusable event pairs
+};
+
+namespace {
+
+char g_create_error[256] = {0};
+
+int fail(camera_ctx* ctx, int code, const char* fmt, ...) {
+  char* dst = ctx ? ctx->err : g_create_error;
+  const size_t cap = ctx ? sizeof(ctx->err) : sizeof(g_create_error);
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(dst, cap, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int fail_hip(camera_ctx* ctx, hipError_t e, const char* what) {
+  return fail(ctx, CAMERA_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define CAMERA_HIP(call, what)                          \
+  do {                                                  \
+    hipError_t e_ = (call);                             \
+    if (e_ != hipSuccess) return fail_hip(ctx, e_, what); \
+  } while (0)
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Makes ctx->device current for the duration of a call and restores the caller's device.
+struct DeviceGuard {
+  int prev = -1;
+  bool changed = false;
+  hipError_t enter(int device) {
+    hipError_t e = hipGetDevice(&prev);
+    if (e != hipSuccess) return e;
+    if (prev != device) {
+      e = hipSetDevice(device);
+      changed = e == hipSuccess;
+    }
+    return e;
+  }
+  ~DeviceGuard() {
+    if (changed) (void)hipSetDevice(prev);
+  }
+};
+
+// Bump allocator over the context workspace; sizes are rounded up to 256 bytes.
+struct Carver {
+  size_t used = 0;
+  size_t take(size_t bytes) {
+    const size_t at = used;
+    used += (bytes + 255) & ~size_t(255);
+    return at;
+  }
+};
+
+int ensure_workspace(camera_ctx* ctx, size_t bytes) {
+  if (bytes <= ctx->ws_bytes) return CAMERA_OK;
+  if (ctx->ws) {
+    hipError_t e = hipFree(ctx->ws);  // waits for the device: earlier calls are done with it
+    ctx->ws = nullptr;
+    ctx->ws_bytes = 0;
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipFree(workspace)");
+  }
+  const size_t want = bytes + bytes / 4 + (1u << 20);
+  hipError_t e = hipMalloc(&ctx->ws, want);
+  if (e != hipSuccess) {
+    ctx->ws = nullptr;
+    (void)hipGetLastError();
+    return fail(ctx, CAMERA_EWORKSPACE, "workspace of %zu bytes: %s", want, hipGetErrorString(e));
+  }
+  ctx->ws_bytes = want;
+  return CAMERA_OK;
+}
+
+// Event bracket around one launch group when profiling is on.
+struct Bracket {
+  camera_ctx* ctx;
+  hipStream_t stream;
+  int id;
+  camera_ctx::Span span{};
+  bool live = false;
+  Bracket(camera_ctx* c, hipStream_t s, int kernel_id) : ctx(c), stream(s), id(kernel_id) {
+    if (!ctx->profiling) return;
+    if (!ctx->free_spans.empty()) {
+      span = ctx->free_spans.back();
+      ctx->free_spans.pop_back();
+    } else if (hipEventCreate(&span.begin) != hipSuccess || hipEventCreate(&span.end) != hipSuccess) {
+      return;
+    }
+    live = hipEventRecord(span.begin, stream) == hipSuccess;
+  }
+  ~Bracket() {
+    if (!live) return;
+    if (hipEventRecord(span.end, stream) == hipSuccess) ctx->spans[id].push_back(span);
+  }
+};
+
+int check_common(camera_ctx* ctx, const void* X, int dtype, int64_t n, int64_t d_model, int64_t ldx) {
+  if (dtype != CAMERA_F32 && dtype != CAMERA_BF16) return fail(ctx, CAMERA_EDTYPE, "dtype: unknown code %d", dtype);
+  if (n < 0) return fail(ctx, CAMERA_EINVAL, "n: negative");
+  if (d_model <= 0) return fail(ctx, CAMERA_EINVAL, "d_model: must be positive");
+  const int v = dtype == CAMERA_BF16 ? 8 : 4;
+  if (d_model % v != 0) return fail(ctx, CAMERA_ESHAPE, "d_model: must be a multiple of %d for this dtype", v);
+  if (ldx < d_model || ldx % v != 0) return fail(ctx, CAMERA_ESHAPE, "ldx: must be >= d_model and a multiple of %d", v);
+  if (d_model > (1 << 24)) return fail(ctx, CAMERA_ESHAPE, "d_model: too large");
+  if (n > 0 && X == nullptr) return fail(ctx, CAMERA_EINVAL, "X: NULL");
+  if (!aligned16(X)) return fail(ctx, CAMERA_ESHAPE, "X: not 16-byte aligned");
+  return CAMERA_OK;
+}
+
+int64_t floor_count(double fraction, int64_t n) { return (int64_t)std::floor(fraction * (double)n + 1e-6); }
+
+int check_segments(camera_ctx* ctx, const int64_t* seg_offsets, int n_seg, int64_t n_micro, camera::SegTable* out) {
+  if (n_seg < 1 || n_seg > CAMERA_MAX_SEGMENTS)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "n_seg: must be in [1, %d]", CAMERA_MAX_SEGMENTS);
+  if (seg_offsets == nullptr) return fail(ctx, CAMERA_EINVAL, "seg_offsets: NULL");
+  if (seg_offsets[0] != 0 || seg_offsets[n_seg] != n_micro)
+    return fail(ctx, CAMERA_EINVAL, "seg_offsets: must start at 0 and end at n_micro");
+  out->n_seg = n_seg;
+  for (int s = 0; s <= n_seg; ++s) {
+    if (s > 0 && seg_offsets[s] < seg_offsets[s - 1]) return fail(ctx, CAMERA_EINVAL, "seg_offsets: not rising");
+    out->off[s] = (int32_t)seg_offsets[s];
+  }
+  return CAMERA_OK;
+}
+
+int check_energy(camera_ctx* ctx, const float* energy, int64_t n_micro) {
+  if (n_micro < 0) return fail(ctx, CAMERA_EINVAL, "n_micro: negative");
+  if (n_micro >= (int64_t(1) << 31) - 1024) return fail(ctx, CAMERA_ESHAPE, "n_micro: too large");
+  if (n_micro > 0 && energy == nullptr) return fail(ctx, CAMERA_EINVAL, "energy: NULL");
+  if (!aligned16(energy)) return fail(ctx, CAMERA_ESHAPE, "energy: not 16-byte aligned");
+  return CAMERA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int camera_version(void) { return 1; }
+
+int camera_create(camera_ctx** out, int device) {
+  if (out == nullptr) return fail(nullptr, CAMERA_EINVAL, "out: NULL");
+  *out = nullptr;
+  if (device < 0) return fail(nullptr, CAMERA_EINVAL, "device: negative");
+  camera_ctx* ctx = new (std::nothrow) camera_ctx();
+  if (!ctx) return fail(nullptr, CAMERA_EWORKSPACE, "out of host memory");
+  ctx->device = device;
+  *out = ctx;
+  return CAMERA_OK;
+}
+
+int camera_destroy(camera_ctx* ctx) {
+  if (ctx == nullptr) return CAMERA_OK;
+  int rc = CAMERA_OK;
+  if (ctx->ws || !ctx->free_spans.empty()) {
+    DeviceGuard guard;
+    (void)guard.enter(ctx->device);
+    for (auto& v : ctx->spans)
+      for (auto& s : v) ctx->free_spans.push_back(s);
+    for (auto& s : ctx->free_spans) {
+      (void)hipEventDestroy(s.begin);
+      (void)hipEventDestroy(s.end);
+    }
+    if (ctx->ws && hipFree(ctx->ws) != hipSuccess) rc = CAMERA_EHIP;
+  }
+  delete ctx;
+  return rc;
+}
+
+const char* camera_last_error(const camera_ctx* ctx) { return ctx ? ctx->err : g_create_error; }
+
+int camera_profile_enable(camera_ctx* ctx, int on) {
+  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
+  ctx->profiling = on != 0;
+  return CAMERA_OK;
+}
+
+int camera_profile_read(camera_ctx* ctx, int kernel_id, double* total_ms, int64_t* launches) {
+  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
+  if (kernel_id < 0 || kernel_id >= CAMERA_K_COUNT) return fail(ctx, CAMERA_EINVAL, "kernel_id: out of range");
+  if (total_ms == nullptr || launches == nullptr) return fail(ctx, CAMERA_EINVAL, "total_ms / launches: NULL");
+  DeviceGuard guard;
+  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
+  double sum = 0.0;
+  int64_t count = 0;
+  for (auto& s : ctx->spans[kernel_id]) {
+    CAMERA_HIP(hipEventSynchronize(s.end), "hipEventSynchronize");
+    float ms = 0.0f;
+    CAMERA_HIP(hipEventElapsedTime(&ms, s.begin, s.end), "hipEventElapsedTime");
+    sum += ms;
+    ++count;
+    ctx->free_spans.push_back(s);
+  }
+  ctx->spans[kernel_id].clear();
+  *total_ms = sum;
+  *launches = count;
+  return CAMERA_OK;
+}
+
+int camera_route_topk(camera_ctx* ctx, void* stream_, const void* X, int dtype, int64_t n, int64_t d_model,
+                      int64_t ldx, const void* W_r, int64_t ldr, const float* bias, int n_experts, int top_k,
+                      int renorm, int32_t* topk_idx, float* topk_w) {
+  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
+  if (int rc = check_common(ctx, X, dtype, n, d_model, ldx)) return rc;
+  if (n_experts < 1 || n_experts > CAMERA_MAX_EXPERTS)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "n_experts: must be in [1, %d]", CAMERA_MAX_EXPERTS);
+  if (top_k < 1 || top_k > n_experts) return fail(ctx, CAMERA_EINVAL, "top_k: must be in [1, n_experts]");
+  if (W_r == nullptr) return fail(ctx, CAMERA_EINVAL, "W_r: NULL");
+  const int v = dtype == CAMERA_BF16 ? 8 : 4;
+  if (ldr < d_model || ldr % v != 0) return fail(ctx, CAMERA_ESHAPE, "ldr: must be >= d_model and a multiple of %d", v);
+  if (!aligned16(W_r)) return fail(ctx, CAMERA_ESHAPE, "W_r: not 16-byte aligned");
+  if (n > 0 && (topk_idx == nullptr || topk_w == nullptr)) return fail(ctx, CAMERA_EINVAL, "topk_idx / topk_w: NULL");
+  if (n * (int64_t)top_k >= (int64_t(1) << 31)) return fail(ctx, CAMERA_ESHAPE, "n * top_k: must be below 2^31");
+  if (n == 0) return CAMERA_OK;
+
+  DeviceGuard guard;
+  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  Bracket b(ctx, stream, CAMERA_K_ROUTE);
+  CAMERA_HIP(camera::launch_route_topk(stream, X, dtype, n, d_model, ldx, W_r, ldr, bias, n_experts, top_k, renorm,
+                                       topk_idx, topk_w),
+             "route_topk launch");
+  return CAMERA_OK;
+}
+
+int camera_score_layer(camera_ctx* ctx, void* stream_, const void* X, int dtype, int64_t n, int64_t d_model,
+                       int64_t ldx, const int32_t* topk_idx, const float* topk_w, int top_k, int n_experts,
+                       int64_t d_ff, const void* W_gate, const void* W_up, int64_t stride_gu, const void* W_down,
+                       int64_t stride_down, float alpha, int flags, float* phi2, float* phi_inf, float* omega2,
+                       float* energy) {
+  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
+  if (int rc = check_common(ctx, X, dtype, n, d_model, ldx)) return rc;
+  const bool dense = topk_idx == nullptr && topk_w == nullptr;
+  if (!dense && (topk_idx == nullptr || topk_w == nullptr))
+    return fail(ctx, CAMERA_EINVAL, "topk_idx / topk_w: give both or neither");
+  if (n_experts < 1 || n_experts > CAMERA_MAX_EXPERTS)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "n_experts: must be in [1, %d]", CAMERA_MAX_EXPERTS);
+  if (!dense && (top_k < 1 || top_k > n_experts)) return fail(ctx, CAMERA_EINVAL, "top_k: must be in [1, n_experts]");
+  if (d_ff <= 0) return fail(ctx, CAMERA_EINVAL, "d_ff: must be positive");
+  if (flags & ~(CAMERA_ACCUMULATE | CAMERA_NO_FINALIZE)) return fail(ctx, CAMERA_EINVAL, "flags: unknown bits");
+  if (!(alpha >= 0.0f && alpha <= 1.0f)) return fail(ctx, CAMERA_EINVAL, "alpha: must be in [0, 1]");
+  const bool finalize = !(flags & CAMERA_NO_FINALIZE);
+  const bool accumulate = (flags & CAMERA_ACCUMULATE) != 0;
+  if (W_gate == nullptr || W_up == nullptr) return fail(ctx, CAMERA_EINVAL, "W_gate / W_up: NULL");
+  if (finalize && W_down == nullptr) return fail(ctx, CAMERA_EINVAL, "W_down: NULL");
+  if (phi2 == nullptr || phi_inf == nullptr) return fail(ctx, CAMERA_EINVAL, "phi2 / phi_inf: NULL");
+  if (finalize && (omega2 == nullptr || energy == nullptr)) return fail(ctx, CAMERA_EINVAL, "omega2 / energy: NULL");
+  const int v = dtype == CAMERA_BF16 ? 8 : 4;
+  if (stride_gu < d_ff * d_model || stride_gu % v != 0)
+    return fail(ctx, CAMERA_ESHAPE, "stride_gu: must be >= d_ff*d_model and a multiple of %d", v);
+  if (finalize && stride_down < d_ff * d_model) return fail(ctx, CAMERA_ESHAPE, "stride_down: must be >= d_model*d_ff");
+  if (!aligned16(W_gate) || !aligned16(W_up) || !aligned16(W_down))
+    return fail(ctx, CAMERA_ESHAPE, "W_gate / W_up / W_down: not 16-byte aligned");
+  const int64_t n_micro = (int64_t)n_experts * d_ff;
+  if (n_micro >= (int64_t(1) << 31) - 1024) return fail(ctx, CAMERA_ESHAPE, "n_experts * d_ff: too large");
+  const int64_t n_pairs = dense ? n * n_experts : n * (int64_t)top_k;
+  if (n_pairs >= (int64_t(1) << 31) - 1024) return fail(ctx, CAMERA_ESHAPE, "routed pairs: must be below 2^31");
+
+  const int tile_m = camera::gemm_tile_m(dtype, d_ff);
+  const int64_t max_tiles64 = n == 0 ? 0 : (dense ? n_experts * ((n + tile_m - 1) / tile_m) : n_pairs / tile_m + n_experts);
+  if (max_tiles64 > 65535)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "too many token tiles (%lld) for one call: feed the tokens in chunks with CAMERA_ACCUMULATE",
+                (long long)max_tiles64);
+  const int max_tiles = (int)max_tiles64;
+  const int splits = finalize ? camera::down_norm_splits(n_experts, d_model, d_ff) : 0;
+  const int64_t n_blocks = dense ? 0 : camera::bucket_blocks(n_pairs);
+
+  Carver cv;
+  const size_t o_counts = cv.take(sizeof(int32_t) * n_experts);
+  const size_t o_offsets = cv.take(sizeof(int32_t) * (n_experts + 1));
+  const size_t o_tile_off = cv.take(sizeof(int32_t) * (n_experts + 1));
+  const size_t o_tile_exp = cv.take(sizeof(int32_t) * (max_tiles + 1));
+  const size_t o_perm = cv.take(dense ? 0 : sizeof(int32_t) * n_pairs);
+  const size_t o_wperm = cv.take(dense ? 0 : sizeof(float) * n_pairs);
+  const size_t o_hist = cv.take(sizeof(int32_t) * n_blocks * n_experts);
+  const size_t o_p2 = cv.take(sizeof(float) * (size_t)max_tiles * d_ff);
+  const size_t o_pm = cv.take(sizeof(float) * (size_t)max_tiles * d_ff);
+  const size_t o_omega = cv.take(sizeof(float) * (size_t)splits * n_micro);
+
+  DeviceGuard guard;
+  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
+  if (int rc = ensure_workspace(ctx, cv.used)) return rc;
+  char* ws = static_cast<char*>(ctx->ws);
+  camera::BucketTables t;
+  t.counts = reinterpret_cast<int32_t*>(ws + o_counts);
+  t.offsets = reinterpret_cast<int32_t*>(ws + o_offsets);
+  t.tile_offset = reinterpret_cast<int32_t*>(ws + o_tile_off);
+  t.tile_expert = reinterpret_cast<int32_t*>(ws + o_tile_exp);
+  t.perm = dense ? nullptr : reinterpret_cast<int32_t*>(ws + o_perm);
+  t.w_perm = dense ? nullptr : reinterpret_cast<float*>(ws + o_wperm);
+  t.block_hist = reinterpret_cast<int32_t*>(ws + o_hist);
+  float* part_phi2 = reinterpret_cast<float*>(ws + o_p2);
+  float* part_max = reinterpret_cast<float*>(ws + o_pm);
+  float* omega_part = reinterpret_cast<float*>(ws + o_omega);
+
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  {
+    Bracket b(ctx, stream, CAMERA_K_BUCKET);
+    if (dense || n == 0)
+      CAMERA_HIP(camera::launch_dense_tables(stream, n, n_experts, tile_m, max_tiles, t), "dense tables launch");
+    else
+      CAMERA_HIP(camera::launch_bucket(stream, topk_idx, topk_w, n, top_k, n_experts, tile_m, max_tiles, t),
+                 "bucket launch");
+  }
+  if (n > 0) {
+    Bracket b(ctx, stream, CAMERA_K_GEMM);
+    CAMERA_HIP(camera::launch_grouped_gemm(stream, dtype, X, ldx, d_model, d_ff, n_experts, W_gate, W_up, stride_gu,
+                                           max_tiles, t, part_phi2, part_max),
+               "grouped gemm launch");
+  }
+  if (finalize) {
+    Bracket b(ctx, stream, CAMERA_K_DOWN_NORM);
+    CAMERA_HIP(camera::launch_down_norm(stream, dtype, W_down, stride_down, n_experts, d_model, d_ff, splits,
+                                        omega_part),
+               "down norm launch");
+  }
+  {
+    Bracket b(ctx, stream, CAMERA_K_FINALIZE);
+    CAMERA_HIP(camera::launch_finalize(stream, n_experts, d_ff, t, part_phi2, part_max, omega_part, splits, alpha,
+                                       accumulate ? 1 : 0, finalize ? 1 : 0, phi2, phi_inf, omega2, energy),
+               "finalize launch");
+  }
+  return CAMERA_OK;
+}
+
+int camera_select_prune(camera_ctx* ctx, void* stream_, const float* energy, int64_t n_micro,
+                        const int64_t* seg_offsets, int n_seg, double ratio, uint8_t* keep_mask,
+                        int32_t* kept_per_expert, int32_t* kept_idx, uint32_t* rank) {
+  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
+  if (int rc = check_energy(ctx, energy, n_micro)) return rc;
+  camera::SegTable seg;
+  if (int rc = check_segments(ctx, seg_offsets, n_seg, n_micro, &seg)) return rc;
+  if (!(ratio >= 0.0 && ratio <= 1.0)) return fail(ctx, CAMERA_EINVAL, "ratio: must be in [0, 1]");
+  if (kept_per_expert == nullptr) return fail(ctx, CAMERA_EINVAL, "kept_per_expert: NULL");
+  if (n_micro > 0 && keep_mask == nullptr) return fail(ctx, CAMERA_EINVAL, "keep_mask: NULL");
+
+  camera::RankCuts cuts;
+  memset(&cuts, 0, sizeof(cuts));
+  cuts.n_cuts = 1;
+  cuts.cut_rank[0] = floor_count(ratio, n_micro);  // n_prune
+  cuts.out_of_below[0] = 1;                        // below no cut: kept
+  cuts.out_of_below[1] = 0;
+
+  Carver cv;
+  const size_t o_class = cv.take((size_t)n_micro + 64);
+  const size_t o_sort = cv.take(rank ? sizeof(int32_t) * camera::rank_workspace_words(n_micro, 1) : 0);
+  DeviceGuard guard;
+  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
+  if (int rc = ensure_workspace(ctx, cv.used)) return rc;
+  char* ws = static_cast<char*>(ctx->ws);
+  uint8_t* class_buf = reinterpret_cast<uint8_t*>(ws + o_class);
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  Bracket b(ctx, stream, CAMERA_K_RANK);
+  CAMERA_HIP(camera::launch_classify(stream, energy, n_micro, cuts, class_buf, keep_mask, kept_idx, nullptr),
+             "classify launch");
+  CAMERA_HIP(camera::launch_segment_counts(stream, class_buf, seg, 1, 1, kept_per_expert, nullptr),
+             "segment counts launch");
+  if (rank)
+    CAMERA_HIP(camera::launch_full_rank(stream, energy, n_micro, rank, reinterpret_cast<int32_t*>(ws + o_sort)),
+               "rank launch");
+  return CAMERA_OK;
+}
+
+int camera_alloc_bits(camera_ctx* ctx, void* stream_, const float* energy, int64_t n_micro,
+                      const int64_t* seg_offsets, int n_seg, int n_levels, const int* bits, const double* ratios,
+                      uint8_t* bit_of, int32_t* level_count, int32_t* perm) {
+  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
+  if (int rc = check_energy(ctx, energy, n_micro)) return rc;
+  camera::SegTable seg;
+  if (int rc = check_segments(ctx, seg_offsets, n_seg, n_micro, &seg)) return rc;
+  if (n_levels < 1 || n_levels > CAMERA_MAX_LEVELS)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "n_levels: must be in [1, %d]", CAMERA_MAX_LEVELS);
+  if (bits == nullptr || ratios == nullptr) return fail(ctx, CAMERA_EINVAL, "bits / ratios: NULL");
+  double total = 0.0;
+  for (int m = 0; m < n_levels; ++m) {
+    if (!(ratios[m] >= 0.0)) return fail(ctx, CAMERA_EINVAL, "ratios[%d]: negative", m);
+    if (bits[m] < 0 || bits[m] > 255) return fail(ctx, CAMERA_EINVAL, "bits[%d]: must be in [0, 255]", m);
+    total += ratios[m];
+  }
+  if (std::fabs(total - 1.0) > 1e-9) return fail(ctx, CAMERA_EINVAL, "ratios: must sum to 1");
+  if (level_count == nullptr) return fail(ctx, CAMERA_EINVAL, "level_count: NULL");
+  if (n_micro > 0 && bit_of == nullptr) return fail(ctx, CAMERA_EINVAL, "bit_of: NULL");
+
+  // Class m ends, counted from the most important end, at cut_m = floor((r_1+..+r_m) n + 1e-6);
+  // an element is below ascending-rank cut n - cut_m iff it is not in classes 0..m.
+  camera::RankCuts cuts;
+  memset(&cuts, 0, sizeof(cuts));
+  cuts.n_cuts = n_levels - 1;
+  double acc = 0.0;
+  for (int m = 0; m + 1 < n_levels; ++m) {
+    acc += ratios[m];
+    cuts.cut_rank[m] = n_micro - floor_count(acc, n_micro);
+  }
+  for (int m = 0; m < n_levels; ++m) cuts.out_of_below[m] = (uint8_t)bits[m];
+
+  Carver cv;
+  const size_t o_class = cv.take((size_t)n_micro + 64);
+  DeviceGuard guard;
+  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
+  if (int rc = ensure_workspace(ctx, cv.used)) return rc;
+  uint8_t* class_buf = reinterpret_cast<uint8_t*>(static_cast<char*>(ctx->ws) + o_class);
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  Bracket b(ctx, stream, CAMERA_K_RANK);
+  CAMERA_HIP(camera::launch_classify(stream, energy, n_micro, cuts, class_buf, bit_of, nullptr, nullptr),
+             "classify launch");
+  CAMERA_HIP(camera::launch_segment_counts(stream, class_buf, seg, n_levels, 0, level_count, perm),
+             "segment counts launch");
+  return CAMERA_OK;
+}
+
+}  // extern "C"

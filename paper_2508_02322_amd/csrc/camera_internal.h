@@ -1,0 +1,91 @@
+// Internal declarations shared by the translation units of libcamera_hip.
+// Host-side launchers; each enqueues on `stream` and returns hipGetLastError().
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/camera.h"
+
+namespace camera {
+
+// ---- device-side helpers used by several kernels ---------------------------
+constexpr int kWave = 64;
+
+// Tables that describe how the routed (token, expert) pairs are laid out after
+// bucketing.  All live in the context workspace.
+struct BucketTables {
+  int32_t* counts;        // [n_experts]        pairs per expert
+  int32_t* offsets;       // [n_experts + 1]    first slot of each expert
+  int32_t* tile_offset;   // [n_experts + 1]    first M-tile of each expert
+  int32_t* tile_expert;   // [max_tiles]        expert of each M-tile slot
+  int32_t* perm;          // [P]                token id of each slot (NULL: identity per expert)
+  float* w_perm;          // [P]                routing weight of each slot (NULL: 1)
+  int32_t* block_hist;    // [n_blocks x n_experts] scratch of the counting sort
+};
+
+// ---- route.hip --------------------------------------------------------------
+hipError_t launch_route_topk(hipStream_t stream, const void* X, int dtype, int64_t n, int64_t d_model,
+                             int64_t ldx, const void* W_r, int64_t ldr, const float* bias, int n_experts,
+                             int top_k, int renorm, int32_t* topk_idx, float* topk_w);
+
+// ---- bucket.hip -------------------------------------------------------------
+// Pairs per block of the counting sort.
+constexpr int kBucketChunk = 1024;
+inline int64_t bucket_blocks(int64_t n_pairs) { return (n_pairs + kBucketChunk - 1) / kBucketChunk; }
+
+// Stable counting sort of the n*top_k pairs by expert, then the M-tile tables
+// for tiles of `tile_m` rows.
+hipError_t launch_bucket(hipStream_t stream, const int32_t* topk_idx, const float* topk_w, int64_t n, int top_k,
+                         int n_experts, int tile_m, int max_tiles, const BucketTables& t);
+// Tables for the dense case: every expert sees tokens 0..n-1 with weight 1.
+hipError_t launch_dense_tables(hipStream_t stream, int64_t n, int n_experts, int tile_m, int max_tiles,
+                               const BucketTables& t);
+
+// ---- gemm.hip ---------------------------------------------------------------
+// M-tile height used by the grouped contraction for `dtype`.
+int gemm_tile_m(int dtype, int64_t d_ff);
+// part_phi2 / part_max: [max_tiles x d_ff] per-M-tile column statistics.
+hipError_t launch_grouped_gemm(hipStream_t stream, int dtype, const void* X, int64_t ldx, int64_t d_model,
+                               int64_t d_ff, int n_experts, const void* W_gate, const void* W_up,
+                               int64_t stride_gu, int max_tiles, const BucketTables& t, float* part_phi2,
+                               float* part_max);
+
+// ---- norm.hip ---------------------------------------------------------------
+// Row splits used for a [d_model x d_ff] matrix; omega_part is [splits x n_experts*d_ff].
+int down_norm_splits(int n_experts, int64_t d_model, int64_t d_ff);
+hipError_t launch_down_norm(hipStream_t stream, int dtype, const void* W_down, int64_t stride_down,
+                            int n_experts, int64_t d_model, int64_t d_ff, int splits, float* omega_part);
+
+// Reduce the per-tile statistics in tile order, merge with earlier chunks,
+// reduce omega partials in split order and form the energy.
+hipError_t launch_finalize(hipStream_t stream, int n_experts, int64_t d_ff, const BucketTables& t,
+                           const float* part_phi2, const float* part_max, const float* omega_part, int splits,
+                           float alpha, int accumulate, int finalize, float* phi2, float* phi_inf,
+                           float* omega2, float* energy);
+
+// ---- rank.hip ---------------------------------------------------------------
+struct RankCuts {
+  int n_cuts;                          // <= CAMERA_MAX_LEVELS - 1
+  int64_t cut_rank[CAMERA_MAX_LEVELS]; // element is "below cut q" iff its ascending rank < cut_rank[q]
+  uint8_t out_of_below[CAMERA_MAX_LEVELS + 1];  // output byte for "below k cuts"
+};
+struct SegTable {
+  int n_seg;
+  int32_t off[CAMERA_MAX_SEGMENTS + 1];
+};
+// Workspace (int32 words) the rank kernels need for n_micro keys.
+int64_t rank_workspace_words(int64_t n_micro, int want_rank);
+// class_out[i] = number of cuts element i is below; byte_out[i] = out_of_below[class_out[i]].
+// kept_idx (optional): ascending indices of the elements below no cut.
+hipError_t launch_classify(hipStream_t stream, const float* energy, int64_t n_micro, const RankCuts& cuts,
+                           uint8_t* class_out, uint8_t* byte_out, int32_t* kept_idx, int32_t* ws);
+// Per segment: count[s][c] for c in [0, n_classes) of class_out (or, when
+// `kept_only`, the single count of class 0), and the optional stable partition.
+hipError_t launch_segment_counts(hipStream_t stream, const uint8_t* class_out, const SegTable& seg,
+                                 int n_classes, int kept_only, int32_t* counts, int32_t* perm);
+// Full stable ascending rank by LSD radix sort.
+hipError_t launch_full_rank(hipStream_t stream, const float* energy, int64_t n_micro, uint32_t* rank,
+                            int32_t* ws);
+
+}  // namespace camera

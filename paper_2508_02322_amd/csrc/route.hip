@@ -1,0 +1,179 @@
+// A = Top&Norm(R X): router logits, softmax, top-k and renormalisation
+// (Algorithm 1, line 2; the weights A_i(x) of Eq. 2).
+//
+// Logits L[j, e] = <x_j, R_e> (+ bias_e) are accumulated in float32: for bf16 on
+// v_mfma_f32_32x32x16_bf16 (one wave = 32 tokens x all experts, fragments read
+// straight from global memory -- R is small and stays in L2), for float32 with
+// FMA and a wave reduction.  The logits of a block's tokens go through LDS so
+// that one lane can walk all experts of one token: top_k rounds of "largest
+// remaining logit, lower index on ties".  Selection is on the logits (softmax is
+// increasing, so this is the top-k of the probabilities); the kept weights are
+// exp(L - max) over the softmax denominator, renormalised over the kept ones.
+#include <hip/hip_bf16.h>
+
+#include "camera_internal.h"
+
+namespace camera {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int kTokens = 32;  // tokens per block
+
+// One lane, one token: logits of the token are s_row[0 .. n_experts).
+__device__ void topk_of_token(const float* s_row, int n_experts, int top_k, int renorm, int32_t* idx_out,
+                              float* w_out) {
+  float row_max = -INFINITY;
+  for (int e = 0; e < n_experts; ++e) row_max = fmaxf(row_max, s_row[e]);
+  float denom = 0.0f;
+  if (!renorm)
+    for (int e = 0; e < n_experts; ++e) denom += __expf(s_row[e] - row_max);
+  float prev_v = INFINITY;
+  int prev_i = -1;
+  float kept_sum = 0.0f;
+  for (int r = 0; r < top_k; ++r) {
+    float best_v = -INFINITY;
+    int best_i = -1;
+    for (int e = 0; e < n_experts; ++e) {
+      const float v = s_row[e];
+      const bool after_prev = v < prev_v || (v == prev_v && e > prev_i);  // not yet taken
+      if (after_prev && (best_i < 0 || v > best_v)) {  // strict >: lower index wins ties
+        best_v = v;
+        best_i = e;
+      }
+    }
+    const float p = __expf(best_v - row_max);
+    idx_out[r] = best_i;
+    w_out[r] = p;
+    kept_sum += p;
+    prev_v = best_v;
+    prev_i = best_i;
+  }
+  const float inv = 1.0f / (renorm ? kept_sum : denom);
+  for (int r = 0; r < top_k; ++r) w_out[r] *= inv;
+}
+
+// bf16: one wave per block, 32 tokens, NT tiles of 32 experts.
+template <int NT>
+__global__ __launch_bounds__(kWave) void route_bf16_kernel(const __hip_bfloat16* __restrict__ X, int64_t n,
+                                                           int d_model, int64_t ldx,
+                                                           const __hip_bfloat16* __restrict__ R, int64_t ldr,
+                                                           const float* __restrict__ bias, int n_experts,
+                                                           int top_k, int renorm, int32_t* __restrict__ topk_idx,
+                                                           float* __restrict__ topk_w) {
+  __shared__ float s_logit[kTokens][NT * 32 + 1];
+  const int lane = threadIdx.x;
+  const int frag_row = lane % 32, frag_half = lane / 32;
+  const int64_t tok0 = (int64_t)blockIdx.x * kTokens;
+  const int64_t tok = tok0 + frag_row;
+  const __hip_bfloat16* x_src = tok < n ? X + tok * ldx + frag_half * 8 : nullptr;
+  const __hip_bfloat16* r_src[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int e = t * 32 + frag_row;
+    r_src[t] = e < n_experts ? R + (int64_t)e * ldr + frag_half * 8 : nullptr;
+  }
+  f32x16 acc[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+  for (int k0 = 0; k0 < d_model; k0 += 16) {
+    const bool k_ok = k0 + frag_half * 8 < d_model;  // d_model is a multiple of 8
+    u32x4 av = (x_src && k_ok) ? *reinterpret_cast<const u32x4*>(x_src + k0) : zero4;
+    const bf16x8 fa = __builtin_bit_cast(bf16x8, av);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      u32x4 bv = (r_src[t] && k_ok) ? *reinterpret_cast<const u32x4*>(r_src[t] + k0) : zero4;
+      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, __builtin_bit_cast(bf16x8, bv), acc[t], 0, 0, 0);
+    }
+  }
+  // accumulator register r of lane l: token row 8*(r/4) + 4*(l/32) + (r%4), expert column l % 32
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int e = t * 32 + frag_row;
+    const float b = (bias && e < n_experts) ? bias[e] : 0.0f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s_logit[(r / 4) * 8 + frag_half * 4 + (r % 4)][e] = acc[t][r] + b;
+  }
+  __syncthreads();
+  if (lane < kTokens && tok0 + lane < n)
+    topk_of_token(s_logit[lane], n_experts, top_k, renorm, topk_idx + (tok0 + lane) * top_k,
+                  topk_w + (tok0 + lane) * top_k);
+}
+
+// float32: four waves per block, 32 tokens, each wave 8 tokens; lanes stride over d_model.
+__global__ __launch_bounds__(256) void route_f32_kernel(const float* __restrict__ X, int64_t n, int d_model,
+                                                        int64_t ldx, const float* __restrict__ R, int64_t ldr,
+                                                        const float* __restrict__ bias, int n_experts, int top_k,
+                                                        int renorm, int32_t* __restrict__ topk_idx,
+                                                        float* __restrict__ topk_w) {
+  __shared__ float s_logit[kTokens][CAMERA_MAX_EXPERTS + 1];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int64_t tok0 = (int64_t)blockIdx.x * kTokens;
+  for (int t = 0; t < 8; ++t) {
+    const int64_t tok = tok0 + wave * 8 + t;
+    if (tok >= n) break;  // wave-uniform
+    const float* x = X + tok * ldx;
+    for (int e = 0; e < n_experts; ++e) {
+      const float* rr = R + (int64_t)e * ldr;
+      float s = 0.0f;
+      for (int c = lane * 4; c < d_model; c += kWave * 4) {  // d_model is a multiple of 4
+        const float4 xv = *reinterpret_cast<const float4*>(x + c);
+        const float4 rv = *reinterpret_cast<const float4*>(rr + c);
+        s = fmaf(xv.x, rv.x, s);
+        s = fmaf(xv.y, rv.y, s);
+        s = fmaf(xv.z, rv.z, s);
+        s = fmaf(xv.w, rv.w, s);
+      }
+#pragma unroll
+      for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor(s, m);
+      if (lane == 0) s_logit[wave * 8 + t][e] = s + (bias ? bias[e] : 0.0f);
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < kTokens && tok0 + threadIdx.x < n)
+    topk_of_token(s_logit[threadIdx.x], n_experts, top_k, renorm, topk_idx + (tok0 + threadIdx.x) * top_k,
+                  topk_w + (tok0 + threadIdx.x) * top_k);
+}
+
+template <int NT>
+void launch_bf16(hipStream_t stream, int64_t n_blocks, const void* X, int64_t n, int64_t d_model, int64_t ldx,
+                 const void* W_r, int64_t ldr, const float* bias, int n_experts, int top_k, int renorm,
+                 int32_t* topk_idx, float* topk_w) {
+  hipLaunchKernelGGL(route_bf16_kernel<NT>, dim3((unsigned)n_blocks), dim3(kWave), 0, stream,
+                     static_cast<const __hip_bfloat16*>(X), n, (int)d_model, ldx,
+                     static_cast<const __hip_bfloat16*>(W_r), ldr, bias, n_experts, top_k, renorm, topk_idx,
+                     topk_w);
+}
+
+}  // namespace
+
+hipError_t launch_route_topk(hipStream_t stream, const void* X, int dtype, int64_t n, int64_t d_model,
+                             int64_t ldx, const void* W_r, int64_t ldr, const float* bias, int n_experts,
+                             int top_k, int renorm, int32_t* topk_idx, float* topk_w) {
+  if (n <= 0) return hipSuccess;
+  const int64_t n_blocks = (n + kTokens - 1) / kTokens;
+  if (dtype == CAMERA_BF16) {
+    const int nt = (n_experts + 31) / 32;
+#define CAMERA_ROUTE_CASE(NT)                                                                                 \
+  launch_bf16<NT>(stream, n_blocks, X, n, d_model, ldx, W_r, ldr, bias, n_experts, top_k, renorm, topk_idx, \
+                  topk_w)
+    if (nt <= 1) CAMERA_ROUTE_CASE(1);
+    else if (nt <= 2) CAMERA_ROUTE_CASE(2);
+    else if (nt <= 4) CAMERA_ROUTE_CASE(4);
+    else CAMERA_ROUTE_CASE(8);
+#undef CAMERA_ROUTE_CASE
+  } else {
+    hipLaunchKernelGGL(route_f32_kernel, dim3((unsigned)n_blocks), dim3(256), 0, stream,
+                       static_cast<const float*>(X), n, (int)d_model, ldx, static_cast<const float*>(W_r), ldr,
+                       bias, n_experts, top_k, renorm, topk_idx, topk_w);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace camera

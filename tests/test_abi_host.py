@@ -1,0 +1,150 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol include/camera.h declares, and rejects bad arguments before any GPU call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2508_02322_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+vp, i64 = ctypes.c_void_p, ctypes.c_int64
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.load_library()
+
+
+@pytest.fixture()
+def ctx(lib):
+    c = vp()
+    assert lib.camera_create(ctypes.byref(c), 0) == 0   # touches no GPU
+    yield c
+    lib.camera_destroy(c)
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "camera.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(camera_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert hasattr(lib, name), name
+    assert lib.camera_version() == 1
+
+
+def err(lib, ctx):
+    return lib.camera_last_error(ctx).decode()
+
+
+FAKE = vp(0x1000)   # aligned, never dereferenced: every call below fails validation first
+
+
+def route(lib, ctx, **kw):
+    a = dict(X=FAKE, dtype=1, n=16, d=64, ldx=64, W=FAKE, ldr=64, bias=None, ne=8, k=2, renorm=1, idx=FAKE, w=FAKE)
+    a.update(kw)
+    return lib.camera_route_topk(ctx, None, a["X"], a["dtype"], a["n"], a["d"], a["ldx"], a["W"], a["ldr"], a["bias"],
+                                 a["ne"], a["k"], a["renorm"], a["idx"], a["w"])
+
+
+def test_route_argument_checks(lib, ctx):
+    assert lib.camera_route_topk(None, None, FAKE, 1, 16, 64, 64, FAKE, 64, None, 8, 2, 1, FAKE, FAKE) == -1
+    assert route(lib, ctx, dtype=7) == -3 and "dtype" in err(lib, ctx)
+    assert route(lib, ctx, n=-1) == -1 and "n:" in err(lib, ctx)
+    assert route(lib, ctx, d=60) == -2 and "d_model" in err(lib, ctx)
+    assert route(lib, ctx, ldx=32) == -2 and "ldx" in err(lib, ctx)
+    assert route(lib, ctx, X=None) == -1 and "X" in err(lib, ctx)
+    assert route(lib, ctx, X=vp(0x1004)) == -2 and "aligned" in err(lib, ctx)
+    assert route(lib, ctx, ne=0) == -6 and "n_experts" in err(lib, ctx)
+    assert route(lib, ctx, ne=257) == -6
+    assert route(lib, ctx, k=9) == -1 and "top_k" in err(lib, ctx)
+    assert route(lib, ctx, k=0) == -1
+    assert route(lib, ctx, W=None) == -1 and "W_r" in err(lib, ctx)
+    assert route(lib, ctx, idx=None) == -1 and "topk" in err(lib, ctx)
+    assert route(lib, ctx, n=0) == 0          # empty input: nothing to do, no GPU needed
+
+
+def score(lib, ctx, **kw):
+    a = dict(X=FAKE, dtype=1, n=16, d=64, ldx=64, idx=FAKE, w=FAKE, k=2, ne=8, f=32, Wg=FAKE, Wu=FAKE, sgu=32 * 64,
+             Wd=FAKE, sd=32 * 64, alpha=0.5, flags=0, p2=FAKE, pi=FAKE, o2=FAKE, en=FAKE)
+    a.update(kw)
+    return lib.camera_score_layer(ctx, None, a["X"], a["dtype"], a["n"], a["d"], a["ldx"], a["idx"], a["w"], a["k"],
+                                  a["ne"], a["f"], a["Wg"], a["Wu"], a["sgu"], a["Wd"], a["sd"], a["alpha"], a["flags"],
+                                  a["p2"], a["pi"], a["o2"], a["en"])
+
+
+def test_score_argument_checks(lib, ctx):
+    assert score(lib, ctx, w=None) == -1 and "both or neither" in err(lib, ctx)
+    assert score(lib, ctx, k=0) == -1 and "top_k" in err(lib, ctx)
+    assert score(lib, ctx, f=0) == -1 and "d_ff" in err(lib, ctx)
+    assert score(lib, ctx, alpha=1.5) == -1 and "alpha" in err(lib, ctx)
+    assert score(lib, ctx, alpha=float("nan")) == -1
+    assert score(lib, ctx, flags=8) == -1 and "flags" in err(lib, ctx)
+    assert score(lib, ctx, Wg=None) == -1 and "W_gate" in err(lib, ctx)
+    assert score(lib, ctx, Wd=None) == -1 and "W_down" in err(lib, ctx)
+    assert score(lib, ctx, en=None) == -1 and "energy" in err(lib, ctx)
+    assert score(lib, ctx, p2=None) == -1 and "phi2" in err(lib, ctx)
+    assert score(lib, ctx, sgu=100) == -2 and "stride_gu" in err(lib, ctx)
+    assert score(lib, ctx, sd=100) == -2 and "stride_down" in err(lib, ctx)
+    assert score(lib, ctx, ne=300) == -6
+    assert score(lib, ctx, dtype=0, d=62) == -2
+    assert score(lib, ctx, n=2 ** 31, k=2) == -2 and "pairs" in err(lib, ctx)
+    assert score(lib, ctx, n=2 ** 24, k=8, ne=8) == -6 and "chunks" in err(lib, ctx)
+
+
+def seg_array(vals):
+    return (i64 * len(vals))(*vals)
+
+
+def test_select_and_alloc_argument_checks(lib, ctx):
+    sel = lambda **kw: lib.camera_select_prune(  # noqa: E731
+        ctx, None, kw.get("E", FAKE), kw.get("n", 100), kw.get("seg", seg_array([0, 40, 100])), kw.get("n_seg", 2),
+        kw.get("ratio", 0.4), kw.get("mask", FAKE), kw.get("per", FAKE), None, None)
+    assert sel(E=None) == -1 and "energy" in err(lib, ctx)
+    assert sel(n=-5) == -1
+    assert sel(ratio=1.2) == -1 and "ratio" in err(lib, ctx)
+    assert sel(ratio=-0.1) == -1
+    assert sel(seg=seg_array([0, 40, 90])) == -1 and "seg_offsets" in err(lib, ctx)
+    assert sel(seg=seg_array([0, 140, 100])) == -1 and "rising" in err(lib, ctx)
+    assert sel(seg=seg_array([1, 40, 100])) == -1
+    assert sel(n_seg=0) == -6 and "n_seg" in err(lib, ctx)
+    assert sel(n_seg=513) == -6
+    assert sel(seg=None) == -1
+    assert sel(mask=None) == -1 and "keep_mask" in err(lib, ctx)
+    assert sel(per=None) == -1 and "kept_per_expert" in err(lib, ctx)
+    assert sel(E=vp(0x1008)) == -2
+
+    def alloc(bits=(3, 2, 1), ratios=(0.1, 0.8, 0.1), n_levels=None, **kw):
+        nl = len(bits) if n_levels is None else n_levels
+        return lib.camera_alloc_bits(ctx, None, kw.get("E", FAKE), 100, seg_array([0, 40, 100]), 2, nl,
+                                     (ctypes.c_int * len(bits))(*bits), (ctypes.c_double * len(ratios))(*ratios),
+                                     kw.get("bit_of", FAKE), kw.get("lc", FAKE), None)
+    assert alloc(ratios=(0.5, 0.2, 0.2)) == -1 and "sum to 1" in err(lib, ctx)
+    assert alloc(ratios=(1.2, -0.1, -0.1)) == -1 and "negative" in err(lib, ctx)
+    assert alloc(bits=(300, 2, 1)) == -1 and "bits" in err(lib, ctx)
+    assert alloc(bits=(1,) * 9, ratios=(1.0,) + (0.0,) * 8) == -6 and "n_levels" in err(lib, ctx)
+    assert alloc(n_levels=0) == -6
+    assert alloc(lc=None) == -1 and "level_count" in err(lib, ctx)
+    assert alloc(bit_of=None) == -1
+
+
+def test_create_and_profile_checks(lib, ctx):
+    assert lib.camera_create(None, 0) == -1
+    c = vp()
+    assert lib.camera_create(ctypes.byref(c), -3) == -1 and "device" in lib.camera_last_error(None).decode()
+    assert lib.camera_destroy(None) == 0
+    assert lib.camera_profile_enable(None, 1) == -1
+    ms, cnt = ctypes.c_double(), i64()
+    assert lib.camera_profile_read(ctx, 99, ctypes.byref(ms), ctypes.byref(cnt)) == -1
+    assert lib.camera_profile_read(ctx, 0, None, ctypes.byref(cnt)) == -1
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(FileNotFoundError):
+        binding.load_library(str(tmp_path / "libcamera_hip.so"))

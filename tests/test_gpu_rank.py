@@ -1,0 +1,92 @@
+"""GPU parity of camera_select_prune / camera_alloc_bits: integer work, so bit-exact
+against the oracle on the same float32 energy vector."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import camera_oracle as orc
+from paper_2508_02322_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def even_segments(n, n_seg):
+    return [int(round(s * n / n_seg)) for s in range(n_seg + 1)]
+
+
+def check_select(cam, E, seg, ratio, want_rank=True):
+    keep, per, kept_idx, rank = cam.select_prune(E.cuda(), seg, ratio, want_idx=True, want_rank=want_rank)
+    o_keep, o_per, o_idx, o_rank = orc.select_prune(E.numpy(), seg, ratio)
+    np.testing.assert_array_equal(keep.cpu().numpy(), o_keep)
+    np.testing.assert_array_equal(per.cpu().numpy(), o_per)
+    np.testing.assert_array_equal(kept_idx.cpu().numpy()[:o_idx.size], o_idx)
+    if want_rank:
+        np.testing.assert_array_equal(rank.cpu().numpy().astype(np.int64), o_rank)
+
+
+@pytest.mark.parametrize("n", [1, 5, 255, 256, 257, 1000, 4096, 16385, 98304, 184320, 200001])
+def test_select_sizes(cam, n):
+    E = inputs.energy_like(n, seed=n)
+    seg = even_segments(n, min(n, 7))
+    for ratio in (0.2, 0.4, 0.6):
+        check_select(cam, E, seg, ratio, want_rank=(ratio == 0.4))
+
+
+def test_select_edge_ratios_and_ties(cam):
+    E = inputs.energy_like(5000, seed=1, zero_fraction=0.3, tie_fraction=0.3)
+    seg = [0, 0, 1234, 1234, 4000, 5000]          # empty segments
+    for ratio in (0.0, 1.0, 0.0001, 0.9999, 0.29, 0.31, 0.5):
+        check_select(cam, E, seg, ratio)
+    zeros = torch.zeros(3000)                      # every key equal: order is by index alone
+    check_select(cam, zeros, [0, 1000, 3000], 0.4)
+    const = torch.full((777,), 3.5)
+    check_select(cam, const, [0, 777], 0.5)
+    signed = torch.tensor([0.0, -0.0, 1.0, -1.0, 0.0, -0.0, 2.0, -2.0] * 50)   # -0.0 ranks as +0.0
+    check_select(cam, signed, [0, 200, 400], 0.4)
+    tiny = torch.tensor([1e-45, 0.0, 1e-38, 3e38, 1e-45])                      # denormals and huge values
+    check_select(cam, tiny, [0, 5], 0.4)
+
+
+def test_select_nested_and_counts(cam):
+    E = inputs.energy_like(184320, seed=7)
+    seg = inputs.segment_offsets(inputs.CONFIGS["qwen2-57b-a14b"])
+    masks = []
+    for ratio in (0.2, 0.4, 0.6):
+        keep, per, _, _ = cam.select_prune(E.cuda(), seg, ratio)
+        assert int(keep.sum()) == 184320 - orc.prune_count(ratio, 184320) == int(per.sum())
+        masks.append(keep.cpu().numpy())
+    assert np.all(masks[1] <= masks[0]) and np.all(masks[2] <= masks[1])
+
+
+VARIANTS = [([3, 2, 1], [0.2, 0.6, 0.2]), ([4, 3, 2], [0.1, 0.3, 0.6]), ([4, 3, 2], [0.0, 0.0, 1.0]),
+            ([3, 2, 1], [0.1, 0.8, 0.1]), ([8, 7, 6, 5, 4, 3, 2, 1], [0.125] * 8), ([5], [1.0]), ([4, 2], [0.5, 0.5])]
+
+
+@pytest.mark.parametrize("n", [3, 640, 5000, 98304])
+def test_alloc_bits(cam, n):
+    E = inputs.energy_like(n, seed=100 + n, zero_fraction=0.1, tie_fraction=0.1)
+    seg = even_segments(n, min(n, 11))
+    for bits, ratios in VARIANTS:
+        bit_of, level_count, perm = cam.alloc_bits(E.cuda(), seg, bits, ratios, want_perm=True)
+        o_bits, o_count, o_perm = orc.alloc_bits(E.numpy(), seg, bits, ratios)
+        np.testing.assert_array_equal(bit_of.cpu().numpy(), o_bits)
+        np.testing.assert_array_equal(level_count.cpu().numpy(), o_count)
+        np.testing.assert_array_equal(perm.cpu().numpy(), o_perm)
+
+
+def test_alloc_lowest_class_matches_prune_mask(cam):
+    E = inputs.energy_like(98300, seed=9).cuda()
+    seg = [0, 98300]
+    bit_of, _, _ = cam.alloc_bits(E, seg, [3, 2, 1], [0.2, 0.6, 0.2])
+    keep, _, _, _ = cam.select_prune(E, seg, 0.2)
+    assert torch.equal(bit_of == 1, keep == 0)
+    avg = bit_of.double().mean().item()
+    assert abs(avg - 2.0) < 1e-12
+
+
+def test_repeatable(cam):
+    E = inputs.energy_like(50000, seed=3).cuda()
+    a = cam.select_prune(E, [0, 50000], 0.4, want_idx=True, want_rank=True)
+    b = cam.select_prune(E, [0, 50000], 0.4, want_idx=True, want_rank=True)
+    for x, y in zip(a, b):
+        assert torch.equal(x[:30000], y[:30000])
