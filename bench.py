@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the CAMERA scoring hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one pass of the whole hot path over every MoE layer of the workload:
+route (Top&Norm) -> bucket -> grouped gate/up contraction with fused epilogue ->
+W_down column norms -> energy -> CAMERA-P masks / CAMERA-Q bit allocation.  All
+inputs (seeded synthetic tensors of the model's shapes) are resident in HBM
+before the timed region starts.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3       # MI355X fp32 vector
+
+# Decisions taken per layer after scoring: CAMERA-P ratios and CAMERA-Q (bits, ratios) settings.
+DECISIONS = {
+    "tiny": dict(prune=[0.4], alloc=[]),
+    "mixtral": dict(prune=[0.2, 0.4, 0.6], alloc=[]),
+    "deepseek-moe-16b": dict(prune=[0.2, 0.4, 0.6], alloc=[]),
+    "qwen2-57b-a14b": dict(prune=[0.2, 0.4, 0.6], alloc=[([3, 2, 1], [0.2, 0.6, 0.2])]),
+    "qwen3-30b-a3b": dict(prune=[], alloc=[([3, 2, 1], [0.2, 0.6, 0.2]), ([4, 3, 2], [0.1, 0.3, 0.6]),
+                                           ([4, 3, 2], [0.0, 0.0, 1.0])]),
+}
+
+# HBM bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/);
+# None until measured for a workload.
+PMC_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="qwen2-57b-a14b", choices=sorted(DECISIONS))
+    ap.add_argument("--layers", type=int, default=0, help="debug: only this many layers (the result is then not the named workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+class LayerRunner:
+    """Owns the resident tensors of one layer and its preallocated outputs."""
+
+    def __init__(self, cam, cfg, layer_idx, torch, inputs):
+        self.cfg = cfg
+        self.t = inputs.make_layer(cfg, layer_idx, device="cuda")
+        n_micro = cfg.n_micro
+        self.out = {k: torch.empty(n_micro, dtype=torch.float32, device="cuda")
+                    for k in ("phi2", "phi_inf", "omega2", "energy")}
+        nr = cfg.n_micro_routed
+        self.out_routed = {k: v[:nr] for k, v in self.out.items()}
+        self.out_shared = {k: v[nr:] for k, v in self.out.items()}
+        self.seg = inputs.segment_offsets(cfg)
+
+    def run(self, cam, decisions):
+        cfg, t = self.cfg, self.t
+        idx, w = cam.route_topk(t["X"], t["W_r"], t["bias"], cfg.top_k)
+        cam.score_layer(t["X"], idx, w, t["W_gate"], t["W_up"], t["W_down"], cfg.alpha, out=self.out_routed)
+        if cfg.n_shared:
+            cam.score_layer(t["X"], None, None, t["Ws_gate"], t["Ws_up"], t["Ws_down"], cfg.alpha, out=self.out_shared)
+        res = []
+        for ratio in decisions["prune"]:
+            res.append(cam.select_prune(self.out["energy"], self.seg, ratio))
+        for bits, ratios in decisions["alloc"]:
+            res.append(cam.alloc_bits(self.out["energy"], self.seg, bits, ratios))
+        return res
+
+
+def cpu_baseline(cfg, inputs):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload: layer 0 with
+    every expert cut down to a slice of its micro-experts (they are scored independently, so
+    the cost is proportional to the slice); the time is scaled back to whole layers."""
+    import numpy as np
+    import torch
+    from oracle import camera_oracle as orc
+
+    def f64(t):
+        return None if t is None else t.to(torch.float32).numpy().astype(np.float64)
+
+    def score(prefix, A, channels):
+        Wg, Wu, Wd = (layer[prefix + s][:, :channels] if s != "_down" else layer[prefix + s][:, :, :channels]
+                      for s in ("_gate", "_up", "_down"))
+        ne = Wg.shape[0]
+        return orc.score_layer(f64(layer["X"]), A, [f64(Wg[e]) for e in range(ne)], [f64(Wu[e]) for e in range(ne)],
+                               [f64(Wd[e]) for e in range(ne)], cfg.alpha)["energy"]
+
+    layer = inputs.make_layer(cfg, 0, device="cpu")
+    # aim at roughly 15 s at ~40 GFLOP/s of float64 matmul
+    budget_flops = 6e11
+    frac = min(1.0, budget_flops / cfg.gemm_flops_per_layer())
+    ch = max(8, int(cfg.d_ff * frac))
+    ch_s = max(8, int(cfg.d_ff_shared * frac)) if cfg.n_shared else 0
+    t0 = time.perf_counter()
+    L = orc.router_logits(f64(layer["X"]), f64(layer["W_r"]), f64(layer["bias"]))
+    _, _, A = orc.top_and_norm(L, cfg.top_k)
+    E = [score("W", A, ch)]
+    if cfg.n_shared:
+        E.append(score("Ws", np.ones((cfg.n_tokens, cfg.n_shared)), ch_s))
+    E = np.concatenate(E).astype(np.float32)
+    orc.select_prune(E, [0, E.size], 0.4)
+    dt = time.perf_counter() - t0
+    scored = cfg.n_experts * ch + cfg.n_shared * ch_s
+    full_layer_s = dt * cfg.n_micro / scored
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = torch.get_num_threads()
+    return {"value": cfg.n_tokens / full_layer_s, "unit": "tokens*layers/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"layer 0, first {ch} of {cfg.d_ff} micro-experts of each routed expert"
+                      + (f" and first {ch_s} of {cfg.d_ff_shared} of each shared expert" if cfg.n_shared else "")
+                      + f", all {cfg.n_tokens} tokens, {dt:.1f} s measured, scaled by {cfg.n_micro / scored:.1f}x to a whole layer"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no second device); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2508_02322_amd import binding, inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    cfg = inputs.CONFIGS[args.workload]
+    n_layers = args.layers if args.layers > 0 else cfg.n_layers
+    decisions = DECISIONS[args.workload]
+    cam = binding.Camera(device=0)
+
+    t_gen = time.perf_counter()
+    layers = [LayerRunner(cam, cfg, i, torch, inputs) for i in range(n_layers)]
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    def step():
+        for lr in layers:
+            lr.run(cam, decisions)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    for k in range(binding.K_RANK + 1):
+        cam.profile_read(k)
+    cam.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    cam.profile_enable(False)
+
+    kernel_ms = {}
+    for k, name in enumerate(binding.KERNEL_NAMES):
+        ms, count = cam.profile_read(k)
+        kernel_ms[name] = {"ms_total": round(ms, 3), "launches": count}
+    gemm = kernel_ms["gemm"]
+    flops_per_step = cfg.gemm_flops_per_layer() * n_layers
+    gemm_launches_per_step = gemm["launches"] / max(1, args.steps)
+    flops_per_launch = flops_per_step / max(1.0, gemm_launches_per_step)
+    avg_launch_s = gemm["ms_total"] / max(1, gemm["launches"]) * 1e-3
+    achieved = flops_per_launch / avg_launch_s / 1e12 if avg_launch_s > 0 else 0.0
+    bf16 = cfg.dtype == "bf16"
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_TFLOPS
+    roofline = {"kernel": "grouped_gemm_" + ("bf16" if bf16 else "f32"), "bound": "mfma" if bf16 else "alu",
+                "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                "traffic": PMC_TRAFFIC_BYTES.get(args.workload),
+                "flops_per_launch": flops_per_launch, "avg_launch_ms": round(avg_launch_s * 1e3, 4)}
+
+    ms_per_step = elapsed / args.steps * 1e3
+    value = cfg.n_tokens * n_layers * args.steps / elapsed
+    result = {
+        "metric": "calibration tokens x layers scored/sec; MFMA util % of bf16 peak",
+        "value": round(value, 1), "unit": "tokens*layers/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name + ("" if n_layers == cfg.n_layers else f"[first {n_layers} layers only]"),
+                   "layers": n_layers, "tokens": cfg.n_tokens, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
+                   "experts": cfg.n_experts, "top_k": cfg.top_k, "shared_experts": cfg.n_shared,
+                   "d_ff_shared": cfg.d_ff_shared, "alpha": cfg.alpha, "decisions": decisions,
+                   "full_analysis_seconds": round(ms_per_step * 1e-3, 4), "input_generation_s": round(t_gen, 1)},
+        "mfma_util_pct_of_bf16_peak": round(100.0 * achieved / PEAK_BF16_TFLOPS, 2) if bf16 else None,
+        "roofline": roofline,
+        "kernel_ms": kernel_ms,
+    }
+    if not args.no_cpu_baseline:
+        del layers
+        torch.cuda.empty_cache()
+        result["cpu_baseline"] = cpu_baseline(cfg, inputs)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
