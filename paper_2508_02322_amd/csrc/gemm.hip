@@ -15,9 +15,13 @@
 // rows (A operand, gathered through the bucket permutation) and weight rows (B
 // operand) are both K-contiguous, so both fragments are 16-byte LDS reads; the
 // LDS tiles are [row][8 chunks of 8 bf16] with the chunk index XOR-ed by
-// (row & 7), which spreads the rows a fragment read touches over all banks.
+// ((row >> 1) & 7): the LDS has 64 four-byte banks, so two 128-byte tile rows
+// fill one bank row and 16 consecutive rows reading the same K chunk (one
+// quarter of a fragment read) then hit 16 different 16-byte bank groups.
 // fp32: plain FMA tiles (used by the float32 configuration only).
 #include <hip/hip_bf16.h>
+
+#include <type_traits>
 
 #include "camera_internal.h"
 
@@ -28,136 +32,112 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-__device__ __forceinline__ float silu_f32(float g) { return g / (1.0f + __expf(-g)); }
+// silu(g) = g / (1 + exp(-g)); exp2 and rcp are single hardware instructions (about 1 ulp each)
+__device__ __forceinline__ float silu_f32(float g) {
+  return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g * -1.4426950408889634f));
+}
 
 // ---------------------------------------------------------------------------
 // bf16 MFMA kernel.
-//   block = WM x WN waves; a wave owns (TM*32 tokens) x (TN*32 channels) of
-//   both the gate and the up product; block tile BM = WM*TM*32 tokens by
-//   BN = WN*TN*32 channels; K advances KT = 64 elements per stage.
+//   256 threads = 2 x 2 waves.  A wave owns TM 32-row blocks of tokens (blocks
+//   wave_m, wave_m + 2, ... of the tile, so that a short last tile of an expert
+//   is shared evenly and its empty blocks are skipped) by TN*32 channels, for
+//   both the gate and the up product.  Block tile BM = 64*TM tokens by
+//   BN = 64*TN channels; K advances KT = 64 elements per LDS stage, two stages.
+//   Schedule per K tile: global loads of the next tile are issued first, the
+//   four 16-wide K steps run MFMAs on one fragment set while the next set is
+//   read from LDS, the next tile is written to the other stage half way, and the
+//   workgroup barrier sits before the last K step so that the first fragments of
+//   the next tile are already in flight while that step's MFMAs run.
 // ---------------------------------------------------------------------------
 constexpr int KT = 64;
 constexpr int kChunks = KT / 8;  // 16-byte chunks per tile row: one 128-byte LDS row
+constexpr int kGemmThreads = 256;
+constexpr int kXcds = 8;     // accelerator dies, each with a private L2
+constexpr int kPatchM = 4;   // M-tile slots per patch
+constexpr int kPatchN = 8;   // N-tiles per patch
 
-template <int WM_, int WN_, int TM_, int TN_>
+template <int TM_, int TN_>
 struct GemmCfg {
-  static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_;
-  static constexpr int kWaves = WM * WN;
-  static constexpr int kThreads = kWaves * kWave;
-  static constexpr int BM = WM * TM * 32;
-  static constexpr int BN = WN * TN * 32;
+  static constexpr int TM = TM_, TN = TN_;
+  static constexpr int BM = 64 * TM;
+  static constexpr int BN = 64 * TN;
   static constexpr int kATileBytes = BM * KT * 2;
   static constexpr int kBTileBytes = BN * KT * 2;  // one of gate / up
   static constexpr int kStageBytes = kATileBytes + 2 * kBTileBytes;
-  static constexpr int kAChunksPerThread = BM * kChunks / kThreads;
-  static constexpr int kBChunksPerThread = BN * kChunks / kThreads;  // per matrix
-  static constexpr int kSmemBytes = 2 * kStageBytes + BM * 8 + 2 * WM * BN * 4;
-  static_assert((BM * kChunks) % kThreads == 0 && (BN * kChunks) % kThreads == 0, "whole chunks per thread");
+  static constexpr int kARows = BM / 32;  // 16-byte chunks of the A tile per thread
+  static constexpr int kBRows = BN / 32;  // per matrix
+  static constexpr int kSmemBytes = 2 * kStageBytes + BM * 8 + 4 * BN * 4;
 };
 
-__device__ __forceinline__ int swizzled(int row, int chunk) {
-  // byte offset of 16-byte chunk `chunk` of tile row `row` (rows are 128 bytes)
-  return row * 128 + ((chunk ^ (row & 7)) << 4);
-}
-
+// Everything a workgroup needs after its set-up, so that the K loop can be instantiated
+// once per number of active row blocks (ACT) without run-time branches inside it.
 template <class C>
-__global__ __launch_bounds__(C::kThreads) void grouped_gemm_bf16_kernel(
-    const __hip_bfloat16* __restrict__ X, int64_t ldx, int d_model, int d_ff,
-    const __hip_bfloat16* __restrict__ Wg, const __hip_bfloat16* __restrict__ Wu, int64_t stride_gu,
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_offset,
-    const int32_t* __restrict__ tile_expert, const int32_t* __restrict__ perm, const float* __restrict__ w_perm,
-    int n_experts, float* __restrict__ part_phi2, float* __restrict__ part_max) {
-  constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN, WM = C::WM;
-  const int slot = blockIdx.y;
-  if (slot >= tile_offset[n_experts]) return;  // block-uniform: unused M-tile slot
-  const int e = tile_expert[slot];
-  const int tile_in_expert = slot - tile_offset[e];
-  const int row_first = offsets[e] + tile_in_expert * BM;  // first bucket slot of this tile
-  const int m_len = min(BM, offsets[e + 1] - row_first);
-  const int n0 = blockIdx.x * BN;
+struct TileState {
+  unsigned char* smem;
+  const float* s_a;
+  float* s_red;
+  // staging (global -> registers -> LDS)
+  const __hip_bfloat16* a_src[C::kARows];
+  const __hip_bfloat16* wg_src[C::kBRows];
+  const __hip_bfloat16* wu_src[C::kBRows];
+  int st_dst;     // byte offset of this thread's chunk in a tile (row stride 32 rows = 4096 bytes)
+  int st_k;       // first K element of this thread's chunk inside a K tile
+  int d_model;
+  // fragments
+  int a_frag_base, b_frag_base;
+  int k_swz[KT / 16];
+  int wave_m, wave_n, frag_row, frag_half;
+};
 
-  extern __shared__ __align__(16) unsigned char smem[];
-  int32_t* s_tok = reinterpret_cast<int32_t*>(smem + 2 * C::kStageBytes);  // [BM] token id or -1
-  float* s_a = reinterpret_cast<float*>(s_tok + BM);                       // [BM] routing weight
-  float* s_red = s_a + BM;                                                 // [2][WM][BN]
+template <class C, int ACT, bool TAIL>
+__device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_ff, int slot,
+                                          float* __restrict__ part_phi2, float* __restrict__ part_max) {
+  constexpr int BN = C::BN, TN = C::TN;
+  constexpr int NA = ACT > 0 ? ACT : 1;
+  unsigned char* const smem = st.smem;
+  // Two register staging sets: tile kt+2 is on its way from HBM / L2 while tile kt+1 waits in the
+  // other set to be written to LDS, so a load has two K tiles of MFMA time to arrive.
+  struct Staging {
+    u32x4 a[C::kARows], g[C::kBRows], u[C::kBRows];
+  };
 
-  const int tid = threadIdx.x;
-  const int lane = tid % kWave;
-  const int wave = tid / kWave;
-  const int wave_m = wave % WM;  // which TM*32-row band of the block tile
-  const int wave_n = wave / WM;  // which TN*32-channel band
-
-  for (int r = tid; r < BM; r += C::kThreads) {
-    int tok = -1;
-    float a = 0.0f;
-    if (r < m_len) {
-      tok = perm ? perm[row_first + r] : tile_in_expert * BM + r;
-      a = w_perm ? w_perm[row_first + r] : 1.0f;
+  // TAIL (d_model not a multiple of KT): chunks past d_model read as zero.  Without it no load is conditional.
+  auto load_global = [&](Staging& r, int k0) {
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    const bool k_ok = !TAIL || k0 + st.st_k < st.d_model;
+#pragma unroll
+    for (int i = 0; i < C::kARows; ++i) {
+      if constexpr (TAIL) r.a[i] = k_ok ? *reinterpret_cast<const u32x4*>(st.a_src[i] + k0) : zero4;
+      else r.a[i] = *reinterpret_cast<const u32x4*>(st.a_src[i] + k0);
     }
-    s_tok[r] = tok;
-    s_a[r] = a;
-  }
-  __syncthreads();
-
-  // Global -> register staging: this thread's chunks of the A tile and of the two B tiles.
-  const __hip_bfloat16* a_src[C::kAChunksPerThread];
-  int a_dst[C::kAChunksPerThread];
-  int a_k[C::kAChunksPerThread];
 #pragma unroll
-  for (int i = 0; i < C::kAChunksPerThread; ++i) {
-    const int q = tid + i * C::kThreads;
-    const int row = q / kChunks, ck = q % kChunks;
-    const int tok = s_tok[row];
-    a_src[i] = tok >= 0 ? X + (int64_t)tok * ldx + ck * 8 : nullptr;
-    a_dst[i] = swizzled(row, ck);
-    a_k[i] = ck * 8;
-  }
-  const __hip_bfloat16* bg_src[C::kBChunksPerThread];
-  const __hip_bfloat16* bu_src[C::kBChunksPerThread];
-  int b_dst[C::kBChunksPerThread];
-  int b_k[C::kBChunksPerThread];
-#pragma unroll
-  for (int i = 0; i < C::kBChunksPerThread; ++i) {
-    const int q = tid + i * C::kThreads;
-    const int row = q / kChunks, ck = q % kChunks;
-    const int c = n0 + row;
-    const int64_t off = (int64_t)e * stride_gu + (int64_t)c * d_model + ck * 8;
-    bg_src[i] = c < d_ff ? Wg + off : nullptr;
-    bu_src[i] = c < d_ff ? Wu + off : nullptr;
-    b_dst[i] = swizzled(row, ck);
-    b_k[i] = ck * 8;
-  }
-
-  u32x4 a_reg[C::kAChunksPerThread], bg_reg[C::kBChunksPerThread], bu_reg[C::kBChunksPerThread];
-  const u32x4 zero4 = {0u, 0u, 0u, 0u};
-
-  auto load_global = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < C::kAChunksPerThread; ++i)
-      a_reg[i] = (a_src[i] && k0 + a_k[i] < d_model) ? *reinterpret_cast<const u32x4*>(a_src[i] + k0) : zero4;
-#pragma unroll
-    for (int i = 0; i < C::kBChunksPerThread; ++i) {
-      const bool ok = bg_src[i] && k0 + b_k[i] < d_model;
-      bg_reg[i] = ok ? *reinterpret_cast<const u32x4*>(bg_src[i] + k0) : zero4;
-      bu_reg[i] = ok ? *reinterpret_cast<const u32x4*>(bu_src[i] + k0) : zero4;
+    for (int i = 0; i < C::kBRows; ++i) {
+      if constexpr (TAIL) {
+        r.g[i] = k_ok ? *reinterpret_cast<const u32x4*>(st.wg_src[i] + k0) : zero4;
+        r.u[i] = k_ok ? *reinterpret_cast<const u32x4*>(st.wu_src[i] + k0) : zero4;
+      } else {
+        r.g[i] = *reinterpret_cast<const u32x4*>(st.wg_src[i] + k0);
+        r.u[i] = *reinterpret_cast<const u32x4*>(st.wu_src[i] + k0);
+      }
     }
   };
-  auto store_lds = [&](int buf) {
-    unsigned char* sA = smem + buf * C::kStageBytes;
-    unsigned char* sBg = sA + C::kATileBytes;
-    unsigned char* sBu = sBg + C::kBTileBytes;
+  auto store_lds = [&](const Staging& r, int buf) {
+    unsigned char* sA = smem + buf * C::kStageBytes + st.st_dst;
+    unsigned char* sG = sA + C::kATileBytes;
+    unsigned char* sU = sG + C::kBTileBytes;
 #pragma unroll
-    for (int i = 0; i < C::kAChunksPerThread; ++i) *reinterpret_cast<u32x4*>(sA + a_dst[i]) = a_reg[i];
+    for (int i = 0; i < C::kARows; ++i) *reinterpret_cast<u32x4*>(sA + i * 32 * 128) = r.a[i];
 #pragma unroll
-    for (int i = 0; i < C::kBChunksPerThread; ++i) {
-      *reinterpret_cast<u32x4*>(sBg + b_dst[i]) = bg_reg[i];
-      *reinterpret_cast<u32x4*>(sBu + b_dst[i]) = bu_reg[i];
+    for (int i = 0; i < C::kBRows; ++i) {
+      *reinterpret_cast<u32x4*>(sG + i * 32 * 128) = r.g[i];
+      *reinterpret_cast<u32x4*>(sU + i * 32 * 128) = r.u[i];
     }
   };
 
-  f32x16 acc_g[TM][TN], acc_u[TM][TN];
+  f32x16 acc_g[NA][TN], acc_u[NA][TN];
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < NA; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -166,57 +146,85 @@ __global__ __launch_bounds__(C::kThreads) void grouped_gemm_bf16_kernel(
         acc_u[i][j][r] = 0.0f;
       }
 
-  // Fragment addressing: lane l holds row (l % 32), K elements 8*(l / 32) .. +7 of a 16-wide K step.
-  const int frag_row = lane % 32;
-  const int frag_half = lane / 32;
-  const int a_row0 = wave_m * TM * 32 + frag_row;
-  const int b_row0 = wave_n * TN * 32 + frag_row;
-
-  const int n_k = (d_model + KT - 1) / KT;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-  for (int kt = 0; kt < n_k; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < n_k) load_global((kt + 1) * KT);
-    const unsigned char* sA = smem + buf * C::kStageBytes;
-    const unsigned char* sBg = sA + C::kATileBytes;
-    const unsigned char* sBu = sBg + C::kBTileBytes;
+  struct Frags {
+    bf16x8 a[NA], g[TN], u[TN];
+  };
+  auto read_frags = [&](Frags& f, int buf, int ks) {
+    if constexpr (ACT > 0) {
+      const unsigned char* sA = smem + buf * C::kStageBytes + st.k_swz[ks];
+      const unsigned char* sG = sA + C::kATileBytes + st.b_frag_base;
+      const unsigned char* sU = sG + C::kBTileBytes;
 #pragma unroll
-    for (int ks = 0; ks < KT / 16; ++ks) {
-      const int chunk = ks * 2 + frag_half;
-      bf16x8 fa[TM], fg[TN], fu[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(sA + swizzled(a_row0 + i * 32, chunk));
+      for (int i = 0; i < ACT; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(sA + st.a_frag_base + i * 64 * 128);
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        fg[j] = *reinterpret_cast<const bf16x8*>(sBg + swizzled(b_row0 + j * 32, chunk));
-        fu[j] = *reinterpret_cast<const bf16x8*>(sBu + swizzled(b_row0 + j * 32, chunk));
+        f.g[j] = *reinterpret_cast<const bf16x8*>(sG + j * 32 * 128);
+        f.u[j] = *reinterpret_cast<const bf16x8*>(sU + j * 32 * 128);
       }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          acc_g[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fg[j], acc_g[i][j], 0, 0, 0);
-          acc_u[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fu[j], acc_u[i][j], 0, 0, 0);
-        }
     }
-    if (kt + 1 < n_k) store_lds(buf ^ 1);
-    __syncthreads();
+  };
+  auto mfma_step = [&](const Frags& f) {
+#pragma unroll
+    for (int i = 0; i < ACT; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        acc_g[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.g[j], acc_g[i][j], 0, 0, 0);
+        acc_u[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.u[j], acc_u[i][j], 0, 0, 0);
+      }
+  };
+
+  // One loop body for every K tile: tiles past the end are clamped to the last one (two redundant
+  // tile loads per workgroup) instead of branching around the prefetch.
+  // __builtin_amdgcn_sched_barrier(0) pins the phase order: without it the compiler sinks the
+  // global loads down to their LDS stores (exposing the whole memory latency every tile) and folds
+  // the two fragment sets into one.
+  const int n_k = (st.d_model + KT - 1) / KT;
+  const int k_last = (n_k - 1) * KT;
+  Frags f0, f1;
+  Staging r0, r1;
+  auto k_tile = [&](int kt, Staging& r_load, const Staging& r_store) {
+    const int buf = kt & 1;
+    load_global(r_load, min((kt + 2) * KT, k_last));  // tile kt + 2
+    read_frags(f1, buf, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_step(f0);
+    read_frags(f0, buf, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_step(f1);
+    read_frags(f1, buf, 3);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_step(f0);
+    store_lds(r_store, buf ^ 1);  // tile kt + 1, loaded one iteration ago
+    __syncthreads();              // the next stage is complete; every read of this stage has returned
+    read_frags(f0, buf ^ 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_step(f1);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  load_global(r0, 0);
+  load_global(r1, min(KT, k_last));
+  store_lds(r0, 0);
+  __syncthreads();
+  read_frags(f0, 0, 0);
+  int kt = 0;
+  for (; kt + 1 < n_k; kt += 2) {
+    k_tile(kt, r0, r1);
+    k_tile(kt + 1, r1, r0);
   }
+  if (kt < n_k) k_tile(kt, r0, r1);
 
   // Epilogue.  Accumulator register r of lane l is output row 8*(r/4) + 4*(l/32) + (r%4),
-  // column l % 32 of its 32x32 tile: a lane owns one channel and 16 token rows.
+  // column l % 32 of its 32x32 tile: a lane owns one channel and 16 token rows per tile.
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     float sum = 0.0f, mx = 0.0f;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int band = wave_m * TM * 32 + i * 32 + frag_half * 4;
+    for (int i = 0; i < ACT; ++i) {
+      const int band = (2 * i + st.wave_m) * 32 + st.frag_half * 4;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = band + (r / 4) * 8 + (r % 4);
-        const float lam = s_a[row] * silu_f32(acc_g[i][j][r]) * acc_u[i][j][r];
+        const float lam = st.s_a[row] * silu_f32(acc_g[i][j][r]) * acc_u[i][j][r];
         const float l2 = lam * lam;
         sum += l2;
         mx = fmaxf(mx, l2);
@@ -224,25 +232,103 @@ __global__ __launch_bounds__(C::kThreads) void grouped_gemm_bf16_kernel(
     }
     sum += __shfl_xor(sum, 32);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    if (frag_half == 0) {
-      const int col = wave_n * TN * 32 + j * 32 + frag_row;
-      s_red[wave_m * BN + col] = sum;
-      s_red[(WM + wave_m) * BN + col] = mx;
+    if (st.frag_half == 0) {
+      const int col = st.wave_n * TN * 32 + j * 32 + st.frag_row;
+      st.s_red[st.wave_m * BN + col] = sum;
+      st.s_red[(2 + st.wave_m) * BN + col] = mx;
     }
   }
   __syncthreads();
-  for (int col = tid; col < BN; col += C::kThreads) {
+  for (int col = threadIdx.x; col < BN; col += kGemmThreads) {
     if (n0 + col < d_ff) {
-      float sum = 0.0f, mx = 0.0f;
-#pragma unroll
-      for (int w = 0; w < WM; ++w) {  // fixed order
-        sum += s_red[w * BN + col];
-        mx = fmaxf(mx, s_red[(WM + w) * BN + col]);
-      }
+      const float sum = st.s_red[col] + st.s_red[BN + col];  // fixed order
+      const float mx = fmaxf(st.s_red[2 * BN + col], st.s_red[3 * BN + col]);
       part_phi2[(int64_t)slot * d_ff + n0 + col] = sum;
       part_max[(int64_t)slot * d_ff + n0 + col] = mx;
     }
   }
+}
+
+template <class C, bool TAIL>
+__global__ __launch_bounds__(kGemmThreads) void grouped_gemm_bf16_kernel(
+    const __hip_bfloat16* __restrict__ X, int64_t ldx, int d_model, int d_ff,
+    const __hip_bfloat16* __restrict__ Wg, const __hip_bfloat16* __restrict__ Wu, int64_t stride_gu,
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_offset,
+    const int32_t* __restrict__ tile_expert, const int32_t* __restrict__ perm, const float* __restrict__ w_perm,
+    int n_experts, float* __restrict__ part_phi2, float* __restrict__ part_max) {
+  constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN;
+  // Workgroup -> tile mapping.  The hardware deals consecutive workgroup ids round-robin to the 8
+  // XCDs, each with its own L2.  Give every XCD a contiguous run of logical ids, and order logical
+  // ids in patches of kPatchM M-tile slots x kPatchN N-tiles (= the 32 workgroups an XCD runs at a
+  // time): a patch re-reads only kPatchM token tiles and kPatchN weight tiles through its L2.
+  const int per_xcd = gridDim.x / kXcds;
+  const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+  const int patch = logical / (kPatchM * kPatchN), in_patch = logical % (kPatchM * kPatchN);
+  const int n_tiles_n = (d_ff + BN - 1) / BN;
+  const int patches_n = (n_tiles_n + kPatchN - 1) / kPatchN;
+  const int slot = (patch / patches_n) * kPatchM + in_patch % kPatchM;
+  const int tile_n = (patch % patches_n) * kPatchN + in_patch / kPatchM;
+  if (tile_n >= n_tiles_n || slot >= tile_offset[n_experts]) return;  // block-uniform: nothing here
+  const int e = tile_expert[slot];
+  const int tile_in_expert = slot - tile_offset[e];
+  const int row_first = offsets[e] + tile_in_expert * BM;  // first bucket slot of this tile
+  const int m_len = min(BM, offsets[e + 1] - row_first);   // >= 1
+  const int n0 = tile_n * BN;
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  int32_t* s_tok = reinterpret_cast<int32_t*>(smem + 2 * C::kStageBytes);  // [BM] token id
+  float* s_a = reinterpret_cast<float*>(s_tok + BM);                       // [BM] routing weight
+  const int tid = threadIdx.x;
+  const int lane = tid % kWave;
+  const int wave = tid / kWave;
+
+  // Rows past the end of the expert's bucket read token row 0 of the tile again with weight 0:
+  // their Lambda is exactly 0 (finite projections times a = 0), so no load in the K loop is conditional.
+  for (int r = tid; r < BM; r += kGemmThreads) {
+    const int rr = r < m_len ? r : 0;
+    s_tok[r] = perm ? perm[row_first + rr] : tile_in_expert * BM + rr;
+    s_a[r] = r < m_len ? (w_perm ? w_perm[row_first + rr] : 1.0f) : 0.0f;
+  }
+  __syncthreads();
+
+  TileState<C> st;
+  st.smem = smem;
+  st.s_a = s_a;
+  st.s_red = s_a + BM;  // [2 stats][2 wave_m][BN]
+  st.d_model = d_model;
+  st.wave_m = wave & 1;
+  st.wave_n = wave >> 1;
+  st.frag_row = lane % 32;
+  st.frag_half = lane / 32;
+  // Staging: thread t moves 16-byte chunk (t % 8) of tile rows t/8, t/8 + 32, ...
+  const int st_row = tid / kChunks, st_ck = tid % kChunks;
+  st.st_dst = st_row * 128 + ((st_ck ^ ((st_row >> 1) & 7)) << 4);  // the swizzle key repeats every 16 rows
+  st.st_k = st_ck * 8;
+#pragma unroll
+  for (int i = 0; i < C::kARows; ++i) st.a_src[i] = X + (int64_t)s_tok[st_row + 32 * i] * ldx + st_ck * 8;
+#pragma unroll
+  for (int i = 0; i < C::kBRows; ++i) {
+    // channels past d_ff read the last channel again; their statistics are never written
+    const int c = min(n0 + st_row + 32 * i, d_ff - 1);
+    const int64_t off = (int64_t)e * stride_gu + (int64_t)c * d_model + st_ck * 8;
+    st.wg_src[i] = Wg + off;
+    st.wu_src[i] = Wu + off;
+  }
+  // Fragments: lane l holds tile row (l % 32), K elements 8*(l / 32) .. +7 of a 16-wide K step.
+  st.a_frag_base = (st.wave_m * 32 + st.frag_row) * 128;        // + i * 64 * 128: row block 2*i + wave_m
+  st.b_frag_base = (st.wave_n * TN * 32 + st.frag_row) * 128;   // + j * 32 * 128
+#pragma unroll
+  for (int ks = 0; ks < KT / 16; ++ks) st.k_swz[ks] = ((ks * 2 + st.frag_half) ^ ((st.frag_row >> 1) & 7)) << 4;
+
+  // accumulator i of this wave covers row block 2*i + wave_m; blocks past m_len are skipped
+  const int n_row_blocks = (m_len + 31) / 32;
+  const int act = (n_row_blocks - st.wave_m + 1) / 2;  // wave-uniform, 0 .. TM
+  static_assert(TM == 4 || TM == 2, "dispatch below covers TM = 2 and 4");
+  if (act >= TM) tile_body<C, TM, TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
+  else if (act == 3) tile_body<C, (TM > 3 ? 3 : 0), TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
+  else if (act == 2) tile_body<C, (TM > 2 ? 2 : 0), TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
+  else if (act == 1) tile_body<C, 1, TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
+  else tile_body<C, 0, TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
 }
 
 // ---------------------------------------------------------------------------
@@ -349,8 +435,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
   }
 }
 
-// Tile shape of the bf16 kernel: 2x2 waves, each 64 tokens x 64 channels (gate and up).
-using Bf16Cfg = GemmCfg<2, 2, 2, 2>;
+// Tile shape of the bf16 kernel: 256 tokens x 128 channels (gate and up) per workgroup.
+using Bf16Cfg = GemmCfg<4, 2>;
 
 }  // namespace
 
@@ -366,16 +452,21 @@ hipError_t launch_grouped_gemm(hipStream_t stream, int dtype, const void* X, int
   if (max_tiles <= 0) return hipSuccess;
   if (dtype == CAMERA_BF16) {
     using C = Bf16Cfg;
-    static bool attr_set = false;
-    auto kern = grouped_gemm_bf16_kernel<C>;
-    if (!attr_set) {
+    const bool tail = d_model % KT != 0;
+    auto kern = tail ? grouped_gemm_bf16_kernel<C, true> : grouped_gemm_bf16_kernel<C, false>;
+    static bool attr_set[2] = {false, false};
+    if (!attr_set[tail]) {
       hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kSmemBytes);
       if (err != hipSuccess) return err;
-      attr_set = true;
+      attr_set[tail] = true;
     }
-    dim3 grid((unsigned)((d_ff + C::BN - 1) / C::BN), (unsigned)max_tiles);
-    hipLaunchKernelGGL(kern, grid, dim3(C::kThreads), C::kSmemBytes, stream,
+    const int64_t patches_n = ((d_ff + C::BN - 1) / C::BN + kPatchN - 1) / kPatchN;
+    const int64_t patches_m = (max_tiles + kPatchM - 1) / kPatchM;
+    const int64_t n_blocks = (patches_n * patches_m * kPatchM * kPatchN + kXcds - 1) / kXcds * kXcds;
+    if (n_blocks >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+    dim3 grid((unsigned)n_blocks);
+    hipLaunchKernelGGL(kern, grid, dim3(kGemmThreads), C::kSmemBytes, stream,
                        static_cast<const __hip_bfloat16*>(X), ldx, (int)d_model, (int)d_ff,
                        static_cast<const __hip_bfloat16*>(W_gate), static_cast<const __hip_bfloat16*>(W_up),
                        stride_gu, t.offsets, t.tile_offset, t.tile_expert, t.perm, t.w_perm, n_experts, part_phi2,
