@@ -39,35 +39,40 @@ __device__ __forceinline__ float silu_f32(float g) {
 
 // ---------------------------------------------------------------------------
 // bf16 MFMA kernel.
-//   256 threads = 2 x 2 waves.  A wave owns TM 32-row blocks of tokens (blocks
-//   wave_m, wave_m + 2, ... of the tile, so that a short last tile of an expert
-//   is shared evenly and its empty blocks are skipped) by TN*32 channels, for
-//   both the gate and the up product.  Block tile BM = 64*TM tokens by
-//   BN = 64*TN channels; K advances KT = 64 elements per LDS stage, two stages.
-//   Schedule per K tile: global loads of the next tile are issued first, the
-//   four 16-wide K steps run MFMAs on one fragment set while the next set is
-//   read from LDS, the next tile is written to the other stage half way, and the
-//   workgroup barrier sits before the last K step so that the first fragments of
-//   the next tile are already in flight while that step's MFMAs run.
+//   A workgroup is WM x WN waves.  A wave owns TM 32-row blocks of tokens
+//   (blocks wave_m, wave_m + WM, ... of the tile, so that a short last tile of an
+//   expert is shared evenly and its empty blocks are skipped) by TN*32 channels,
+//   for both the gate and the up product.  Block tile BM = 32*WM*TM tokens by
+//   BN = 32*WN*TN channels; K advances KT = 64 elements per LDS stage, two
+//   stages.  Schedule per K tile: global loads of the tile after next are issued
+//   first (two register staging sets), the four 16-wide K steps run MFMAs on one
+//   fragment set while the next set is read from LDS, the next tile is written
+//   to the other stage, and the workgroup barrier sits before the last K step so
+//   that the first fragments of the next tile are in flight while that step's
+//   MFMAs run.
 // ---------------------------------------------------------------------------
 constexpr int KT = 64;
 constexpr int kChunks = KT / 8;  // 16-byte chunks per tile row: one 128-byte LDS row
-constexpr int kGemmThreads = 256;
-constexpr int kXcds = 8;     // accelerator dies, each with a private L2
-constexpr int kPatchM = 4;   // M-tile slots per patch
-constexpr int kPatchN = 8;   // N-tiles per patch
+constexpr int kXcds = 8;         // accelerator dies, each with a private L2
+constexpr int kPatchM = 4;       // M-tile slots per patch
+constexpr int kPatchN = 8;       // N-tiles per patch
 
-template <int TM_, int TN_>
+enum Sched { kSchedNone = 0, kSchedPhases = 1 };
+
+template <int WM_, int WN_, int TM_, int TN_, int SCHED_>
 struct GemmCfg {
-  static constexpr int TM = TM_, TN = TN_;
-  static constexpr int BM = 64 * TM;
-  static constexpr int BN = 64 * TN;
+  static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_, SCHED = SCHED_;
+  static constexpr int kThreads = 64 * WM * WN;
+  static constexpr int BM = 32 * WM * TM;
+  static constexpr int BN = 32 * WN * TN;
   static constexpr int kATileBytes = BM * KT * 2;
   static constexpr int kBTileBytes = BN * KT * 2;  // one of gate / up
   static constexpr int kStageBytes = kATileBytes + 2 * kBTileBytes;
-  static constexpr int kARows = BM / 32;  // 16-byte chunks of the A tile per thread
-  static constexpr int kBRows = BN / 32;  // per matrix
-  static constexpr int kSmemBytes = 2 * kStageBytes + BM * 8 + 4 * BN * 4;
+  static constexpr int kRowsPerPass = kThreads / kChunks;  // tile rows one staging pass of the block covers
+  static constexpr int kARows = BM / kRowsPerPass;         // 16-byte chunks of the A tile per thread
+  static constexpr int kBRows = BN / kRowsPerPass;         // per matrix
+  static constexpr int kSmemBytes = 2 * kStageBytes + BM * 8 + 2 * WM * BN * 4;
+  static_assert(kRowsPerPass % 16 == 0 && BM % kRowsPerPass == 0 && BN % kRowsPerPass == 0, "staging shape");
 };
 
 // Everything a workgroup needs after its set-up, so that the K loop can be instantiated
@@ -81,8 +86,8 @@ struct TileState {
   const __hip_bfloat16* a_src[C::kARows];
   const __hip_bfloat16* wg_src[C::kBRows];
   const __hip_bfloat16* wu_src[C::kBRows];
-  int st_dst;     // byte offset of this thread's chunk in a tile (row stride 32 rows = 4096 bytes)
-  int st_k;       // first K element of this thread's chunk inside a K tile
+  int st_dst;  // byte offset of this thread's chunk in a tile (+ kRowsPerPass * 128 per further row)
+  int st_k;    // first K element of this thread's chunk inside a K tile
   int d_model;
   // fragments
   int a_frag_base, b_frag_base;
@@ -93,33 +98,29 @@ struct TileState {
 template <class C, int ACT, bool TAIL>
 __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_ff, int slot,
                                           float* __restrict__ part_phi2, float* __restrict__ part_max) {
-  constexpr int BN = C::BN, TN = C::TN;
+  constexpr int BN = C::BN, TN = C::TN, WM = C::WM;
   constexpr int NA = ACT > 0 ? ACT : 1;
+  constexpr int kPassBytes = C::kRowsPerPass * 128;
   unsigned char* const smem = st.smem;
+
   // Two register staging sets: tile kt+2 is on its way from HBM / L2 while tile kt+1 waits in the
   // other set to be written to LDS, so a load has two K tiles of MFMA time to arrive.
   struct Staging {
     u32x4 a[C::kARows], g[C::kBRows], u[C::kBRows];
   };
-
   // TAIL (d_model not a multiple of KT): chunks past d_model read as zero.  Without it no load is conditional.
-  auto load_global = [&](Staging& r, int k0) {
+  auto ld = [&](const __hip_bfloat16* p, int k0) -> u32x4 {
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    const bool k_ok = !TAIL || k0 + st.st_k < st.d_model;
+    if constexpr (TAIL) return (k0 + st.st_k < st.d_model) ? *reinterpret_cast<const u32x4*>(p + k0) : zero4;
+    else return *reinterpret_cast<const u32x4*>(p + k0);
+  };
+  auto load_global = [&](Staging& r, int k0) {
 #pragma unroll
-    for (int i = 0; i < C::kARows; ++i) {
-      if constexpr (TAIL) r.a[i] = k_ok ? *reinterpret_cast<const u32x4*>(st.a_src[i] + k0) : zero4;
-      else r.a[i] = *reinterpret_cast<const u32x4*>(st.a_src[i] + k0);
-    }
+    for (int i = 0; i < C::kARows; ++i) r.a[i] = ld(st.a_src[i], k0);
 #pragma unroll
     for (int i = 0; i < C::kBRows; ++i) {
-      if constexpr (TAIL) {
-        r.g[i] = k_ok ? *reinterpret_cast<const u32x4*>(st.wg_src[i] + k0) : zero4;
-        r.u[i] = k_ok ? *reinterpret_cast<const u32x4*>(st.wu_src[i] + k0) : zero4;
-      } else {
-        r.g[i] = *reinterpret_cast<const u32x4*>(st.wg_src[i] + k0);
-        r.u[i] = *reinterpret_cast<const u32x4*>(st.wu_src[i] + k0);
-      }
+      r.g[i] = ld(st.wg_src[i], k0);
+      r.u[i] = ld(st.wu_src[i], k0);
     }
   };
   auto store_lds = [&](const Staging& r, int buf) {
@@ -127,11 +128,11 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
     unsigned char* sG = sA + C::kATileBytes;
     unsigned char* sU = sG + C::kBTileBytes;
 #pragma unroll
-    for (int i = 0; i < C::kARows; ++i) *reinterpret_cast<u32x4*>(sA + i * 32 * 128) = r.a[i];
+    for (int i = 0; i < C::kARows; ++i) *reinterpret_cast<u32x4*>(sA + i * kPassBytes) = r.a[i];
 #pragma unroll
     for (int i = 0; i < C::kBRows; ++i) {
-      *reinterpret_cast<u32x4*>(sG + i * 32 * 128) = r.g[i];
-      *reinterpret_cast<u32x4*>(sU + i * 32 * 128) = r.u[i];
+      *reinterpret_cast<u32x4*>(sG + i * kPassBytes) = r.g[i];
+      *reinterpret_cast<u32x4*>(sU + i * kPassBytes) = r.u[i];
     }
   };
 
@@ -155,7 +156,8 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
       const unsigned char* sG = sA + C::kATileBytes + st.b_frag_base;
       const unsigned char* sU = sG + C::kBTileBytes;
 #pragma unroll
-      for (int i = 0; i < ACT; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(sA + st.a_frag_base + i * 64 * 128);
+      for (int i = 0; i < ACT; ++i)
+        f.a[i] = *reinterpret_cast<const bf16x8*>(sA + st.a_frag_base + i * WM * 32 * 128);
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         f.g[j] = *reinterpret_cast<const bf16x8*>(sG + j * 32 * 128);
@@ -172,12 +174,14 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
         acc_u[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.u[j], acc_u[i][j], 0, 0, 0);
       }
   };
+  auto pin = [&]() {
+    // keeps the compiler from sinking the global loads down to their LDS stores (which exposes
+    // the memory latency every tile) and from folding the two fragment sets into one
+    if constexpr (C::SCHED == kSchedPhases) __builtin_amdgcn_sched_barrier(0);
+  };
 
   // One loop body for every K tile: tiles past the end are clamped to the last one (two redundant
   // tile loads per workgroup) instead of branching around the prefetch.
-  // __builtin_amdgcn_sched_barrier(0) pins the phase order: without it the compiler sinks the
-  // global loads down to their LDS stores (exposing the whole memory latency every tile) and folds
-  // the two fragment sets into one.
   const int n_k = (st.d_model + KT - 1) / KT;
   const int k_last = (n_k - 1) * KT;
   Frags f0, f1;
@@ -186,20 +190,20 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
     const int buf = kt & 1;
     load_global(r_load, min((kt + 2) * KT, k_last));  // tile kt + 2
     read_frags(f1, buf, 1);
-    __builtin_amdgcn_sched_barrier(0);
+    pin();
     mfma_step(f0);
     read_frags(f0, buf, 2);
-    __builtin_amdgcn_sched_barrier(0);
+    pin();
     mfma_step(f1);
     read_frags(f1, buf, 3);
-    __builtin_amdgcn_sched_barrier(0);
+    pin();
     mfma_step(f0);
     store_lds(r_store, buf ^ 1);  // tile kt + 1, loaded one iteration ago
     __syncthreads();              // the next stage is complete; every read of this stage has returned
     read_frags(f0, buf ^ 1, 0);
-    __builtin_amdgcn_sched_barrier(0);
+    pin();
     mfma_step(f1);
-    __builtin_amdgcn_sched_barrier(0);
+    pin();
   };
   load_global(r0, 0);
   load_global(r1, min(KT, k_last));
@@ -220,7 +224,7 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
     float sum = 0.0f, mx = 0.0f;
 #pragma unroll
     for (int i = 0; i < ACT; ++i) {
-      const int band = (2 * i + st.wave_m) * 32 + st.frag_half * 4;
+      const int band = (WM * i + st.wave_m) * 32 + st.frag_half * 4;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = band + (r / 4) * 8 + (r % 4);
@@ -235,14 +239,18 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
     if (st.frag_half == 0) {
       const int col = st.wave_n * TN * 32 + j * 32 + st.frag_row;
       st.s_red[st.wave_m * BN + col] = sum;
-      st.s_red[(2 + st.wave_m) * BN + col] = mx;
+      st.s_red[(WM + st.wave_m) * BN + col] = mx;
     }
   }
   __syncthreads();
-  for (int col = threadIdx.x; col < BN; col += kGemmThreads) {
+  for (int col = threadIdx.x; col < BN; col += C::kThreads) {
     if (n0 + col < d_ff) {
-      const float sum = st.s_red[col] + st.s_red[BN + col];  // fixed order
-      const float mx = fmaxf(st.s_red[2 * BN + col], st.s_red[3 * BN + col]);
+      float sum = 0.0f, mx = 0.0f;
+#pragma unroll
+      for (int w = 0; w < WM; ++w) {  // fixed order
+        sum += st.s_red[w * BN + col];
+        mx = fmaxf(mx, st.s_red[(WM + w) * BN + col]);
+      }
       part_phi2[(int64_t)slot * d_ff + n0 + col] = sum;
       part_max[(int64_t)slot * d_ff + n0 + col] = mx;
     }
@@ -250,13 +258,13 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
 }
 
 template <class C, bool TAIL>
-__global__ __launch_bounds__(kGemmThreads) void grouped_gemm_bf16_kernel(
+__global__ __launch_bounds__(C::kThreads) void grouped_gemm_bf16_kernel(
     const __hip_bfloat16* __restrict__ X, int64_t ldx, int d_model, int d_ff,
     const __hip_bfloat16* __restrict__ Wg, const __hip_bfloat16* __restrict__ Wu, int64_t stride_gu,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_offset,
     const int32_t* __restrict__ tile_expert, const int32_t* __restrict__ perm, const float* __restrict__ w_perm,
     int n_experts, float* __restrict__ part_phi2, float* __restrict__ part_max) {
-  constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN;
+  constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN, WM = C::WM;
   // Workgroup -> tile mapping.  The hardware deals consecutive workgroup ids round-robin to the 8
   // XCDs, each with its own L2.  Give every XCD a contiguous run of logical ids, and order logical
   // ids in patches of kPatchM M-tile slots x kPatchN N-tiles (= the 32 workgroups an XCD runs at a
@@ -284,7 +292,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_bf16_kernel(
 
   // Rows past the end of the expert's bucket read token row 0 of the tile again with weight 0:
   // their Lambda is exactly 0 (finite projections times a = 0), so no load in the K loop is conditional.
-  for (int r = tid; r < BM; r += kGemmThreads) {
+  for (int r = tid; r < BM; r += C::kThreads) {
     const int rr = r < m_len ? r : 0;
     s_tok[r] = perm ? perm[row_first + rr] : tile_in_expert * BM + rr;
     s_a[r] = r < m_len ? (w_perm ? w_perm[row_first + rr] : 1.0f) : 0.0f;
@@ -294,40 +302,41 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_bf16_kernel(
   TileState<C> st;
   st.smem = smem;
   st.s_a = s_a;
-  st.s_red = s_a + BM;  // [2 stats][2 wave_m][BN]
+  st.s_red = s_a + BM;  // [2 stats][WM][BN]
   st.d_model = d_model;
-  st.wave_m = wave & 1;
-  st.wave_n = wave >> 1;
+  st.wave_m = wave % WM;
+  st.wave_n = wave / WM;
   st.frag_row = lane % 32;
   st.frag_half = lane / 32;
-  // Staging: thread t moves 16-byte chunk (t % 8) of tile rows t/8, t/8 + 32, ...
+  // Staging: thread t moves 16-byte chunk (t % 8) of tile rows t/8, t/8 + kRowsPerPass, ...
   const int st_row = tid / kChunks, st_ck = tid % kChunks;
   st.st_dst = st_row * 128 + ((st_ck ^ ((st_row >> 1) & 7)) << 4);  // the swizzle key repeats every 16 rows
   st.st_k = st_ck * 8;
 #pragma unroll
-  for (int i = 0; i < C::kARows; ++i) st.a_src[i] = X + (int64_t)s_tok[st_row + 32 * i] * ldx + st_ck * 8;
+  for (int i = 0; i < C::kARows; ++i)
+    st.a_src[i] = X + (int64_t)s_tok[st_row + C::kRowsPerPass * i] * ldx + st_ck * 8;
 #pragma unroll
   for (int i = 0; i < C::kBRows; ++i) {
     // channels past d_ff read the last channel again; their statistics are never written
-    const int c = min(n0 + st_row + 32 * i, d_ff - 1);
+    const int c = min(n0 + st_row + C::kRowsPerPass * i, d_ff - 1);
     const int64_t off = (int64_t)e * stride_gu + (int64_t)c * d_model + st_ck * 8;
     st.wg_src[i] = Wg + off;
     st.wu_src[i] = Wu + off;
   }
   // Fragments: lane l holds tile row (l % 32), K elements 8*(l / 32) .. +7 of a 16-wide K step.
-  st.a_frag_base = (st.wave_m * 32 + st.frag_row) * 128;        // + i * 64 * 128: row block 2*i + wave_m
-  st.b_frag_base = (st.wave_n * TN * 32 + st.frag_row) * 128;   // + j * 32 * 128
+  st.a_frag_base = (st.wave_m * 32 + st.frag_row) * 128;       // + i * WM * 32 * 128: row block WM*i + wave_m
+  st.b_frag_base = (st.wave_n * TN * 32 + st.frag_row) * 128;  // + j * 32 * 128
 #pragma unroll
   for (int ks = 0; ks < KT / 16; ++ks) st.k_swz[ks] = ((ks * 2 + st.frag_half) ^ ((st.frag_row >> 1) & 7)) << 4;
 
-  // accumulator i of this wave covers row block 2*i + wave_m; blocks past m_len are skipped
+  // accumulator i of this wave covers row block WM*i + wave_m; blocks past m_len are skipped
   const int n_row_blocks = (m_len + 31) / 32;
-  const int act = (n_row_blocks - st.wave_m + 1) / 2;  // wave-uniform, 0 .. TM
-  static_assert(TM == 4 || TM == 2, "dispatch below covers TM = 2 and 4");
+  const int act = max(0, (n_row_blocks - st.wave_m + WM - 1) / WM);  // wave-uniform, 0 .. TM
+  static_assert(TM == 4 || TM == 2 || TM == 1, "dispatch below covers TM = 1, 2 and 4");
   if (act >= TM) tile_body<C, TM, TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
   else if (act == 3) tile_body<C, (TM > 3 ? 3 : 0), TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
   else if (act == 2) tile_body<C, (TM > 2 ? 2 : 0), TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
-  else if (act == 1) tile_body<C, 1, TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
+  else if (act == 1) tile_body<C, (TM > 1 ? 1 : 0), TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
   else tile_body<C, 0, TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
 }
 
@@ -435,8 +444,11 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
   }
 }
 
-// Tile shape of the bf16 kernel: 256 tokens x 128 channels (gate and up) per workgroup.
-using Bf16Cfg = GemmCfg<4, 2>;
+// Tile shape of the bf16 kernel (token rows x channels per workgroup, waves, schedule).
+#ifndef CAMERA_GEMM_CFG
+#define CAMERA_GEMM_CFG 4, 2, 2, 2, kSchedNone
+#endif
+using Bf16Cfg = GemmCfg<CAMERA_GEMM_CFG>;
 
 }  // namespace
 
@@ -466,7 +478,7 @@ hipError_t launch_grouped_gemm(hipStream_t stream, int dtype, const void* X, int
     const int64_t n_blocks = (patches_n * patches_m * kPatchM * kPatchN + kXcds - 1) / kXcds * kXcds;
     if (n_blocks >= (int64_t(1) << 31)) return hipErrorInvalidValue;
     dim3 grid((unsigned)n_blocks);
-    hipLaunchKernelGGL(kern, grid, dim3(kGemmThreads), C::kSmemBytes, stream,
+    hipLaunchKernelGGL(kern, grid, dim3(C::kThreads), C::kSmemBytes, stream,
                        static_cast<const __hip_bfloat16*>(X), ldx, (int)d_model, (int)d_ff,
                        static_cast<const __hip_bfloat16*>(W_gate), static_cast<const __hip_bfloat16*>(W_up),
                        stride_gu, t.offsets, t.tile_offset, t.tile_expert, t.perm, t.w_perm, n_experts, part_phi2,
