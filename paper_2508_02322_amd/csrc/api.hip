@@ -15,6 +15,7 @@ struct camera_ctx {
   char err[512] = {0};
   void* ws = nullptr;
   size_t ws_bytes = 0;
+  void* zeros = nullptr;                         // 256 zero bytes, made on first use
   bool profiling = false;
   struct Span {
     hipEvent_t begin, end;
@@ -78,6 +79,17 @@ struct Carver {
 };
 
 int ensure_workspace(camera_ctx* ctx, size_t bytes) {
+  if (ctx->zeros == nullptr) {
+    hipError_t e = hipMalloc(&ctx->zeros, 256);
+    if (e == hipSuccess) e = hipMemset(ctx->zeros, 0, 256);
+    if (e == hipSuccess) e = hipDeviceSynchronize();  // once: visible to every stream from here on
+    if (e != hipSuccess) {
+      if (ctx->zeros) (void)hipFree(ctx->zeros);
+      ctx->zeros = nullptr;
+      (void)hipGetLastError();
+      return fail(ctx, CAMERA_EWORKSPACE, "zero page: %s", hipGetErrorString(e));
+    }
+  }
   if (bytes <= ctx->ws_bytes) return CAMERA_OK;
   if (ctx->ws) {
     hipError_t e = hipFree(ctx->ws);  // waits for the device: earlier calls are done with it
@@ -176,7 +188,7 @@ int camera_create(camera_ctx** out, int device) {
 int camera_destroy(camera_ctx* ctx) {
   if (ctx == nullptr) return CAMERA_OK;
   int rc = CAMERA_OK;
-  if (ctx->ws || !ctx->free_spans.empty()) {
+  if (ctx->ws || ctx->zeros || !ctx->free_spans.empty()) {
     DeviceGuard guard;
     (void)guard.enter(ctx->device);
     for (auto& v : ctx->spans)
@@ -186,6 +198,7 @@ int camera_destroy(camera_ctx* ctx) {
       (void)hipEventDestroy(s.end);
     }
     if (ctx->ws && hipFree(ctx->ws) != hipSuccess) rc = CAMERA_EHIP;
+    if (ctx->zeros && hipFree(ctx->zeros) != hipSuccess) rc = CAMERA_EHIP;
   }
   delete ctx;
   return rc;
@@ -313,6 +326,7 @@ int camera_score_layer(camera_ctx* ctx, void* stream_, const void* X, int dtype,
   t.perm = dense ? nullptr : reinterpret_cast<int32_t*>(ws + o_perm);
   t.w_perm = dense ? nullptr : reinterpret_cast<float*>(ws + o_wperm);
   t.block_hist = reinterpret_cast<int32_t*>(ws + o_hist);
+  t.zeros = ctx->zeros;
   float* part_phi2 = reinterpret_cast<float*>(ws + o_p2);
   float* part_max = reinterpret_cast<float*>(ws + o_pm);
   float* omega_part = reinterpret_cast<float*>(ws + o_omega);

@@ -22,6 +22,7 @@ struct BucketTables {
   int32_t* perm;          // [P]                token id of each slot (NULL: identity per expert)
   float* w_perm;          // [P]                routing weight of each slot (NULL: 1)
   int32_t* block_hist;    // [n_blocks x n_experts] scratch of the counting sort
+  const void* zeros;      // 256 zero bytes (source of K-tail chunks for direct-to-LDS loads)
 };
 
 // ---- route.hip --------------------------------------------------------------

@@ -39,41 +39,61 @@ __device__ __forceinline__ float silu_f32(float g) {
 
 // ---------------------------------------------------------------------------
 // bf16 MFMA kernel.
-//   A workgroup is WM x WN waves.  A wave owns TM 32-row blocks of tokens
-//   (blocks wave_m, wave_m + WM, ... of the tile, so that a short last tile of an
-//   expert is shared evenly and its empty blocks are skipped) by TN*32 channels,
-//   for both the gate and the up product.  Block tile BM = 32*WM*TM tokens by
-//   BN = 32*WN*TN channels; K advances KT = 64 elements per LDS stage, two
-//   stages.  Schedule per K tile: global loads of the tile after next are issued
-//   first (two register staging sets), the four 16-wide K steps run MFMAs on one
-//   fragment set while the next set is read from LDS, the next tile is written
-//   to the other stage, and the workgroup barrier sits before the last K step so
-//   that the first fragments of the next tile are in flight while that step's
-//   MFMAs run.
+//   A workgroup is WM x WN waves (two per SIMD with the default 4 x 2).  A wave
+//   owns TM 32-row blocks of tokens (blocks wave_m, wave_m + WM, ... of the tile,
+//   so that a short last tile of an expert is shared evenly and its empty blocks
+//   are skipped) by TN*32 channels, for both the gate and the up product.  Block
+//   tile BM = 32*WM*TM tokens by BN = 32*WN*TN channels.
+//
+//   K advances KT = 32 elements per LDS stage through a ring of kStages stages.
+//   Tiles go from global memory straight into LDS (global_load_lds_dwordx4, no
+//   staging registers, no LDS store instructions): the loads of tile kt+3 are
+//   issued, a few MFMAs apart, while tile kt is multiplied.  Spacing them matters
+//   more than anything else here: a wave that issues its loads back to back
+//   stalls on the full vector-memory queue and stops feeding the matrix pipe.
+//   One workgroup barrier per K tile publishes the next stage; it sits before
+//   the last 16-wide K step so that the first fragments of the next tile are in
+//   flight while that step's MFMAs run.
 // ---------------------------------------------------------------------------
-constexpr int KT = 64;
-constexpr int kChunks = KT / 8;  // 16-byte chunks per tile row: one 128-byte LDS row
-constexpr int kXcds = 8;         // accelerator dies, each with a private L2
-constexpr int kPatchM = 4;       // M-tile slots per patch
-constexpr int kPatchN = 8;       // N-tiles per patch
+constexpr int kXcds = 8;    // accelerator dies, each with a private L2
+constexpr int kPatchM = 4;  // M-tile slots per patch
+constexpr int kPatchN = 8;  // N-tiles per patch
 
-enum Sched { kSchedNone = 0, kSchedPhases = 1 };
-
-template <int WM_, int WN_, int TM_, int TN_, int SCHED_>
+template <int WM_, int WN_, int TM_, int TN_, int KT_, int STAGES_>
 struct GemmCfg {
-  static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_, SCHED = SCHED_;
-  static constexpr int kThreads = 64 * WM * WN;
+  static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_, KT = KT_, kStages = STAGES_;
+  static constexpr int kWaves = WM * WN;
+  static constexpr int kThreads = 64 * kWaves;
   static constexpr int BM = 32 * WM * TM;
   static constexpr int BN = 32 * WN * TN;
-  static constexpr int kATileBytes = BM * KT * 2;
-  static constexpr int kBTileBytes = BN * KT * 2;  // one of gate / up
+  static constexpr int kChunks = KT / 8;          // 16-byte chunks per tile row
+  static constexpr int kRowBytes = KT * 2;        // 64 or 128
+  static constexpr int kRowsPerBankRow = 256 / kRowBytes;  // tile rows that share one 256-byte LDS bank row
+  static constexpr int kSteps = KT / 16;          // MFMA K steps per tile
+  static constexpr int kATileBytes = BM * kRowBytes;
+  static constexpr int kBTileBytes = BN * kRowBytes;  // one of gate / up
   static constexpr int kStageBytes = kATileBytes + 2 * kBTileBytes;
-  static constexpr int kRowsPerPass = kThreads / kChunks;  // tile rows one staging pass of the block covers
-  static constexpr int kARows = BM / kRowsPerPass;         // 16-byte chunks of the A tile per thread
-  static constexpr int kBRows = BN / kRowsPerPass;         // per matrix
-  static constexpr int kSmemBytes = 2 * kStageBytes + BM * 8 + 2 * WM * BN * 4;
-  static_assert(kRowsPerPass % 16 == 0 && BM % kRowsPerPass == 0 && BN % kRowsPerPass == 0, "staging shape");
+  // one wave instruction fills 1 KiB of LDS = kDmaRows consecutive tile rows
+  static constexpr int kDmaRows = 1024 / kRowBytes;
+  static constexpr int kADma = BM / kWaves / kDmaRows;  // instructions per wave per tile, A
+  static constexpr int kBDma = BN / kWaves / kDmaRows;  // per weight matrix
+  static constexpr int kLoadsPerTile = kADma + 2 * kBDma;
+  static constexpr int kSmemBytes = kStages * kStageBytes + BM * 8 + 2 * WM * BN * 4;
+  static_assert(KT == 32 || KT == 64, "K tile");
+  static_assert(kStages >= 3, "the ring needs a stage that nobody reads while it is filled");
+  static_assert(kADma >= 1 && kBDma >= 1 && BM % (kWaves * kDmaRows) == 0 && BN % (kWaves * kDmaRows) == 0,
+                "every wave fills whole 1 KiB groups");
+  static_assert(kSmemBytes <= 160 * 1024, "LDS per workgroup");
 };
+
+// LDS image of a tile: row r is kRowBytes long; its 16-byte chunk c sits at chunk position
+// c ^ swizzle_key(r).  The LDS has 64 four-byte banks, so kRowsPerBankRow tile rows share a bank
+// row; with this key the 16 rows that a quarter of a fragment read touches (same c) fall on 16
+// different 16-byte bank groups.
+template <class C>
+__device__ __forceinline__ int swizzle_key(int row) {
+  return (row / C::kRowsPerBankRow) % C::kChunks;
+}
 
 // Everything a workgroup needs after its set-up, so that the K loop can be instantiated
 // once per number of active row blocks (ACT) without run-time branches inside it.
@@ -82,57 +102,52 @@ struct TileState {
   unsigned char* smem;
   const float* s_a;
   float* s_red;
-  // staging (global -> registers -> LDS)
-  const __hip_bfloat16* a_src[C::kARows];
-  const __hip_bfloat16* wg_src[C::kBRows];
-  const __hip_bfloat16* wu_src[C::kBRows];
-  int st_dst;  // byte offset of this thread's chunk in a tile (+ kRowsPerPass * 128 per further row)
-  int st_k;    // first K element of this thread's chunk inside a K tile
+  // direct-to-LDS: per-lane source of each of this wave's row groups, wave-uniform LDS offsets
+  const __hip_bfloat16* a_src[C::kADma];
+  const __hip_bfloat16* g_src[C::kBDma];
+  const __hip_bfloat16* u_src[C::kBDma];
+  const __hip_bfloat16* zeros;  // 16 readable zero bytes (K tail)
+  int a_lds, b_lds;             // byte offset of the wave's first A row / weight row in a tile
+  int a_k[C::kADma];            // first K element (inside a tile) each A instruction of this lane reads
+  int b_k[C::kBDma];
   int d_model;
   // fragments
   int a_frag_base, b_frag_base;
-  int k_swz[KT / 16];
+  int k_swz[C::kSteps];
   int wave_m, wave_n, frag_row, frag_half;
 };
 
 template <class C, int ACT, bool TAIL>
 __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_ff, int slot,
                                           float* __restrict__ part_phi2, float* __restrict__ part_max) {
-  constexpr int BN = C::BN, TN = C::TN, WM = C::WM;
+  constexpr int BN = C::BN, TN = C::TN, WM = C::WM, KT = C::KT;
   constexpr int NA = ACT > 0 ? ACT : 1;
-  constexpr int kPassBytes = C::kRowsPerPass * 128;
   unsigned char* const smem = st.smem;
 
-  // Two register staging sets: tile kt+2 is on its way from HBM / L2 while tile kt+1 waits in the
-  // other set to be written to LDS, so a load has two K tiles of MFMA time to arrive.
-  struct Staging {
-    u32x4 a[C::kARows], g[C::kBRows], u[C::kBRows];
+  // Lane l of a wave instruction writes LDS bytes [16 l, 16 l + 16) after the wave-uniform base,
+  // i.e. chunk position l % kChunks of row l / kChunks of its row group; to produce the swizzled
+  // image it reads logical chunk (l % kChunks) ^ swizzle_key(row) of that row (set up by the caller).
+  // TAIL (d_model not a multiple of KT): chunks past d_model come from a page of zeros.
+  auto dma = [&](const __hip_bfloat16* src, int k, int k0, unsigned char* dst) {
+    const __hip_bfloat16* p = src + k0;
+    if constexpr (TAIL) p = (k0 + k < st.d_model) ? p : st.zeros;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                     (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
   };
-  // TAIL (d_model not a multiple of KT): chunks past d_model read as zero.  Without it no load is conditional.
-  auto ld = [&](const __hip_bfloat16* p, int k0) -> u32x4 {
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    if constexpr (TAIL) return (k0 + st.st_k < st.d_model) ? *reinterpret_cast<const u32x4*>(p + k0) : zero4;
-    else return *reinterpret_cast<const u32x4*>(p + k0);
-  };
-  auto load_global = [&](Staging& r, int k0) {
-#pragma unroll
-    for (int i = 0; i < C::kARows; ++i) r.a[i] = ld(st.a_src[i], k0);
-#pragma unroll
-    for (int i = 0; i < C::kBRows; ++i) {
-      r.g[i] = ld(st.wg_src[i], k0);
-      r.u[i] = ld(st.wu_src[i], k0);
-    }
-  };
-  auto store_lds = [&](const Staging& r, int buf) {
-    unsigned char* sA = smem + buf * C::kStageBytes + st.st_dst;
-    unsigned char* sG = sA + C::kATileBytes;
+  // the loads of one tile in two halves, so that they can be issued apart
+  auto dma_tile = [&](int stage, int k0, int half) {
+    unsigned char* sA = smem + stage * C::kStageBytes + st.a_lds;
+    unsigned char* sG = smem + stage * C::kStageBytes + C::kATileBytes + st.b_lds;
     unsigned char* sU = sG + C::kBTileBytes;
+    if (half == 0) {
 #pragma unroll
-    for (int i = 0; i < C::kARows; ++i) *reinterpret_cast<u32x4*>(sA + i * kPassBytes) = r.a[i];
+      for (int j = 0; j < C::kADma; ++j) dma(st.a_src[j], st.a_k[j], k0, sA + j * 1024);
+    } else {
 #pragma unroll
-    for (int i = 0; i < C::kBRows; ++i) {
-      *reinterpret_cast<u32x4*>(sG + i * kPassBytes) = r.g[i];
-      *reinterpret_cast<u32x4*>(sU + i * kPassBytes) = r.u[i];
+      for (int j = 0; j < C::kBDma; ++j) {
+        dma(st.g_src[j], st.b_k[j], k0, sG + j * 1024);
+        dma(st.u_src[j], st.b_k[j], k0, sU + j * 1024);
+      }
     }
   };
 
@@ -150,18 +165,18 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
   struct Frags {
     bf16x8 a[NA], g[TN], u[TN];
   };
-  auto read_frags = [&](Frags& f, int buf, int ks) {
+  auto read_frags = [&](Frags& f, int stage, int ks) {
     if constexpr (ACT > 0) {
-      const unsigned char* sA = smem + buf * C::kStageBytes + st.k_swz[ks];
+      const unsigned char* sA = smem + stage * C::kStageBytes + st.k_swz[ks];
       const unsigned char* sG = sA + C::kATileBytes + st.b_frag_base;
       const unsigned char* sU = sG + C::kBTileBytes;
 #pragma unroll
       for (int i = 0; i < ACT; ++i)
-        f.a[i] = *reinterpret_cast<const bf16x8*>(sA + st.a_frag_base + i * WM * 32 * 128);
+        f.a[i] = *reinterpret_cast<const bf16x8*>(sA + st.a_frag_base + i * WM * 32 * C::kRowBytes);
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        f.g[j] = *reinterpret_cast<const bf16x8*>(sG + j * 32 * 128);
-        f.u[j] = *reinterpret_cast<const bf16x8*>(sU + j * 32 * 128);
+        f.g[j] = *reinterpret_cast<const bf16x8*>(sG + j * 32 * C::kRowBytes);
+        f.u[j] = *reinterpret_cast<const bf16x8*>(sU + j * 32 * C::kRowBytes);
       }
     }
   };
@@ -174,48 +189,46 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
         acc_u[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.u[j], acc_u[i][j], 0, 0, 0);
       }
   };
-  auto pin = [&]() {
-    // keeps the compiler from sinking the global loads down to their LDS stores (which exposes
-    // the memory latency every tile) and from folding the two fragment sets into one
-    if constexpr (C::SCHED == kSchedPhases) __builtin_amdgcn_sched_barrier(0);
-  };
 
-  // One loop body for every K tile: tiles past the end are clamped to the last one (two redundant
-  // tile loads per workgroup) instead of branching around the prefetch.
+  // Ring schedule.  Tiles past the end are clamped to the last one (kStages - 1 redundant tile
+  // loads per workgroup) so that the loop body and the outstanding-load count never change.
   const int n_k = (st.d_model + KT - 1) / KT;
   const int k_last = (n_k - 1) * KT;
-  Frags f0, f1;
-  Staging r0, r1;
-  auto k_tile = [&](int kt, Staging& r_load, const Staging& r_store) {
-    const int buf = kt & 1;
-    load_global(r_load, min((kt + 2) * KT, k_last));  // tile kt + 2
-    read_frags(f1, buf, 1);
-    pin();
-    mfma_step(f0);
-    read_frags(f0, buf, 2);
-    pin();
-    mfma_step(f1);
-    read_frags(f1, buf, 3);
-    pin();
-    mfma_step(f0);
-    store_lds(r_store, buf ^ 1);  // tile kt + 1, loaded one iteration ago
-    __syncthreads();              // the next stage is complete; every read of this stage has returned
-    read_frags(f0, buf ^ 1, 0);
-    pin();
-    mfma_step(f1);
-    pin();
-  };
-  load_global(r0, 0);
-  load_global(r1, min(KT, k_last));
-  store_lds(r0, 0);
-  __syncthreads();
-  read_frags(f0, 0, 0);
-  int kt = 0;
-  for (; kt + 1 < n_k; kt += 2) {
-    k_tile(kt, r0, r1);
-    k_tile(kt + 1, r1, r0);
+  constexpr int kAhead = C::kStages - 1;                           // tiles in flight or landed ahead of kt
+  constexpr int kMayFly = (C::kStages - 2) * C::kLoadsPerTile;     // loads younger than tile kt + 1
+  Frags f[2];
+#pragma unroll
+  for (int t = 0; t < kAhead; ++t) {
+    dma_tile(t, min(t * KT, k_last), 0);
+    dma_tile(t, min(t * KT, k_last), 1);
   }
-  if (kt < n_k) k_tile(kt, r0, r1);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly) : "memory");  // tile 0 has landed (loads return in order)
+  __syncthreads();
+  read_frags(f[0], 0, 0);
+  int stage = 0;               // stage of tile kt
+  int fill = kAhead;           // stage tile kt + kAhead goes to: the one tile kt - 1 was read from
+  for (int kt = 0; kt < n_k; ++kt) {
+    const int k_fill = min((kt + kAhead) * KT, k_last);
+    const int next = stage + 1 == C::kStages ? 0 : stage + 1;
+#pragma unroll
+    for (int ks = 0; ks < C::kSteps; ++ks) {
+      if (ks == 0) dma_tile(fill, k_fill, 0);
+      if (ks + 1 < C::kSteps) {
+        read_frags(f[(ks + 1) & 1], stage, ks + 1);
+      } else {
+        // tile kt + 1 has landed for this wave; after the barrier for every wave, and every wave
+        // has finished reading the stage that the next iteration refills
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly) : "memory");
+        __syncthreads();
+        read_frags(f[(ks + 1) & 1], next, 0);
+      }
+      mfma_step(f[ks & 1]);
+      if (ks == 0) dma_tile(fill, k_fill, 1);
+    }
+    fill = stage;
+    stage = next;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS at exit
 
   // Epilogue.  Accumulator register r of lane l is output row 8*(r/4) + 4*(l/32) + (r%4),
   // column l % 32 of its 32x32 tile: a lane owns one channel and 16 token rows per tile.
@@ -263,7 +276,8 @@ __global__ __launch_bounds__(C::kThreads) void grouped_gemm_bf16_kernel(
     const __hip_bfloat16* __restrict__ Wg, const __hip_bfloat16* __restrict__ Wu, int64_t stride_gu,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_offset,
     const int32_t* __restrict__ tile_expert, const int32_t* __restrict__ perm, const float* __restrict__ w_perm,
-    int n_experts, float* __restrict__ part_phi2, float* __restrict__ part_max) {
+    int n_experts, const __hip_bfloat16* __restrict__ zeros, float* __restrict__ part_phi2,
+    float* __restrict__ part_max) {
   constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN, WM = C::WM;
   // Workgroup -> tile mapping.  The hardware deals consecutive workgroup ids round-robin to the 8
   // XCDs, each with its own L2.  Give every XCD a contiguous run of logical ids, and order logical
@@ -284,8 +298,8 @@ __global__ __launch_bounds__(C::kThreads) void grouped_gemm_bf16_kernel(
   const int n0 = tile_n * BN;
 
   extern __shared__ __align__(16) unsigned char smem[];
-  int32_t* s_tok = reinterpret_cast<int32_t*>(smem + 2 * C::kStageBytes);  // [BM] token id
-  float* s_a = reinterpret_cast<float*>(s_tok + BM);                       // [BM] routing weight
+  int32_t* s_tok = reinterpret_cast<int32_t*>(smem + C::kStages * C::kStageBytes);  // [BM] token id
+  float* s_a = reinterpret_cast<float*>(s_tok + BM);                                // [BM] routing weight
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
   const int wave = tid / kWave;
@@ -304,30 +318,38 @@ __global__ __launch_bounds__(C::kThreads) void grouped_gemm_bf16_kernel(
   st.s_a = s_a;
   st.s_red = s_a + BM;  // [2 stats][WM][BN]
   st.d_model = d_model;
+  st.zeros = zeros;
   st.wave_m = wave % WM;
   st.wave_n = wave / WM;
   st.frag_row = lane % 32;
   st.frag_half = lane / 32;
-  // Staging: thread t moves 16-byte chunk (t % 8) of tile rows t/8, t/8 + kRowsPerPass, ...
-  const int st_row = tid / kChunks, st_ck = tid % kChunks;
-  st.st_dst = st_row * 128 + ((st_ck ^ ((st_row >> 1) & 7)) << 4);  // the swizzle key repeats every 16 rows
-  st.st_k = st_ck * 8;
+  // direct-to-LDS sources of this lane
+  const int a_row0 = wave * (BM / C::kWaves), b_row0 = wave * (BN / C::kWaves);
+  st.a_lds = a_row0 * C::kRowBytes;
+  st.b_lds = b_row0 * C::kRowBytes;
 #pragma unroll
-  for (int i = 0; i < C::kARows; ++i)
-    st.a_src[i] = X + (int64_t)s_tok[st_row + C::kRowsPerPass * i] * ldx + st_ck * 8;
+  for (int j = 0; j < C::kADma; ++j) {
+    const int row = a_row0 + j * C::kDmaRows + lane / C::kChunks;
+    const int ck = (lane % C::kChunks) ^ swizzle_key<C>(row);
+    st.a_k[j] = ck * 8;
+    st.a_src[j] = X + (int64_t)s_tok[row] * ldx + ck * 8;
+  }
 #pragma unroll
-  for (int i = 0; i < C::kBRows; ++i) {
-    // channels past d_ff read the last channel again; their statistics are never written
-    const int c = min(n0 + st_row + C::kRowsPerPass * i, d_ff - 1);
-    const int64_t off = (int64_t)e * stride_gu + (int64_t)c * d_model + st_ck * 8;
-    st.wg_src[i] = Wg + off;
-    st.wu_src[i] = Wu + off;
+  for (int j = 0; j < C::kBDma; ++j) {
+    const int row = b_row0 + j * C::kDmaRows + lane / C::kChunks;
+    const int ck = (lane % C::kChunks) ^ swizzle_key<C>(row);
+    const int c = min(n0 + row, d_ff - 1);  // channels past d_ff read the last channel again; never written
+    const int64_t off = (int64_t)e * stride_gu + (int64_t)c * d_model + ck * 8;
+    st.b_k[j] = ck * 8;
+    st.g_src[j] = Wg + off;
+    st.u_src[j] = Wu + off;
   }
   // Fragments: lane l holds tile row (l % 32), K elements 8*(l / 32) .. +7 of a 16-wide K step.
-  st.a_frag_base = (st.wave_m * 32 + st.frag_row) * 128;       // + i * WM * 32 * 128: row block WM*i + wave_m
-  st.b_frag_base = (st.wave_n * TN * 32 + st.frag_row) * 128;  // + j * 32 * 128
+  // swizzle_key(row) only depends on row % 32 here (32-row blocks), so one key per lane.
+  st.a_frag_base = (st.wave_m * 32 + st.frag_row) * C::kRowBytes;       // + i*WM*32 rows: block WM*i + wave_m
+  st.b_frag_base = (st.wave_n * TN * 32 + st.frag_row) * C::kRowBytes;  // + j*32 rows
 #pragma unroll
-  for (int ks = 0; ks < KT / 16; ++ks) st.k_swz[ks] = ((ks * 2 + st.frag_half) ^ ((st.frag_row >> 1) & 7)) << 4;
+  for (int ks = 0; ks < C::kSteps; ++ks) st.k_swz[ks] = ((ks * 2 + st.frag_half) ^ swizzle_key<C>(st.frag_row)) << 4;
 
   // accumulator i of this wave covers row block WM*i + wave_m; blocks past m_len are skipped
   const int n_row_blocks = (m_len + 31) / 32;
@@ -444,9 +466,9 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
   }
 }
 
-// Tile shape of the bf16 kernel (token rows x channels per workgroup, waves, schedule).
+// Shape of the bf16 kernel: waves (M x N), 32x32 blocks per wave (M x N), K tile, LDS stages.
 #ifndef CAMERA_GEMM_CFG
-#define CAMERA_GEMM_CFG 4, 2, 2, 2, kSchedNone
+#define CAMERA_GEMM_CFG 4, 2, 2, 2, 32, 4
 #endif
 using Bf16Cfg = GemmCfg<CAMERA_GEMM_CFG>;
 
@@ -464,7 +486,7 @@ hipError_t launch_grouped_gemm(hipStream_t stream, int dtype, const void* X, int
   if (max_tiles <= 0) return hipSuccess;
   if (dtype == CAMERA_BF16) {
     using C = Bf16Cfg;
-    const bool tail = d_model % KT != 0;
+    const bool tail = d_model % C::KT != 0;
     auto kern = tail ? grouped_gemm_bf16_kernel<C, true> : grouped_gemm_bf16_kernel<C, false>;
     static bool attr_set[2] = {false, false};
     if (!attr_set[tail]) {
@@ -481,8 +503,8 @@ hipError_t launch_grouped_gemm(hipStream_t stream, int dtype, const void* X, int
     hipLaunchKernelGGL(kern, grid, dim3(C::kThreads), C::kSmemBytes, stream,
                        static_cast<const __hip_bfloat16*>(X), ldx, (int)d_model, (int)d_ff,
                        static_cast<const __hip_bfloat16*>(W_gate), static_cast<const __hip_bfloat16*>(W_up),
-                       stride_gu, t.offsets, t.tile_offset, t.tile_expert, t.perm, t.w_perm, n_experts, part_phi2,
-                       part_max);
+                       stride_gu, t.offsets, t.tile_offset, t.tile_expert, t.perm, t.w_perm, n_experts,
+                       static_cast<const __hip_bfloat16*>(t.zeros), part_phi2, part_max);
   } else {
     dim3 grid((unsigned)((d_ff + F32_BN - 1) / F32_BN), (unsigned)max_tiles);
     hipLaunchKernelGGL(grouped_gemm_f32_kernel, grid, dim3(256), 0, stream, static_cast<const float*>(X), ldx,
