@@ -80,7 +80,7 @@ struct GemmCfg {
   static constexpr int kLoadsPerTile = kADma + 2 * kBDma;
   static constexpr int kSmemBytes = kStages * kStageBytes + BM * 8 + 2 * WM * BN * 4;
   static_assert(KT == 32 || KT == 64, "K tile");
-  static_assert(kStages >= 3, "the ring needs a stage that nobody reads while it is filled");
+  static_assert(kStages >= 2, "at least the stage being read and the stage being filled");
   static_assert(kADma >= 1 && kBDma >= 1 && BM % (kWaves * kDmaRows) == 0 && BN % (kWaves * kDmaRows) == 0,
                 "every wave fills whole 1 KiB groups");
   static_assert(kSmemBytes <= 160 * 1024, "LDS per workgroup");
@@ -190,42 +190,40 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
       }
   };
 
-  // Ring schedule.  Tiles past the end are clamped to the last one (kStages - 1 redundant tile
-  // loads per workgroup) so that the loop body and the outstanding-load count never change.
+  // Ring schedule.  kStages tiles are in LDS or on their way; the barrier of iteration kt says that
+  // tile kt + 1 has landed and that nobody reads tile kt's stage any more, so the loads of tile
+  // kt + kStages go into that stage right behind the barrier and have kStages - 1 K tiles of MFMA
+  // time to arrive.  Tiles past the end are clamped to the last one (kStages redundant tile loads
+  // per workgroup) so that the loop body and the outstanding-load count never change.
   const int n_k = (st.d_model + KT - 1) / KT;
   const int k_last = (n_k - 1) * KT;
-  constexpr int kAhead = C::kStages - 1;                           // tiles in flight or landed ahead of kt
-  constexpr int kMayFly = (C::kStages - 2) * C::kLoadsPerTile;     // loads younger than tile kt + 1
+  constexpr int kMayFly = (C::kStages - 2) * C::kLoadsPerTile;  // loads younger than tile kt + 1
   Frags f[2];
 #pragma unroll
-  for (int t = 0; t < kAhead; ++t) {
+  for (int t = 0; t < C::kStages; ++t) {
     dma_tile(t, min(t * KT, k_last), 0);
     dma_tile(t, min(t * KT, k_last), 1);
   }
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly) : "memory");  // tile 0 has landed (loads return in order)
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly + C::kLoadsPerTile) : "memory");  // tile 0 (loads return in order)
   __syncthreads();
   read_frags(f[0], 0, 0);
-  int stage = 0;               // stage of tile kt
-  int fill = kAhead;           // stage tile kt + kAhead goes to: the one tile kt - 1 was read from
+  int stage = 0;  // stage of tile kt
   for (int kt = 0; kt < n_k; ++kt) {
-    const int k_fill = min((kt + kAhead) * KT, k_last);
     const int next = stage + 1 == C::kStages ? 0 : stage + 1;
 #pragma unroll
     for (int ks = 0; ks < C::kSteps; ++ks) {
-      if (ks == 0) dma_tile(fill, k_fill, 0);
       if (ks + 1 < C::kSteps) {
         read_frags(f[(ks + 1) & 1], stage, ks + 1);
       } else {
-        // tile kt + 1 has landed for this wave; after the barrier for every wave, and every wave
-        // has finished reading the stage that the next iteration refills
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly) : "memory");
         __syncthreads();
+        const int k_fill = min((kt + C::kStages) * KT, k_last);
+        dma_tile(stage, k_fill, 0);
+        dma_tile(stage, k_fill, 1);
         read_frags(f[(ks + 1) & 1], next, 0);
       }
       mfma_step(f[ks & 1]);
-      if (ks == 0) dma_tile(fill, k_fill, 1);
     }
-    fill = stage;
     stage = next;
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS at exit
@@ -468,7 +466,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
 
 // Shape of the bf16 kernel: waves (M x N), 32x32 blocks per wave (M x N), K tile, LDS stages.
 #ifndef CAMERA_GEMM_CFG
-#define CAMERA_GEMM_CFG 4, 2, 2, 2, 32, 4
+#define CAMERA_GEMM_CFG 4, 2, 2, 2, 64, 2
 #endif
 using Bf16Cfg = GemmCfg<CAMERA_GEMM_CFG>;
 
