@@ -53,7 +53,20 @@ __global__ __launch_bounds__(CAMERA_MAX_EXPERTS) void bucket_scan_kernel(int32_t
   const int e = threadIdx.x;
   int32_t total = 0;
   if (e < n_experts) {
-    for (int b = 0; b < n_blocks; ++b) {  // exclusive prefix over blocks, in place
+    // exclusive prefix over blocks, in place; eight independent loads at a time, because a lone
+    // workgroup has nothing else to hide their latency with
+    int b = 0;
+    for (; b + 8 <= n_blocks; b += 8) {
+      int32_t c[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) c[u] = block_hist[(int64_t)(b + u) * n_experts + e];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        block_hist[(int64_t)(b + u) * n_experts + e] = total;
+        total += c[u];
+      }
+    }
+    for (; b < n_blocks; ++b) {
       const int32_t c = block_hist[(int64_t)b * n_experts + e];
       block_hist[(int64_t)b * n_experts + e] = total;
       total += c;

@@ -62,6 +62,50 @@ constexpr int kClsThreads = 1024;
 constexpr int kClsWaves = kClsThreads / kWave;
 constexpr int kBins = 2048;
 constexpr int kReplicas = kMaxCuts;  // pass 0 spreads one histogram over the per-cut slots
+constexpr int kInFlight = 4;         // independent 16-byte loads a thread keeps in flight
+
+__device__ __forceinline__ Keys4 keys_of(float4 v) {
+  Keys4 k;
+  k.k[0] = key_of(v.x);
+  k.k[1] = key_of(v.y);
+  k.k[2] = key_of(v.z);
+  k.k[3] = key_of(v.w);
+  k.valid[0] = k.valid[1] = k.valid[2] = k.valid[3] = true;
+  return k;
+}
+
+// Every thread of the block visits groups of 4 keys, block-strided; the order does not matter.
+// One workgroup cannot hide memory latency with occupancy, so kInFlight loads are issued before
+// the first is used.
+template <class F>
+__device__ __forceinline__ void sweep_block(const float* __restrict__ E, int64_t n, F&& f) {
+  constexpr int64_t step = (int64_t)kClsThreads * 4;
+  int64_t i = (int64_t)threadIdx.x * 4;
+  for (; i + (kInFlight - 1) * step + 3 < n; i += kInFlight * step) {
+    float4 v[kInFlight];
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) v[u] = *reinterpret_cast<const float4*>(E + i + u * step);
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) f(keys_of(v[u]));
+  }
+  for (; i < n; i += step) f(load_keys4(E, i, n));
+}
+
+// A wave visits its contiguous index range [begin, end) in order, 256 indices per step (lane l
+// holds 4 l .. 4 l + 3 of the step); f(keys, first index of the lane) runs on whole waves, so it
+// may ballot.  Loads of kInFlight steps are issued together.
+template <class F>
+__device__ __forceinline__ void walk_wave(const float* __restrict__ E, int64_t begin, int64_t end, int lane, F&& f) {
+  int64_t i0 = begin;
+  for (; i0 + kInFlight * 256 <= end; i0 += kInFlight * 256) {
+    float4 v[kInFlight];
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) v[u] = *reinterpret_cast<const float4*>(E + i0 + u * 256 + lane * 4);
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) f(keys_of(v[u]), i0 + u * 256 + lane * 4);
+  }
+  for (; i0 < end; i0 += 256) f(load_keys4(E, i0 + lane * 4, end), i0 + lane * 4);
+}
 
 // exclusive prefix of v over the block (thread order); s_wave is [kClsWaves + 1] scratch
 __device__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s_wave) {
@@ -123,33 +167,35 @@ __global__ __launch_bounds__(kClsThreads) void classify_kernel(const float* __re
       if (pass == 0) {
         // no prefix yet: one histogram serves every cut; lanes spread over replicas to
         // thin out same-address LDS atomics (energies share their top bits)
-        const int rep = lane % kReplicas;
-        for (int64_t i = (int64_t)tid * 4; i < n; i += (int64_t)kClsThreads * 4) {
-          const Keys4 k = load_keys4(E, i, n);
+        uint32_t* my_hist = hist[lane % kReplicas];
+        sweep_block(E, n, [&](const Keys4& k) {
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            if (k.valid[j]) atomicAdd(&hist[rep][k.k[j] >> shift], 1u);
-        }
+            if (k.valid[j]) atomicAdd(&my_hist[k.k[j] >> shift], 1u);
+        });
         __syncthreads();
         for (int b = tid; b < kBins; b += kClsThreads) {
-          uint32_t s = 0;
+          uint32_t sum = 0;
 #pragma unroll
-          for (int r = 0; r < kReplicas; ++r) s += hist[r][b];
-          for (int r = 0; r < kReplicas; ++r) hist[r][b] = s;  // bin b is touched by this thread only
+          for (int r = 0; r < kReplicas; ++r) sum += hist[r][b];
+          for (int r = 0; r < kReplicas; ++r) hist[r][b] = sum;  // bin b is touched by this thread only
         }
         __syncthreads();
       } else {
         const int prev_shift = shift + bits_of[pass];
-        for (int64_t i = (int64_t)tid * 4; i < n; i += (int64_t)kClsThreads * 4) {
-          const Keys4 k = load_keys4(E, i, n);
-          for (int q = 0; q < n_cuts; ++q) {
-            if (s_mode[q] != 0) continue;
-            const uint32_t want = s_prefix[q];
+        uint32_t want[kMaxCuts];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-              if (k.valid[j] && (k.k[j] >> prev_shift) == want) atomicAdd(&hist[q][(k.k[j] >> shift) & mask], 1u);
+        for (int q = 0; q < kMaxCuts; ++q) want[q] = (q < n_cuts && s_mode[q] == 0) ? s_prefix[q] : 0xffffffffu;
+        sweep_block(E, n, [&](const Keys4& k) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            if (!k.valid[j]) continue;
+            const uint32_t top = k.k[j] >> prev_shift;  // at most 22 bits: never 0xffffffff
+#pragma unroll
+            for (int q = 0; q < kMaxCuts; ++q)
+              if (top == want[q]) atomicAdd(&hist[q][(k.k[j] >> shift) & mask], 1u);
           }
-        }
+        });
         __syncthreads();
       }
       // locate, for every cut, the bin that holds rank s_rem[q]
@@ -172,35 +218,35 @@ __global__ __launch_bounds__(kClsThreads) void classify_kernel(const float* __re
   }
   // s_prefix[q] is now the full key K_q, s_rem[q] the number of keys equal to K_q below the cut.
 
-  // Ordered walk.  Wave w owns indices [w*span, (w+1)*span); a step covers 256 consecutive
-  // indices, lane l holding 4*l .. 4*l+3.
+  // Ordered walk.  Wave w owns indices [w*span, (w+1)*span).
   const int64_t span = ((n + kClsWaves * 256 - 1) / (kClsWaves * 256)) * 256;
-  const int64_t w_begin = (int64_t)wave * span;
+  const int64_t w_begin = min(n, (int64_t)wave * span);
   const int64_t w_end = min(n, w_begin + span);
   const uint64_t lower = (1ull << lane) - 1ull;
 
   uint32_t K[kMaxCuts], R[kMaxCuts];
   int mode[kMaxCuts];
+  bool ties_split = false;  // some cut runs through a group of equal keys: their index order matters
 #pragma unroll
   for (int q = 0; q < kMaxCuts; ++q) {
     K[q] = s_prefix[q];
     R[q] = s_rem[q];
     mode[q] = q < n_cuts ? s_mode[q] : 1;
+    ties_split |= mode[q] == 0 && R[q] > 0;
   }
 
-  if (any_select) {  // T1: equal-key counts per wave
+  if (ties_split) {  // equal-key counts per wave, then their exclusive prefix over the waves
     uint32_t cnt[kMaxCuts];
 #pragma unroll
     for (int q = 0; q < kMaxCuts; ++q) cnt[q] = 0;
-    for (int64_t i0 = w_begin; i0 < w_end; i0 += 256) {
-      const Keys4 k = load_keys4(E, i0 + lane * 4, w_end);
+    walk_wave(E, w_begin, w_end, lane, [&](const Keys4& k, int64_t) {
 #pragma unroll
       for (int q = 0; q < kMaxCuts; ++q) {
-        if (mode[q] != 0) continue;
+        if (mode[q] != 0 || R[q] == 0) continue;
 #pragma unroll
         for (int j = 0; j < 4; ++j) cnt[q] += __popcll(__ballot(k.valid[j] && k.k[j] == K[q]));
       }
-    }
+    });
     if (lane == 0) {
 #pragma unroll
       for (int q = 0; q < kMaxCuts; ++q) s_tie[q][wave] = cnt[q];
@@ -219,11 +265,9 @@ __global__ __launch_bounds__(kClsThreads) void classify_kernel(const float* __re
 
   uint32_t tie_base[kMaxCuts];
 #pragma unroll
-  for (int q = 0; q < kMaxCuts; ++q) tie_base[q] = any_select ? s_tie[q][wave] : 0u;
+  for (int q = 0; q < kMaxCuts; ++q) tie_base[q] = ties_split ? s_tie[q][wave] : 0u;
   uint32_t kept = 0;
-  for (int64_t i0 = w_begin; i0 < w_end; i0 += 256) {  // T2: classify
-    const int64_t i = i0 + lane * 4;
-    const Keys4 k = load_keys4(E, i, w_end);
+  walk_wave(E, w_begin, w_end, lane, [&](const Keys4& k, int64_t i) {
     int below[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int q = 0; q < kMaxCuts; ++q) {
@@ -231,6 +275,11 @@ __global__ __launch_bounds__(kClsThreads) void classify_kernel(const float* __re
       if (mode[q] == 2) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) below[j] += 1;
+        continue;
+      }
+      if (R[q] == 0) {  // no key equal to K is below this cut
+#pragma unroll
+        for (int j = 0; j < 4; ++j) below[j] += k.k[j] < K[q] ? 1 : 0;
         continue;
       }
       bool eq[4];
@@ -250,22 +299,34 @@ __global__ __launch_bounds__(kClsThreads) void classify_kernel(const float* __re
       }
       tie_base[q] += total;
     }
+    if (k.valid[3]) {  // whole group inside: one 4-byte store per output
+      const uint32_t cls4 = (uint32_t)below[0] | ((uint32_t)below[1] << 8) | ((uint32_t)below[2] << 16) |
+                            ((uint32_t)below[3] << 24);
+      const uint32_t out4 = (uint32_t)cuts.out_of_below[below[0]] | ((uint32_t)cuts.out_of_below[below[1]] << 8) |
+                            ((uint32_t)cuts.out_of_below[below[2]] << 16) |
+                            ((uint32_t)cuts.out_of_below[below[3]] << 24);
+      *reinterpret_cast<uint32_t*>(class_out + i) = cls4;
+      *reinterpret_cast<uint32_t*>(byte_out + i) = out4;
+    } else {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (k.valid[j]) {
-        class_out[i + j] = (uint8_t)below[j];
-        byte_out[i + j] = cuts.out_of_below[below[j]];
-      }
-      kept += __popcll(__ballot(k.valid[j] && below[j] == 0));
+      for (int j = 0; j < 4; ++j)
+        if (k.valid[j]) {
+          class_out[i + j] = (uint8_t)below[j];
+          byte_out[i + j] = cuts.out_of_below[below[j]];
+        }
     }
-  }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) kept += __popcll(__ballot(k.valid[j] && below[j] == 0));
+  });
   if (kept_idx == nullptr) return;  // block-uniform
 
   if (lane == 0) s_kept[wave] = kept;
   __syncthreads();
   uint32_t pos = 0;
   for (int w = 0; w < wave; ++w) pos += s_kept[w];
-  for (int64_t i0 = w_begin; i0 < w_end; i0 += 256) {  // T3: ascending list of the kept indices
+  // ascending list of the kept indices: re-derive "kept" from the keys instead of re-reading class_out
+  // (same arithmetic as above restricted to "below no cut")
+  for (int64_t i0 = w_begin; i0 < w_end; i0 += 256) {
     const int64_t i = i0 + lane * 4;
     bool is_kept[4];
     uint32_t lanes_before = 0, total = 0;
@@ -299,19 +360,25 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(const uint8_t* __r
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int begin = seg.off[s], end = seg.off[s + 1];
   const int span = ((end - begin + kSegWaves * kWave - 1) / (kSegWaves * kWave)) * kWave;
-  const int w_begin = begin + wave * span;
+  const int w_begin = min(end, begin + wave * span);
   const int w_end = min(end, w_begin + span);
   const uint64_t lower = (1ull << lane) - 1ull;
 
   uint32_t cnt[CAMERA_MAX_LEVELS];
 #pragma unroll
   for (int m = 0; m < CAMERA_MAX_LEVELS; ++m) cnt[m] = 0;
-  for (int i0 = w_begin; i0 < w_end; i0 += kWave) {
-    const int i = i0 + lane;
-    const int c = i < w_end ? (int)class_in[i] : -1;
+  for (int i0 = w_begin; i0 < w_end; i0 += 4 * kWave) {  // four independent byte loads in flight
+    int c[4];
 #pragma unroll
-    for (int m = 0; m < CAMERA_MAX_LEVELS; ++m)
-      if (m < n_classes) cnt[m] += __popcll(__ballot(c == m));
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + u * kWave + lane;
+      c[u] = i < w_end ? (int)class_in[i] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int m = 0; m < CAMERA_MAX_LEVELS; ++m)
+        if (m < n_classes) cnt[m] += __popcll(__ballot(c[u] == m));
   }
   if (lane == 0) {
 #pragma unroll
@@ -342,15 +409,23 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(const uint8_t* __r
       }
     }
   }
-  for (int i0 = w_begin; i0 < w_end; i0 += kWave) {
-    const int i = i0 + lane;
-    const int c = i < w_end ? (int)class_in[i] : -1;
+  for (int i0 = w_begin; i0 < w_end; i0 += 4 * kWave) {
+    int c[4];
 #pragma unroll
-    for (int m = 0; m < CAMERA_MAX_LEVELS; ++m) {
-      if (m < n_classes) {
-        const uint64_t b = __ballot(c == m);
-        if (c == m) perm[slot[m] + __popcll(b & lower)] = i;
-        slot[m] += __popcll(b);
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + u * kWave + lane;
+      c[u] = i < w_end ? (int)class_in[i] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + u * kWave + lane;
+#pragma unroll
+      for (int m = 0; m < CAMERA_MAX_LEVELS; ++m) {
+        if (m < n_classes) {
+          const uint64_t b = __ballot(c[u] == m);
+          if (c[u] == m) perm[slot[m] + __popcll(b & lower)] = i;
+          slot[m] += __popcll(b);
+        }
       }
     }
   }

@@ -1,0 +1,163 @@
+"""Parity on the five benchmark configurations.
+
+* scaled-down copies of every configuration (same structure: shared experts, bias kind, alpha,
+  decisions) small enough for the full oracle, end to end: route -> score -> masks / bits, with the
+  decidable-band rule for decisions taken on energies that are only known to the score tolerance;
+* the configurations at their full sizes, one layer, through the same calls and launch shapes that
+  bench.py times, checked on sampled tokens (routing) and sampled micro-experts (scores), and bit-exact
+  on the integer stages given the GPU's own energies.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import camera_oracle as orc
+from paper_2508_02322_amd import inputs
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+SCALED = {
+    "mixtral": dict(n_tokens=700, d_model=256, d_ff=448, n_experts=8, top_k=2, outlier_channels=4),
+    "deepseek-moe-16b": dict(n_tokens=1024, d_model=256, d_ff=176, n_experts=16, top_k=6, n_shared=2,
+                             d_ff_shared=176, n_layers=2),
+    "qwen2-57b-a14b": dict(n_tokens=1000, d_model=320, d_ff=160, n_experts=16, top_k=8, n_shared=1,
+                           d_ff_shared=1280, outlier_channels=4, n_layers=2),
+    "qwen3-30b-a3b": dict(n_tokens=2048, d_model=256, d_ff=96, n_experts=32, top_k=8, n_layers=2),
+}
+DECISIONS = {
+    "mixtral": dict(prune=[0.2, 0.4, 0.6], alloc=[]),
+    "deepseek-moe-16b": dict(prune=[0.2, 0.4, 0.6], alloc=[]),
+    "qwen2-57b-a14b": dict(prune=[0.2, 0.4, 0.6], alloc=[([3, 2, 1], [0.2, 0.6, 0.2])]),
+    "qwen3-30b-a3b": dict(prune=[], alloc=[([3, 2, 1], [0.2, 0.6, 0.2]), ([4, 3, 2], [0.1, 0.3, 0.6]),
+                                           ([4, 3, 2], [0.0, 0.0, 1.0])]),
+}
+
+
+def run_layer(cam, cfg, dev):
+    idx, w = cam.route_topk(dev["X"], dev["W_r"], dev["bias"], cfg.top_k)
+    out = {k: torch.empty(cfg.n_micro, dtype=torch.float32, device="cuda") for k in
+           ("phi2", "phi_inf", "omega2", "energy")}
+    nr = cfg.n_micro_routed
+    cam.score_layer(dev["X"], idx, w, dev["W_gate"], dev["W_up"], dev["W_down"], cfg.alpha,
+                    out={k: v[:nr] for k, v in out.items()})
+    if cfg.n_shared:
+        cam.score_layer(dev["X"], None, None, dev["Ws_gate"], dev["Ws_up"], dev["Ws_down"], cfg.alpha,
+                        out={k: v[nr:] for k, v in out.items()})
+    torch.cuda.synchronize()
+    return idx, w, out
+
+
+def check_decisions(cam, cfg, name, energy_gpu, energy_orc=None):
+    """Integer stages: bit-exact against the oracle on the GPU's energies; and, when the oracle's
+    energies are given, consistent with them wherever the score tolerance can decide."""
+    seg = inputs.segment_offsets(cfg)
+    E = energy_gpu.cpu().numpy()
+    N = E.size
+    report = {}
+    for ratio in DECISIONS[name]["prune"]:
+        keep, per, kept_idx, _ = cam.select_prune(energy_gpu, seg, ratio, want_idx=True)
+        o_keep, o_per, o_idx, _ = orc.select_prune(E, seg, ratio)
+        np.testing.assert_array_equal(keep.cpu().numpy(), o_keep)
+        np.testing.assert_array_equal(per.cpu().numpy(), o_per)
+        np.testing.assert_array_equal(kept_idx.cpu().numpy()[:o_idx.size], o_idx)
+        n_prune = orc.prune_count(ratio, N)
+        assert int(keep.sum()) == N - n_prune
+        if energy_orc is not None:
+            must_prune, must_keep = H.decidable_masks(energy_orc, n_prune, TOL)
+            k = keep.cpu().numpy().astype(bool)
+            assert not np.any(k[must_prune]) and np.all(k[must_keep])
+            report[f"undecidable@{ratio}"] = 1.0 - (must_prune.sum() + must_keep.sum()) / N
+    for bits, ratios in DECISIONS[name]["alloc"]:
+        bit_of, level_count, perm = cam.alloc_bits(energy_gpu, seg, bits, ratios, want_perm=True)
+        o_bits, o_count, o_perm = orc.alloc_bits(E, seg, bits, ratios)
+        np.testing.assert_array_equal(bit_of.cpu().numpy(), o_bits)
+        np.testing.assert_array_equal(level_count.cpu().numpy(), o_count)
+        np.testing.assert_array_equal(perm.cpu().numpy(), o_perm)
+        if energy_orc is not None:
+            cuts = orc.class_cuts(ratios, N)
+            b = bit_of.cpu().numpy()
+            for m in range(len(bits) - 1):          # boundary between class m and m + 1
+                n_below = N - cuts[m]
+                must_below, must_above = H.decidable_masks(energy_orc, n_below, TOL)
+                cls_of = {bw: i for i, bw in enumerate(bits)} if len(set(bits)) == len(bits) else None
+                if cls_of is None:
+                    continue
+                cls = np.vectorize(cls_of.get)(b)
+                assert np.all(cls[must_below] > m) and np.all(cls[must_above] <= m)
+    return report
+
+
+@pytest.mark.parametrize("name", list(SCALED))
+def test_scaled_config_end_to_end(cam, name):
+    cfg = inputs.scaled(inputs.CONFIGS[name], **SCALED[name])
+    for layer_idx in range(min(2, cfg.n_layers)):
+        layer = inputs.make_layer(cfg, layer_idx)
+        dev = H.to_dev(layer)
+        idx, w, out = run_layer(cam, cfg, dev)
+        L, idx_o, w_o, _ = H.oracle_route(layer, cfg.top_k)
+        flagged, differ = H.check_routing(L, idx_o, w_o, idx.cpu().numpy(), w.cpu().numpy(), cfg.top_k)
+        # oracle scores on the GPU's routing (identical to the oracle's own off the tie margin)
+        A = orc.dense_routing(idx.cpu().numpy(), w.cpu().numpy().astype(np.float64), cfg.n_experts)
+        want = [H.oracle_score(layer, A, cfg.alpha)["energy"]]
+        if cfg.n_shared:
+            want.append(H.oracle_score(layer, np.ones((cfg.n_tokens, cfg.n_shared)), cfg.alpha, prefix="Ws")["energy"])
+        want = np.concatenate(want)
+        got = out["energy"].cpu().numpy().astype(np.float64)
+        err = H.rel_err(got, want, want.max() * 1e-9)
+        assert err <= TOL, err
+        report = check_decisions(cam, cfg, name, out["energy"], want)
+        print(f"{name} layer {layer_idx}: flagged {flagged} differ {differ} energy rel err {err:.2e} {report}")
+
+
+FULL = ["mixtral", "deepseek-moe-16b", "qwen2-57b-a14b", "qwen3-30b-a3b"]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_layer_sampled(cam, name):
+    cfg = inputs.CONFIGS[name]
+    layer_idx = cfg.n_layers - 1
+    dev = inputs.make_layer(cfg, layer_idx, device="cuda")      # the bytes bench.py would time
+    idx, w, out = run_layer(cam, cfg, dev)
+    rng = np.random.default_rng(7)
+
+    # routing on sampled tokens
+    tok = np.sort(rng.choice(cfg.n_tokens, size=256, replace=False))
+    sub = {"X": dev["X"][torch.as_tensor(tok).cuda()].cpu(), "W_r": dev["W_r"].cpu(),
+           "bias": None if dev["bias"] is None else dev["bias"].cpu()}
+    L, idx_o, w_o, _ = H.oracle_route(sub, cfg.top_k)
+    flagged, differ = H.check_routing(L, idx_o, w_o, idx.cpu().numpy()[tok], w.cpu().numpy()[tok], cfg.top_k)
+
+    # scores of sampled micro-experts of every expert, all tokens, with the GPU's routing
+    X = H.f64(dev["X"])
+    A = orc.dense_routing(idx.cpu().numpy(), w.cpu().numpy().astype(np.float64), cfg.n_experts)
+    n_ch = 4
+    worst = 0.0
+    for prefix, n_exp, f, A_mat, base in (("W", cfg.n_experts, cfg.d_ff, A, 0),
+                                          ("Ws", cfg.n_shared, cfg.d_ff_shared,
+                                           np.ones((cfg.n_tokens, max(cfg.n_shared, 1))), cfg.n_micro_routed)):
+        if n_exp == 0:
+            continue
+        ch = np.sort(rng.choice(f, size=n_ch if prefix == "W" else 64, replace=False))
+        cht = torch.as_tensor(ch).cuda()
+        Wg = H.f64(dev[prefix + "_gate"][:, cht])
+        Wu = H.f64(dev[prefix + "_up"][:, cht])
+        Wd = H.f64(dev[prefix + "_down"][:, :, cht])
+        want = orc.score_layer(X, A_mat[:, :n_exp], Wg, Wu, Wd, cfg.alpha)
+        index = (base + np.arange(n_exp)[:, None] * f + ch[None, :]).ravel()
+        for key in ("phi2", "phi_inf", "omega2", "energy"):
+            got = out[key].cpu().numpy().astype(np.float64)[index]
+            err = H.rel_err(got, want[key], max(want[key].max() * 1e-9, 1e-300))
+            worst = max(worst, err)
+            assert err <= TOL, (prefix, key, err)
+    # properties that hold at any size, then the integer stages bit-exact on the GPU's energies
+    E = out["energy"]
+    assert torch.isfinite(E).all() and (E >= 0).all()
+    counts = torch.bincount(idx.flatten().long(), minlength=cfg.n_experts).cpu().numpy()
+    empty = np.nonzero(counts == 0)[0]
+    for e in empty:
+        assert torch.all(E[e * cfg.d_ff:(e + 1) * cfg.d_ff] == 0)
+    check_decisions(cam, cfg, name, E)
+    print(f"{name} layer {layer_idx}: routing flagged {flagged} differ {differ} of 256 sampled tokens; "
+          f"worst sampled rel err {worst:.2e}; tokens per expert min {counts.min()} max {counts.max()}")
