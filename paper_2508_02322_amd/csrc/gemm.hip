@@ -79,6 +79,9 @@ struct GemmCfg {
   static constexpr int kBDma = BN / kWaves / kDmaRows;  // per weight matrix
   static constexpr int kLoadsPerTile = kADma + 2 * kBDma;
   static constexpr int kSmemBytes = kStages * kStageBytes + BM * 8 + 2 * WM * BN * 4;
+  // workgroups that fit one CU by LDS (160 KiB), hence waves per SIMD the registers must allow
+  static constexpr int kBlocksPerCu = (160 * 1024) / kSmemBytes >= 2 ? 2 : 1;
+  static constexpr int kWavesPerSimd = kBlocksPerCu * kWaves / 4 > 0 ? kBlocksPerCu * kWaves / 4 : 1;
   static_assert(KT == 32 || KT == 64, "K tile");
   static_assert(kStages >= 2, "at least the stage being read and the stage being filled");
   static_assert(kADma >= 1 && kBDma >= 1 && BM % (kWaves * kDmaRows) == 0 && BN % (kWaves * kDmaRows) == 0,
@@ -269,7 +272,7 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
 }
 
 template <class C, bool TAIL>
-__global__ __launch_bounds__(C::kThreads) void grouped_gemm_bf16_kernel(
+__global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf16_kernel(
     const __hip_bfloat16* __restrict__ X, int64_t ldx, int d_model, int d_ff,
     const __hip_bfloat16* __restrict__ Wg, const __hip_bfloat16* __restrict__ Wu, int64_t stride_gu,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_offset,
