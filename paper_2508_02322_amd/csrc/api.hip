@@ -381,7 +381,7 @@ int camera_select_prune(camera_ctx* ctx, void* stream_, const float* energy, int
 
   Carver cv;
   const size_t o_class = cv.take((size_t)n_micro + 64);
-  const size_t o_sort = cv.take(rank ? sizeof(int32_t) * camera::rank_workspace_words(n_micro, 1) : 0);
+  const size_t o_rank = cv.take(sizeof(int32_t) * camera::rank_workspace_words(n_micro, rank ? 1 : 0));
   DeviceGuard guard;
   CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
   if (int rc = ensure_workspace(ctx, cv.used)) return rc;
@@ -389,12 +389,13 @@ int camera_select_prune(camera_ctx* ctx, void* stream_, const float* energy, int
   uint8_t* class_buf = reinterpret_cast<uint8_t*>(ws + o_class);
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   Bracket b(ctx, stream, CAMERA_K_RANK);
-  CAMERA_HIP(camera::launch_classify(stream, energy, n_micro, cuts, class_buf, keep_mask, kept_idx, nullptr),
+  CAMERA_HIP(camera::launch_classify(stream, energy, n_micro, cuts, class_buf, keep_mask, kept_idx,
+                                     reinterpret_cast<int32_t*>(ws + o_rank)),
              "classify launch");
   CAMERA_HIP(camera::launch_segment_counts(stream, class_buf, seg, 1, 1, kept_per_expert, nullptr),
              "segment counts launch");
   if (rank)
-    CAMERA_HIP(camera::launch_full_rank(stream, energy, n_micro, rank, reinterpret_cast<int32_t*>(ws + o_sort)),
+    CAMERA_HIP(camera::launch_full_rank(stream, energy, n_micro, rank, reinterpret_cast<int32_t*>(ws + o_rank)),
                "rank launch");
   return CAMERA_OK;
 }
@@ -433,13 +434,15 @@ int camera_alloc_bits(camera_ctx* ctx, void* stream_, const float* energy, int64
 
   Carver cv;
   const size_t o_class = cv.take((size_t)n_micro + 64);
+  const size_t o_rank = cv.take(sizeof(int32_t) * camera::rank_workspace_words(n_micro, 0));
   DeviceGuard guard;
   CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
   if (int rc = ensure_workspace(ctx, cv.used)) return rc;
   uint8_t* class_buf = reinterpret_cast<uint8_t*>(static_cast<char*>(ctx->ws) + o_class);
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   Bracket b(ctx, stream, CAMERA_K_RANK);
-  CAMERA_HIP(camera::launch_classify(stream, energy, n_micro, cuts, class_buf, bit_of, nullptr, nullptr),
+  CAMERA_HIP(camera::launch_classify(stream, energy, n_micro, cuts, class_buf, bit_of, nullptr,
+                                     reinterpret_cast<int32_t*>(static_cast<char*>(ctx->ws) + o_rank)),
              "classify launch");
   CAMERA_HIP(camera::launch_segment_counts(stream, class_buf, seg, n_levels, 0, level_count, perm),
              "segment counts launch");

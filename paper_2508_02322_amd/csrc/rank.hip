@@ -11,9 +11,9 @@
 // walk: every wave owns a contiguous index range, ballots + popcounts give the
 // order inside 256-element steps.
 //
-// classify_kernel: one workgroup of 16 waves does the select passes and the
-// walk for all cuts at once (<= 184 320 keys per layer in the paper's models:
-// the pass is latency-bound, not bandwidth-bound).
+// rank_* kernels: the select passes and the walk for all cuts at once, one
+// workgroup per 4096 keys (<= 184 320 keys per layer in the paper's models:
+// latency- and launch-bound, not bandwidth-bound).
 // segment_kernel: one workgroup per expert: class sizes and the stable
 // partition of its micro-experts by class.
 // full rank: LSD radix sort (4 x 8 bits) of (key, index) built from a stable
@@ -56,13 +56,33 @@ __device__ __forceinline__ Keys4 load_keys4(const float* __restrict__ E, int64_t
 }
 
 // ---------------------------------------------------------------------------
-// classify
+// classify: radix select for every cut, then the ordered classification walk.
+//
+// A layer has at most a few hundred thousand keys, so every pass is latency- and launch-bound:
+// the work is spread over one workgroup per 4096 keys (each thread has its 16 keys in flight at
+// once) and chained as short kernels on the stream.  After each histogram pass the workgroup
+// that finishes last (a ticket from an atomic counter after a __threadfence; nobody waits for
+// anybody) picks, for every cut, the bin that holds the cut element and publishes prefix / rest.
+//   zero      clears histograms and tickets, seeds (mode, rest) per cut
+//   hist<P>   P = 0, 1, 2: 11 + 11 + 10 key bits; keys that share the cut's prefix so far
+//   ties      equal-key counts per workgroup, only if a cut runs through a group of equal keys
+//   label     ordered walk: class byte, output byte, kept counts per workgroup
+//   compact   (optional) ascending list of the kept indices
 // ---------------------------------------------------------------------------
-constexpr int kClsThreads = 1024;
-constexpr int kClsWaves = kClsThreads / kWave;
+constexpr int kRankThreads = 256;
+constexpr int kRankWaves = kRankThreads / kWave;
+constexpr int kKeysPerBlock = kRankThreads * 16;  // 4096
+constexpr int kKeysPerWave = kKeysPerBlock / kRankWaves;  // 1024 consecutive keys
 constexpr int kBins = 2048;
-constexpr int kReplicas = kMaxCuts;  // pass 0 spreads one histogram over the per-cut slots
-constexpr int kInFlight = 4;         // independent 16-byte loads a thread keeps in flight
+
+struct RankState {  // lives in the workspace
+  uint32_t hist[3][kMaxCuts][kBins];
+  uint32_t ticket[4];
+  uint32_t prefix[kMaxCuts];  // key bits fixed so far (right-aligned); after pass 2 the key K of the cut element
+  uint32_t rest[kMaxCuts];    // rank of the cut among keys sharing the prefix; after pass 2: equal keys below the cut
+  int32_t mode[kMaxCuts];     // 0 select, 1 nothing below, 2 everything below
+  uint32_t ties_split;        // some cut runs through a group of equal keys
+};
 
 __device__ __forceinline__ Keys4 keys_of(float4 v) {
   Keys4 k;
@@ -74,40 +94,32 @@ __device__ __forceinline__ Keys4 keys_of(float4 v) {
   return k;
 }
 
-// Every thread of the block visits groups of 4 keys, block-strided; the order does not matter.
-// One workgroup cannot hide memory latency with occupancy, so kInFlight loads are issued before
-// the first is used.
-template <class F>
-__device__ __forceinline__ void sweep_block(const float* __restrict__ E, int64_t n, F&& f) {
-  constexpr int64_t step = (int64_t)kClsThreads * 4;
-  int64_t i = (int64_t)threadIdx.x * 4;
-  for (; i + (kInFlight - 1) * step + 3 < n; i += kInFlight * step) {
-    float4 v[kInFlight];
+// The 16 keys of this thread: wave w of the block owns 1024 consecutive keys, step u of the wave
+// 256 of them, lane l keys 4 l .. 4 l + 3 of the step.  All four loads are issued together.
+struct Keys16 {
+  Keys4 g[4];
+  int64_t first[4];
+};
+__device__ __forceinline__ Keys16 load_keys16(const float* __restrict__ E, int64_t n) {
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int64_t base = (int64_t)blockIdx.x * kKeysPerBlock + (int64_t)wave * kKeysPerWave + lane * 4;
+  Keys16 out;
+  if ((int64_t)blockIdx.x * kKeysPerBlock + kKeysPerBlock <= n) {  // block-uniform: whole block inside
+    float4 v[4];
 #pragma unroll
-    for (int u = 0; u < kInFlight; ++u) v[u] = *reinterpret_cast<const float4*>(E + i + u * step);
+    for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4*>(E + base + u * 256);
 #pragma unroll
-    for (int u = 0; u < kInFlight; ++u) f(keys_of(v[u]));
+    for (int u = 0; u < 4; ++u) out.g[u] = keys_of(v[u]);
+  } else {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) out.g[u] = load_keys4(E, base + u * 256, n);
   }
-  for (; i < n; i += step) f(load_keys4(E, i, n));
+#pragma unroll
+  for (int u = 0; u < 4; ++u) out.first[u] = base + u * 256;
+  return out;
 }
 
-// A wave visits its contiguous index range [begin, end) in order, 256 indices per step (lane l
-// holds 4 l .. 4 l + 3 of the step); f(keys, first index of the lane) runs on whole waves, so it
-// may ballot.  Loads of kInFlight steps are issued together.
-template <class F>
-__device__ __forceinline__ void walk_wave(const float* __restrict__ E, int64_t begin, int64_t end, int lane, F&& f) {
-  int64_t i0 = begin;
-  for (; i0 + kInFlight * 256 <= end; i0 += kInFlight * 256) {
-    float4 v[kInFlight];
-#pragma unroll
-    for (int u = 0; u < kInFlight; ++u) v[u] = *reinterpret_cast<const float4*>(E + i0 + u * 256 + lane * 4);
-#pragma unroll
-    for (int u = 0; u < kInFlight; ++u) f(keys_of(v[u]), i0 + u * 256 + lane * 4);
-  }
-  for (; i0 < end; i0 += 256) f(load_keys4(E, i0 + lane * 4, end), i0 + lane * 4);
-}
-
-// exclusive prefix of v over the block (thread order); s_wave is [kClsWaves + 1] scratch
+// exclusive prefix of v over the block (thread order); s_wave is [kRankWaves] scratch
 __device__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s_wave) {
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   uint32_t inc = v;
@@ -124,150 +136,193 @@ __device__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s_wave) {
   return base + inc - v;
 }
 
-__global__ __launch_bounds__(kClsThreads) void classify_kernel(const float* __restrict__ E, int64_t n,
-                                                               RankCuts cuts, uint8_t* __restrict__ class_out,
-                                                               uint8_t* __restrict__ byte_out,
-                                                               int32_t* __restrict__ kept_idx) {
-  __shared__ uint32_t hist[kMaxCuts][kBins];
-  __shared__ uint32_t s_wave[kClsWaves + 1];
-  __shared__ uint32_t s_prefix[kMaxCuts];  // key bits fixed so far (right-aligned)
-  __shared__ uint32_t s_rem[kMaxCuts];     // rank of the cut among the keys that share the prefix
-  __shared__ int s_mode[kMaxCuts];         // 0 select, 1 nothing below, 2 everything below
-  __shared__ uint32_t s_tie[kMaxCuts][kClsWaves];
-  __shared__ uint32_t s_kept[kClsWaves];
-
-  const int tid = threadIdx.x;
-  const int lane = tid % kWave, wave = tid / kWave;
-  const int n_cuts = cuts.n_cuts;
-  if (tid < kMaxCuts) {
+__global__ __launch_bounds__(kRankThreads) void rank_zero_kernel(RankState* __restrict__ st, RankCuts cuts,
+                                                                int64_t n) {
+  const int n_words = 3 * kMaxCuts * kBins;
+  for (int i = blockIdx.x * kRankThreads + threadIdx.x; i < n_words; i += gridDim.x * kRankThreads)
+    (&st->hist[0][0][0])[i] = 0u;
+  if (blockIdx.x == 0 && threadIdx.x < kMaxCuts) {
+    const int q = threadIdx.x;
     int mode = 1;
-    uint32_t rem = 0;
-    if (tid < n_cuts) {
-      const int64_t t = cuts.cut_rank[tid];
+    uint32_t rest = 0;
+    if (q < cuts.n_cuts) {
+      const int64_t t = cuts.cut_rank[q];
       mode = t <= 0 ? 1 : (t >= n ? 2 : 0);
-      rem = mode == 0 ? (uint32_t)t : 0u;
+      rest = mode == 0 ? (uint32_t)t : 0u;
     }
-    s_mode[tid] = mode;
-    s_rem[tid] = rem;
-    s_prefix[tid] = 0u;
+    st->mode[q] = mode;
+    st->rest[q] = rest;
+    st->prefix[q] = 0u;
+    if (q < 4) st->ticket[q] = 0u;
+    if (q == 0) st->ties_split = 0u;
   }
-  __syncthreads();
-  bool any_select = false;
-  for (int q = 0; q < n_cuts; ++q) any_select |= s_mode[q] == 0;
+}
 
-  if (any_select) {
-    const int shift_of[3] = {21, 10, 0};
-    const int bits_of[3] = {11, 11, 10};
-#pragma unroll 1
-    for (int pass = 0; pass < 3; ++pass) {
-      const int shift = shift_of[pass];
-      const uint32_t mask = (1u << bits_of[pass]) - 1u;
-      for (int i = tid; i < kMaxCuts * kBins; i += kClsThreads) (&hist[0][0])[i] = 0u;
-      __syncthreads();
-      if (pass == 0) {
-        // no prefix yet: one histogram serves every cut; lanes spread over replicas to
-        // thin out same-address LDS atomics (energies share their top bits)
-        uint32_t* my_hist = hist[lane % kReplicas];
-        sweep_block(E, n, [&](const Keys4& k) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if (k.valid[j]) atomicAdd(&my_hist[k.k[j] >> shift], 1u);
-        });
-        __syncthreads();
-        for (int b = tid; b < kBins; b += kClsThreads) {
-          uint32_t sum = 0;
-#pragma unroll
-          for (int r = 0; r < kReplicas; ++r) sum += hist[r][b];
-          for (int r = 0; r < kReplicas; ++r) hist[r][b] = sum;  // bin b is touched by this thread only
-        }
-        __syncthreads();
-      } else {
-        const int prev_shift = shift + bits_of[pass];
-        uint32_t want[kMaxCuts];
-#pragma unroll
-        for (int q = 0; q < kMaxCuts; ++q) want[q] = (q < n_cuts && s_mode[q] == 0) ? s_prefix[q] : 0xffffffffu;
-        sweep_block(E, n, [&](const Keys4& k) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            if (!k.valid[j]) continue;
-            const uint32_t top = k.k[j] >> prev_shift;  // at most 22 bits: never 0xffffffff
-#pragma unroll
-            for (int q = 0; q < kMaxCuts; ++q)
-              if (top == want[q]) atomicAdd(&hist[q][(k.k[j] >> shift) & mask], 1u);
-          }
-        });
-        __syncthreads();
-      }
-      // locate, for every cut, the bin that holds rank s_rem[q]
-      for (int q = 0; q < n_cuts; ++q) {
-        if (s_mode[q] != 0) continue;  // block-uniform
-        const uint32_t h0 = hist[q][2 * tid], h1 = hist[q][2 * tid + 1];
-        const uint32_t before = block_exclusive_scan(h0 + h1, s_wave);
-        const uint32_t rem = s_rem[q];
-        __syncthreads();
-        if (rem >= before && rem < before + h0) {
-          s_prefix[q] = (s_prefix[q] << bits_of[pass]) | (uint32_t)(2 * tid);
-          s_rem[q] = rem - before;
-        } else if (rem >= before + h0 && rem < before + h0 + h1) {
-          s_prefix[q] = (s_prefix[q] << bits_of[pass]) | (uint32_t)(2 * tid + 1);
-          s_rem[q] = rem - before - h0;
-        }
-        __syncthreads();
-      }
-    }
-  }
-  // s_prefix[q] is now the full key K_q, s_rem[q] the number of keys equal to K_q below the cut.
+// Histogram pass P over the keys that share each cut's prefix, then (last workgroup) the pick.
+template <int P>
+__global__ __launch_bounds__(kRankThreads) void rank_hist_kernel(const float* __restrict__ E, int64_t n, int n_cuts,
+                                                                RankState* __restrict__ st) {
+  constexpr int kShift = P == 0 ? 21 : (P == 1 ? 10 : 0);
+  constexpr int kBits = P == 2 ? 10 : 11;
+  constexpr int kPrevShift = kShift + kBits;
+  constexpr uint32_t kMask = (1u << kBits) - 1u;
+  constexpr int kHists = P == 0 ? 1 : kMaxCuts;  // pass 0 has no prefix yet: one histogram serves every cut
+  __shared__ uint32_t hist[kHists][kBins];
+  __shared__ uint32_t s_wave[kRankWaves];
+  __shared__ uint32_t s_last;
+  const int tid = threadIdx.x;
 
-  // Ordered walk.  Wave w owns indices [w*span, (w+1)*span).
-  const int64_t span = ((n + kClsWaves * 256 - 1) / (kClsWaves * 256)) * 256;
-  const int64_t w_begin = min(n, (int64_t)wave * span);
-  const int64_t w_end = min(n, w_begin + span);
-  const uint64_t lower = (1ull << lane) - 1ull;
-
-  uint32_t K[kMaxCuts], R[kMaxCuts];
-  int mode[kMaxCuts];
-  bool ties_split = false;  // some cut runs through a group of equal keys: their index order matters
+  uint32_t want[kMaxCuts];
+  bool any = false;
 #pragma unroll
   for (int q = 0; q < kMaxCuts; ++q) {
-    K[q] = s_prefix[q];
-    R[q] = s_rem[q];
-    mode[q] = q < n_cuts ? s_mode[q] : 1;
-    ties_split |= mode[q] == 0 && R[q] > 0;
+    const bool on = q < n_cuts && st->mode[q] == 0;
+    want[q] = on ? st->prefix[q] : 0xffffffffu;  // a real prefix has at most 22 bits
+    any |= on;
   }
+  if (!any) return;  // block-uniform: no cut needs a select
+  const int n_hists = P == 0 ? 1 : n_cuts;
+  for (int i = tid; i < n_hists * kBins; i += kRankThreads) (&hist[0][0])[i] = 0u;
+  __syncthreads();
+  const Keys16 keys = load_keys16(E, n);
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (!keys.g[u].valid[j]) continue;
+      const uint32_t k = keys.g[u].k[j];
+      if constexpr (P == 0) {
+        atomicAdd(&hist[0][k >> kShift], 1u);
+      } else {
+        const uint32_t top = k >> kPrevShift;
+#pragma unroll
+        for (int q = 0; q < kMaxCuts; ++q)
+          if (top == want[q]) atomicAdd(&hist[q][(k >> kShift) & kMask], 1u);
+      }
+    }
+  __syncthreads();
+  for (int i = tid; i < n_hists * kBins; i += kRankThreads) {
+    const uint32_t c = (&hist[0][0])[i];
+    if (c) atomicAdd(&st->hist[P][0][0] + i, c);
+  }
+  // last workgroup to get here sees every other workgroup's additions
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) s_last = atomicAdd(&st->ticket[P], 1u) == gridDim.x - 1 ? 1u : 0u;
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  for (int q = 0; q < n_cuts; ++q) {
+    if (want[q] == 0xffffffffu) continue;  // block-uniform
+    const uint32_t* h = st->hist[P][P == 0 ? 0 : q];
+    uint32_t c[kBins / kRankThreads], mine = 0;
+#pragma unroll
+    for (int i = 0; i < kBins / kRankThreads; ++i) {
+      c[i] = h[tid * (kBins / kRankThreads) + i];
+      mine += c[i];
+    }
+    uint32_t before = block_exclusive_scan(mine, s_wave);
+    const uint32_t rest = st->rest[q];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kBins / kRankThreads; ++i) {
+      if (rest >= before && rest < before + c[i]) {
+        st->prefix[q] = (want[q] << kBits) | (uint32_t)(tid * (kBins / kRankThreads) + i);
+        st->rest[q] = rest - before;
+        if (P == 2 && rest - before > 0) st->ties_split = 1u;
+      }
+      before += c[i];
+    }
+    __syncthreads();
+  }
+}
 
-  if (ties_split) {  // equal-key counts per wave, then their exclusive prefix over the waves
-    uint32_t cnt[kMaxCuts];
+// Equal-key counts per workgroup for the cuts that run through a group of equal keys.
+__global__ __launch_bounds__(kRankThreads) void rank_ties_kernel(const float* __restrict__ E, int64_t n, int n_cuts,
+                                                                const RankState* __restrict__ st,
+                                                                uint32_t* __restrict__ tie_cnt /*[kMaxCuts][grid]*/) {
+  if (!st->ties_split) return;  // block-uniform
+  __shared__ uint32_t s_cnt[kMaxCuts];
+  if (threadIdx.x < kMaxCuts) s_cnt[threadIdx.x] = 0u;
+  __syncthreads();
+  const Keys16 keys = load_keys16(E, n);
+  for (int q = 0; q < n_cuts; ++q) {
+    if (st->mode[q] != 0 || st->rest[q] == 0) continue;  // block-uniform
+    const uint32_t K = st->prefix[q];
+    uint32_t c = 0;
 #pragma unroll
-    for (int q = 0; q < kMaxCuts; ++q) cnt[q] = 0;
-    walk_wave(E, w_begin, w_end, lane, [&](const Keys4& k, int64_t) {
+    for (int u = 0; u < 4; ++u)
 #pragma unroll
-      for (int q = 0; q < kMaxCuts; ++q) {
-        if (mode[q] != 0 || R[q] == 0) continue;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) cnt[q] += __popcll(__ballot(k.valid[j] && k.k[j] == K[q]));
-      }
-    });
-    if (lane == 0) {
-#pragma unroll
-      for (int q = 0; q < kMaxCuts; ++q) s_tie[q][wave] = cnt[q];
-    }
-    __syncthreads();
-    if (tid < kMaxCuts) {
-      uint32_t run = 0;
-      for (int w = 0; w < kClsWaves; ++w) {
-        const uint32_t c = s_tie[tid][w];
-        s_tie[tid][w] = run;
-        run += c;
-      }
-    }
-    __syncthreads();
+      for (int j = 0; j < 4; ++j) c += (keys.g[u].valid[j] && keys.g[u].k[j] == K) ? 1u : 0u;
+    if (c) atomicAdd(&s_cnt[q], c);
   }
+  __syncthreads();
+  if (threadIdx.x < kMaxCuts) tie_cnt[threadIdx.x * gridDim.x + blockIdx.x] = s_cnt[threadIdx.x];
+}
+
+// Ordered walk: an element is below cut q iff key < K_q, or key == K_q and fewer than rest_q equal
+// keys precede it (by index).  Writes the class (number of cuts it is below) and the output byte.
+__global__ __launch_bounds__(kRankThreads) void rank_label_kernel(const float* __restrict__ E, int64_t n,
+                                                                 RankCuts cuts, const RankState* __restrict__ st,
+                                                                 const uint32_t* __restrict__ tie_cnt,
+                                                                 uint8_t* __restrict__ class_out,
+                                                                 uint8_t* __restrict__ byte_out,
+                                                                 uint32_t* __restrict__ kept_cnt /*[grid] or NULL*/) {
+  __shared__ uint32_t s_tie[kMaxCuts][kRankWaves];
+  __shared__ uint32_t s_kept[kRankWaves];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const uint64_t lower = (1ull << lane) - 1ull;
+  const bool ties_split = st->ties_split != 0;
+  uint32_t K[kMaxCuts], R[kMaxCuts];
+  int mode[kMaxCuts];
+#pragma unroll
+  for (int q = 0; q < kMaxCuts; ++q) {
+    mode[q] = q < cuts.n_cuts ? st->mode[q] : 1;
+    K[q] = st->prefix[q];
+    R[q] = mode[q] == 0 ? st->rest[q] : 0u;
+  }
+  const Keys16 keys = load_keys16(E, n);
 
   uint32_t tie_base[kMaxCuts];
 #pragma unroll
-  for (int q = 0; q < kMaxCuts; ++q) tie_base[q] = ties_split ? s_tie[q][wave] : 0u;
+  for (int q = 0; q < kMaxCuts; ++q) tie_base[q] = 0u;
+  if (ties_split) {  // block-uniform
+    // equal keys before this wave: earlier workgroups (global counts) + earlier waves of this one
+    uint32_t mine[kMaxCuts];
+#pragma unroll
+    for (int q = 0; q < kMaxCuts; ++q) {
+      mine[q] = 0u;
+      if (mode[q] == 0 && R[q] > 0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            mine[q] += __popcll(__ballot(keys.g[u].valid[j] && keys.g[u].k[j] == K[q]));
+      }
+    }
+    if (lane == 0) {
+#pragma unroll
+      for (int q = 0; q < kMaxCuts; ++q) s_tie[q][wave] = mine[q];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kMaxCuts; ++q) {
+      if (mode[q] == 0 && R[q] > 0) {
+        uint32_t run = 0;
+        for (int b = lane; b < (int)blockIdx.x; b += kWave) run += tie_cnt[q * gridDim.x + b];
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) run += __shfl_xor(run, m);
+        for (int w = 0; w < wave; ++w) run += s_tie[q][w];
+        tie_base[q] = run;
+      }
+    }
+  }
+
   uint32_t kept = 0;
-  walk_wave(E, w_begin, w_end, lane, [&](const Keys4& k, int64_t i) {
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const Keys4& k = keys.g[u];
+    const int64_t i = keys.first[u];
     int below[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int q = 0; q < kMaxCuts; ++q) {
@@ -317,30 +372,64 @@ __global__ __launch_bounds__(kClsThreads) void classify_kernel(const float* __re
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) kept += __popcll(__ballot(k.valid[j] && below[j] == 0));
-  });
-  if (kept_idx == nullptr) return;  // block-uniform
-
+  }
+  if (kept_cnt == nullptr) return;  // block-uniform
   if (lane == 0) s_kept[wave] = kept;
   __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t total = 0;
+    for (int w = 0; w < kRankWaves; ++w) total += s_kept[w];
+    kept_cnt[blockIdx.x] = total;
+  }
+}
+
+// Ascending list of the indices of class 0 (below no cut).
+__global__ __launch_bounds__(kRankThreads) void rank_compact_kernel(const uint8_t* __restrict__ class_in, int64_t n,
+                                                                   const uint32_t* __restrict__ kept_cnt,
+                                                                   int32_t* __restrict__ kept_idx) {
+  __shared__ uint32_t s_kept[kRankWaves];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const uint64_t lower = (1ull << lane) - 1ull;
+  const int64_t base = (int64_t)blockIdx.x * kKeysPerBlock + (int64_t)wave * kKeysPerWave + lane * 4;
+  bool is_kept[4][4];
+  uint32_t mine = 0;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int64_t i = base + u * 256;
+    uint32_t c4 = 0x01010101u;
+    if (i + 3 < n) {
+      c4 = *reinterpret_cast<const uint32_t*>(class_in + i);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (i + j < n) c4 = (c4 & ~(0xffu << (8 * j))) | ((uint32_t)class_in[i + j] << (8 * j));
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      is_kept[u][j] = ((c4 >> (8 * j)) & 0xffu) == 0u;
+      mine += __popcll(__ballot(is_kept[u][j]));
+    }
+  }
+  if (lane == 0) s_kept[wave] = mine;
+  __syncthreads();
   uint32_t pos = 0;
+  for (int b = lane; b < (int)blockIdx.x; b += kWave) pos += kept_cnt[b];
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) pos += __shfl_xor(pos, m);
   for (int w = 0; w < wave; ++w) pos += s_kept[w];
-  // ascending list of the kept indices: re-derive "kept" from the keys instead of re-reading class_out
-  // (same arithmetic as above restricted to "below no cut")
-  for (int64_t i0 = w_begin; i0 < w_end; i0 += 256) {
-    const int64_t i = i0 + lane * 4;
-    bool is_kept[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
     uint32_t lanes_before = 0, total = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      is_kept[j] = i + j < w_end && class_out[i + j] == 0;  // written by this same lane above
-      const uint64_t b = __ballot(is_kept[j]);
+      const uint64_t b = __ballot(is_kept[u][j]);
       lanes_before += __popcll(b & lower);
       total += __popcll(b);
     }
     uint32_t p = pos + lanes_before;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-      if (is_kept[j]) kept_idx[p++] = (int32_t)(i + j);
+      if (is_kept[u][j]) kept_idx[p++] = (int32_t)(base + u * 256 + j);
     pos += total;
   }
 }
@@ -551,8 +640,11 @@ static_assert(kSortThreads == kDigits, "one thread per digit in the scatter prol
 
 }  // namespace
 
+int64_t rank_blocks(int64_t n_micro) { return (n_micro + kKeysPerBlock - 1) / kKeysPerBlock; }
+
 int64_t rank_workspace_words(int64_t n_micro, int want_rank) {
-  int64_t words = n_micro / 4 + 64;  // class bytes
+  const int64_t g = rank_blocks(n_micro);
+  int64_t words = (int64_t)(sizeof(RankState) / 4) + 64 + (kMaxCuts + 1) * g + 64;
   if (want_rank) {
     const int64_t n_blocks = (n_micro + kSortChunk - 1) / kSortChunk;
     words += 4 * (n_micro + 64) + n_blocks * kDigits;
@@ -562,10 +654,22 @@ int64_t rank_workspace_words(int64_t n_micro, int want_rank) {
 
 hipError_t launch_classify(hipStream_t stream, const float* energy, int64_t n_micro, const RankCuts& cuts,
                            uint8_t* class_out, uint8_t* byte_out, int32_t* kept_idx, int32_t* ws) {
-  (void)ws;
   if (n_micro <= 0) return hipSuccess;
-  hipLaunchKernelGGL(classify_kernel, dim3(1), dim3(kClsThreads), 0, stream, energy, n_micro, cuts, class_out,
-                     byte_out, kept_idx);
+  const unsigned g = (unsigned)rank_blocks(n_micro);
+  RankState* st = reinterpret_cast<RankState*>(ws);
+  uint32_t* tie_cnt = reinterpret_cast<uint32_t*>(ws) + sizeof(RankState) / 4 + 64;
+  uint32_t* kept_cnt = tie_cnt + (size_t)kMaxCuts * g;
+  hipLaunchKernelGGL(rank_zero_kernel, dim3(32), dim3(kRankThreads), 0, stream, st, cuts, n_micro);
+  hipLaunchKernelGGL(rank_hist_kernel<0>, dim3(g), dim3(kRankThreads), 0, stream, energy, n_micro, cuts.n_cuts, st);
+  hipLaunchKernelGGL(rank_hist_kernel<1>, dim3(g), dim3(kRankThreads), 0, stream, energy, n_micro, cuts.n_cuts, st);
+  hipLaunchKernelGGL(rank_hist_kernel<2>, dim3(g), dim3(kRankThreads), 0, stream, energy, n_micro, cuts.n_cuts, st);
+  hipLaunchKernelGGL(rank_ties_kernel, dim3(g), dim3(kRankThreads), 0, stream, energy, n_micro, cuts.n_cuts, st,
+                     tie_cnt);
+  hipLaunchKernelGGL(rank_label_kernel, dim3(g), dim3(kRankThreads), 0, stream, energy, n_micro, cuts, st, tie_cnt,
+                     class_out, byte_out, kept_idx ? kept_cnt : nullptr);
+  if (kept_idx)
+    hipLaunchKernelGGL(rank_compact_kernel, dim3(g), dim3(kRankThreads), 0, stream, class_out, n_micro, kept_cnt,
+                       kept_idx);
   return hipGetLastError();
 }
 
@@ -581,6 +685,7 @@ hipError_t launch_full_rank(hipStream_t stream, const float* energy, int64_t n_m
                             int32_t* ws) {
   if (n_micro <= 0) return hipSuccess;
   const int64_t padded = n_micro + 64;
+  ws += rank_workspace_words(n_micro, 0);  // behind the select state
   uint32_t* keys_a = reinterpret_cast<uint32_t*>(ws);
   uint32_t* keys_b = keys_a + padded;
   uint32_t* idx_a = keys_b + padded;
