@@ -2,13 +2,14 @@
 // (Algorithm 1, line 2; the weights A_i(x) of Eq. 2).
 //
 // Logits L[j, e] = <x_j, R_e> (+ bias_e) are accumulated in float32: for bf16 on
-// v_mfma_f32_32x32x16_bf16 (one wave = 32 tokens x all experts, fragments read
-// straight from global memory -- R is small and stays in L2), for float32 with
-// FMA and a wave reduction.  The logits of a block's tokens go through LDS so
-// that one lane can walk all experts of one token: top_k rounds of "largest
-// remaining logit, lower index on ties".  Selection is on the logits (softmax is
-// increasing, so this is the top-k of the probabilities); the kept weights are
-// exp(L - max) over the softmax denominator, renormalised over the kept ones.
+// v_mfma_f32_32x32x16_bf16 (a block = 32 tokens x all experts, its four waves
+// split d_model, fragments read straight from global memory -- R is small and
+// stays in L2), for float32 with FMA and a wave reduction.  The logits of a
+// block's tokens go through LDS so that eight lanes can walk the experts of
+// one token: top_k rounds of "largest remaining logit, lower index on ties".
+// Selection is on the logits (softmax is increasing, so this is the top-k of
+// the probabilities); the kept weights are exp(L - max) over the softmax
+// denominator, renormalised over the kept ones.
 #include <hip/hip_bf16.h>
 
 #include "camera_internal.h"
@@ -21,50 +22,74 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int kTokens = 32;  // tokens per block
+constexpr int kSub = 8;      // lanes that share one token in the top-k stage
 
-// One lane, one token: logits of the token are s_row[0 .. n_experts).
-__device__ void topk_of_token(const float* s_row, int n_experts, int top_k, int renorm, int32_t* idx_out,
-                              float* w_out) {
+// Top-k of one token by kSub consecutive lanes: lane `sub` scans experts sub, sub + kSub, ...; each
+// round takes the largest logit not yet taken (ties: lower index) and the lanes agree on it with
+// three xor-shuffles.  s_row[0 .. n_experts) are the token's logits.
+__device__ void topk_of_token(const float* s_row, int n_experts, int top_k, int renorm, int sub,
+                              int32_t* idx_out, float* w_out) {
   float row_max = -INFINITY;
-  for (int e = 0; e < n_experts; ++e) row_max = fmaxf(row_max, s_row[e]);
+  for (int e = sub; e < n_experts; e += kSub) row_max = fmaxf(row_max, s_row[e]);
+#pragma unroll
+  for (int m = kSub / 2; m >= 1; m >>= 1) row_max = fmaxf(row_max, __shfl_xor(row_max, m));
   float denom = 0.0f;
-  if (!renorm)
-    for (int e = 0; e < n_experts; ++e) denom += __expf(s_row[e] - row_max);
+  if (!renorm) {
+    for (int e = sub; e < n_experts; e += kSub) denom += __expf(s_row[e] - row_max);
+#pragma unroll
+    for (int m = kSub / 2; m >= 1; m >>= 1) denom += __shfl_xor(denom, m);
+  }
   float prev_v = INFINITY;
   int prev_i = -1;
   float kept_sum = 0.0f;
   for (int r = 0; r < top_k; ++r) {
     float best_v = -INFINITY;
-    int best_i = -1;
-    for (int e = 0; e < n_experts; ++e) {
+    int best_i = 0x7fffffff;
+    for (int e = sub; e < n_experts; e += kSub) {
       const float v = s_row[e];
-      const bool after_prev = v < prev_v || (v == prev_v && e > prev_i);  // not yet taken
-      if (after_prev && (best_i < 0 || v > best_v)) {  // strict >: lower index wins ties
+      const bool not_taken = v < prev_v || (v == prev_v && e > prev_i);
+      if (not_taken && (v > best_v || (v == best_v && e < best_i))) {
         best_v = v;
         best_i = e;
       }
     }
+#pragma unroll
+    for (int m = kSub / 2; m >= 1; m >>= 1) {
+      const float ov = __shfl_xor(best_v, m);
+      const int oi = __shfl_xor(best_i, m);
+      if (ov > best_v || (ov == best_v && oi < best_i)) {
+        best_v = ov;
+        best_i = oi;
+      }
+    }
     const float p = __expf(best_v - row_max);
-    idx_out[r] = best_i;
-    w_out[r] = p;
+    if (sub == 0) {
+      idx_out[r] = best_i;
+      w_out[r] = p;
+    }
     kept_sum += p;
     prev_v = best_v;
     prev_i = best_i;
   }
-  const float inv = 1.0f / (renorm ? kept_sum : denom);
-  for (int r = 0; r < top_k; ++r) w_out[r] *= inv;
+  if (sub == 0) {
+    const float inv = 1.0f / (renorm ? kept_sum : denom);
+    for (int r = 0; r < top_k; ++r) w_out[r] *= inv;
+  }
 }
 
-// bf16: one wave per block, 32 tokens, NT tiles of 32 experts.
+// bf16: 32 tokens per block, NT tiles of 32 experts; the four waves split d_model between them
+// (a lone wave per 32 tokens leaves the chip idle and waits for every load in turn) and keep
+// kUnroll K steps of loads in flight; partial logits are added through LDS in wave order.
 template <int NT>
-__global__ __launch_bounds__(kWave) void route_bf16_kernel(const __hip_bfloat16* __restrict__ X, int64_t n,
-                                                           int d_model, int64_t ldx,
-                                                           const __hip_bfloat16* __restrict__ R, int64_t ldr,
-                                                           const float* __restrict__ bias, int n_experts,
-                                                           int top_k, int renorm, int32_t* __restrict__ topk_idx,
-                                                           float* __restrict__ topk_w) {
+__global__ __launch_bounds__(256) void route_bf16_kernel(const __hip_bfloat16* __restrict__ X, int64_t n,
+                                                         int d_model, int64_t ldx,
+                                                         const __hip_bfloat16* __restrict__ R, int64_t ldr,
+                                                         const float* __restrict__ bias, int n_experts,
+                                                         int top_k, int renorm, int32_t* __restrict__ topk_idx,
+                                                         float* __restrict__ topk_w) {
+  constexpr int kUnroll = NT <= 2 ? 8 : (NT == 4 ? 4 : 2);
   __shared__ float s_logit[kTokens][NT * 32 + 1];
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int frag_row = lane % 32, frag_half = lane / 32;
   const int64_t tok0 = (int64_t)blockIdx.x * kTokens;
   const int64_t tok = tok0 + frag_row;
@@ -81,29 +106,49 @@ __global__ __launch_bounds__(kWave) void route_bf16_kernel(const __hip_bfloat16*
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
 
+  // this wave's share of the K steps (16 elements each)
+  const int n_steps = (d_model + 15) / 16;
+  const int per_wave = (n_steps + 3) / 4;
+  const int k_begin = wave * per_wave * 16;
+  const int k_end = min(d_model, (wave + 1) * per_wave * 16);
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
-  for (int k0 = 0; k0 < d_model; k0 += 16) {
-    const bool k_ok = k0 + frag_half * 8 < d_model;  // d_model is a multiple of 8
-    u32x4 av = (x_src && k_ok) ? *reinterpret_cast<const u32x4*>(x_src + k0) : zero4;
-    const bf16x8 fa = __builtin_bit_cast(bf16x8, av);
+  for (int k0 = k_begin; k0 < k_end; k0 += 16 * kUnroll) {
+    u32x4 av[kUnroll], bv[kUnroll][NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      u32x4 bv = (r_src[t] && k_ok) ? *reinterpret_cast<const u32x4*>(r_src[t] + k0) : zero4;
-      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, __builtin_bit_cast(bf16x8, bv), acc[t], 0, 0, 0);
+    for (int u = 0; u < kUnroll; ++u) {
+      const int k = k0 + 16 * u;
+      const bool k_ok = k + frag_half * 8 < k_end;  // d_model and the wave shares are multiples of 8
+      av[u] = (x_src && k_ok) ? *reinterpret_cast<const u32x4*>(x_src + k) : zero4;
+#pragma unroll
+      for (int t = 0; t < NT; ++t) bv[u][t] = (r_src[t] && k_ok) ? *reinterpret_cast<const u32x4*>(r_src[t] + k) : zero4;
     }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[u]),
+                                                          __builtin_bit_cast(bf16x8, bv[u][t]), acc[t], 0, 0, 0);
   }
   // accumulator register r of lane l: token row 8*(r/4) + 4*(l/32) + (r%4), expert column l % 32
+  for (int w = 0; w < 4; ++w) {  // fixed order: wave 0 stores (with the bias), waves 1..3 add
+    if (wave == w) {
 #pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    const int e = t * 32 + frag_row;
-    const float b = (bias && e < n_experts) ? bias[e] : 0.0f;
+      for (int t = 0; t < NT; ++t) {
+        const int e = t * 32 + frag_row;
+        const float b = (w == 0 && bias && e < n_experts) ? bias[e] : 0.0f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s_logit[(r / 4) * 8 + frag_half * 4 + (r % 4)][e] = acc[t][r] + b;
+        for (int r = 0; r < 16; ++r) {
+          float* dst = &s_logit[(r / 4) * 8 + frag_half * 4 + (r % 4)][e];
+          *dst = (w == 0 ? 0.0f : *dst) + acc[t][r] + b;
+        }
+      }
+    }
+    __syncthreads();
   }
-  __syncthreads();
-  if (lane < kTokens && tok0 + lane < n)
-    topk_of_token(s_logit[lane], n_experts, top_k, renorm, topk_idx + (tok0 + lane) * top_k,
-                  topk_w + (tok0 + lane) * top_k);
+  const int t_local = threadIdx.x / kSub, sub = threadIdx.x % kSub;  // 256 threads = 32 tokens x 8 lanes
+  if (tok0 + t_local < n)
+    topk_of_token(s_logit[t_local], n_experts, top_k, renorm, sub, topk_idx + (tok0 + t_local) * top_k,
+                  topk_w + (tok0 + t_local) * top_k);
 }
 
 // float32: four waves per block, 32 tokens, each wave 8 tokens; lanes stride over d_model.
@@ -136,16 +181,17 @@ __global__ __launch_bounds__(256) void route_f32_kernel(const float* __restrict_
     }
   }
   __syncthreads();
-  if (threadIdx.x < kTokens && tok0 + threadIdx.x < n)
-    topk_of_token(s_logit[threadIdx.x], n_experts, top_k, renorm, topk_idx + (tok0 + threadIdx.x) * top_k,
-                  topk_w + (tok0 + threadIdx.x) * top_k);
+  const int t_local = threadIdx.x / kSub, sub = threadIdx.x % kSub;  // 256 threads = 32 tokens x 8 lanes
+  if (tok0 + t_local < n)
+    topk_of_token(s_logit[t_local], n_experts, top_k, renorm, sub, topk_idx + (tok0 + t_local) * top_k,
+                  topk_w + (tok0 + t_local) * top_k);
 }
 
 template <int NT>
 void launch_bf16(hipStream_t stream, int64_t n_blocks, const void* X, int64_t n, int64_t d_model, int64_t ldx,
                  const void* W_r, int64_t ldr, const float* bias, int n_experts, int top_k, int renorm,
                  int32_t* topk_idx, float* topk_w) {
-  hipLaunchKernelGGL(route_bf16_kernel<NT>, dim3((unsigned)n_blocks), dim3(kWave), 0, stream,
+  hipLaunchKernelGGL(route_bf16_kernel<NT>, dim3((unsigned)n_blocks), dim3(256), 0, stream,
                      static_cast<const __hip_bfloat16*>(X), n, (int)d_model, ldx,
                      static_cast<const __hip_bfloat16*>(W_r), ldr, bias, n_experts, top_k, renorm, topk_idx,
                      topk_w);
