@@ -87,6 +87,7 @@ struct GemmCfg {
   static_assert(kADma >= 1 && kBDma >= 1 && BM % (kWaves * kDmaRows) == 0 && BN % (kWaves * kDmaRows) == 0,
                 "every wave fills whole 1 KiB groups");
   static_assert(kSmemBytes <= 160 * 1024, "LDS per workgroup");
+  static_assert(kADma <= 4 && kBDma <= 4, "immediate offsets 1024 j must stay below 4096");
 };
 
 // LDS image of a tile: row r is kRowBytes long; its 16-byte chunk c sits at chunk position
@@ -131,26 +132,43 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
   // i.e. chunk position l % kChunks of row l / kChunks of its row group; to produce the swizzled
   // image it reads logical chunk (l % kChunks) ^ swizzle_key(row) of that row (set up by the caller).
   // TAIL (d_model not a multiple of KT): chunks past d_model come from a page of zeros.
-  auto dma = [&](const __hip_bfloat16* src, int k, int k0, unsigned char* dst) {
-    const __hip_bfloat16* p = src + k0;
-    if constexpr (TAIL) p = (k0 + k < st.d_model) ? p : st.zeros;
+  // The instruction's immediate offset is added to the global and to the LDS address alike, so the
+  // j-th group of a wave uses immediate 1024 j on sources that were moved back by 1024 j bytes at
+  // set-up: one LDS base (M0) per matrix and tile instead of one per instruction.
+  auto dma = [&](const __hip_bfloat16* src, int k, int k0, unsigned char* dst, auto group) {
+    constexpr int kOff = decltype(group)::value * 1024;
+    const unsigned char* p = reinterpret_cast<const unsigned char*>(src + k0);
+    if constexpr (TAIL) p = (k0 + k < st.d_model) ? p : reinterpret_cast<const unsigned char*>(st.zeros) - kOff;
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
-                                     (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+                                     (__attribute__((address_space(3))) void*)dst, 16, kOff, 0);
+  };
+  auto dma_a = [&](int k0, unsigned char* sA, auto group) {
+    constexpr int j = decltype(group)::value;
+    if constexpr (j < C::kADma) dma(st.a_src[j], st.a_k[j], k0, sA, group);
+  };
+  auto dma_b = [&](int k0, unsigned char* sG, unsigned char* sU, auto group) {
+    constexpr int j = decltype(group)::value;
+    if constexpr (j < C::kBDma) {
+      dma(st.g_src[j], st.b_k[j], k0, sG, group);
+      dma(st.u_src[j], st.b_k[j], k0, sU, group);
+    }
   };
   // the loads of one tile in two halves, so that they can be issued apart
   auto dma_tile = [&](int stage, int k0, int half) {
     unsigned char* sA = smem + stage * C::kStageBytes + st.a_lds;
     unsigned char* sG = smem + stage * C::kStageBytes + C::kATileBytes + st.b_lds;
     unsigned char* sU = sG + C::kBTileBytes;
+    using std::integral_constant;
     if (half == 0) {
-#pragma unroll
-      for (int j = 0; j < C::kADma; ++j) dma(st.a_src[j], st.a_k[j], k0, sA + j * 1024);
+      dma_a(k0, sA, integral_constant<int, 0>{});
+      dma_a(k0, sA, integral_constant<int, 1>{});
+      dma_a(k0, sA, integral_constant<int, 2>{});
+      dma_a(k0, sA, integral_constant<int, 3>{});
     } else {
-#pragma unroll
-      for (int j = 0; j < C::kBDma; ++j) {
-        dma(st.g_src[j], st.b_k[j], k0, sG + j * 1024);
-        dma(st.u_src[j], st.b_k[j], k0, sU + j * 1024);
-      }
+      dma_b(k0, sG, sU, integral_constant<int, 0>{});
+      dma_b(k0, sG, sU, integral_constant<int, 1>{});
+      dma_b(k0, sG, sU, integral_constant<int, 2>{});
+      dma_b(k0, sG, sU, integral_constant<int, 3>{});
     }
   };
 
@@ -333,7 +351,7 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
     const int row = a_row0 + j * C::kDmaRows + lane / C::kChunks;
     const int ck = (lane % C::kChunks) ^ swizzle_key<C>(row);
     st.a_k[j] = ck * 8;
-    st.a_src[j] = X + (int64_t)s_tok[row] * ldx + ck * 8;
+    st.a_src[j] = X + (int64_t)s_tok[row] * ldx + ck * 8 - j * 512;  // immediate offset 1024 j bytes comes back
   }
 #pragma unroll
   for (int j = 0; j < C::kBDma; ++j) {
@@ -342,8 +360,8 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
     const int c = min(n0 + row, d_ff - 1);  // channels past d_ff read the last channel again; never written
     const int64_t off = (int64_t)e * stride_gu + (int64_t)c * d_model + ck * 8;
     st.b_k[j] = ck * 8;
-    st.g_src[j] = Wg + off;
-    st.u_src[j] = Wu + off;
+    st.g_src[j] = Wg + off - j * 512;
+    st.u_src[j] = Wu + off - j * 512;
   }
   // Fragments: lane l holds tile row (l % 32), K elements 8*(l / 32) .. +7 of a 16-wide K step.
   // swizzle_key(row) only depends on row % 32 here (32-row blocks), so one key per lane.
