@@ -33,9 +33,9 @@ DECISIONS = {
                                            ([4, 3, 2], [0.0, 0.0, 1.0])]),
 }
 
-# HBM bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/);
-# None until measured for a workload.
-PMC_TRAFFIC_BYTES = {}
+# HBM-side bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by what the same
+# counters read for a plain 1 GiB copy (profiles/grouped_gemm_bf16_qwen2-57b-a14b_hbm_traffic.txt); None where not measured.
+PMC_TRAFFIC_BYTES = {"qwen2-57b-a14b": 4.671e9}
 
 
 def parse_args():
