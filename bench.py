@@ -45,6 +45,11 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="qwen2-57b-a14b", choices=sorted(DECISIONS))
     ap.add_argument("--layers", type=int, default=0, help="debug: only this many layers (the result is then not the named workload)")
+    ap.add_argument("--calib-tokens", type=int, default=0,
+                    help="calibration tokens per layer (default: the configuration's own); more than that are fed "
+                         "in chunks of the configuration's size through CAMERA_ACCUMULATE (the paper calibrates on "
+                         "128 x 2048 = 262144 tokens)")
+    ap.add_argument("--chunk-tokens", type=int, default=0, help="chunk size for --calib-tokens (default: the configuration's token count)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -52,9 +57,11 @@ def parse_args():
 class LayerRunner:
     """Owns the resident tensors of one layer and its preallocated outputs."""
 
-    def __init__(self, cam, cfg, layer_idx, torch, inputs):
+    def __init__(self, cam, cfg, layer_idx, torch, inputs, calib_tokens, chunk_tokens):
         self.cfg = cfg
-        self.t = inputs.make_layer(cfg, layer_idx, device="cuda")
+        gen_cfg = cfg if calib_tokens == cfg.n_tokens else inputs.scaled(cfg, n_tokens=calib_tokens)
+        self.t = inputs.make_layer(gen_cfg, layer_idx, device="cuda")
+        self.chunks = [(lo, min(calib_tokens, lo + chunk_tokens)) for lo in range(0, calib_tokens, chunk_tokens)]
         n_micro = cfg.n_micro
         self.out = {k: torch.empty(n_micro, dtype=torch.float32, device="cuda")
                     for k in ("phi2", "phi_inf", "omega2", "energy")}
@@ -63,12 +70,17 @@ class LayerRunner:
         self.out_shared = {k: v[nr:] for k, v in self.out.items()}
         self.seg = inputs.segment_offsets(cfg)
 
-    def run(self, cam, decisions):
+    def run(self, cam, decisions, binding):
         cfg, t = self.cfg, self.t
-        idx, w = cam.route_topk(t["X"], t["W_r"], t["bias"], cfg.top_k)
-        cam.score_layer(t["X"], idx, w, t["W_gate"], t["W_up"], t["W_down"], cfg.alpha, out=self.out_routed)
-        if cfg.n_shared:
-            cam.score_layer(t["X"], None, None, t["Ws_gate"], t["Ws_up"], t["Ws_down"], cfg.alpha, out=self.out_shared)
+        last = len(self.chunks) - 1
+        for c, (lo, hi) in enumerate(self.chunks):
+            X = t["X"][lo:hi]
+            flags = (binding.ACCUMULATE if c > 0 else 0) | (binding.NO_FINALIZE if c < last else 0)
+            idx, w = cam.route_topk(X, t["W_r"], t["bias"], cfg.top_k)
+            cam.score_layer(X, idx, w, t["W_gate"], t["W_up"], t["W_down"], cfg.alpha, flags=flags, out=self.out_routed)
+            if cfg.n_shared:
+                cam.score_layer(X, None, None, t["Ws_gate"], t["Ws_up"], t["Ws_down"], cfg.alpha, flags=flags,
+                                out=self.out_shared)
         res = []
         for ratio in decisions["prune"]:
             res.append(cam.select_prune(self.out["energy"], self.seg, ratio))
@@ -141,13 +153,15 @@ def main():
     cam = binding.Camera(device=0)
 
     t_gen = time.perf_counter()
-    layers = [LayerRunner(cam, cfg, i, torch, inputs) for i in range(n_layers)]
+    calib_tokens = args.calib_tokens if args.calib_tokens > 0 else cfg.n_tokens
+    chunk_tokens = args.chunk_tokens if args.chunk_tokens > 0 else cfg.n_tokens
+    layers = [LayerRunner(cam, cfg, i, torch, inputs, calib_tokens, chunk_tokens) for i in range(n_layers)]
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
     def step():
         for lr in layers:
-            lr.run(cam, decisions)
+            lr.run(cam, decisions, binding)
 
     for _ in range(args.warmup):
         step()
@@ -167,7 +181,7 @@ def main():
         ms, count = cam.profile_read(k)
         kernel_ms[name] = {"ms_total": round(ms, 3), "launches": count}
     gemm = kernel_ms["gemm"]
-    flops_per_step = cfg.gemm_flops_per_layer() * n_layers
+    flops_per_step = cfg.gemm_flops_per_layer() * n_layers * (calib_tokens / cfg.n_tokens)
     gemm_launches_per_step = gemm["launches"] / max(1, args.steps)
     flops_per_launch = flops_per_step / max(1.0, gemm_launches_per_step)
     avg_launch_s = gemm["ms_total"] / max(1, gemm["launches"]) * 1e-3
@@ -180,14 +194,15 @@ def main():
                 "flops_per_launch": flops_per_launch, "avg_launch_ms": round(avg_launch_s * 1e3, 4)}
 
     ms_per_step = elapsed / args.steps * 1e3
-    value = cfg.n_tokens * n_layers * args.steps / elapsed
+    value = calib_tokens * n_layers * args.steps / elapsed
     result = {
         "metric": "calibration tokens x layers scored/sec; MFMA util % of bf16 peak",
         "value": round(value, 1), "unit": "tokens*layers/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": cfg.name + ("" if n_layers == cfg.n_layers else f"[first {n_layers} layers only]"),
-                   "layers": n_layers, "tokens": cfg.n_tokens, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
+        "config": {"workload": cfg.name + ("" if n_layers == cfg.n_layers else f"[first {n_layers} layers only]")
+                   + ("" if calib_tokens == cfg.n_tokens else f"[{calib_tokens} calibration tokens in chunks of {chunk_tokens}]"),
+                   "layers": n_layers, "tokens": calib_tokens, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
                    "experts": cfg.n_experts, "top_k": cfg.top_k, "shared_experts": cfg.n_shared,
                    "d_ff_shared": cfg.d_ff_shared, "alpha": cfg.alpha, "decisions": decisions,
                    "full_analysis_seconds": round(ms_per_step * 1e-3, 4), "input_generation_s": round(t_gen, 1)},
