@@ -437,7 +437,7 @@ __global__ __launch_bounds__(kRankThreads) void rank_compact_kernel(const uint8_
 // ---------------------------------------------------------------------------
 // per-segment class sizes and stable partition
 // ---------------------------------------------------------------------------
-constexpr int kSegThreads = 256;
+constexpr int kSegThreads = 1024;  // a shared expert can be a 20 480-element segment: 16 waves walk it
 constexpr int kSegWaves = kSegThreads / kWave;
 
 __global__ __launch_bounds__(kSegThreads) void segment_kernel(const uint8_t* __restrict__ class_in, SegTable seg,
