@@ -55,9 +55,19 @@ __device__ __forceinline__ float silu_f32(float g) {
 //   the last 16-wide K step so that the first fragments of the next tile are in
 //   flight while that step's MFMAs run.
 // ---------------------------------------------------------------------------
+// f(integral_constant<int, LO>), ..., f(integral_constant<int, HI - 1>)
+template <int LO, int HI, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (LO < HI) {
+    f(std::integral_constant<int, LO>{});
+    static_for<LO + 1, HI>(f);
+  }
+}
+
 constexpr int kXcds = 8;    // accelerator dies, each with a private L2
-constexpr int kPatchM = 4;  // M-tile slots per patch
-constexpr int kPatchN = 8;  // N-tiles per patch
+constexpr int kPatch = 32;     // workgroups an XCD runs at a time (one per CU)
+constexpr int kChunkMax = 6;   // an expert with up to this many M-tiles runs them all side by side
+constexpr int kChunkM = 4;     // otherwise this many
 
 template <int WM_, int WN_, int TM_, int TN_, int KT_, int STAGES_>
 struct GemmCfg {
@@ -82,6 +92,23 @@ struct GemmCfg {
   // workgroups that fit one CU by LDS (160 KiB), hence waves per SIMD the registers must allow
   static constexpr int kBlocksPerCu = (160 * 1024) / kSmemBytes >= 2 ? 2 : 1;
   static constexpr int kWavesPerSimd = kBlocksPerCu * kWaves / 4 > 0 ? kBlocksPerCu * kWaves / 4 : 1;
+  // Issue slots: a K step is two slots, slot 0 is the first one behind the barrier.  The loads of
+  // a tile are dealt evenly over the first half of the slots (extra ones in the middle); the second
+  // half stays empty, which is the time the youngest load has to land before the next barrier.
+  static constexpr int kSlots = 2 * kSteps;
+  static constexpr int kBusySlots = kSlots >= 2 ? kSlots / 2 : 1;
+  static constexpr int issue_count(int p) {
+    if (p < 0 || p >= kBusySlots) return 0;
+    const int base = kLoadsPerTile / kBusySlots, extra = kLoadsPerTile % kBusySlots;
+    const int first_extra = (kBusySlots - extra) / 2;
+    return base + ((p >= first_extra && p < first_extra + extra) ? 1 : 0);
+  }
+  static constexpr int issue_begin(int p) {  // loads issued by the slots before p
+    int n = 0;
+    for (int q = 0; q < p; ++q) n += issue_count(q);
+    return n;
+  }
+  static_assert(issue_begin(kSlots) == kLoadsPerTile, "every load has a slot");
   static_assert(KT == 32 || KT == 64, "K tile");
   static_assert(kStages >= 2, "at least the stage being read and the stage being filled");
   static_assert(kADma >= 1 && kBDma >= 1 && BM % (kWaves * kDmaRows) == 0 && BN % (kWaves * kDmaRows) == 0,
@@ -142,34 +169,26 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
                                      (__attribute__((address_space(3))) void*)dst, 16, kOff, 0);
   };
-  auto dma_a = [&](int k0, unsigned char* sA, auto group) {
-    constexpr int j = decltype(group)::value;
-    if constexpr (j < C::kADma) dma(st.a_src[j], st.a_k[j], k0, sA, group);
-  };
-  auto dma_b = [&](int k0, unsigned char* sG, unsigned char* sU, auto group) {
-    constexpr int j = decltype(group)::value;
-    if constexpr (j < C::kBDma) {
-      dma(st.g_src[j], st.b_k[j], k0, sG, group);
-      dma(st.u_src[j], st.b_k[j], k0, sU, group);
-    }
-  };
-  // the loads of one tile in two halves, so that they can be issued apart
-  auto dma_tile = [&](int stage, int k0, int half) {
+  // Load d of a tile's kLoadsPerTile wave instructions: the token groups first, then the gate
+  // groups, then the up groups (loads that share an LDS base follow each other).
+  auto dma_one = [&](int stage, int k0, auto index) {
+    constexpr int d = decltype(index)::value;
+    using std::integral_constant;
     unsigned char* sA = smem + stage * C::kStageBytes + st.a_lds;
     unsigned char* sG = smem + stage * C::kStageBytes + C::kATileBytes + st.b_lds;
-    unsigned char* sU = sG + C::kBTileBytes;
-    using std::integral_constant;
-    if (half == 0) {
-      dma_a(k0, sA, integral_constant<int, 0>{});
-      dma_a(k0, sA, integral_constant<int, 1>{});
-      dma_a(k0, sA, integral_constant<int, 2>{});
-      dma_a(k0, sA, integral_constant<int, 3>{});
+    if constexpr (d < C::kADma) {
+      dma(st.a_src[d], st.a_k[d], k0, sA, integral_constant<int, d>{});
+    } else if constexpr (d < C::kADma + C::kBDma) {
+      dma(st.g_src[d - C::kADma], st.b_k[d - C::kADma], k0, sG, integral_constant<int, d - C::kADma>{});
     } else {
-      dma_b(k0, sG, sU, integral_constant<int, 0>{});
-      dma_b(k0, sG, sU, integral_constant<int, 1>{});
-      dma_b(k0, sG, sU, integral_constant<int, 2>{});
-      dma_b(k0, sG, sU, integral_constant<int, 3>{});
+      constexpr int j = d - C::kADma - C::kBDma;
+      dma(st.u_src[j], st.b_k[j], k0, sG + C::kBTileBytes, integral_constant<int, j>{});
     }
+  };
+  // loads [C::issue_begin(P), C::issue_begin(P + 1)) of a tile: the share of issue slot P
+  auto dma_slot = [&](int stage, int k0, auto slot_index) {
+    constexpr int P = decltype(slot_index)::value;
+    static_for<C::issue_begin(P), C::issue_begin(P + 1)>([&](auto d) { dma_one(stage, k0, d); });
   };
 
   f32x16 acc_g[NA][TN], acc_u[NA][TN];
@@ -201,50 +220,66 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
       }
     }
   };
-  auto mfma_step = [&](const Frags& f) {
-#pragma unroll
-    for (int i = 0; i < ACT; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
+  // MFMAs [LO, HI) of one K step, numbered (row block i, channel block j, gate / up)
+  auto mfma_range = [&](const Frags& f, auto lo, auto hi) {
+    static_for<decltype(lo)::value, decltype(hi)::value>([&](auto m) {
+      constexpr int i = decltype(m)::value / (2 * TN), j = (decltype(m)::value / 2) % TN;
+      if constexpr (decltype(m)::value % 2 == 0)
         acc_g[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.g[j], acc_g[i][j], 0, 0, 0);
+      else
         acc_u[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.u[j], acc_u[i][j], 0, 0, 0);
-      }
+    });
   };
 
   // Ring schedule.  kStages tiles are in LDS or on their way; the barrier of iteration kt says that
-  // tile kt + 1 has landed and that nobody reads tile kt's stage any more, so the loads of tile
-  // kt + kStages go into that stage right behind the barrier and have kStages - 1 K tiles of MFMA
-  // time to arrive.  Tiles past the end are clamped to the last one (kStages redundant tile loads
-  // per workgroup) so that the loop body and the outstanding-load count never change.
+  // tile kt + 1 has landed and that nobody reads tile kt's stage any more, so tile kt + kStages goes
+  // into that stage.  Its loads are not issued in one go: a K step is two issue slots (half of the
+  // step's MFMAs each), the barrier sits before the last K step, and slot P counted from the barrier
+  // issues its share C::issue_begin(P) .. of the loads behind its MFMAs.  The order is pinned with
+  // scheduling barriers.  Back-to-back loads fill the wave's vector-memory queue and stall its
+  // MFMAs behind them; one or two at a time between groups of four MFMAs cost next to nothing.
+  // The last slots before the barrier stay empty, which is the time the youngest load has to land.
+  // Tiles past the end are clamped to the last one (redundant loads, never read) so that the loop
+  // body and the outstanding-load count never change.
   const int n_k = (st.d_model + KT - 1) / KT;
   const int k_last = (n_k - 1) * KT;
   constexpr int kMayFly = (C::kStages - 2) * C::kLoadsPerTile;  // loads younger than tile kt + 1
+  constexpr int kHalf = ACT * TN, kFull = 2 * ACT * TN;         // MFMAs of half a K step, of a K step
+  using std::integral_constant;
   Frags f[2];
 #pragma unroll
-  for (int t = 0; t < C::kStages; ++t) {
-    dma_tile(t, min(t * KT, k_last), 0);
-    dma_tile(t, min(t * KT, k_last), 1);
-  }
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly + C::kLoadsPerTile) : "memory");  // tile 0 (loads return in order)
+  for (int t = 0; t + 1 < C::kStages; ++t)
+    static_for<0, C::kLoadsPerTile>([&](auto d) { dma_one(t, min(t * KT, k_last), d); });
+  // the tile whose loads are under way: slots 0 and 1 here, the rest in the first iteration
+  int fill_stage = C::kStages - 1, fill_k = min((C::kStages - 1) * KT, k_last);
+  dma_slot(fill_stage, fill_k, integral_constant<int, 0>{});
+  dma_slot(fill_stage, fill_k, integral_constant<int, 1>{});
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly + C::issue_begin(2)) : "memory");  // tile 0 (loads return in order)
   __syncthreads();
   read_frags(f[0], 0, 0);
   int stage = 0;  // stage of tile kt
   for (int kt = 0; kt < n_k; ++kt) {
     const int next = stage + 1 == C::kStages ? 0 : stage + 1;
-#pragma unroll
-    for (int ks = 0; ks < C::kSteps; ++ks) {
-      if (ks + 1 < C::kSteps) {
+    static_for<0, C::kSteps>([&](auto step) {
+      constexpr int ks = decltype(step)::value;
+      constexpr bool last = ks + 1 == C::kSteps;
+      constexpr int P = last ? 0 : 2 * ks + 2;  // issue slot of this step's first half
+      if constexpr (!last) {
         read_frags(f[(ks + 1) & 1], stage, ks + 1);
       } else {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly) : "memory");
         __syncthreads();
-        const int k_fill = min((kt + C::kStages) * KT, k_last);
-        dma_tile(stage, k_fill, 0);
-        dma_tile(stage, k_fill, 1);
+        fill_stage = stage;
+        fill_k = min((kt + C::kStages) * KT, k_last);
         read_frags(f[(ks + 1) & 1], next, 0);
       }
-      mfma_step(f[ks & 1]);
-    }
+      mfma_range(f[ks & 1], integral_constant<int, 0>{}, integral_constant<int, kHalf>{});
+      dma_slot(fill_stage, fill_k, integral_constant<int, P>{});
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_range(f[ks & 1], integral_constant<int, kHalf>{}, integral_constant<int, kFull>{});
+      dma_slot(fill_stage, fill_k, integral_constant<int, P + 1>{});
+      __builtin_amdgcn_sched_barrier(0);
+    });
     stage = next;
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS at exit
@@ -299,18 +334,33 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
     float* __restrict__ part_max) {
   constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN, WM = C::WM;
   // Workgroup -> tile mapping.  The hardware deals consecutive workgroup ids round-robin to the 8
-  // XCDs, each with its own L2.  Give every XCD a contiguous run of logical ids, and order logical
-  // ids in patches of kPatchM M-tile slots x kPatchN N-tiles (= the 32 workgroups an XCD runs at a
-  // time): a patch re-reads only kPatchM token tiles and kPatchN weight tiles through its L2.
-  const int per_xcd = gridDim.x / kXcds;
-  const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-  const int patch = logical / (kPatchM * kPatchN), in_patch = logical % (kPatchM * kPatchN);
+  // XCDs, each with its own L2 and 32 CUs, and an XCD starts its workgroups in id order.  Every
+  // XCD gets an equal, contiguous run of logical ids (sized from the real tile count, which only
+  // the device knows), and logical ids are ordered so that the ~32 workgroups an XCD runs at a
+  // time form a patch that shares tiles through its L2, and so that the next patch needs the same
+  // weight tiles again: expert, then groups of kGroupN-ish N-tiles, then chunks of up to kChunkM
+  // M-tiles of that expert (innermost in time: the weight tiles of the group come back from the
+  // memory-side cache instead of HBM, and an expert's weights leave HBM once), then the tiles of
+  // the chunk.
   const int n_tiles_n = (d_ff + BN - 1) / BN;
-  const int patches_n = (n_tiles_n + kPatchN - 1) / kPatchN;
-  const int slot = (patch / patches_n) * kPatchM + in_patch % kPatchM;
-  const int tile_n = (patch % patches_n) * kPatchN + in_patch / kPatchM;
-  if (tile_n >= n_tiles_n || slot >= tile_offset[n_experts]) return;  // block-uniform: nothing here
-  const int e = tile_expert[slot];
+  const int total = tile_offset[n_experts] * n_tiles_n;
+  const int per_xcd = (total + kXcds - 1) / kXcds;
+  const int seq = blockIdx.x / kXcds;
+  const int logical = (blockIdx.x % kXcds) * per_xcd + seq;
+  if (seq >= per_xcd || logical >= total) return;  // block-uniform: nothing here
+  const int e = tile_expert[logical / n_tiles_n];  // expert e owns logical ids tile_offset[e] * n_tiles_n ..
+  const int m_e = tile_offset[e + 1] - tile_offset[e];
+  const int local = logical - tile_offset[e] * n_tiles_n;
+  const int chunk_m = m_e <= kChunkMax ? m_e : kChunkM;       // M-tiles that run side by side
+  const int group_n = max(1, kPatch / chunk_m);               // N-tiles that run side by side
+  const int group = local / (m_e * group_n);                  // all groups but the last are full
+  const int group_w = min(group_n, n_tiles_n - group * group_n);
+  const int in_group = local - group * m_e * group_n;
+  const int chunk = in_group / (chunk_m * group_w);           // all chunks but the last are full
+  const int chunk_h = min(chunk_m, m_e - chunk * chunk_m);
+  const int in_chunk = in_group - chunk * chunk_m * group_w;
+  const int tile_n = group * group_n + in_chunk / chunk_h;
+  const int slot = tile_offset[e] + chunk * chunk_m + in_chunk % chunk_h;
   const int tile_in_expert = slot - tile_offset[e];
   const int row_first = offsets[e] + tile_in_expert * BM;  // first bucket slot of this tile
   const int m_len = min(BM, offsets[e + 1] - row_first);   // >= 1
@@ -514,9 +564,8 @@ hipError_t launch_grouped_gemm(hipStream_t stream, int dtype, const void* X, int
       if (err != hipSuccess) return err;
       attr_set[tail] = true;
     }
-    const int64_t patches_n = ((d_ff + C::BN - 1) / C::BN + kPatchN - 1) / kPatchN;
-    const int64_t patches_m = (max_tiles + kPatchM - 1) / kPatchM;
-    const int64_t n_blocks = (patches_n * patches_m * kPatchM * kPatchN + kXcds - 1) / kXcds * kXcds;
+    const int64_t n_tiles_n = (d_ff + C::BN - 1) / C::BN;
+    const int64_t n_blocks = (max_tiles * n_tiles_n + kXcds - 1) / kXcds * kXcds;
     if (n_blocks >= (int64_t(1) << 31)) return hipErrorInvalidValue;
     dim3 grid((unsigned)n_blocks);
     hipLaunchKernelGGL(kern, grid, dim3(C::kThreads), C::kSmemBytes, stream,
