@@ -45,15 +45,14 @@ __device__ __forceinline__ float silu_f32(float g) {
 //   are skipped) by TN*32 channels, for both the gate and the up product.  Block
 //   tile BM = 32*WM*TM tokens by BN = 32*WN*TN channels.
 //
-//   K advances KT = 32 elements per LDS stage through a ring of kStages stages.
-//   Tiles go from global memory straight into LDS (global_load_lds_dwordx4, no
-//   staging registers, no LDS store instructions): the loads of tile kt+3 are
-//   issued, a few MFMAs apart, while tile kt is multiplied.  Spacing them matters
-//   more than anything else here: a wave that issues its loads back to back
-//   stalls on the full vector-memory queue and stops feeding the matrix pipe.
-//   One workgroup barrier per K tile publishes the next stage; it sits before
-//   the last 16-wide K step so that the first fragments of the next tile are in
-//   flight while that step's MFMAs run.
+//   K advances KT elements per LDS stage through a ring of kStages stages (64 and 2 in the
+//   built configuration: 64 KiB per stage).  Tiles go from global memory straight into LDS
+//   (global_load_lds_dwordx4, no staging registers, no LDS store instructions).  The loads of a
+//   tile are not issued in one go but one or two at a time between groups of MFMAs: a wave that
+//   issues eight loads back to back sits on the vector-memory queue and stops feeding the matrix
+//   pipe.  One workgroup barrier per K tile publishes the next stage; it sits before the last
+//   16-wide K step so that the first fragments of the next tile are in flight while that step's
+//   MFMAs run.
 // ---------------------------------------------------------------------------
 // f(integral_constant<int, LO>), ..., f(integral_constant<int, HI - 1>)
 template <int LO, int HI, class F>
