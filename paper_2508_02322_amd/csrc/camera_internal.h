@@ -89,4 +89,11 @@ hipError_t launch_segment_counts(hipStream_t stream, const uint8_t* class_out, c
 hipError_t launch_full_rank(hipStream_t stream, const float* energy, int64_t n_micro, uint32_t* rank,
                             int32_t* ws);
 
+// Machine probes (probe.hip).  The MFMA probe's workspace holds its per-thread sink and, in its last
+// 256 bytes, two 64-bit counters (shader cycles, 100 MHz ticks) that the kernel adds to.
+size_t probe_mfma_workspace_bytes();
+hipError_t launch_probe_mfma(hipStream_t stream, bool random_operands, int iters, void* workspace);
+double probe_mfma_flops(int iters);
+hipError_t launch_probe_hbm(hipStream_t stream, const void* src, int64_t bytes, void* sink);
+
 }  // namespace camera

@@ -1,0 +1,135 @@
+// Measured ceilings of the machine, for benchmark reports.
+//
+// probe_mfma: a register-resident v_mfma_f32_32x32x16_bf16 loop on every CU (two waves
+// per SIMD, eight accumulators, eight A and eight B fragments cycled through), nothing
+// else: no LDS, no memory.  With constant operands it runs at the published peak; with
+// random operand values the chip lowers its clock to stay inside its power limit, and the
+// sustained rate is what a bf16 contraction of real data can reach at best.
+// probe_hbm: a streaming read of a buffer much larger than the caches.
+#include "camera_internal.h"
+
+namespace camera {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int kProbeBlocks = 256;   // one per CU
+constexpr int kProbeThreads = 512;  // two waves per SIMD
+constexpr int kMfmaPerIter = 128;   // unrolled MFMAs per loop iteration and wave
+
+__device__ __forceinline__ uint32_t mix(uint32_t h) {
+  h ^= h >> 16;
+  h *= 0x7feb352du;
+  h ^= h >> 15;
+  h *= 0x846ca68bu;
+  h ^= h >> 16;
+  return h;
+}
+
+// roughly normal (sum of four uniforms), unit variance
+__device__ __forceinline__ float approx_normal(uint32_t h) {
+  float s = 0.0f;
+  for (int r = 0; r < 4; ++r) {
+    h = mix(h + r);
+    s += (h & 0xffffu) * (1.0f / 65536.0f) - 0.5f;
+  }
+  return s * 1.7320508f;
+}
+
+__device__ __forceinline__ uint32_t bf16_bits(float v) {
+  const uint32_t u = __float_as_uint(v);
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// clocks[0] += shader cycles, clocks[1] += 100 MHz reference ticks of one wave per block
+template <bool RANDOM>
+__global__ __launch_bounds__(kProbeThreads, 2) void probe_mfma_kernel(float* __restrict__ sink, int iters,
+                                                                      unsigned long long* __restrict__ clocks) {
+  const unsigned long long c0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
+  bf16x8 a[8], b[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    u32x4 av, bv;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      if (RANDOM) {  // activations of unit scale, weights of scale 0.02, different in every lane and fragment
+        const uint32_t h1 = mix(threadIdx.x * 131u + blockIdx.x * 7919u + i * 31u + w), h2 = mix(h1 + 12345u);
+        av[w] = bf16_bits(approx_normal(h1)) | (bf16_bits(approx_normal(h1 ^ 0x9e3779b9u)) << 16);
+        bv[w] = bf16_bits(0.02f * approx_normal(h2)) | (bf16_bits(0.02f * approx_normal(h2 ^ 0x9e3779b9u)) << 16);
+      } else {
+        av[w] = 0x3f803f80u;  // 1.0, 1.0
+        bv[w] = 0x3f803f80u;
+      }
+    }
+    a[i] = __builtin_bit_cast(bf16x8, av);
+    b[i] = __builtin_bit_cast(bf16x8, bv);
+  }
+  f32x16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+  for (int it = 0; it < iters; ++it) {  // every register index below is a compile-time constant
+#pragma unroll
+    for (int m = 0; m < kMfmaPerIter; ++m)
+      acc[m & 7] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(m * 3 + m / 32) & 7], b[(m * 5 + m / 64) & 7], acc[m & 7],
+                                                           0, 0, 0);
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  sink[blockIdx.x * kProbeThreads + threadIdx.x] = s;
+  if (threadIdx.x == 0) {
+    atomicAdd(&clocks[0], __builtin_readcyclecounter() - c0);
+    atomicAdd(&clocks[1], __builtin_amdgcn_s_memrealtime() - r0);
+  }
+}
+
+// grid-stride 16-byte loads, four in flight per lane; the sum keeps the loads alive
+__global__ __launch_bounds__(256) void probe_hbm_kernel(const u32x4* __restrict__ src, int64_t n_vec,
+                                                        uint32_t* __restrict__ sink) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  uint32_t s = 0;
+  for (; i + 3 * stride < n_vec; i += 4 * stride) {
+    const u32x4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
+    s += v0[0] ^ v0[1] ^ v0[2] ^ v0[3] ^ v1[0] ^ v1[1] ^ v1[2] ^ v1[3] ^ v2[0] ^ v2[1] ^ v2[2] ^ v2[3] ^ v3[0] ^ v3[1] ^
+         v3[2] ^ v3[3];
+  }
+  for (; i < n_vec; i += stride) {
+    const u32x4 v = src[i];
+    s += v[0] ^ v[1] ^ v[2] ^ v[3];
+  }
+  if (s == 0x9e3779b9u) sink[0] = s;  // practically never: the store only keeps the compiler honest
+}
+
+}  // namespace
+
+size_t probe_mfma_workspace_bytes() { return sizeof(float) * kProbeBlocks * kProbeThreads + 256; }
+
+hipError_t launch_probe_mfma(hipStream_t stream, bool random_operands, int iters, void* workspace) {
+  float* sink = static_cast<float*>(workspace);
+  unsigned long long* clocks =
+      reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + sizeof(float) * kProbeBlocks * kProbeThreads);
+  if (random_operands)
+    hipLaunchKernelGGL(probe_mfma_kernel<true>, dim3(kProbeBlocks), dim3(kProbeThreads), 0, stream, sink, iters, clocks);
+  else
+    hipLaunchKernelGGL(probe_mfma_kernel<false>, dim3(kProbeBlocks), dim3(kProbeThreads), 0, stream, sink, iters, clocks);
+  return hipGetLastError();
+}
+
+double probe_mfma_flops(int iters) {
+  return 2.0 * 32 * 32 * 16 * kMfmaPerIter * (double)iters * (kProbeThreads / kWave) * kProbeBlocks;
+}
+
+hipError_t launch_probe_hbm(hipStream_t stream, const void* src, int64_t bytes, void* sink) {
+  hipLaunchKernelGGL(probe_hbm_kernel, dim3(256 * 16), dim3(256), 0, stream, static_cast<const u32x4*>(src), bytes / 16,
+                     static_cast<uint32_t*>(sink));
+  return hipGetLastError();
+}
+
+}  // namespace camera

@@ -28,7 +28,7 @@ def ctx(lib):
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "camera.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(camera_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(camera_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -143,6 +143,13 @@ def test_create_and_profile_checks(lib, ctx):
     ms, cnt = ctypes.c_double(), i64()
     assert lib.camera_profile_read(ctx, 99, ctypes.byref(ms), ctypes.byref(cnt)) == -1
     assert lib.camera_profile_read(ctx, 0, None, ctypes.byref(cnt)) == -1
+    tf, mhz = ctypes.c_double(), ctypes.c_double()
+    assert lib.camera_probe_mfma_bf16(None, None, 1, 1, ctypes.byref(tf), ctypes.byref(mhz)) == -1
+    assert lib.camera_probe_mfma_bf16(ctx, None, 1, 0, ctypes.byref(tf), ctypes.byref(mhz)) == -1
+    assert lib.camera_probe_mfma_bf16(ctx, None, 1, 1, None, ctypes.byref(mhz)) == -1
+    assert lib.camera_probe_hbm_read(ctx, None, 1000, 1, ctypes.byref(tf)) == -1
+    assert lib.camera_probe_hbm_read(ctx, None, 1 << 30, 0, ctypes.byref(tf)) == -1
+    assert lib.camera_probe_hbm_read(ctx, None, 1 << 30, 1, None) == -1
 
 
 def test_missing_library_fails_loudly(tmp_path):
