@@ -147,7 +147,11 @@ struct TileState {
   int wave_m, wave_n, frag_row, frag_half;
 };
 
-template <class C, int ACT, bool TAIL>
+// ACT: active 32-row blocks of this wave's accumulators.  DEAD: every token row that this wave
+// loads lies past the end of the expert's bucket (a short last tile); such rows only have to hold
+// finite values (their routing weight is 0), so they are loaded once, in the prologue, and
+// the K loop skips their loads.
+template <class C, int ACT, bool TAIL, bool DEAD>
 __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_ff, int slot,
                                           float* __restrict__ part_phi2, float* __restrict__ part_max) {
   constexpr int BN = C::BN, TN = C::TN, WM = C::WM, KT = C::KT;
@@ -187,7 +191,9 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
   // loads [C::issue_begin(P), C::issue_begin(P + 1)) of a tile: the share of issue slot P
   auto dma_slot = [&](int stage, int k0, auto slot_index) {
     constexpr int P = decltype(slot_index)::value;
-    static_for<C::issue_begin(P), C::issue_begin(P + 1)>([&](auto d) { dma_one(stage, k0, d); });
+    static_for<C::issue_begin(P), C::issue_begin(P + 1)>([&](auto d) {
+      if constexpr (!(DEAD && decltype(d)::value < C::kADma)) dma_one(stage, k0, d);
+    });
   };
 
   f32x16 acc_g[NA][TN], acc_u[NA][TN];
@@ -246,14 +252,19 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
   constexpr int kHalf = ACT * TN, kFull = 2 * ACT * TN;         // MFMAs of half a K step, of a K step
   using std::integral_constant;
   Frags f[2];
+  // the tile whose loads are under way after the prologue: slots 0 and 1 here, the rest in the first iteration
+  int fill_stage = C::kStages - 1, fill_k = min((C::kStages - 1) * KT, k_last);
+  if constexpr (DEAD)  // first of all (oldest): the one-time fill of the token rows that the loop never loads
+    static_for<0, C::kADma>([&](auto d) { dma_one(fill_stage, fill_k, d); });
 #pragma unroll
   for (int t = 0; t + 1 < C::kStages; ++t)
     static_for<0, C::kLoadsPerTile>([&](auto d) { dma_one(t, min(t * KT, k_last), d); });
-  // the tile whose loads are under way: slots 0 and 1 here, the rest in the first iteration
-  int fill_stage = C::kStages - 1, fill_k = min((C::kStages - 1) * KT, k_last);
   dma_slot(fill_stage, fill_k, integral_constant<int, 0>{});
   dma_slot(fill_stage, fill_k, integral_constant<int, 1>{});
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly + C::issue_begin(2)) : "memory");  // tile 0 (loads return in order)
+  // loads issued by slots 0 and 1 (they may still fly; loads return in order, so tile 0 has landed)
+  constexpr int kSlots01 = DEAD ? C::issue_begin(2) - (C::issue_begin(2) < C::kADma ? C::issue_begin(2) : C::kADma)
+                                : C::issue_begin(2);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly + kSlots01) : "memory");
   __syncthreads();
   read_frags(f[0], 0, 0);
   int stage = 0;  // stage of tile kt
@@ -370,7 +381,7 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
   float* s_a = reinterpret_cast<float*>(s_tok + BM);                                // [BM] routing weight
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
-  const int wave = tid / kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // in a scalar register: wave-uniform addresses and branches
 
   // Rows past the end of the expert's bucket read token row 0 of the tile again with weight 0:
   // their Lambda is exactly 0 (finite projections times a = 0), so no load in the K loop is conditional.
@@ -422,12 +433,20 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
   // accumulator i of this wave covers row block WM*i + wave_m; blocks past m_len are skipped
   const int n_row_blocks = (m_len + 31) / 32;
   const int act = max(0, (n_row_blocks - st.wave_m + WM - 1) / WM);  // wave-uniform, 0 .. TM
+  // With two stages the K loop waits for every outstanding load, so a wave may issue fewer of them.
+  const bool dead = C::kStages == 2 && a_row0 >= m_len;
   static_assert(TM == 4 || TM == 2 || TM == 1, "dispatch below covers TM = 1, 2 and 4");
-  if (act >= TM) tile_body<C, TM, TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
-  else if (act == 3) tile_body<C, (TM > 3 ? 3 : 0), TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
-  else if (act == 2) tile_body<C, (TM > 2 ? 2 : 0), TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
-  else if (act == 1) tile_body<C, (TM > 1 ? 1 : 0), TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
-  else tile_body<C, 0, TAIL>(st, n0, d_ff, slot, part_phi2, part_max);
+#define CAMERA_TILE_BODY(A)                                                              \
+  do {                                                                                   \
+    if (dead) tile_body<C, (A), TAIL, true>(st, n0, d_ff, slot, part_phi2, part_max);    \
+    else tile_body<C, (A), TAIL, false>(st, n0, d_ff, slot, part_phi2, part_max);        \
+  } while (0)
+  if (act >= TM) tile_body<C, TM, TAIL, false>(st, n0, d_ff, slot, part_phi2, part_max);
+  else if (act == 3) CAMERA_TILE_BODY((TM > 3 ? 3 : 0));
+  else if (act == 2) CAMERA_TILE_BODY((TM > 2 ? 2 : 0));
+  else if (act == 1) CAMERA_TILE_BODY((TM > 1 ? 1 : 0));
+  else CAMERA_TILE_BODY(0);
+#undef CAMERA_TILE_BODY
 }
 
 // ---------------------------------------------------------------------------
