@@ -21,6 +21,8 @@ Analysis"):
   squared column norms of W_down; energy; argsort.
 * CAMERA-P's TopSelect (Algorithm 2) and CAMERA-Q's ListSplitByRatio /
   GetSubIndex (Algorithm 3).
+* Applying a selection (Algorithm 2, lines 10-13): the kept gate / up rows and
+  down columns of every expert, gathered in index order.
 
 Readings taken where the paper is silent (each is listed in the design notes):
 0-based experts and channels with half-open ranges; Top&Norm = softmax over
@@ -34,7 +36,9 @@ from the most important end.
 
 Parity pins: every function here is pinned by tests/test_oracle_*.py
 (brute-force ablation of the plain layer forward, the Lemma, closed forms,
-library softmax / SiLU, symmetries, brute-force sorting).  The absolute score
+library softmax / SiLU, symmetries, brute-force sorting; for the gather, the
+layer rebuilt from the compacted weights against the layer with the pruned
+vectors zeroed).  The absolute score
 values on the model-shaped configs are not printed anywhere in the paper:
 for those, parity is pinned only through this oracle.
 """
@@ -283,3 +287,47 @@ def alloc_bits(E, seg_offsets, bits, ratios):
             perm[pos:pos + members.size] = members
             pos += members.size
     return bits[cls].astype(np.uint8), level_count, perm
+
+
+# --------------------------------------------------------------------------
+# Applying a selection: W_up, W_gate, W_down <- W_up[S,:], W_gate[S,:], W_down[:,S]
+#                                                        (Algorithm 2, l.10-13)
+# --------------------------------------------------------------------------
+def gather_micro_experts(W_gate, W_up, W_down, index, count, index_base=0):
+    """Keeps the micro-experts listed in ``index``, in that order.
+
+    W_gate, W_up [N_E, d_ff, d_model]; W_down [N_E, d_model, d_ff].  ``index``
+    holds global micro-expert indices index_base + e*d_ff + c grouped by
+    expert in expert order, ``count[e]`` of them for expert e (the kept_idx /
+    kept_per_expert of ``select_prune``, or the perm of ``alloc_bits`` with
+    count = d_ff: the reordering that colocates equal precision, Section
+    "Mixed-precision Strategy CAMERA-Q").  Returns
+
+      gate_out, up_out  [len(index), d_model]: row r is the gate / up row of
+                        micro-expert index[r];
+      down_out          list over experts of [d_model, count[e]] matrices whose
+                        column j is the down column of the expert's j-th entry.
+
+    Same dtype as the inputs: the values are copied, never recomputed.
+    """
+    W_gate, W_up, W_down = np.asarray(W_gate), np.asarray(W_up), np.asarray(W_down)
+    n_experts, d_ff, d_model = W_gate.shape
+    if W_up.shape != W_gate.shape or W_down.shape != (n_experts, d_model, d_ff):
+        raise ValueError("weight shapes disagree")
+    index = np.asarray(index, dtype=np.int64)
+    count = np.asarray(count, dtype=np.int64)
+    if count.shape != (n_experts,) or count.sum() != index.size or np.any(count < 0):
+        raise ValueError("count must give the number of entries of every expert")
+    gate_out = np.empty((index.size, d_model), dtype=W_gate.dtype)
+    up_out = np.empty((index.size, d_model), dtype=W_up.dtype)
+    down_out = []
+    pos = 0
+    for e in range(n_experts):
+        mine = index[pos:pos + count[e]] - index_base - e * d_ff      # channels of expert e
+        if np.any(mine < 0) or np.any(mine >= d_ff):
+            raise ValueError("an index lies outside its expert")
+        gate_out[pos:pos + count[e]] = W_gate[e][mine, :]
+        up_out[pos:pos + count[e]] = W_up[e][mine, :]
+        down_out.append(W_down[e][:, mine].copy())
+        pos += int(count[e])
+    return gate_out, up_out, down_out
