@@ -167,7 +167,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    for k in range(binding.K_RANK + 1):
+    for k in range(len(binding.KERNEL_NAMES)):
         cam.profile_read(k)
     cam.profile_enable(True)
     t0 = time.perf_counter()

@@ -66,7 +66,8 @@ enum camera_kernel_id {
   CAMERA_K_DOWN_NORM = 3,
   CAMERA_K_FINALIZE = 4,
   CAMERA_K_RANK = 5,
-  CAMERA_K_COUNT = 6
+  CAMERA_K_GATHER = 6,   /* camera_gather_micro_experts */
+  CAMERA_K_COUNT = 7
 };
 
 /* Create / destroy a context bound to HIP device `device`.  Creation touches no
@@ -185,6 +186,37 @@ int camera_alloc_bits(camera_ctx* ctx, void* stream,
                       const int64_t* seg_offsets, int n_seg,
                       int n_levels, const int* bits, const double* ratios,
                       uint8_t* bit_of, int32_t* level_count, int32_t* perm);
+
+/*
+ * W_up, W_gate, W_down <- W_up[S,:], W_gate[S,:], W_down[:,S]  -- Algorithm 2 (CAMERA-P), lines 10-13: only
+ * the micro-experts in S are kept, and all three of their vectors move together.  With the `perm` of
+ * camera_alloc_bits as the index list (count NULL) the same call is the reordering inside every expert
+ * that colocates micro-experts of equal precision (Section "Mixed-precision Strategy CAMERA-Q").
+ *
+ *   W_gate, W_up, W_down, strides, n_experts, d_ff, d_model, dtype: one group of experts, as in
+ *               camera_score_layer.  d_ff * element size must not exceed 65536 bytes.
+ *   index       int32 [n_index]: global micro-expert indices index_base + e*d_ff + c, grouped by
+ *               expert in expert order -- camera_select_prune's kept_idx or camera_alloc_bits' perm
+ *               (for the second group of a layer: its slice of them, with index_base = the global
+ *               index of the group's first micro-expert)
+ *   count       int32 [n_experts]: entries of `index` that belong to each expert (camera_select_prune's
+ *               kept_per_expert), or NULL: d_ff each
+ *   W_gate_out, W_up_out   [n_index][d_model] out, `dtype`: row r is the gate / up row of index[r]
+ *   W_down_out  out, `dtype`, n_index * d_model elements: expert e's block starts at element
+ *               d_model * (count[0] + ... + count[e-1]) and is [d_model][count[e]] row-major; its column
+ *               j is the down column of the expert's j-th entry
+ *   Any of the three outputs may be NULL (skipped); the matching input may then be NULL too.
+ * Values are copied bit for bit.  An entry that does not lie inside its expert's range gives a zero
+ * row / column; if the counts add up to less than n_index the remaining output rows are left
+ * untouched, if to more, the surplus entries are ignored.  n_index == 0 does nothing.
+ */
+int camera_gather_micro_experts(camera_ctx* ctx, void* stream, int dtype,
+                                int n_experts, int64_t d_ff, int64_t d_model,
+                                const void* W_gate, const void* W_up, int64_t stride_gu,
+                                const void* W_down, int64_t stride_down,
+                                const int32_t* index, int64_t n_index, int64_t index_base,
+                                const int32_t* count,
+                                void* W_gate_out, void* W_up_out, void* W_down_out);
 
 /*
  * Per-kernel-group timing for benchmarks.  With profiling on, every launch

@@ -17,11 +17,12 @@ LIB_PATH = os.path.join(HERE, "libcamera_hip.so")
 
 F32, BF16 = 0, 1
 ACCUMULATE, NO_FINALIZE = 1, 2
-K_ROUTE, K_BUCKET, K_GEMM, K_DOWN_NORM, K_FINALIZE, K_RANK = range(6)
-KERNEL_NAMES = ["route", "bucket", "gemm", "down_norm", "finalize", "rank"]
+K_ROUTE, K_BUCKET, K_GEMM, K_DOWN_NORM, K_FINALIZE, K_RANK, K_GATHER = range(7)
+KERNEL_NAMES = ["route", "bucket", "gemm", "down_norm", "finalize", "rank", "gather"]
 
 EXPORTS = ["camera_create", "camera_destroy", "camera_last_error", "camera_version", "camera_route_topk",
-           "camera_score_layer", "camera_select_prune", "camera_alloc_bits", "camera_profile_enable",
+           "camera_score_layer", "camera_select_prune", "camera_alloc_bits", "camera_gather_micro_experts",
+           "camera_profile_enable",
            "camera_profile_read", "camera_probe_mfma_bf16", "camera_probe_hbm_read"]
 
 _c = ctypes
@@ -51,6 +52,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.camera_select_prune.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _d, _vp, _vp, _vp, _vp]
     lib.camera_alloc_bits.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _i, _c.POINTER(_i),
                                       _c.POINTER(_d), _vp, _vp, _vp]
+    lib.camera_gather_micro_experts.argtypes = [_vp, _vp, _i, _i, _i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, _i64,
+                                                _i64, _vp, _vp, _vp, _vp]
     lib.camera_profile_enable.argtypes = [_vp, _i]
     lib.camera_profile_read.argtypes = [_vp, _i, _c.POINTER(_d), _c.POINTER(_i64)]
     lib.camera_probe_mfma_bf16.argtypes = [_vp, _vp, _i, _i, _c.POINTER(_d), _c.POINTER(_d)]
@@ -159,6 +162,25 @@ class Camera:
             self._ctx, _stream_handle(self.device), _ptr(energy), n_micro, seg, n_seg, n_levels,
             (_i * n_levels)(*bits), (_d * len(ratios))(*ratios), _ptr(bit_of), _ptr(level_count), _ptr(perm)))
         return bit_of, level_count, perm
+
+    def gather_micro_experts(self, W_gate, W_up, W_down, index, count=None, index_base=0, out=None):
+        """Kept gate / up rows and down columns of one group of experts (Algorithm 2, lines 10-13).
+        W_gate, W_up [N_E, d_ff, d_model], W_down [N_E, d_model, d_ff] (any of them may be None: skipped);
+        index int32 [n_index] global indices grouped by expert; count int32 [N_E] or None (d_ff each).
+        Returns (gate_out [n_index, d_model], up_out, down_out flat [n_index * d_model])."""
+        ref = W_gate if W_gate is not None else (W_up if W_up is not None else W_down)
+        n_experts = ref.shape[0]
+        d_ff, d_model = (ref.shape[1], ref.shape[2]) if ref is not W_down else (ref.shape[2], ref.shape[1])
+        n_index = index.numel()
+        stride_gu = (W_gate if W_gate is not None else W_up).stride(0) if (W_gate is not None or W_up is not None) else 0
+        if out is None:
+            mk = lambda src, shape: None if src is None else torch.empty(shape, dtype=src.dtype, device=self.device)
+            out = (mk(W_gate, (n_index, d_model)), mk(W_up, (n_index, d_model)), mk(W_down, (n_index * d_model,)))
+        self._check(self.lib.camera_gather_micro_experts(
+            self._ctx, _stream_handle(self.device), _dtype_code(ref), n_experts, d_ff, d_model, _ptr(W_gate), _ptr(W_up),
+            stride_gu, _ptr(W_down), W_down.stride(0) if W_down is not None else 0, _ptr(index), n_index,
+            int(index_base), _ptr(count), _ptr(out[0]), _ptr(out[1]), _ptr(out[2])))
+        return out
 
     # ---- profiling ---------------------------------------------------------
     def profile_enable(self, on: bool):

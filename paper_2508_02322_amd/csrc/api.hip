@@ -234,6 +234,57 @@ int camera_profile_read(camera_ctx* ctx, int kernel_id, double* total_ms, int64_
   return CAMERA_OK;
 }
 
+int camera_gather_micro_experts(camera_ctx* ctx, void* stream_, int dtype, int n_experts, int64_t d_ff,
+                                int64_t d_model, const void* W_gate, const void* W_up, int64_t stride_gu,
+                                const void* W_down, int64_t stride_down, const int32_t* index, int64_t n_index,
+                                int64_t index_base, const int32_t* count, void* W_gate_out, void* W_up_out,
+                                void* W_down_out) {
+  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
+  if (dtype != CAMERA_F32 && dtype != CAMERA_BF16) return fail(ctx, CAMERA_EDTYPE, "dtype: unknown code %d", dtype);
+  const int es = dtype == CAMERA_BF16 ? 2 : 4;
+  if (n_experts < 1 || n_experts > CAMERA_MAX_EXPERTS)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "n_experts: must be in [1, %d]", CAMERA_MAX_EXPERTS);
+  if (d_ff < 1 || d_model < 1) return fail(ctx, CAMERA_ESHAPE, "d_ff / d_model: must be positive");
+  if (d_ff * es > 65536) return fail(ctx, CAMERA_EUNSUPPORTED, "d_ff: a W_down row must not exceed 65536 bytes");
+  if ((d_model * es) % 16 != 0) return fail(ctx, CAMERA_ESHAPE, "d_model: rows must be whole 16-byte vectors");
+  if (n_index < 0 || n_index > (int64_t)n_experts * d_ff)
+    return fail(ctx, CAMERA_EINVAL, "n_index: must be in [0, n_experts * d_ff]");
+  if (count == nullptr && n_index != (int64_t)n_experts * d_ff)
+    return fail(ctx, CAMERA_EINVAL, "count: NULL needs n_index == n_experts * d_ff");
+  if (n_index * d_model >= (int64_t(1) << 40)) return fail(ctx, CAMERA_ESHAPE, "n_index * d_model: too large");
+  if (index_base < 0 || index_base > (int64_t(1) << 31) - (int64_t)n_experts * d_ff)
+    return fail(ctx, CAMERA_EINVAL, "index_base: indices must fit 32 bits");
+  const bool rows = W_gate_out != nullptr || W_up_out != nullptr;
+  if (W_gate_out != nullptr && W_gate == nullptr) return fail(ctx, CAMERA_EINVAL, "W_gate: NULL");
+  if (W_up_out != nullptr && W_up == nullptr) return fail(ctx, CAMERA_EINVAL, "W_up: NULL");
+  if (W_down_out != nullptr && W_down == nullptr) return fail(ctx, CAMERA_EINVAL, "W_down: NULL");
+  if (rows && (stride_gu < d_ff * d_model || (stride_gu * es) % 16 != 0))
+    return fail(ctx, CAMERA_ESHAPE, "stride_gu: must be >= d_ff * d_model and a whole number of 16-byte vectors");
+  if (W_down_out != nullptr && stride_down < d_ff * d_model)
+    return fail(ctx, CAMERA_ESHAPE, "stride_down: must be >= d_model * d_ff");
+  if ((W_gate_out && (!aligned16(W_gate) || !aligned16(W_gate_out))) || (W_up_out && (!aligned16(W_up) || !aligned16(W_up_out))))
+    return fail(ctx, CAMERA_ESHAPE, "W_gate / W_up / their outputs: not 16-byte aligned");
+  if (n_index == 0 || (!rows && W_down_out == nullptr)) return CAMERA_OK;
+  if (index == nullptr) return fail(ctx, CAMERA_EINVAL, "index: NULL");
+
+  DeviceGuard guard;
+  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  Carver cv;
+  const size_t o_off = cv.take(sizeof(int32_t) * (CAMERA_MAX_EXPERTS + 1));
+  if (int rc = ensure_workspace(ctx, cv.used)) return rc;
+  int32_t* off = reinterpret_cast<int32_t*>(static_cast<char*>(ctx->ws) + o_off);
+  Bracket bracket(ctx, stream, CAMERA_K_GATHER);
+  CAMERA_HIP(camera::launch_gather_offsets(stream, count, n_experts, d_ff, off), "gather offsets");
+  CAMERA_HIP(camera::launch_gather_rows(stream, dtype, W_gate, W_up, stride_gu, n_experts, d_ff, d_model, index, n_index,
+                                        index_base, off, W_gate_out, W_up_out),
+             "gather rows");
+  CAMERA_HIP(camera::launch_gather_cols(stream, dtype, W_down, stride_down, n_experts, d_ff, d_model, index, n_index,
+                                        index_base, off, W_down_out),
+             "gather columns");
+  return CAMERA_OK;
+}
+
 int camera_probe_mfma_bf16(camera_ctx* ctx, void* stream_, int random_operands, int launches, double* tflops,
                            double* shader_mhz) {
   if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");

@@ -89,6 +89,16 @@ hipError_t launch_segment_counts(hipStream_t stream, const uint8_t* class_out, c
 hipError_t launch_full_rank(hipStream_t stream, const float* energy, int64_t n_micro, uint32_t* rank,
                             int32_t* ws);
 
+// Gather of kept micro-experts (gather.hip).  off: [n_experts + 1] exclusive prefix of the per-expert
+// entry counts (count == nullptr: d_ff each), written by launch_gather_offsets.
+hipError_t launch_gather_offsets(hipStream_t stream, const int32_t* count, int n_experts, int64_t d_ff, int32_t* off);
+hipError_t launch_gather_rows(hipStream_t stream, int dtype, const void* W_gate, const void* W_up, int64_t stride_gu,
+                              int n_experts, int64_t d_ff, int64_t d_model, const int32_t* index, int64_t n_index,
+                              int64_t index_base, const int32_t* off, void* gate_out, void* up_out);
+hipError_t launch_gather_cols(hipStream_t stream, int dtype, const void* W_down, int64_t stride_down, int n_experts,
+                              int64_t d_ff, int64_t d_model, const int32_t* index, int64_t n_index,
+                              int64_t index_base, const int32_t* off, void* down_out);
+
 // Machine probes (probe.hip).  The MFMA probe's workspace holds its per-thread sink and, in its last
 // 256 bytes, two 64-bit counters (shader cycles, 100 MHz ticks) that the kernel adds to.
 size_t probe_mfma_workspace_bytes();

@@ -155,3 +155,28 @@ def test_create_and_profile_checks(lib, ctx):
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(FileNotFoundError):
         binding.load_library(str(tmp_path / "libcamera_hip.so"))
+
+
+def test_gather_argument_checks(lib, ctx):
+    vpp = ctypes.c_void_p
+    fake = vpp(4096)          # never dereferenced: every check below fails on the host
+    def gather(dtype=1, n_experts=2, d_ff=64, d_model=16, wg=fake, wu=fake, stride_gu=64 * 16, wd=fake,
+               stride_down=64 * 16, index=fake, n_index=10, base=0, count=fake, og=fake, ou=fake, od=fake, c=ctx):
+        return lib.camera_gather_micro_experts(c, None, dtype, n_experts, d_ff, d_model, wg, wu, stride_gu, wd,
+                                               stride_down, index, n_index, base, count, og, ou, od)
+    assert gather(c=None) == -1
+    assert gather(dtype=7) == -3
+    assert gather(n_experts=0) == -6 and gather(n_experts=257) == -6
+    assert gather(d_ff=0) == -2
+    assert gather(d_ff=40000, stride_gu=40000 * 16, stride_down=40000 * 16) == -6 and "65536" in err(lib, ctx)
+    assert gather(d_model=12) == -2 and "16-byte" in err(lib, ctx)
+    assert gather(n_index=-1) == -1 and gather(n_index=129) == -1
+    assert gather(count=None, n_index=10) == -1 and "count" in err(lib, ctx)
+    assert gather(wg=None) == -1 and "W_gate" in err(lib, ctx)
+    assert gather(wd=None) == -1 and "W_down" in err(lib, ctx)
+    assert gather(stride_gu=100) == -2 and gather(stride_down=100) == -2
+    assert gather(og=vpp(4100)) == -2 and "aligned" in err(lib, ctx)
+    assert gather(index=None) == -1 and "index" in err(lib, ctx)
+    assert gather(base=-1) == -1
+    assert gather(n_index=0) == 0                      # nothing to do
+    assert gather(og=None, ou=None, od=None) == 0      # every output skipped
