@@ -52,6 +52,8 @@ def parse_args():
     ap.add_argument("--chunk-tokens", type=int, default=0, help="chunk size for --calib-tokens (default: the configuration's token count)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the measured MFMA / HBM ceilings (about 1 s)")
+    ap.add_argument("--no-apply", action="store_true",
+                    help="skip the measurement of applying a 40 %% mask (gather of the kept micro-experts)")
     return ap.parse_args()
 
 
@@ -88,6 +90,62 @@ class LayerRunner:
         for bits, ratios in decisions["alloc"]:
             res.append(cam.alloc_bits(self.out["energy"], self.seg, bits, ratios))
         return res
+
+
+def measure_apply(cam, cfg, layers, torch, binding, ratio=0.4, reps=3):
+    """Applies a CAMERA-P mask: gathers the kept gate / up rows and down columns of every expert of up to
+    four layers (outside the timed step: it is the stage after the scoring path).  Returns the HBM-bound
+    roofline of that launch group: algorithmic bytes = each kept vector read once and written once."""
+    use = layers[:4]
+    es = 2 if cfg.dtype == "bf16" else 4
+    n_keep_max = cfg.n_micro
+    bufs = [torch.empty(n_keep_max * cfg.d_model, dtype=use[0].t["W_gate"].dtype, device="cuda") for _ in range(3)]
+    plans = []
+    for lr in use:
+        keep, per, kept_idx, _ = cam.select_prune(lr.out["energy"], lr.seg, ratio, want_idx=True)
+        per_h = per.cpu()
+        groups = [("W", cfg.n_experts, 0, 0)]
+        if cfg.n_shared:
+            groups.append(("Ws", cfg.n_shared, cfg.n_experts, cfg.n_micro_routed))
+        pos, plan = 0, []
+        for prefix, n_e, seg0, base in groups:
+            n_idx = int(per_h[seg0:seg0 + n_e].sum())
+            plan.append((lr.t[prefix + "_gate"], lr.t[prefix + "_up"], lr.t[prefix + "_down"], kept_idx[pos:pos + n_idx],
+                         per[seg0:seg0 + n_e], base, n_idx))
+            pos += n_idx
+        plans.append(plan)
+    kept_vectors = 0
+
+    def run():
+        total = 0
+        for plan in plans:
+            at = 0
+            for Wg, Wu, Wd, idx, cnt, base, n_idx in plan:
+                if n_idx == 0:
+                    continue
+                d = cfg.d_model
+                out = (bufs[0][at * d:(at + n_idx) * d].view(n_idx, d), bufs[1][at * d:(at + n_idx) * d].view(n_idx, d),
+                       bufs[2][at * d:(at + n_idx) * d])
+                cam.gather_micro_experts(Wg, Wu, Wd, idx, cnt, base, out=out)
+                at += n_idx
+            total += at
+        return total
+
+    run()
+    torch.cuda.synchronize()
+    cam.profile_read(binding.K_GATHER)
+    cam.profile_enable(True)
+    for _ in range(reps):
+        kept_vectors = run()
+    torch.cuda.synchronize()
+    cam.profile_enable(False)
+    ms, launches = cam.profile_read(binding.K_GATHER)
+    ms_per_layer = ms / (reps * len(use))
+    bytes_per_layer = 6.0 * (kept_vectors / len(use)) * cfg.d_model * es
+    gbs = bytes_per_layer / (ms_per_layer * 1e-3) / 1e9
+    return {"what": f"gather of the kept micro-experts at lambda = {ratio} (Algorithm 2, lines 10-13), {len(use)} layers",
+            "ms_per_layer": round(ms_per_layer, 4), "bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0,
+            "unit": "GB/s", "frac": round(gbs / 8000.0, 4), "algorithmic_bytes_per_layer": bytes_per_layer}
 
 
 def cpu_baseline(cfg, inputs):
@@ -206,6 +264,8 @@ def main():
             "hbm_read_gbs": round(hbm, 1),
             "achieved_over_random_operand_ceiling": round(achieved / tf_rand, 4) if bf16 and tf_rand > 0 else None}
 
+    apply_mask = None if args.no_apply else measure_apply(cam, cfg, layers, torch, binding)
+
     ms_per_step = elapsed / args.steps * 1e3
     value = calib_tokens * n_layers * args.steps / elapsed
     result = {
@@ -223,6 +283,8 @@ def main():
         "roofline": roofline,
         "kernel_ms": kernel_ms,
     }
+    if apply_mask is not None:
+        result["apply_mask"] = apply_mask
     if not args.no_cpu_baseline:
         del layers
         torch.cuda.empty_cache()
