@@ -41,8 +41,8 @@ PMC_TRAFFIC_BYTES = {"qwen2-57b-a14b": 5.254e9}
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="qwen2-57b-a14b", choices=sorted(DECISIONS))
     ap.add_argument("--layers", type=int, default=0, help="debug: only this many layers (the result is then not the named workload)")
     ap.add_argument("--calib-tokens", type=int, default=0,

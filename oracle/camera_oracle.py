@@ -23,6 +23,9 @@ Analysis"):
   GetSubIndex (Algorithm 3).
 * Applying a selection (Algorithm 2, lines 10-13): the kept gate / up rows and
   down columns of every expert, gathered in index order.
+* The layer output with a subset of the micro-experts (Eq. 1-2; the recomputed
+  output of Algorithm 2, line 14) and its distance from the original output:
+  the Lemma's decoding error, L2 and cosine.
 
 Readings taken where the paper is silent (each is listed in the design notes):
 0-based experts and channels with half-open ranges; Top&Norm = softmax over
@@ -38,7 +41,8 @@ Parity pins: every function here is pinned by tests/test_oracle_*.py
 (brute-force ablation of the plain layer forward, the Lemma, closed forms,
 library softmax / SiLU, symmetries, brute-force sorting; for the gather, the
 layer rebuilt from the compacted weights against the layer with the pruned
-vectors zeroed).  The absolute score
+vectors zeroed; for the layer output, a loop-written forward pass, the
+one-removed-index equality of the Lemma and the library's bfloat16 rounding).  The absolute score
 values on the model-shaped configs are not printed anywhere in the paper:
 for those, parity is pinned only through this oracle.
 """
@@ -331,3 +335,63 @@ def gather_micro_experts(W_gate, W_up, W_down, index, count, index_base=0):
         down_out.append(W_down[e][:, mine].copy())
         pos += int(count[e])
     return gate_out, up_out, down_out
+
+
+# --------------------------------------------------------------------------
+# Layer output with a subset of the micro-experts, and its decoding error
+#                    (Eq. 1-2; Algorithm 2, l.14; the Lemma's epsilon; the
+#                     L2 / cosine comparison of hidden states after pruning)
+# --------------------------------------------------------------------------
+def round_to_bf16(a):
+    """Nearest bfloat16 (ties to even) of every element, returned as float64.
+
+    bfloat16 is the upper half of a float32: the value is first rounded to
+    float32, then the low 16 bits are rounded away.  Finite inputs only."""
+    f32 = np.asarray(a, dtype=np.float32)
+    u = f32.view(np.uint32).astype(np.uint64)
+    keep_odd = (u >> np.uint64(16)) & np.uint64(1)
+    u = (u + np.uint64(0x7FFF) + keep_odd) >> np.uint64(16) << np.uint64(16)
+    return u.astype(np.uint32).view(np.float32).astype(F64).reshape(f32.shape)
+
+
+def layer_forward(X, A, W_gate, W_up, W_down, keep=None, round_hidden=None):
+    """y_j = sum_e W_down,e Lambda_e[j, :]  with  Lambda_e = A[:, e] * silu(X W_gate,e^T) * (X W_up,e^T)
+    (Eq. 1-2 with the coefficient of Eq. 4), over the kept micro-experts only.
+
+    keep: None or a 0/1 vector over the layer's micro-experts (index e*d_ff + c):
+    a pruned micro-expert contributes nothing (its three vectors are zeroed together).
+    round_hidden: None, or a function applied to Lambda before the down
+    projection (``round_to_bf16`` for a 16-bit model, whose hidden activations
+    are stored in that format).  Returns Y [n, d_model].
+    """
+    X, A = _f64(X), _f64(A)
+    n, d_model = X.shape
+    Y = np.zeros((n, d_model), dtype=F64)
+    pos = 0
+    for e in range(len(W_gate)):
+        Wd = _f64(W_down[e])
+        d_ff = Wd.shape[1]
+        lam = lambda_matrix(X, A[:, e], W_gate[e], W_up[e])
+        if keep is not None:
+            lam = lam * _f64(np.asarray(keep)[pos:pos + d_ff])[None, :]
+        if round_hidden is not None:
+            lam = round_hidden(lam)
+        Y += lam @ Wd.T
+        pos += d_ff
+    return Y
+
+
+def output_error(Y, Y_hat):
+    """How far the pruned layer's output is from the original one: per token
+    d2 = ||y - y_hat||^2, yy = ||y||^2, hh = ||y_hat||^2, yh = <y, y_hat>, and
+    from them l2 = ||Y - Y_hat||_F (the square root of the Lemma's epsilon),
+    cosine = <Y, Y_hat> / (||Y||_F ||Y_hat||_F) over the whole calibration set, and
+    cosine_mean = the mean of the per-token cosines (tokens with a zero norm left out)."""
+    Y, Y_hat = _f64(Y), _f64(Y_hat)
+    diff = Y - Y_hat
+    d2, yy, hh, yh = (diff * diff).sum(1), (Y * Y).sum(1), (Y_hat * Y_hat).sum(1), (Y * Y_hat).sum(1)
+    ok = (yy > 0) & (hh > 0)
+    flat_den = np.sqrt(yy.sum() * hh.sum())
+    return {"d2": d2, "yy": yy, "hh": hh, "yh": yh, "l2": float(np.sqrt(d2.sum())),
+            "cosine": float(yh.sum() / flat_den) if flat_den > 0 else float("nan"),
+            "cosine_mean": float(np.mean(yh[ok] / np.sqrt(yy[ok] * hh[ok]))) if ok.any() else float("nan")}
