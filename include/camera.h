@@ -67,7 +67,9 @@ enum camera_kernel_id {
   CAMERA_K_FINALIZE = 4,
   CAMERA_K_RANK = 5,
   CAMERA_K_GATHER = 6,   /* camera_gather_micro_experts */
-  CAMERA_K_COUNT = 7
+  CAMERA_K_DOWN_GEMM = 7, /* camera_layer_forward: hidden activations times W_down^T */
+  CAMERA_K_COMBINE = 8,  /* camera_layer_forward: sum over a token's experts; camera_output_error */
+  CAMERA_K_COUNT = 9
 };
 
 /* Create / destroy a context bound to HIP device `device`.  Creation touches no
@@ -217,6 +219,38 @@ int camera_gather_micro_experts(camera_ctx* ctx, void* stream, int dtype,
                                 const int32_t* index, int64_t n_index, int64_t index_base,
                                 const int32_t* count,
                                 void* W_gate_out, void* W_up_out, void* W_down_out);
+
+/*
+ * The layer output over a subset of the micro-experts (Eq. 1-2; the output recomputed after pruning in
+ * Algorithm 2, line 14):
+ *   Y[j, :] = sum over experts e and kept channels c of  Lambda_e[j, c] * W_down,e[:, c],
+ *   Lambda_e[j, c] = a_j,e * silu(<w_gate_c, x_j>) * <w_up_c, x_j>           (Eq. 4)
+ * X, routing, weights, strides: as in camera_score_layer (CAMERA_BF16 only; d_ff and stride_down multiples of 8).
+ *   keep_mask  uint8 [n_experts * d_ff], 0 = pruned (gate row, up row and down column all drop out), or NULL:
+ *              every micro-expert kept (the original layer).  For the second group of a layer pass the
+ *              group's slice of camera_select_prune's keep_mask.
+ *   flags      0: Y is overwritten; CAMERA_ACCUMULATE: the group's output is added to Y (routed experts
+ *              first, then the shared ones into the same Y)
+ *   Y          float32 [n x d_model] in-out, rows contiguous
+ * Lambda is rounded to bf16 before the second contraction, as the hidden activations of a 16-bit model
+ * are; both contractions accumulate in float32, and a token's experts are added in the order of its
+ * top-k list (no floating-point atomics: the result does not depend on launch order).  The context
+ * workspace grows by n*top_k*(2*d_ff + 4*d_model) bytes.  n == 0 does nothing.
+ *
+ * camera_output_error: distance of a pruned layer's output from the original one, per token
+ *   per_token [n x 4] float32 out: ||y - y_hat||^2, ||y||^2, ||y_hat||^2, <y, y_hat>
+ * (their sums over tokens give the decoding error of the Lemma, ||Y - Y_hat||_F and the cosine
+ * similarity reported for hidden states after pruning).  Y, Y_hat [n x d_model] float32, rows contiguous.
+ */
+int camera_layer_forward(camera_ctx* ctx, void* stream,
+                         const void* X, int dtype, int64_t n, int64_t d_model, int64_t ldx,
+                         const int32_t* topk_idx, const float* topk_w, int top_k,
+                         int n_experts, int64_t d_ff,
+                         const void* W_gate, const void* W_up, int64_t stride_gu,
+                         const void* W_down, int64_t stride_down,
+                         const uint8_t* keep_mask, int flags, float* Y);
+int camera_output_error(camera_ctx* ctx, void* stream, const float* Y, const float* Y_hat,
+                        int64_t n, int64_t d_model, float* per_token);
 
 /*
  * Per-kernel-group timing for benchmarks.  With profiling on, every launch

@@ -17,11 +17,11 @@ LIB_PATH = os.path.join(HERE, "libcamera_hip.so")
 
 F32, BF16 = 0, 1
 ACCUMULATE, NO_FINALIZE = 1, 2
-K_ROUTE, K_BUCKET, K_GEMM, K_DOWN_NORM, K_FINALIZE, K_RANK, K_GATHER = range(7)
-KERNEL_NAMES = ["route", "bucket", "gemm", "down_norm", "finalize", "rank", "gather"]
+K_ROUTE, K_BUCKET, K_GEMM, K_DOWN_NORM, K_FINALIZE, K_RANK, K_GATHER, K_DOWN_GEMM, K_COMBINE = range(9)
+KERNEL_NAMES = ["route", "bucket", "gemm", "down_norm", "finalize", "rank", "gather", "down_gemm", "combine"]
 
 EXPORTS = ["camera_create", "camera_destroy", "camera_last_error", "camera_version", "camera_route_topk",
-           "camera_score_layer", "camera_select_prune", "camera_alloc_bits", "camera_gather_micro_experts",
+           "camera_score_layer", "camera_select_prune", "camera_alloc_bits", "camera_gather_micro_experts", "camera_layer_forward", "camera_output_error",
            "camera_profile_enable",
            "camera_profile_read", "camera_probe_mfma_bf16", "camera_probe_hbm_read"]
 
@@ -54,6 +54,9 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
                                       _c.POINTER(_d), _vp, _vp, _vp]
     lib.camera_gather_micro_experts.argtypes = [_vp, _vp, _i, _i, _i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, _i64,
                                                 _i64, _vp, _vp, _vp, _vp]
+    lib.camera_layer_forward.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _vp, _i, _i, _i64, _vp, _vp, _i64,
+                                         _vp, _i64, _vp, _i, _vp]
+    lib.camera_output_error.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _vp]
     lib.camera_profile_enable.argtypes = [_vp, _i]
     lib.camera_profile_read.argtypes = [_vp, _i, _c.POINTER(_d), _c.POINTER(_i64)]
     lib.camera_probe_mfma_bf16.argtypes = [_vp, _vp, _i, _i, _c.POINTER(_d), _c.POINTER(_d)]
@@ -180,6 +183,27 @@ class Camera:
             self._ctx, _stream_handle(self.device), _dtype_code(ref), n_experts, d_ff, d_model, _ptr(W_gate), _ptr(W_up),
             stride_gu, _ptr(W_down), W_down.stride(0) if W_down is not None else 0, _ptr(index), n_index,
             int(index_base), _ptr(count), _ptr(out[0]), _ptr(out[1]), _ptr(out[2])))
+        return out
+
+    def layer_forward(self, X, topk_idx, topk_w, W_gate, W_up, W_down, keep_mask=None, Y=None, accumulate=False):
+        """Layer output over the kept micro-experts of one group of experts (Eq. 1-2); Y float32 [n, d_model]."""
+        n, d = X.shape
+        n_experts, d_ff, _ = W_gate.shape
+        top_k = 0 if topk_idx is None else topk_idx.shape[1]
+        if Y is None:
+            Y = torch.empty((n, d), dtype=torch.float32, device=self.device)
+        self._check(self.lib.camera_layer_forward(
+            self._ctx, _stream_handle(self.device), _ptr(X), _dtype_code(X), n, d, X.stride(0), _ptr(topk_idx),
+            _ptr(topk_w), top_k, n_experts, d_ff, _ptr(W_gate), _ptr(W_up), W_gate.stride(0), _ptr(W_down),
+            W_down.stride(0), _ptr(keep_mask), ACCUMULATE if accumulate else 0, _ptr(Y)))
+        return Y
+
+    def output_error(self, Y, Y_hat):
+        """Per-token [n, 4]: ||y - y_hat||^2, ||y||^2, ||y_hat||^2, <y, y_hat>."""
+        n, d = Y.shape
+        out = torch.empty((n, 4), dtype=torch.float32, device=self.device)
+        self._check(self.lib.camera_output_error(self._ctx, _stream_handle(self.device), _ptr(Y), _ptr(Y_hat), n, d,
+                                                 _ptr(out)))
         return out
 
     # ---- profiling ---------------------------------------------------------

@@ -438,6 +438,7 @@ int camera_score_layer(camera_ctx* ctx, void* stream_, const void* X, int dtype,
   t.tile_expert = reinterpret_cast<int32_t*>(ws + o_tile_exp);
   t.perm = dense ? nullptr : reinterpret_cast<int32_t*>(ws + o_perm);
   t.w_perm = dense ? nullptr : reinterpret_cast<float*>(ws + o_wperm);
+  t.slot_of = nullptr;
   t.block_hist = reinterpret_cast<int32_t*>(ws + o_hist);
   t.zeros = ctx->zeros;
   float* part_phi2 = reinterpret_cast<float*>(ws + o_p2);
@@ -455,8 +456,11 @@ int camera_score_layer(camera_ctx* ctx, void* stream_, const void* X, int dtype,
   }
   if (n > 0) {
     Bracket b(ctx, stream, CAMERA_K_GEMM);
+    camera::GemmEpilogue ep;
+    ep.part_phi2 = part_phi2;
+    ep.part_max = part_max;
     CAMERA_HIP(camera::launch_grouped_gemm(stream, dtype, X, ldx, d_model, d_ff, n_experts, W_gate, W_up, stride_gu,
-                                           max_tiles, t, part_phi2, part_max),
+                                           max_tiles, t, ep),
                "grouped gemm launch");
   }
   if (finalize) {
@@ -471,6 +475,132 @@ int camera_score_layer(camera_ctx* ctx, void* stream_, const void* X, int dtype,
                                        accumulate ? 1 : 0, finalize ? 1 : 0, phi2, phi_inf, omega2, energy),
                "finalize launch");
   }
+  return CAMERA_OK;
+}
+
+int camera_layer_forward(camera_ctx* ctx, void* stream_, const void* X, int dtype, int64_t n, int64_t d_model,
+                         int64_t ldx, const int32_t* topk_idx, const float* topk_w, int top_k, int n_experts,
+                         int64_t d_ff, const void* W_gate, const void* W_up, int64_t stride_gu, const void* W_down,
+                         int64_t stride_down, const uint8_t* keep_mask, int flags, float* Y) {
+  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
+  if (int rc = check_common(ctx, X, dtype, n, d_model, ldx)) return rc;
+  if (dtype != CAMERA_BF16) return fail(ctx, CAMERA_EUNSUPPORTED, "dtype: the layer output is built for CAMERA_BF16 only");
+  const bool dense = topk_idx == nullptr && topk_w == nullptr;
+  if (!dense && (topk_idx == nullptr || topk_w == nullptr))
+    return fail(ctx, CAMERA_EINVAL, "topk_idx / topk_w: give both or neither");
+  if (n_experts < 1 || n_experts > CAMERA_MAX_EXPERTS)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "n_experts: must be in [1, %d]", CAMERA_MAX_EXPERTS);
+  if (!dense && (top_k < 1 || top_k > n_experts)) return fail(ctx, CAMERA_EINVAL, "top_k: must be in [1, n_experts]");
+  if (d_ff <= 0 || d_ff % 8 != 0) return fail(ctx, CAMERA_ESHAPE, "d_ff: must be a positive multiple of 8");
+  if (flags & ~CAMERA_ACCUMULATE) return fail(ctx, CAMERA_EINVAL, "flags: only CAMERA_ACCUMULATE is accepted");
+  if (W_gate == nullptr || W_up == nullptr || W_down == nullptr)
+    return fail(ctx, CAMERA_EINVAL, "W_gate / W_up / W_down: NULL");
+  if (n > 0 && Y == nullptr) return fail(ctx, CAMERA_EINVAL, "Y: NULL");
+  if (stride_gu < d_ff * d_model || stride_gu % 8 != 0)
+    return fail(ctx, CAMERA_ESHAPE, "stride_gu: must be >= d_ff*d_model and a multiple of 8");
+  if (stride_down < d_ff * d_model || stride_down % 8 != 0)
+    return fail(ctx, CAMERA_ESHAPE, "stride_down: must be >= d_model*d_ff and a multiple of 8");
+  if (!aligned16(W_gate) || !aligned16(W_up) || !aligned16(W_down) || !aligned16(Y))
+    return fail(ctx, CAMERA_ESHAPE, "W_gate / W_up / W_down / Y: not 16-byte aligned");
+  const int64_t n_micro = (int64_t)n_experts * d_ff;
+  if (n_micro >= (int64_t(1) << 31) - 1024) return fail(ctx, CAMERA_ESHAPE, "n_experts * d_ff: too large");
+  const int64_t n_pairs = dense ? n * n_experts : n * (int64_t)top_k;
+  if (n_pairs >= (int64_t(1) << 31) - 1024) return fail(ctx, CAMERA_ESHAPE, "routed pairs: must be below 2^31");
+  if (n == 0) return CAMERA_OK;
+
+  const int tile_m = camera::gemm_tile_m(dtype, d_ff);
+  const int64_t max_tiles64 = dense ? n_experts * ((n + tile_m - 1) / tile_m) : n_pairs / tile_m + n_experts;
+  if (max_tiles64 > 65535)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "too many token tiles (%lld) for one call: feed the tokens in chunks",
+                (long long)max_tiles64);
+  const int max_tiles = (int)max_tiles64;
+  const int64_t n_blocks = dense ? 0 : camera::bucket_blocks(n_pairs);
+
+  Carver cv;
+  const size_t o_counts = cv.take(sizeof(int32_t) * n_experts);
+  const size_t o_offsets = cv.take(sizeof(int32_t) * (n_experts + 1));
+  const size_t o_tile_off = cv.take(sizeof(int32_t) * (n_experts + 1));
+  const size_t o_tile_exp = cv.take(sizeof(int32_t) * (max_tiles + 1));
+  const size_t o_perm = cv.take(dense ? 0 : sizeof(int32_t) * n_pairs);
+  const size_t o_wperm = cv.take(dense ? 0 : sizeof(float) * n_pairs);
+  const size_t o_slot = cv.take(dense ? 0 : sizeof(int32_t) * n_pairs);
+  const size_t o_hist = cv.take(sizeof(int32_t) * n_blocks * n_experts);
+  const size_t o_hidden = cv.take(sizeof(uint16_t) * (size_t)n_pairs * d_ff);
+  const size_t o_product = cv.take(sizeof(float) * (size_t)n_pairs * d_model);
+
+  DeviceGuard guard;
+  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
+  if (int rc = ensure_workspace(ctx, cv.used)) return rc;
+  char* ws = static_cast<char*>(ctx->ws);
+  camera::BucketTables t;
+  t.counts = reinterpret_cast<int32_t*>(ws + o_counts);
+  t.offsets = reinterpret_cast<int32_t*>(ws + o_offsets);
+  t.tile_offset = reinterpret_cast<int32_t*>(ws + o_tile_off);
+  t.tile_expert = reinterpret_cast<int32_t*>(ws + o_tile_exp);
+  t.perm = dense ? nullptr : reinterpret_cast<int32_t*>(ws + o_perm);
+  t.w_perm = dense ? nullptr : reinterpret_cast<float*>(ws + o_wperm);
+  t.slot_of = dense ? nullptr : reinterpret_cast<int32_t*>(ws + o_slot);
+  t.block_hist = reinterpret_cast<int32_t*>(ws + o_hist);
+  t.zeros = ctx->zeros;
+  void* hidden = ws + o_hidden;
+  float* product = reinterpret_cast<float*>(ws + o_product);
+
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  {
+    Bracket b(ctx, stream, CAMERA_K_BUCKET);
+    if (dense)
+      CAMERA_HIP(camera::launch_dense_tables(stream, n, n_experts, tile_m, max_tiles, t), "dense tables launch");
+    else
+      CAMERA_HIP(camera::launch_bucket(stream, topk_idx, topk_w, n, top_k, n_experts, tile_m, max_tiles, t),
+                 "bucket launch");
+  }
+  {
+    Bracket b(ctx, stream, CAMERA_K_GEMM);
+    camera::GemmEpilogue ep;
+    ep.mode = camera::GemmEpilogue::kHidden;
+    ep.hidden = hidden;
+    ep.keep = keep_mask;
+    CAMERA_HIP(camera::launch_grouped_gemm(stream, dtype, X, ldx, d_model, d_ff, n_experts, W_gate, W_up, stride_gu,
+                                           max_tiles, t, ep),
+               "hidden gemm launch");
+  }
+  {
+    // Lambda W_down^T: the hidden activations are the left operand (K = d_ff); the two halves of W_down's rows
+    // (output columns [0, d_model/2) and [d_model/2, d_model)) take the places of the gate and the up matrix.
+    Bracket b(ctx, stream, CAMERA_K_DOWN_GEMM);
+    const int64_t half = d_model / 2;
+    camera::GemmEpilogue ep;
+    ep.mode = camera::GemmEpilogue::kProduct;
+    ep.product = product;
+    ep.ld_product = d_model;
+    ep.col_gap = (int)half;
+    const char* wd = static_cast<const char*>(W_down);
+    CAMERA_HIP(camera::launch_grouped_gemm(stream, dtype, hidden, d_ff, d_ff, half, n_experts, wd,
+                                           wd + sizeof(uint16_t) * half * d_ff, stride_down, max_tiles, t, ep),
+               "down gemm launch");
+  }
+  {
+    Bracket b(ctx, stream, CAMERA_K_COMBINE);
+    CAMERA_HIP(camera::launch_combine(stream, product, t.slot_of, n, top_k, n_experts, d_model,
+                                      (flags & CAMERA_ACCUMULATE) ? 1 : 0, Y),
+               "combine launch");
+  }
+  return CAMERA_OK;
+}
+
+int camera_output_error(camera_ctx* ctx, void* stream_, const float* Y, const float* Y_hat, int64_t n,
+                        int64_t d_model, float* per_token) {
+  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
+  if (n < 0 || d_model < 1) return fail(ctx, CAMERA_ESHAPE, "n / d_model: out of range");
+  if (n > 0 && (Y == nullptr || Y_hat == nullptr || per_token == nullptr))
+    return fail(ctx, CAMERA_EINVAL, "Y / Y_hat / per_token: NULL");
+  if (n == 0) return CAMERA_OK;
+  DeviceGuard guard;
+  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  Bracket b(ctx, stream, CAMERA_K_COMBINE);
+  CAMERA_HIP(camera::launch_output_error(stream, Y, Y_hat, n, d_model, d_model, d_model, per_token),
+             "output error launch");
   return CAMERA_OK;
 }
 

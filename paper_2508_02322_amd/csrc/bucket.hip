@@ -104,7 +104,8 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(const int32_t*
                                                                   const int32_t* __restrict__ block_base,
                                                                   const int32_t* __restrict__ offsets,
                                                                   int32_t* __restrict__ perm,
-                                                                  float* __restrict__ w_perm) {
+                                                                  float* __restrict__ w_perm,
+                                                                  int32_t* __restrict__ slot_of) {
   // next[w][e]: next free slot of expert e for wave w of this block
   __shared__ int32_t next[kWavesPerBlock][CAMERA_MAX_EXPERTS];
   const int wave = threadIdx.x / kWave;
@@ -160,6 +161,7 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(const int32_t*
       perm[slot] = (int32_t)(p / top_k);
       w_perm[slot] = topk_w[p];
     }
+    if (slot_of != nullptr && p < n_pairs) slot_of[p] = e >= 0 ? slot : -1;
   }
 }
 
@@ -189,7 +191,7 @@ hipError_t launch_bucket(hipStream_t stream, const int32_t* topk_idx, const floa
                      n_experts, tile_m, max_tiles, t.counts, t.offsets, t.tile_offset, t.tile_expert);
   if (n_blocks > 0)
     hipLaunchKernelGGL(bucket_scatter_kernel, dim3(n_blocks), dim3(kThreads), 0, stream, topk_idx, topk_w, n_pairs,
-                       top_k, n_experts, t.block_hist, t.offsets, t.perm, t.w_perm);
+                       top_k, n_experts, t.block_hist, t.offsets, t.perm, t.w_perm, t.slot_of);
   return hipGetLastError();
 }
 

@@ -21,6 +21,7 @@ struct BucketTables {
   int32_t* tile_expert;   // [max_tiles]        expert of each M-tile slot
   int32_t* perm;          // [P]                token id of each slot (NULL: identity per expert)
   float* w_perm;          // [P]                routing weight of each slot (NULL: 1)
+  int32_t* slot_of;       // [P]                slot of each (token, k) pair, -1 if its expert id is invalid (optional)
   int32_t* block_hist;    // [n_blocks x n_experts] scratch of the counting sort
   const void* zeros;      // 256 zero bytes (source of K-tail chunks for direct-to-LDS loads)
 };
@@ -46,11 +47,26 @@ hipError_t launch_dense_tables(hipStream_t stream, int64_t n, int n_experts, int
 // ---- gemm.hip ---------------------------------------------------------------
 // M-tile height used by the grouped contraction for `dtype`.
 int gemm_tile_m(int dtype, int64_t d_ff);
-// part_phi2 / part_max: [max_tiles x d_ff] per-M-tile column statistics.
+// What the contraction does with its two products G = X_e W_gate^T and U = X_e W_up^T:
+//   kStats   Lambda = a silu(G) U is reduced to per-M-tile column statistics part_phi2 / part_max [max_tiles x d_ff]
+//   kHidden  Lambda, zeroed where keep[e*d_ff + c] == 0 (keep may be NULL), is stored as bf16 in
+//            hidden[bucket slot][d_ff] (bf16 only)
+//   kProduct G goes to product[slot][c], U to product[slot][c + col_gap], row stride ld_product; in this mode X is
+//            indexed by bucket slot, not by token (the hidden activations are the left operand; bf16 only)
+struct GemmEpilogue {
+  enum Mode { kStats = 0, kHidden = 1, kProduct = 2 };
+  int mode = kStats;
+  float* part_phi2 = nullptr;
+  float* part_max = nullptr;
+  void* hidden = nullptr;
+  const uint8_t* keep = nullptr;
+  float* product = nullptr;
+  int64_t ld_product = 0;
+  int col_gap = 0;
+};
 hipError_t launch_grouped_gemm(hipStream_t stream, int dtype, const void* X, int64_t ldx, int64_t d_model,
                                int64_t d_ff, int n_experts, const void* W_gate, const void* W_up,
-                               int64_t stride_gu, int max_tiles, const BucketTables& t, float* part_phi2,
-                               float* part_max);
+                               int64_t stride_gu, int max_tiles, const BucketTables& t, const GemmEpilogue& ep);
 
 // ---- norm.hip ---------------------------------------------------------------
 // Row splits used for a [d_model x d_ff] matrix; omega_part is [splits x n_experts*d_ff].
@@ -88,6 +104,15 @@ hipError_t launch_segment_counts(hipStream_t stream, const uint8_t* class_out, c
 // Full stable ascending rank by LSD radix sort.
 hipError_t launch_full_rank(hipStream_t stream, const float* energy, int64_t n_micro, uint32_t* rank,
                             int32_t* ws);
+
+// ---- forward.hip -----------------------------------------------------------
+// Y[token] (+)= sum of the product rows of the token's slots (routed: slot_of[token*top_k + k], k ascending;
+// slot_of == nullptr: rows e*n + token for e ascending).  product is [pairs][d_model] float32, Y [n][d_model].
+hipError_t launch_combine(hipStream_t stream, const float* product, const int32_t* slot_of, int64_t n, int top_k,
+                          int n_experts, int64_t d_model, int accumulate, float* Y);
+// per_token [n][4] = ||y - y_hat||^2, ||y||^2, ||y_hat||^2, <y, y_hat>
+hipError_t launch_output_error(hipStream_t stream, const float* Y, const float* Y_hat, int64_t n, int64_t d_model,
+                               int64_t ldy, int64_t ldh, float* per_token);
 
 // Gather of kept micro-experts (gather.hip).  off: [n_experts + 1] exclusive prefix of the per-expert
 // entry counts (count == nullptr: d_ff each), written by launch_gather_offsets.

@@ -68,6 +68,22 @@ constexpr int kPatch = 32;     // workgroups an XCD runs at a time (one per CU)
 constexpr int kChunkMax = 6;   // an expert with up to this many M-tiles runs them all side by side
 constexpr int kChunkM = 4;     // otherwise this many
 
+// What a tile does with its two accumulator sets (named gate and up after their main use).
+//   kEpiStats   : Lambda = a * silu(gate) * up, column sums of Lambda^2 and column maxima -> part_phi2 / part_max
+//   kEpiHidden  : the same Lambda, times the keep flag of its micro-expert, rounded to bf16 -> hidden[slot row][channel]
+//   kEpiProduct : the plain products -> product[slot row][column] (first B matrix) and [column + col_gap] (second);
+//                 the token rows of this mode are the bucket slots themselves (A = the hidden activations)
+enum { kEpiStats = 0, kEpiHidden = 1, kEpiProduct = 2 };
+struct EpiArgs {
+  float* part_phi2;
+  float* part_max;
+  __hip_bfloat16* hidden;  // [pairs][d_ff]
+  const uint8_t* keep;     // [n_experts * d_ff] or nullptr (all kept)
+  float* product;          // [pairs][ld_product]
+  int64_t ld_product;
+  int col_gap;
+};
+
 template <int WM_, int WN_, int TM_, int TN_, int KT_, int STAGES_>
 struct GemmCfg {
   static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_, KT = KT_, kStages = STAGES_;
@@ -145,15 +161,15 @@ struct TileState {
   int a_frag_base, b_frag_base;
   int k_swz[C::kSteps];
   int wave_m, wave_n, frag_row, frag_half;
+  int expert, m_len, row_first;  // for the epilogues that write per token row
 };
 
 // ACT: active 32-row blocks of this wave's accumulators.  DEAD: every token row that this wave
 // loads lies past the end of the expert's bucket (a short last tile); such rows only have to hold
 // finite values (their routing weight is 0), so they are loaded once, in the prologue, and
 // the K loop skips their loads.
-template <class C, int ACT, bool TAIL, bool DEAD>
-__device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_ff, int slot,
-                                          float* __restrict__ part_phi2, float* __restrict__ part_max) {
+template <class C, int ACT, bool TAIL, bool DEAD, int EPI>
+__device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_ff, int slot, const EpiArgs& ep) {
   constexpr int BN = C::BN, TN = C::TN, WM = C::WM, KT = C::KT;
   constexpr int NA = ACT > 0 ? ACT : 1;
   unsigned char* const smem = st.smem;
@@ -296,6 +312,32 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
 
   // Epilogue.  Accumulator register r of lane l is output row 8*(r/4) + 4*(l/32) + (r%4),
   // column l % 32 of its 32x32 tile: a lane owns one channel and 16 token rows per tile.
+  if constexpr (EPI != kEpiStats) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + st.wave_n * TN * 32 + j * 32 + st.frag_row;
+      if (col >= d_ff) continue;
+      float kept = 1.0f;
+      if constexpr (EPI == kEpiHidden) kept = (ep.keep == nullptr || ep.keep[(int64_t)st.expert * d_ff + col]) ? 1.0f : 0.0f;
+#pragma unroll
+      for (int i = 0; i < ACT; ++i) {
+        const int band = (WM * i + st.wave_m) * 32 + st.frag_half * 4;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = band + (r / 4) * 8 + (r % 4);
+          if (row >= st.m_len) continue;
+          const int64_t out_row = st.row_first + row;
+          if constexpr (EPI == kEpiHidden) {
+            const float lam = st.s_a[row] * silu_f32(acc_g[i][j][r]) * acc_u[i][j][r] * kept;
+            ep.hidden[out_row * d_ff + col] = __float2bfloat16(lam);
+          } else {
+            ep.product[out_row * ep.ld_product + col] = acc_g[i][j][r];
+            ep.product[out_row * ep.ld_product + col + ep.col_gap] = acc_u[i][j][r];
+          }
+        }
+      }
+    }
+  } else {
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     float sum = 0.0f, mx = 0.0f;
@@ -328,20 +370,20 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
         sum += st.s_red[w * BN + col];
         mx = fmaxf(mx, st.s_red[(WM + w) * BN + col]);
       }
-      part_phi2[(int64_t)slot * d_ff + n0 + col] = sum;
-      part_max[(int64_t)slot * d_ff + n0 + col] = mx;
+      ep.part_phi2[(int64_t)slot * d_ff + n0 + col] = sum;
+      ep.part_max[(int64_t)slot * d_ff + n0 + col] = mx;
     }
   }
+  }  // statistics epilogue
 }
 
-template <class C, bool TAIL>
+template <class C, bool TAIL, int EPI>
 __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf16_kernel(
     const __hip_bfloat16* __restrict__ X, int64_t ldx, int d_model, int d_ff,
     const __hip_bfloat16* __restrict__ Wg, const __hip_bfloat16* __restrict__ Wu, int64_t stride_gu,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_offset,
     const int32_t* __restrict__ tile_expert, const int32_t* __restrict__ perm, const float* __restrict__ w_perm,
-    int n_experts, const __hip_bfloat16* __restrict__ zeros, float* __restrict__ part_phi2,
-    float* __restrict__ part_max) {
+    int n_experts, const __hip_bfloat16* __restrict__ zeros, EpiArgs ep) {
   constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN, WM = C::WM;
   // Workgroup -> tile mapping.  The hardware deals consecutive workgroup ids round-robin to the 8
   // XCDs, each with its own L2 and 32 CUs, and an XCD starts its workgroups in id order.  Every
@@ -387,7 +429,8 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
   // their Lambda is exactly 0 (finite projections times a = 0), so no load in the K loop is conditional.
   for (int r = tid; r < BM; r += C::kThreads) {
     const int rr = r < m_len ? r : 0;
-    s_tok[r] = perm ? perm[row_first + rr] : tile_in_expert * BM + rr;
+    if constexpr (EPI == kEpiProduct) s_tok[r] = row_first + rr;  // A rows are the bucket slots themselves
+    else s_tok[r] = perm ? perm[row_first + rr] : tile_in_expert * BM + rr;
     s_a[r] = r < m_len ? (w_perm ? w_perm[row_first + rr] : 1.0f) : 0.0f;
   }
   __syncthreads();
@@ -402,6 +445,9 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
   st.wave_n = wave / WM;
   st.frag_row = lane % 32;
   st.frag_half = lane / 32;
+  st.expert = e;
+  st.m_len = m_len;
+  st.row_first = row_first;
   // direct-to-LDS sources of this lane
   const int a_row0 = wave * (BM / C::kWaves), b_row0 = wave * (BN / C::kWaves);
   st.a_lds = a_row0 * C::kRowBytes;
@@ -438,10 +484,10 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
   static_assert(TM == 4 || TM == 2 || TM == 1, "dispatch below covers TM = 1, 2 and 4");
 #define CAMERA_TILE_BODY(A)                                                              \
   do {                                                                                   \
-    if (dead) tile_body<C, (A), TAIL, true>(st, n0, d_ff, slot, part_phi2, part_max);    \
-    else tile_body<C, (A), TAIL, false>(st, n0, d_ff, slot, part_phi2, part_max);        \
+    if (dead) tile_body<C, (A), TAIL, true, EPI>(st, n0, d_ff, slot, ep);                \
+    else tile_body<C, (A), TAIL, false, EPI>(st, n0, d_ff, slot, ep);                    \
   } while (0)
-  if (act >= TM) tile_body<C, TM, TAIL, false>(st, n0, d_ff, slot, part_phi2, part_max);
+  if (act >= TM) tile_body<C, TM, TAIL, false, EPI>(st, n0, d_ff, slot, ep);
   else if (act == 3) CAMERA_TILE_BODY((TM > 3 ? 3 : 0));
   else if (act == 2) CAMERA_TILE_BODY((TM > 2 ? 2 : 0));
   else if (act == 1) CAMERA_TILE_BODY((TM > 1 ? 1 : 0));
@@ -566,38 +612,55 @@ int gemm_tile_m(int dtype, int64_t d_ff) {
   return dtype == CAMERA_BF16 ? Bf16Cfg::BM : F32_BM;
 }
 
+template <int EPI>
+static hipError_t launch_bf16(hipStream_t stream, const void* X, int64_t ldx, int64_t d_model, int64_t d_ff,
+                              int n_experts, const void* W_gate, const void* W_up, int64_t stride_gu, int max_tiles,
+                              const BucketTables& t, const EpiArgs& ep) {
+  using C = Bf16Cfg;
+  const bool tail = d_model % C::KT != 0;
+  auto kern = tail ? grouped_gemm_bf16_kernel<C, true, EPI> : grouped_gemm_bf16_kernel<C, false, EPI>;
+  static bool attr_set[2] = {false, false};
+  if (!attr_set[tail]) {
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, C::kSmemBytes);
+    if (err != hipSuccess) return err;
+    attr_set[tail] = true;
+  }
+  const int64_t n_tiles_n = (d_ff + C::BN - 1) / C::BN;
+  const int64_t n_blocks = (max_tiles * n_tiles_n + kXcds - 1) / kXcds * kXcds;
+  if (n_blocks >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+  dim3 grid((unsigned)n_blocks);
+  hipLaunchKernelGGL(kern, grid, dim3(C::kThreads), C::kSmemBytes, stream, static_cast<const __hip_bfloat16*>(X), ldx,
+                     (int)d_model, (int)d_ff, static_cast<const __hip_bfloat16*>(W_gate),
+                     static_cast<const __hip_bfloat16*>(W_up), stride_gu, t.offsets, t.tile_offset, t.tile_expert,
+                     t.perm, t.w_perm, n_experts, static_cast<const __hip_bfloat16*>(t.zeros), ep);
+  return hipGetLastError();
+}
+
 hipError_t launch_grouped_gemm(hipStream_t stream, int dtype, const void* X, int64_t ldx, int64_t d_model,
                                int64_t d_ff, int n_experts, const void* W_gate, const void* W_up,
-                               int64_t stride_gu, int max_tiles, const BucketTables& t, float* part_phi2,
-                               float* part_max) {
+                               int64_t stride_gu, int max_tiles, const BucketTables& t, const GemmEpilogue& e) {
   if (max_tiles <= 0) return hipSuccess;
   if (dtype == CAMERA_BF16) {
-    using C = Bf16Cfg;
-    const bool tail = d_model % C::KT != 0;
-    auto kern = tail ? grouped_gemm_bf16_kernel<C, true> : grouped_gemm_bf16_kernel<C, false>;
-    static bool attr_set[2] = {false, false};
-    if (!attr_set[tail]) {
-      hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kSmemBytes);
-      if (err != hipSuccess) return err;
-      attr_set[tail] = true;
+    EpiArgs ep{e.part_phi2, e.part_max, static_cast<__hip_bfloat16*>(e.hidden), e.keep, e.product, e.ld_product,
+               e.col_gap};
+    switch (e.mode) {
+      case GemmEpilogue::kStats:
+        return launch_bf16<kEpiStats>(stream, X, ldx, d_model, d_ff, n_experts, W_gate, W_up, stride_gu, max_tiles, t, ep);
+      case GemmEpilogue::kHidden:
+        return launch_bf16<kEpiHidden>(stream, X, ldx, d_model, d_ff, n_experts, W_gate, W_up, stride_gu, max_tiles, t, ep);
+      case GemmEpilogue::kProduct:
+        return launch_bf16<kEpiProduct>(stream, X, ldx, d_model, d_ff, n_experts, W_gate, W_up, stride_gu, max_tiles, t, ep);
+      default:
+        return hipErrorInvalidValue;
     }
-    const int64_t n_tiles_n = (d_ff + C::BN - 1) / C::BN;
-    const int64_t n_blocks = (max_tiles * n_tiles_n + kXcds - 1) / kXcds * kXcds;
-    if (n_blocks >= (int64_t(1) << 31)) return hipErrorInvalidValue;
-    dim3 grid((unsigned)n_blocks);
-    hipLaunchKernelGGL(kern, grid, dim3(C::kThreads), C::kSmemBytes, stream,
-                       static_cast<const __hip_bfloat16*>(X), ldx, (int)d_model, (int)d_ff,
-                       static_cast<const __hip_bfloat16*>(W_gate), static_cast<const __hip_bfloat16*>(W_up),
-                       stride_gu, t.offsets, t.tile_offset, t.tile_expert, t.perm, t.w_perm, n_experts,
-                       static_cast<const __hip_bfloat16*>(t.zeros), part_phi2, part_max);
-  } else {
-    dim3 grid((unsigned)((d_ff + F32_BN - 1) / F32_BN), (unsigned)max_tiles);
-    hipLaunchKernelGGL(grouped_gemm_f32_kernel, grid, dim3(256), 0, stream, static_cast<const float*>(X), ldx,
-                       (int)d_model, (int)d_ff, static_cast<const float*>(W_gate), static_cast<const float*>(W_up),
-                       stride_gu, t.offsets, t.tile_offset, t.tile_expert, t.perm, t.w_perm, n_experts, part_phi2,
-                       part_max);
   }
+  if (e.mode != GemmEpilogue::kStats) return hipErrorNotSupported;  // the float32 kernel only has the statistics epilogue
+  dim3 grid((unsigned)((d_ff + F32_BN - 1) / F32_BN), (unsigned)max_tiles);
+  hipLaunchKernelGGL(grouped_gemm_f32_kernel, grid, dim3(256), 0, stream, static_cast<const float*>(X), ldx,
+                     (int)d_model, (int)d_ff, static_cast<const float*>(W_gate), static_cast<const float*>(W_up),
+                     stride_gu, t.offsets, t.tile_offset, t.tile_expert, t.perm, t.w_perm, n_experts, e.part_phi2,
+                     e.part_max);
   return hipGetLastError();
 }
 

@@ -180,3 +180,31 @@ def test_gather_argument_checks(lib, ctx):
     assert gather(base=-1) == -1
     assert gather(n_index=0) == 0                      # nothing to do
     assert gather(og=None, ou=None, od=None) == 0      # every output skipped
+
+
+def test_layer_forward_and_output_error_argument_checks(lib, ctx):
+    vpp = ctypes.c_void_p
+    fake = vpp(4096)
+    def forward(x=fake, dtype=1, n=16, d_model=64, ldx=64, idx=fake, w=fake, top_k=2, n_experts=4, d_ff=32, wg=fake,
+                wu=fake, stride_gu=32 * 64, wd=fake, stride_down=32 * 64, keep=None, flags=0, y=fake, c=ctx):
+        return lib.camera_layer_forward(c, None, x, dtype, n, d_model, ldx, idx, w, top_k, n_experts, d_ff, wg, wu,
+                                        stride_gu, wd, stride_down, keep, flags, y)
+    lib.camera_layer_forward.restype = ctypes.c_int
+    assert forward(c=None) == -1
+    assert forward(dtype=0) == -6 and "BF16" in err(lib, ctx)
+    assert forward(idx=None) == -1 and "both or neither" in err(lib, ctx)
+    assert forward(top_k=0) == -1 and forward(top_k=5) == -1
+    assert forward(n_experts=0) == -6
+    assert forward(d_ff=12) == -2 and "multiple of 8" in err(lib, ctx)
+    assert forward(flags=2) == -1 and "flags" in err(lib, ctx)
+    assert forward(wd=None) == -1
+    assert forward(y=None) == -1 and "Y" in err(lib, ctx)
+    assert forward(stride_gu=100) == -2 and forward(stride_down=100) == -2
+    assert forward(y=vpp(4100)) == -2
+    assert forward(n=0) == 0
+    def error(y=fake, yh=fake, n=4, d=8, out=fake, c=ctx):
+        return lib.camera_output_error(c, None, y, yh, n, d, out)
+    assert error(c=None) == -1
+    assert error(n=-1) == -2 and error(d=0) == -2
+    assert error(y=None) == -1 and error(out=None) == -1
+    assert error(n=0) == 0
