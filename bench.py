@@ -52,6 +52,8 @@ def parse_args():
     ap.add_argument("--chunk-tokens", type=int, default=0, help="chunk size for --calib-tokens (default: the configuration's token count)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the measured MFMA / HBM ceilings (about 1 s)")
+    ap.add_argument("--no-forward", action="store_true",
+                    help="skip the measurement of the pruned layer's output and its decoding error")
     ap.add_argument("--no-apply", action="store_true",
                     help="skip the measurement of applying a 40 %% mask (gather of the kept micro-experts)")
     return ap.parse_args()
@@ -146,6 +148,69 @@ def measure_apply(cam, cfg, layers, torch, binding, ratio=0.4, reps=3):
     return {"what": f"gather of the kept micro-experts at lambda = {ratio} (Algorithm 2, lines 10-13), {len(use)} layers",
             "ms_per_layer": round(ms_per_layer, 4), "bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0,
             "unit": "GB/s", "frac": round(gbs / 8000.0, 4), "algorithmic_bytes_per_layer": bytes_per_layer}
+
+
+def measure_forward(cam, cfg, layers, torch, binding, ratio=0.4, reps=3):
+    """Output of the original and of the pruned layer (CAMERA-P mask at lambda = ratio) and their distance, for up
+    to two layers, outside the timed step.  Roofline: the second contraction Lambda W_down^T on the MFMA peak,
+    algorithmic flops = 2 * d_ff * d_model per routed (token, expert) pair (+ per token and shared expert)."""
+    if cfg.dtype != "bf16":
+        return None
+    use = layers[:2]
+    n, d = cfg.n_tokens, cfg.d_model
+    Y = torch.empty((n, d), dtype=torch.float32, device="cuda")
+    Y_hat = torch.empty_like(Y)
+    nr = cfg.n_micro_routed
+    stats = []
+
+    def forward(lr, keep, out):
+        t = lr.t
+        X = t["X"][:n]
+        idx, w = cam.route_topk(X, t["W_r"], t["bias"], cfg.top_k)
+        cam.layer_forward(X, idx, w, t["W_gate"], t["W_up"], t["W_down"], keep_mask=None if keep is None else keep[:nr], Y=out)
+        if cfg.n_shared:
+            cam.layer_forward(X, None, None, t["Ws_gate"], t["Ws_up"], t["Ws_down"],
+                              keep_mask=None if keep is None else keep[nr:], Y=out, accumulate=True)
+
+    def run(record):
+        for lr in use:
+            keep = cam.select_prune(lr.out["energy"], lr.seg, ratio)[0]
+            forward(lr, None, Y)
+            forward(lr, keep, Y_hat)
+            per_token = cam.output_error(Y, Y_hat)
+            if record:
+                s4 = per_token.double().sum(dim=0).tolist()
+                pruned = keep == 0
+                e_sum = float((lr.out["phi2"].double() * lr.out["omega2"].double())[pruned].sum())
+                stats.append({"l2": s4[0] ** 0.5, "cosine": s4[3] / max((s4[1] * s4[2]) ** 0.5, 1e-300),
+                              "decoding_error_over_sum_of_pruned_energies_alpha0": s4[0] / max(e_sum, 1e-300)})
+
+    run(False)
+    torch.cuda.synchronize()
+    for k in range(len(binding.KERNEL_NAMES)):
+        cam.profile_read(k)
+    cam.profile_enable(True)
+    for r in range(reps):
+        run(r == 0)
+    torch.cuda.synchronize()
+    cam.profile_enable(False)
+    ms = {name: cam.profile_read(k) for k, name in enumerate(binding.KERNEL_NAMES)}
+    launches = max(1, ms["down_gemm"][1])
+    down_ms = ms["down_gemm"][0] / launches
+    pairs = n * cfg.top_k
+    flops_routed = 2.0 * cfg.d_ff * d * pairs
+    flops_shared = 2.0 * cfg.d_ff_shared * d * n * cfg.n_shared
+    calls_per_forward = 2 if cfg.n_shared else 1
+    flops_per_launch = (flops_routed + flops_shared) / calls_per_forward
+    achieved = flops_per_launch / (down_ms * 1e-3) / 1e12
+    forwards = 2 * reps * len(use)
+    return {"what": f"layer output of the original and of the pruned layer (lambda = {ratio}) and their distance, {len(use)} layers",
+            "ms_per_layer_output": round(sum(ms[k][0] for k in ("route", "bucket", "gemm", "down_gemm", "combine")) / forwards, 3),
+            "kernel_ms_per_launch": {k: round(ms[k][0] / max(1, ms[k][1]), 4) for k in ("gemm", "down_gemm", "combine")},
+            "roofline": {"kernel": "grouped_gemm_bf16 (Lambda W_down^T)", "bound": "mfma", "achieved": round(achieved, 1),
+                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                         "flops_per_launch": flops_per_launch, "avg_launch_ms": round(down_ms, 4)},
+            "synthetic_layers": stats}
 
 
 def cpu_baseline(cfg, inputs):
@@ -265,6 +330,7 @@ def main():
             "achieved_over_random_operand_ceiling": round(achieved / tf_rand, 4) if bf16 and tf_rand > 0 else None}
 
     apply_mask = None if args.no_apply else measure_apply(cam, cfg, layers, torch, binding)
+    forward = None if (args.no_forward or calib_tokens != cfg.n_tokens) else measure_forward(cam, cfg, layers, torch, binding)
 
     ms_per_step = elapsed / args.steps * 1e3
     value = calib_tokens * n_layers * args.steps / elapsed
@@ -285,6 +351,8 @@ def main():
     }
     if apply_mask is not None:
         result["apply_mask"] = apply_mask
+    if forward is not None:
+        result["pruned_layer_output"] = forward
     if not args.no_cpu_baseline:
         del layers
         torch.cuda.empty_cache()
