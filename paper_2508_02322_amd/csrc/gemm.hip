@@ -107,10 +107,11 @@ struct GemmCfg {
   // workgroups that fit one CU by LDS (160 KiB), hence waves per SIMD the registers must allow
   static constexpr int kBlocksPerCu = (160 * 1024) / kSmemBytes >= 2 ? 2 : 1;
   static constexpr int kWavesPerSimd = kBlocksPerCu * kWaves / 4 > 0 ? kBlocksPerCu * kWaves / 4 : 1;
-  // Issue slots: a K step is two slots, slot 0 is the first one behind the barrier.  The loads of
+  // Issue slots: a K step is kParts slots, slot 0 is the first one behind the barrier.  The loads of
   // a tile are dealt evenly over the first half of the slots (extra ones in the middle); the second
   // half stays empty, which is the time the youngest load has to land before the next barrier.
-  static constexpr int kSlots = 2 * kSteps;
+  static constexpr int kParts = (2 * TM * TN) / 4 > 1 ? (2 * TM * TN) / 4 : 1;  // slots per K step: four MFMAs each
+  static constexpr int kSlots = kParts * kSteps;
   static constexpr int kBusySlots = kSlots >= 2 ? kSlots / 2 : 1;
   static constexpr int issue_count(int p) {
     if (p < 0 || p >= kBusySlots) return 0;
@@ -129,7 +130,7 @@ struct GemmCfg {
   static_assert(kADma >= 1 && kBDma >= 1 && BM % (kWaves * kDmaRows) == 0 && BN % (kWaves * kDmaRows) == 0,
                 "every wave fills whole 1 KiB groups");
   static_assert(kSmemBytes <= 160 * 1024, "LDS per workgroup");
-  static_assert(kADma <= 4 && kBDma <= 4, "immediate offsets 1024 j must stay below 4096");
+  static_assert(kADma <= 8 && kBDma <= 8, "two LDS bases of four immediate offsets each");
 };
 
 // LDS image of a tile: row r is kRowBytes long; its 16-byte chunk c sits at chunk position
@@ -182,11 +183,13 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
   // j-th group of a wave uses immediate 1024 j on sources that were moved back by 1024 j bytes at
   // set-up: one LDS base (M0) per matrix and tile instead of one per instruction.
   auto dma = [&](const __hip_bfloat16* src, int k, int k0, unsigned char* dst, auto group) {
-    constexpr int kOff = decltype(group)::value * 1024;
+    // immediate offsets reach 4095 bytes: groups 0-3 use the base, groups 4-7 the base + 4096
+    constexpr int kOff = (decltype(group)::value % 4) * 1024;
+    constexpr int kBase = (decltype(group)::value / 4) * 4096;
     const unsigned char* p = reinterpret_cast<const unsigned char*>(src + k0);
     if constexpr (TAIL) p = (k0 + k < st.d_model) ? p : reinterpret_cast<const unsigned char*>(st.zeros) - kOff;
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
-                                     (__attribute__((address_space(3))) void*)dst, 16, kOff, 0);
+                                     (__attribute__((address_space(3))) void*)(dst + kBase), 16, kOff, 0);
   };
   // Load d of a tile's kLoadsPerTile wave instructions: the token groups first, then the gate
   // groups, then the up groups (loads that share an LDS base follow each other).
@@ -254,7 +257,7 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
 
   // Ring schedule.  kStages tiles are in LDS or on their way; the barrier of iteration kt says that
   // tile kt + 1 has landed and that nobody reads tile kt's stage any more, so tile kt + kStages goes
-  // into that stage.  Its loads are not issued in one go: a K step is two issue slots (half of the
+  // into that stage.  Its loads are not issued in one go: a K step is kParts issue slots (four of the
   // step's MFMAs each), the barrier sits before the last K step, and slot P counted from the barrier
   // issues its share C::issue_begin(P) .. of the loads behind its MFMAs.  The order is pinned with
   // scheduling barriers.  Back-to-back loads fill the wave's vector-memory queue and stall its
@@ -265,22 +268,21 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
   const int n_k = (st.d_model + KT - 1) / KT;
   const int k_last = (n_k - 1) * KT;
   constexpr int kMayFly = (C::kStages - 2) * C::kLoadsPerTile;  // loads younger than tile kt + 1
-  constexpr int kHalf = ACT * TN, kFull = 2 * ACT * TN;         // MFMAs of half a K step, of a K step
+  constexpr int kFull = 2 * ACT * TN;                           // MFMAs of a K step
   using std::integral_constant;
   Frags f[2];
-  // the tile whose loads are under way after the prologue: slots 0 and 1 here, the rest in the first iteration
+  // the tile whose loads are under way after the prologue: the slots of one K step here, the rest in the first iteration
   int fill_stage = C::kStages - 1, fill_k = min((C::kStages - 1) * KT, k_last);
   if constexpr (DEAD)  // first of all (oldest): the one-time fill of the token rows that the loop never loads
     static_for<0, C::kADma>([&](auto d) { dma_one(fill_stage, fill_k, d); });
 #pragma unroll
   for (int t = 0; t + 1 < C::kStages; ++t)
     static_for<0, C::kLoadsPerTile>([&](auto d) { dma_one(t, min(t * KT, k_last), d); });
-  dma_slot(fill_stage, fill_k, integral_constant<int, 0>{});
-  dma_slot(fill_stage, fill_k, integral_constant<int, 1>{});
-  // loads issued by slots 0 and 1 (they may still fly; loads return in order, so tile 0 has landed)
-  constexpr int kSlots01 = DEAD ? C::issue_begin(2) - (C::issue_begin(2) < C::kADma ? C::issue_begin(2) : C::kADma)
-                                : C::issue_begin(2);
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly + kSlots01) : "memory");
+  static_for<0, C::kParts>([&](auto p) { dma_slot(fill_stage, fill_k, p); });
+  // loads issued by these first slots (they may still fly; loads return in order, so tile 0 has landed)
+  constexpr int kFirst = C::issue_begin(C::kParts);
+  constexpr int kSlotsFirst = DEAD ? kFirst - (kFirst < C::kADma ? kFirst : C::kADma) : kFirst;
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly + kSlotsFirst) : "memory");
   __syncthreads();
   read_frags(f[0], 0, 0);
   int stage = 0;  // stage of tile kt
@@ -289,7 +291,7 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
     static_for<0, C::kSteps>([&](auto step) {
       constexpr int ks = decltype(step)::value;
       constexpr bool last = ks + 1 == C::kSteps;
-      constexpr int P = last ? 0 : 2 * ks + 2;  // issue slot of this step's first half
+      constexpr int P = last ? 0 : C::kParts * (ks + 1);  // issue slot of this step's first part
       if constexpr (!last) {
         read_frags(f[(ks + 1) & 1], stage, ks + 1);
       } else {
@@ -299,12 +301,13 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
         fill_k = min((kt + C::kStages) * KT, k_last);
         read_frags(f[(ks + 1) & 1], next, 0);
       }
-      mfma_range(f[ks & 1], integral_constant<int, 0>{}, integral_constant<int, kHalf>{});
-      dma_slot(fill_stage, fill_k, integral_constant<int, P>{});
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_range(f[ks & 1], integral_constant<int, kHalf>{}, integral_constant<int, kFull>{});
-      dma_slot(fill_stage, fill_k, integral_constant<int, P + 1>{});
-      __builtin_amdgcn_sched_barrier(0);
+      static_for<0, C::kParts>([&](auto part) {
+        constexpr int q = decltype(part)::value;
+        mfma_range(f[ks & 1], integral_constant<int, kFull * q / C::kParts>{},
+                   integral_constant<int, kFull * (q + 1) / C::kParts>{});
+        dma_slot(fill_stage, fill_k, integral_constant<int, P + q>{});
+        __builtin_amdgcn_sched_barrier(0);
+      });
     });
     stage = next;
   }
@@ -457,7 +460,7 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
     const int row = a_row0 + j * C::kDmaRows + lane / C::kChunks;
     const int ck = (lane % C::kChunks) ^ swizzle_key<C>(row);
     st.a_k[j] = ck * 8;
-    st.a_src[j] = X + (int64_t)s_tok[row] * ldx + ck * 8 - j * 512;  // immediate offset 1024 j bytes comes back
+    st.a_src[j] = X + (int64_t)s_tok[row] * ldx + ck * 8 - (j % 4) * 512;  // the immediate offset 1024 (j % 4) bytes comes back
   }
 #pragma unroll
   for (int j = 0; j < C::kBDma; ++j) {
@@ -466,8 +469,8 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
     const int c = min(n0 + row, d_ff - 1);  // channels past d_ff read the last channel again; never written
     const int64_t off = (int64_t)e * stride_gu + (int64_t)c * d_model + ck * 8;
     st.b_k[j] = ck * 8;
-    st.g_src[j] = Wg + off - j * 512;
-    st.u_src[j] = Wu + off - j * 512;
+    st.g_src[j] = Wg + off - (j % 4) * 512;
+    st.u_src[j] = Wu + off - (j % 4) * 512;
   }
   // Fragments: lane l holds tile row (l % 32), K elements 8*(l / 32) .. +7 of a 16-wide K step.
   // swizzle_key(row) only depends on row % 32 here (32-row blocks), so one key per lane.
