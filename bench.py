@@ -74,6 +74,7 @@ class LayerRunner:
         self.out_routed = {k: v[:nr] for k, v in self.out.items()}
         self.out_shared = {k: v[nr:] for k, v in self.out.items()}
         self.seg = inputs.segment_offsets(cfg)
+        self.prune_out = None
 
     def run(self, cam, decisions, binding):
         cfg, t = self.cfg, self.t
@@ -87,8 +88,8 @@ class LayerRunner:
                 cam.score_layer(X, None, None, t["Ws_gate"], t["Ws_up"], t["Ws_down"], cfg.alpha, flags=flags,
                                 out=self.out_shared)
         res = []
-        for ratio in decisions["prune"]:
-            res.append(cam.select_prune(self.out["energy"], self.seg, ratio))
+        if decisions["prune"]:   # every CAMERA-P mask of the workload from one pass over the ranking
+            res.append(cam.select_prune_multi(self.out["energy"], self.seg, decisions["prune"], out=self.prune_out))
         for bits, ratios in decisions["alloc"]:
             res.append(cam.alloc_bits(self.out["energy"], self.seg, bits, ratios))
         return res

@@ -167,6 +167,20 @@ int camera_select_prune(camera_ctx* ctx, void* stream,
                         int32_t* kept_idx, uint32_t* rank);
 
 /*
+ * TopSelect at several ratios from one pass over the ranking (the masks at 20 / 40 / 60 % of "Main Results"
+ * come from one set of scores).  Same order and counts as camera_select_prune.
+ *   ratios          HOST [n_ratios], each in [0, 1], not falling; n_ratios <= CAMERA_MAX_LEVELS - 1
+ *   keep_bits       uint8 [n_micro] out: bit k is set iff the micro-expert is kept at ratios[k]
+ *                   (bit k of element i == keep_mask[i] of camera_select_prune at ratios[k])
+ *   kept_per_expert int32 [n_ratios x n_seg] out: row k = kept_per_expert of camera_select_prune at ratios[k]
+ */
+int camera_select_prune_multi(camera_ctx* ctx, void* stream,
+                              const float* energy, int64_t n_micro,
+                              const int64_t* seg_offsets, int n_seg,
+                              int n_ratios, const double* ratios,
+                              uint8_t* keep_bits, int32_t* kept_per_expert);
+
+/*
  * S_1..S_L = ListSplitByRatio(R, r_1..r_L) and the per-expert GetSubIndex --
  * Algorithm 3 (CAMERA-Q), lines 5-8; precision levels and proportions as in the
  * appendix "Mixed-precision Settings".  Class 0 is the fraction ratios[0] with

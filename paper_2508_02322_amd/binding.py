@@ -21,8 +21,8 @@ K_ROUTE, K_BUCKET, K_GEMM, K_DOWN_NORM, K_FINALIZE, K_RANK, K_GATHER, K_DOWN_GEM
 KERNEL_NAMES = ["route", "bucket", "gemm", "down_norm", "finalize", "rank", "gather", "down_gemm", "combine"]
 
 EXPORTS = ["camera_create", "camera_destroy", "camera_last_error", "camera_version", "camera_route_topk",
-           "camera_score_layer", "camera_select_prune", "camera_alloc_bits", "camera_gather_micro_experts", "camera_layer_forward", "camera_output_error",
-           "camera_profile_enable",
+           "camera_score_layer", "camera_select_prune", "camera_select_prune_multi", "camera_alloc_bits",
+           "camera_gather_micro_experts", "camera_layer_forward", "camera_output_error", "camera_profile_enable",
            "camera_profile_read", "camera_probe_mfma_bf16", "camera_probe_hbm_read"]
 
 _c = ctypes
@@ -50,6 +50,7 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.camera_score_layer.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _vp, _i, _i, _i64, _vp, _vp, _i64,
                                        _vp, _i64, _f, _i, _vp, _vp, _vp, _vp]
     lib.camera_select_prune.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _d, _vp, _vp, _vp, _vp]
+    lib.camera_select_prune_multi.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _i, _c.POINTER(_d), _vp, _vp]
     lib.camera_alloc_bits.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _i, _c.POINTER(_i),
                                       _c.POINTER(_d), _vp, _vp, _vp]
     lib.camera_gather_micro_experts.argtypes = [_vp, _vp, _i, _i, _i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, _i64,
@@ -151,6 +152,20 @@ class Camera:
             self._ctx, _stream_handle(self.device), _ptr(energy), n_micro, seg, n_seg, float(ratio), _ptr(keep),
             _ptr(per_expert), _ptr(kept_idx), _ptr(rank)))
         return keep, per_expert, kept_idx, rank
+
+    def select_prune_multi(self, energy, seg_offsets, ratios, out=None):
+        """Masks at several rising ratios from one ranking pass: (keep_bits uint8 [n_micro] with bit k = kept at
+        ratios[k], kept_per_expert int32 [len(ratios), n_seg])."""
+        n_micro = energy.numel()
+        n_seg = len(seg_offsets) - 1
+        seg = (_i64 * (n_seg + 1))(*seg_offsets)
+        if out is None:
+            out = (torch.empty(n_micro, dtype=torch.uint8, device=self.device),
+                   torch.empty((len(ratios), n_seg), dtype=torch.int32, device=self.device))
+        self._check(self.lib.camera_select_prune_multi(
+            self._ctx, _stream_handle(self.device), _ptr(energy), n_micro, seg, n_seg, len(ratios),
+            (_d * len(ratios))(*[float(r) for r in ratios]), _ptr(out[0]), _ptr(out[1])))
+        return out
 
     def alloc_bits(self, energy, seg_offsets: Sequence[int], bits: Sequence[int], ratios: Sequence[float],
                    want_perm=False):

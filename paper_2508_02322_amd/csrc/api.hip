@@ -643,6 +643,53 @@ int camera_select_prune(camera_ctx* ctx, void* stream_, const float* energy, int
   return CAMERA_OK;
 }
 
+int camera_select_prune_multi(camera_ctx* ctx, void* stream_, const float* energy, int64_t n_micro,
+                              const int64_t* seg_offsets, int n_seg, int n_ratios, const double* ratios,
+                              uint8_t* keep_bits, int32_t* kept_per_expert) {
+  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
+  if (int rc = check_energy(ctx, energy, n_micro)) return rc;
+  camera::SegTable seg;
+  if (int rc = check_segments(ctx, seg_offsets, n_seg, n_micro, &seg)) return rc;
+  if (n_ratios < 1 || n_ratios > CAMERA_MAX_LEVELS - 1)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "n_ratios: must be in [1, %d]", CAMERA_MAX_LEVELS - 1);
+  if (ratios == nullptr) return fail(ctx, CAMERA_EINVAL, "ratios: NULL");
+  for (int k = 0; k < n_ratios; ++k) {
+    if (!(ratios[k] >= 0.0 && ratios[k] <= 1.0)) return fail(ctx, CAMERA_EINVAL, "ratios[%d]: must be in [0, 1]", k);
+    if (k > 0 && ratios[k] < ratios[k - 1]) return fail(ctx, CAMERA_EINVAL, "ratios: must not fall");
+  }
+  if (kept_per_expert == nullptr) return fail(ctx, CAMERA_EINVAL, "kept_per_expert: NULL");
+  if (n_micro > 0 && keep_bits == nullptr) return fail(ctx, CAMERA_EINVAL, "keep_bits: NULL");
+
+  // One cut per ratio, rising: an element below c of them is pruned at the c largest ratios and kept at the
+  // n_ratios - c smallest, so its byte has the low n_ratios - c bits set.
+  camera::RankCuts cuts;
+  memset(&cuts, 0, sizeof(cuts));
+  cuts.n_cuts = n_ratios;
+  for (int k = 0; k < n_ratios; ++k) cuts.cut_rank[k] = floor_count(ratios[k], n_micro);
+  for (int c = 0; c <= n_ratios; ++c) cuts.out_of_below[c] = (uint8_t)((1u << (n_ratios - c)) - 1u);
+
+  Carver cv;
+  const size_t o_class = cv.take((size_t)n_micro + 64);
+  const size_t o_count = cv.take(sizeof(int32_t) * (size_t)n_seg * (n_ratios + 1));
+  const size_t o_rank = cv.take(sizeof(int32_t) * camera::rank_workspace_words(n_micro, 0));
+  DeviceGuard guard;
+  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
+  if (int rc = ensure_workspace(ctx, cv.used)) return rc;
+  char* ws = static_cast<char*>(ctx->ws);
+  uint8_t* class_buf = reinterpret_cast<uint8_t*>(ws + o_class);
+  int32_t* class_count = reinterpret_cast<int32_t*>(ws + o_count);
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  Bracket b(ctx, stream, CAMERA_K_RANK);
+  CAMERA_HIP(camera::launch_classify(stream, energy, n_micro, cuts, class_buf, keep_bits, nullptr,
+                                     reinterpret_cast<int32_t*>(ws + o_rank)),
+             "classify launch");
+  CAMERA_HIP(camera::launch_segment_counts(stream, class_buf, seg, n_ratios + 1, 0, class_count, nullptr),
+             "segment counts launch");
+  CAMERA_HIP(camera::launch_kept_from_classes(stream, class_count, n_seg, n_ratios, kept_per_expert),
+             "kept counts launch");
+  return CAMERA_OK;
+}
+
 int camera_alloc_bits(camera_ctx* ctx, void* stream_, const float* energy, int64_t n_micro,
                       const int64_t* seg_offsets, int n_seg, int n_levels, const int* bits, const double* ratios,
                       uint8_t* bit_of, int32_t* level_count, int32_t* perm) {

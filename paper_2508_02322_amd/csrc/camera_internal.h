@@ -101,6 +101,9 @@ hipError_t launch_classify(hipStream_t stream, const float* energy, int64_t n_mi
 // `kept_only`, the single count of class 0), and the optional stable partition.
 hipError_t launch_segment_counts(hipStream_t stream, const uint8_t* class_out, const SegTable& seg,
                                  int n_classes, int kept_only, int32_t* counts, int32_t* perm);
+// kept [n_ratios][n_seg] from class_count [n_seg][n_ratios + 1] of a classification with n_ratios ascending cuts.
+hipError_t launch_kept_from_classes(hipStream_t stream, const int32_t* class_count, int n_seg, int n_ratios,
+                                    int32_t* kept);
 // Full stable ascending rank by LSD radix sort.
 hipError_t launch_full_rank(hipStream_t stream, const float* energy, int64_t n_micro, uint32_t* rank,
                             int32_t* ws);

@@ -638,6 +638,19 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(const uint32
 
 static_assert(kSortThreads == kDigits, "one thread per digit in the scatter prologue");
 
+// Several ratios from one classification: class c = "below c of the m ascending cuts", so an element is kept at
+// ratio k iff c <= m - 1 - k.  kept[k][s] = sum of class_count[s][0 .. m - 1 - k].
+__global__ void kept_from_classes_kernel(const int32_t* __restrict__ class_count, int n_seg, int m,
+                                         int32_t* __restrict__ kept) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= n_seg) return;
+  int32_t run = 0;
+  for (int c = 0; c < m; ++c) {  // after adding class c the sum covers classes 0..c: ratio k = m - 1 - c
+    run += class_count[s * (m + 1) + c];
+    kept[(m - 1 - c) * n_seg + s] = run;
+  }
+}
+
 }  // namespace
 
 int64_t rank_blocks(int64_t n_micro) { return (n_micro + kKeysPerBlock - 1) / kKeysPerBlock; }
@@ -678,6 +691,14 @@ hipError_t launch_segment_counts(hipStream_t stream, const uint8_t* class_out, c
   if (seg.n_seg <= 0) return hipSuccess;
   hipLaunchKernelGGL(segment_kernel, dim3((unsigned)seg.n_seg), dim3(kSegThreads), 0, stream, class_out, seg,
                      n_classes, kept_only, counts, perm);
+  return hipGetLastError();
+}
+
+hipError_t launch_kept_from_classes(hipStream_t stream, const int32_t* class_count, int n_seg, int n_ratios,
+                                    int32_t* kept) {
+  if (n_seg <= 0 || n_ratios <= 0) return hipSuccess;
+  hipLaunchKernelGGL(kept_from_classes_kernel, dim3((unsigned)((n_seg + 255) / 256)), dim3(256), 0, stream, class_count,
+                     n_seg, n_ratios, kept);
   return hipGetLastError();
 }
 

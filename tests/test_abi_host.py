@@ -208,3 +208,18 @@ def test_layer_forward_and_output_error_argument_checks(lib, ctx):
     assert error(n=-1) == -2 and error(d=0) == -2
     assert error(y=None) == -1 and error(out=None) == -1
     assert error(n=0) == 0
+
+
+def test_select_prune_multi_argument_checks(lib, ctx):
+    fake = ctypes.c_void_p(4096)
+    seg = (i64 * 3)(0, 50, 100)
+    def multi(energy=fake, n=100, seg_=seg, n_seg=2, ratios=(0.2, 0.4), n_ratios=None, bits=fake, per=fake, c=ctx):
+        arr = (ctypes.c_double * len(ratios))(*ratios) if ratios is not None else None
+        return lib.camera_select_prune_multi(c, None, energy, n, seg_, n_seg, len(ratios) if n_ratios is None else n_ratios,
+                                             arr, bits, per)
+    assert multi(c=None) == -1
+    assert multi(n_ratios=0) == -6 and multi(ratios=(0.1,) * 8) == -6
+    assert multi(ratios=(0.4, 0.2)) == -1 and "fall" in err(lib, ctx)
+    assert multi(ratios=(0.2, 1.5)) == -1
+    assert multi(per=None) == -1 and multi(bits=None) == -1
+    assert multi(n_seg=0) == -6

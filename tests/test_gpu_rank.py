@@ -90,3 +90,28 @@ def test_repeatable(cam):
     b = cam.select_prune(E, [0, 50000], 0.4, want_idx=True, want_rank=True)
     for x, y in zip(a, b):
         assert torch.equal(x[:30000], y[:30000])
+
+
+def check_multi(cam, E, seg, ratios):
+    keep_bits, per = cam.select_prune_multi(E.cuda(), seg, ratios)
+    keep_bits, per = keep_bits.cpu().numpy(), per.cpu().numpy()
+    assert np.all(keep_bits < (1 << len(ratios)))
+    for k, ratio in enumerate(ratios):
+        o_keep, o_per, _, _ = orc.select_prune(E.numpy(), seg, ratio)
+        np.testing.assert_array_equal((keep_bits >> k) & 1, o_keep)
+        np.testing.assert_array_equal(per[k], o_per)
+
+
+@pytest.mark.parametrize("n", [1, 300, 4096, 98304, 184320])
+def test_select_at_several_ratios_in_one_pass(cam, n):
+    E = inputs.energy_like(n, seed=n + 3)
+    seg = even_segments(n, min(n, 9))
+    check_multi(cam, E, seg, [0.2, 0.4, 0.6])
+    check_multi(cam, E, seg, [0.5])
+    check_multi(cam, E, seg, [0.0, 0.1, 0.1, 0.35, 0.9, 1.0, 1.0])       # seven ratios, equal ones, both ends
+
+
+def test_select_at_several_ratios_with_ties_and_empty_segments(cam):
+    E = inputs.energy_like(5000, seed=2, zero_fraction=0.3, tie_fraction=0.3)
+    check_multi(cam, E, [0, 0, 1234, 1234, 4000, 5000], [0.2, 0.29, 0.31, 0.6])
+    check_multi(cam, torch.zeros(3000), [0, 1000, 3000], [0.25, 0.5, 0.75])
