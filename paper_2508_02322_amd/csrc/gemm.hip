@@ -380,49 +380,25 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
   }  // statistics epilogue
 }
 
-template <class C, bool TAIL, int EPI>
-__global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf16_kernel(
-    const __hip_bfloat16* __restrict__ X, int64_t ldx, int d_model, int d_ff,
-    const __hip_bfloat16* __restrict__ Wg, const __hip_bfloat16* __restrict__ Wu, int64_t stride_gu,
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_offset,
-    const int32_t* __restrict__ tile_expert, const int32_t* __restrict__ perm, const float* __restrict__ w_perm,
-    int n_experts, const __hip_bfloat16* __restrict__ zeros, EpiArgs ep) {
-  constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN, WM = C::WM;
-  // Workgroup -> tile mapping.  The hardware deals consecutive workgroup ids round-robin to the 8
-  // XCDs, each with its own L2 and 32 CUs, and an XCD starts its workgroups in id order.  Every
-  // XCD gets an equal, contiguous run of logical ids (sized from the real tile count, which only
-  // the device knows), and logical ids are ordered so that the ~32 workgroups an XCD runs at a
-  // time form a patch that shares tiles through its L2, and so that the next patch needs the same
-  // weight tiles again: expert, then groups of kGroupN-ish N-tiles, then chunks of up to kChunkM
-  // M-tiles of that expert (innermost in time: the weight tiles of the group come back from the
-  // memory-side cache instead of HBM, and an expert's weights leave HBM once), then the tiles of
-  // the chunk.
-  const int n_tiles_n = (d_ff + BN - 1) / BN;
-  const int total = tile_offset[n_experts] * n_tiles_n;
-  const int per_xcd = (total + kXcds - 1) / kXcds;
-  const int seq = blockIdx.x / kXcds;
-  const int logical = (blockIdx.x % kXcds) * per_xcd + seq;
-  if (seq >= per_xcd || logical >= total) return;  // block-uniform: nothing here
-  const int e = tile_expert[logical / n_tiles_n];  // expert e owns logical ids tile_offset[e] * n_tiles_n ..
-  const int m_e = tile_offset[e + 1] - tile_offset[e];
-  const int local = logical - tile_offset[e] * n_tiles_n;
-  const int chunk_m = m_e <= kChunkMax ? m_e : kChunkM;       // M-tiles that run side by side
-  const int group_n = max(1, kPatch / chunk_m);               // N-tiles that run side by side
-  const int group = local / (m_e * group_n);                  // all groups but the last are full
-  const int group_w = min(group_n, n_tiles_n - group * group_n);
-  const int in_group = local - group * m_e * group_n;
-  const int chunk = in_group / (chunk_m * group_w);           // all chunks but the last are full
-  const int chunk_h = min(chunk_m, m_e - chunk * chunk_m);
-  const int in_chunk = in_group - chunk * chunk_m * group_w;
-  const int tile_n = group * group_n + in_chunk / chunk_h;
-  const int slot = tile_offset[e] + chunk * chunk_m + in_chunk % chunk_h;
-  const int tile_in_expert = slot - tile_offset[e];
-  const int row_first = offsets[e] + tile_in_expert * BM;  // first bucket slot of this tile
-  const int m_len = min(BM, offsets[e + 1] - row_first);   // >= 1
-  const int n0 = tile_n * BN;
+// What a workgroup has to do: tile (slot, n0 / BN) of expert e.
+struct TileWork {
+  int e, slot, row_first, m_len, n0;
+  int tok_first;  // first token of the tile when every expert sees every token (no permutation)
+};
 
+// One tile with the tiling of configuration C.  AUX: byte offset in LDS of the per-tile arrays (token ids,
+// routing weights, the column reduction), behind the stages of the largest configuration in use.
+template <class C, bool TAIL, int EPI, int AUX>
+__device__ __forceinline__ void run_tile(const TileWork& w, const __hip_bfloat16* __restrict__ X, int64_t ldx,
+                                         int d_model, int d_ff, const __hip_bfloat16* __restrict__ Wg,
+                                         const __hip_bfloat16* __restrict__ Wu, int64_t stride_gu,
+                                         const int32_t* __restrict__ perm, const float* __restrict__ w_perm,
+                                         const __hip_bfloat16* __restrict__ zeros, const EpiArgs& ep) {
+  constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN, WM = C::WM;
+  static_assert(C::kStages * C::kStageBytes <= AUX, "the stages must end before the per-tile arrays");
+  const int e = w.e, slot = w.slot, row_first = w.row_first, m_len = w.m_len, n0 = w.n0;
   extern __shared__ __align__(16) unsigned char smem[];
-  int32_t* s_tok = reinterpret_cast<int32_t*>(smem + C::kStages * C::kStageBytes);  // [BM] token id
+  int32_t* s_tok = reinterpret_cast<int32_t*>(smem + AUX);  // [BM] token id
   float* s_a = reinterpret_cast<float*>(s_tok + BM);                                // [BM] routing weight
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
@@ -433,7 +409,7 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
   for (int r = tid; r < BM; r += C::kThreads) {
     const int rr = r < m_len ? r : 0;
     if constexpr (EPI == kEpiProduct) s_tok[r] = row_first + rr;  // A rows are the bucket slots themselves
-    else s_tok[r] = perm ? perm[row_first + rr] : tile_in_expert * BM + rr;
+    else s_tok[r] = perm ? perm[row_first + rr] : w.tok_first + rr;
     s_a[r] = r < m_len ? (w_perm ? w_perm[row_first + rr] : 1.0f) : 0.0f;
   }
   __syncthreads();
@@ -496,6 +472,64 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
   else if (act == 1) CAMERA_TILE_BODY((TM > 1 ? 1 : 0));
   else CAMERA_TILE_BODY(0);
 #undef CAMERA_TILE_BODY
+}
+
+template <class C, class CT, bool TAIL, int EPI>
+__global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf16_kernel(
+    const __hip_bfloat16* __restrict__ X, int64_t ldx, int d_model, int d_ff,
+    const __hip_bfloat16* __restrict__ Wg, const __hip_bfloat16* __restrict__ Wu, int64_t stride_gu,
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ tile_offset,
+    const int32_t* __restrict__ tile_expert, const int32_t* __restrict__ perm, const float* __restrict__ w_perm,
+    int n_experts, const __hip_bfloat16* __restrict__ zeros, EpiArgs ep) {
+  constexpr int BM = C::BM, BN = C::BN;
+  static_assert(CT::BN == C::BN && CT::kSmemBytes <= C::kSmemBytes, "the narrow tiling shares the workgroup's N extent and LDS");
+  // Workgroup -> tile mapping.  The hardware deals consecutive workgroup ids round-robin to the 8
+  // XCDs, each with its own L2 and 32 CUs, and an XCD starts its workgroups in id order.  Every
+  // XCD gets an equal, contiguous run of logical ids (sized from the real tile count, which only
+  // the device knows), and logical ids are ordered so that the ~32 workgroups an XCD runs at a
+  // time form a patch that shares tiles through its L2, and so that the next patch needs the same
+  // weight tiles again: expert, then groups of kGroupN-ish N-tiles, then chunks of up to kChunkM
+  // M-tiles of that expert (innermost in time: the weight tiles of the group come back from the
+  // memory-side cache instead of HBM, and an expert's weights leave HBM once), then the tiles of
+  // the chunk.
+  const int n_tiles_n = (d_ff + BN - 1) / BN;
+  const int total = tile_offset[n_experts] * n_tiles_n;
+  const int per_xcd = (total + kXcds - 1) / kXcds;
+  const int seq = blockIdx.x / kXcds;
+  const int logical = (blockIdx.x % kXcds) * per_xcd + seq;
+  if (seq >= per_xcd || logical >= total) return;  // block-uniform: nothing here
+  const int e = tile_expert[logical / n_tiles_n];  // expert e owns logical ids tile_offset[e] * n_tiles_n ..
+  const int m_e = tile_offset[e + 1] - tile_offset[e];
+  const int local = logical - tile_offset[e] * n_tiles_n;
+  const int chunk_m = m_e <= kChunkMax ? m_e : kChunkM;       // M-tiles that run side by side
+  const int group_n = max(1, kPatch / chunk_m);               // N-tiles that run side by side
+  const int group = local / (m_e * group_n);                  // all groups but the last are full
+  const int group_w = min(group_n, n_tiles_n - group * group_n);
+  const int in_group = local - group * m_e * group_n;
+  const int chunk = in_group / (chunk_m * group_w);           // all chunks but the last are full
+  const int chunk_h = min(chunk_m, m_e - chunk * chunk_m);
+  const int in_chunk = in_group - chunk * chunk_m * group_w;
+  const int tile_n = group * group_n + in_chunk / chunk_h;
+  const int slot = tile_offset[e] + chunk * chunk_m + in_chunk % chunk_h;
+  const int tile_in_expert = slot - tile_offset[e];
+  const int row_first = offsets[e] + tile_in_expert * BM;  // first bucket slot of this tile
+  const int m_len = min(BM, offsets[e + 1] - row_first);   // >= 1
+  const int n0 = tile_n * BN;
+
+  TileWork w;
+  w.e = e;
+  w.slot = slot;
+  w.row_first = row_first;
+  w.m_len = m_len;
+  w.n0 = n0;
+  w.tok_first = tile_in_expert * BM;
+  constexpr int kAux = C::kStages * C::kStageBytes;
+  // A short last tile of an expert is bound by the latency of its loads, not by the matrix pipe: it runs
+  // with the narrow tiling, whose smaller stages leave room for a third one (two K tiles in flight).
+  if (CT::kThreads == C::kThreads && m_len <= CT::BM)
+    run_tile<CT, TAIL, EPI, kAux>(w, X, ldx, d_model, d_ff, Wg, Wu, stride_gu, perm, w_perm, zeros, ep);
+  else
+    run_tile<C, TAIL, EPI, kAux>(w, X, ldx, d_model, d_ff, Wg, Wu, stride_gu, perm, w_perm, zeros, ep);
 }
 
 // ---------------------------------------------------------------------------
@@ -607,6 +641,12 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
 #define CAMERA_GEMM_CFG 4, 2, 2, 2, 64, 2
 #endif
 using Bf16Cfg = GemmCfg<CAMERA_GEMM_CFG>;
+// Tiling of an expert's short last tile (at most 64 token rows): same eight waves and N extent, 2 x 4 waves of
+// one 32 x 32 block each, three stages of 40 KiB.
+#ifndef CAMERA_GEMM_TAIL_CFG
+#define CAMERA_GEMM_TAIL_CFG 2, 4, 1, 1, 64, 3
+#endif
+using Bf16TailCfg = GemmCfg<CAMERA_GEMM_TAIL_CFG>;
 
 }  // namespace
 
@@ -621,7 +661,7 @@ static hipError_t launch_bf16(hipStream_t stream, const void* X, int64_t ldx, in
                               const BucketTables& t, const EpiArgs& ep) {
   using C = Bf16Cfg;
   const bool tail = d_model % C::KT != 0;
-  auto kern = tail ? grouped_gemm_bf16_kernel<C, true, EPI> : grouped_gemm_bf16_kernel<C, false, EPI>;
+  auto kern = tail ? grouped_gemm_bf16_kernel<C, Bf16TailCfg, true, EPI> : grouped_gemm_bf16_kernel<C, Bf16TailCfg, false, EPI>;
   static bool attr_set[2] = {false, false};
   if (!attr_set[tail]) {
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
