@@ -35,7 +35,7 @@ DECISIONS = {
 
 # HBM-side bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by what the same
 # counters read for a plain 1 GiB copy (profiles/grouped_gemm_bf16_qwen2-57b-a14b_hbm_traffic.txt); None where not measured.
-PMC_TRAFFIC_BYTES = {"qwen2-57b-a14b": 5.254e9}
+PMC_TRAFFIC_BYTES = {"qwen2-57b-a14b": 5.759e9}
 
 
 def parse_args():
