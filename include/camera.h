@@ -239,15 +239,16 @@ int camera_gather_micro_experts(camera_ctx* ctx, void* stream, int dtype,
  * Algorithm 2, line 14):
  *   Y[j, :] = sum over experts e and kept channels c of  Lambda_e[j, c] * W_down,e[:, c],
  *   Lambda_e[j, c] = a_j,e * silu(<w_gate_c, x_j>) * <w_up_c, x_j>           (Eq. 4)
- * X, routing, weights, strides: as in camera_score_layer (CAMERA_BF16 only; d_ff and stride_down multiples of 8).
+ * X, routing, weights, strides: as in camera_score_layer; d_ff and stride_down multiples of 8 (CAMERA_BF16) or 4
+ * (CAMERA_F32).
  *   keep_mask  uint8 [n_experts * d_ff], 0 = pruned (gate row, up row and down column all drop out), or NULL:
  *              every micro-expert kept (the original layer).  For the second group of a layer pass the
  *              group's slice of camera_select_prune's keep_mask.
  *   flags      0: Y is overwritten; CAMERA_ACCUMULATE: the group's output is added to Y (routed experts
  *              first, then the shared ones into the same Y)
  *   Y          float32 [n x d_model] in-out, rows contiguous
- * Lambda is rounded to bf16 before the second contraction, as the hidden activations of a 16-bit model
- * are; both contractions accumulate in float32, and a token's experts are added in the order of its
+ * With CAMERA_BF16 Lambda is rounded to bf16 before the second contraction, as the hidden activations of a
+ * 16-bit model are (CAMERA_F32 keeps it in float32); both contractions accumulate in float32, and a token's experts are added in the order of its
  * top-k list (no floating-point atomics: the result does not depend on launch order).  The context
  * workspace grows by n*top_k*(2*d_ff + 4*d_model) bytes.  n == 0 does nothing.
  *

@@ -484,22 +484,22 @@ int camera_layer_forward(camera_ctx* ctx, void* stream_, const void* X, int dtyp
                          int64_t stride_down, const uint8_t* keep_mask, int flags, float* Y) {
   if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
   if (int rc = check_common(ctx, X, dtype, n, d_model, ldx)) return rc;
-  if (dtype != CAMERA_BF16) return fail(ctx, CAMERA_EUNSUPPORTED, "dtype: the layer output is built for CAMERA_BF16 only");
   const bool dense = topk_idx == nullptr && topk_w == nullptr;
   if (!dense && (topk_idx == nullptr || topk_w == nullptr))
     return fail(ctx, CAMERA_EINVAL, "topk_idx / topk_w: give both or neither");
   if (n_experts < 1 || n_experts > CAMERA_MAX_EXPERTS)
     return fail(ctx, CAMERA_EUNSUPPORTED, "n_experts: must be in [1, %d]", CAMERA_MAX_EXPERTS);
   if (!dense && (top_k < 1 || top_k > n_experts)) return fail(ctx, CAMERA_EINVAL, "top_k: must be in [1, n_experts]");
-  if (d_ff <= 0 || d_ff % 8 != 0) return fail(ctx, CAMERA_ESHAPE, "d_ff: must be a positive multiple of 8");
+  const int v = dtype == CAMERA_BF16 ? 8 : 4;  // elements per 16 bytes: d_ff is the K extent of the second contraction
+  if (d_ff <= 0 || d_ff % v != 0) return fail(ctx, CAMERA_ESHAPE, "d_ff: must be a positive multiple of %d", v);
   if (flags & ~CAMERA_ACCUMULATE) return fail(ctx, CAMERA_EINVAL, "flags: only CAMERA_ACCUMULATE is accepted");
   if (W_gate == nullptr || W_up == nullptr || W_down == nullptr)
     return fail(ctx, CAMERA_EINVAL, "W_gate / W_up / W_down: NULL");
   if (n > 0 && Y == nullptr) return fail(ctx, CAMERA_EINVAL, "Y: NULL");
-  if (stride_gu < d_ff * d_model || stride_gu % 8 != 0)
-    return fail(ctx, CAMERA_ESHAPE, "stride_gu: must be >= d_ff*d_model and a multiple of 8");
-  if (stride_down < d_ff * d_model || stride_down % 8 != 0)
-    return fail(ctx, CAMERA_ESHAPE, "stride_down: must be >= d_model*d_ff and a multiple of 8");
+  if (stride_gu < d_ff * d_model || stride_gu % v != 0)
+    return fail(ctx, CAMERA_ESHAPE, "stride_gu: must be >= d_ff*d_model and a multiple of %d", v);
+  if (stride_down < d_ff * d_model || stride_down % v != 0)
+    return fail(ctx, CAMERA_ESHAPE, "stride_down: must be >= d_model*d_ff and a multiple of %d", v);
   if (!aligned16(W_gate) || !aligned16(W_up) || !aligned16(W_down) || !aligned16(Y))
     return fail(ctx, CAMERA_ESHAPE, "W_gate / W_up / W_down / Y: not 16-byte aligned");
   const int64_t n_micro = (int64_t)n_experts * d_ff;
@@ -525,7 +525,8 @@ int camera_layer_forward(camera_ctx* ctx, void* stream_, const void* X, int dtyp
   const size_t o_wperm = cv.take(dense ? 0 : sizeof(float) * n_pairs);
   const size_t o_slot = cv.take(dense ? 0 : sizeof(int32_t) * n_pairs);
   const size_t o_hist = cv.take(sizeof(int32_t) * n_blocks * n_experts);
-  const size_t o_hidden = cv.take(sizeof(uint16_t) * (size_t)n_pairs * d_ff);
+  const size_t es = dtype == CAMERA_BF16 ? 2 : 4;
+  const size_t o_hidden = cv.take(es * (size_t)n_pairs * d_ff);
   const size_t o_product = cv.take(sizeof(float) * (size_t)n_pairs * d_model);
 
   DeviceGuard guard;
@@ -576,7 +577,7 @@ int camera_layer_forward(camera_ctx* ctx, void* stream_, const void* X, int dtyp
     ep.col_gap = (int)half;
     const char* wd = static_cast<const char*>(W_down);
     CAMERA_HIP(camera::launch_grouped_gemm(stream, dtype, hidden, d_ff, d_ff, half, n_experts, wd,
-                                           wd + sizeof(uint16_t) * half * d_ff, stride_down, max_tiles, t, ep),
+                                           wd + es * half * d_ff, stride_down, max_tiles, t, ep),
                "down gemm launch");
   }
   {

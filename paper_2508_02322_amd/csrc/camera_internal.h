@@ -49,10 +49,10 @@ hipError_t launch_dense_tables(hipStream_t stream, int64_t n, int n_experts, int
 int gemm_tile_m(int dtype, int64_t d_ff);
 // What the contraction does with its two products G = X_e W_gate^T and U = X_e W_up^T:
 //   kStats   Lambda = a silu(G) U is reduced to per-M-tile column statistics part_phi2 / part_max [max_tiles x d_ff]
-//   kHidden  Lambda, zeroed where keep[e*d_ff + c] == 0 (keep may be NULL), is stored as bf16 in
-//            hidden[bucket slot][d_ff] (bf16 only)
+//   kHidden  Lambda, zeroed where keep[e*d_ff + c] == 0 (keep may be NULL), is stored in hidden[bucket slot][d_ff],
+//            rounded to bf16 by the bf16 kernel, as float32 by the float32 kernel
 //   kProduct G goes to product[slot][c], U to product[slot][c + col_gap], row stride ld_product; in this mode X is
-//            indexed by bucket slot, not by token (the hidden activations are the left operand; bf16 only)
+//            indexed by bucket slot, not by token (the hidden activations are the left operand)
 struct GemmEpilogue {
   enum Mode { kStats = 0, kHidden = 1, kProduct = 2 };
   int mode = kStats;

@@ -77,7 +77,7 @@ enum { kEpiStats = 0, kEpiHidden = 1, kEpiProduct = 2 };
 struct EpiArgs {
   float* part_phi2;
   float* part_max;
-  __hip_bfloat16* hidden;  // [pairs][d_ff]
+  void* hidden;            // [pairs][d_ff], bf16 (MFMA kernel) or float32 (FMA kernel)
   const uint8_t* keep;     // [n_experts * d_ff] or nullptr (all kept)
   float* product;          // [pairs][ld_product]
   int64_t ld_product;
@@ -332,7 +332,7 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
           const int64_t out_row = st.row_first + row;
           if constexpr (EPI == kEpiHidden) {
             const float lam = st.s_a[row] * silu_f32(acc_g[i][j][r]) * acc_u[i][j][r] * kept;
-            ep.hidden[out_row * d_ff + col] = __float2bfloat16(lam);
+            static_cast<__hip_bfloat16*>(ep.hidden)[out_row * d_ff + col] = __float2bfloat16(lam);
           } else {
             ep.product[out_row * ep.ld_product + col] = acc_g[i][j][r];
             ep.product[out_row * ep.ld_product + col + ep.col_gap] = acc_u[i][j][r];
@@ -538,12 +538,12 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
 // ---------------------------------------------------------------------------
 constexpr int F32_BM = 64, F32_BN = 64, F32_KT = 16;
 
+template <int EPI>
 __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
     const float* __restrict__ X, int64_t ldx, int d_model, int d_ff, const float* __restrict__ Wg,
     const float* __restrict__ Wu, int64_t stride_gu, const int32_t* __restrict__ offsets,
     const int32_t* __restrict__ tile_offset, const int32_t* __restrict__ tile_expert,
-    const int32_t* __restrict__ perm, const float* __restrict__ w_perm, int n_experts,
-    float* __restrict__ part_phi2, float* __restrict__ part_max) {
+    const int32_t* __restrict__ perm, const float* __restrict__ w_perm, int n_experts, EpiArgs ep) {
   const int slot = blockIdx.y;
   if (slot >= tile_offset[n_experts]) return;
   const int e = tile_expert[slot];
@@ -565,7 +565,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
     int tok = -1;
     float a = 0.0f;
     if (r < m_len) {
-      tok = perm ? perm[row_first + r] : tile_in_expert * F32_BM + r;
+      if constexpr (EPI == kEpiProduct) tok = row_first + r;  // the left operand is indexed by bucket slot
+      else tok = perm ? perm[row_first + r] : tile_in_expert * F32_BM + r;
       a = w_perm ? w_perm[row_first + r] : 1.0f;
     }
     s_tok[r] = tok;
@@ -612,6 +613,27 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
         }
     }
   }
+  if constexpr (EPI != kEpiStats) {  // per token row: hidden activations (float32 here) or the plain products
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int col = n0 + tx * 4 + j;
+      if (col >= d_ff) continue;
+      float kept = 1.0f;
+      if constexpr (EPI == kEpiHidden) kept = (ep.keep == nullptr || ep.keep[(int64_t)e * d_ff + col]) ? 1.0f : 0.0f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = ty * 4 + i;
+        if (row >= m_len) continue;
+        const int64_t out_row = row_first + row;
+        if constexpr (EPI == kEpiHidden) {
+          static_cast<float*>(ep.hidden)[out_row * d_ff + col] = s_a[row] * silu_f32(acc_g[i][j]) * acc_u[i][j] * kept;
+        } else {
+          ep.product[out_row * ep.ld_product + col] = acc_g[i][j];
+          ep.product[out_row * ep.ld_product + col + ep.col_gap] = acc_u[i][j];
+        }
+      }
+    }
+  } else {
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     float sum = 0.0f, mx = 0.0f;
@@ -631,9 +653,10 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
       sum += s_red[0][r][tid];
       mx = fmaxf(mx, s_red[1][r][tid]);
     }
-    part_phi2[(int64_t)slot * d_ff + n0 + tid] = sum;
-    part_max[(int64_t)slot * d_ff + n0 + tid] = mx;
+    ep.part_phi2[(int64_t)slot * d_ff + n0 + tid] = sum;
+    ep.part_max[(int64_t)slot * d_ff + n0 + tid] = mx;
   }
+  }  // statistics epilogue
 }
 
 // Shape of the bf16 kernel: waves (M x N), 32x32 blocks per wave (M x N), K tile, LDS stages.
@@ -684,9 +707,8 @@ hipError_t launch_grouped_gemm(hipStream_t stream, int dtype, const void* X, int
                                int64_t d_ff, int n_experts, const void* W_gate, const void* W_up,
                                int64_t stride_gu, int max_tiles, const BucketTables& t, const GemmEpilogue& e) {
   if (max_tiles <= 0) return hipSuccess;
+  EpiArgs ep{e.part_phi2, e.part_max, e.hidden, e.keep, e.product, e.ld_product, e.col_gap};
   if (dtype == CAMERA_BF16) {
-    EpiArgs ep{e.part_phi2, e.part_max, static_cast<__hip_bfloat16*>(e.hidden), e.keep, e.product, e.ld_product,
-               e.col_gap};
     switch (e.mode) {
       case GemmEpilogue::kStats:
         return launch_bf16<kEpiStats>(stream, X, ldx, d_model, d_ff, n_experts, W_gate, W_up, stride_gu, max_tiles, t, ep);
@@ -698,12 +720,14 @@ hipError_t launch_grouped_gemm(hipStream_t stream, int dtype, const void* X, int
         return hipErrorInvalidValue;
     }
   }
-  if (e.mode != GemmEpilogue::kStats) return hipErrorNotSupported;  // the float32 kernel only has the statistics epilogue
   dim3 grid((unsigned)((d_ff + F32_BN - 1) / F32_BN), (unsigned)max_tiles);
-  hipLaunchKernelGGL(grouped_gemm_f32_kernel, grid, dim3(256), 0, stream, static_cast<const float*>(X), ldx,
-                     (int)d_model, (int)d_ff, static_cast<const float*>(W_gate), static_cast<const float*>(W_up),
-                     stride_gu, t.offsets, t.tile_offset, t.tile_expert, t.perm, t.w_perm, n_experts, e.part_phi2,
-                     e.part_max);
+  auto kern = e.mode == GemmEpilogue::kStats    ? grouped_gemm_f32_kernel<kEpiStats>
+              : e.mode == GemmEpilogue::kHidden ? grouped_gemm_f32_kernel<kEpiHidden>
+                                                : grouped_gemm_f32_kernel<kEpiProduct>;
+  if (e.mode < GemmEpilogue::kStats || e.mode > GemmEpilogue::kProduct) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, static_cast<const float*>(X), ldx, (int)d_model, (int)d_ff,
+                     static_cast<const float*>(W_gate), static_cast<const float*>(W_up), stride_gu, t.offsets,
+                     t.tile_offset, t.tile_expert, t.perm, t.w_perm, n_experts, ep);
   return hipGetLastError();
 }
 

@@ -191,7 +191,8 @@ def test_layer_forward_and_output_error_argument_checks(lib, ctx):
                                         stride_gu, wd, stride_down, keep, flags, y)
     lib.camera_layer_forward.restype = ctypes.c_int
     assert forward(c=None) == -1
-    assert forward(dtype=0) == -6 and "BF16" in err(lib, ctx)
+    assert forward(dtype=0, d_ff=30) == -2 and "multiple of 4" in err(lib, ctx)
+    assert forward(dtype=9) == -3
     assert forward(idx=None) == -1 and "both or neither" in err(lib, ctx)
     assert forward(top_k=0) == -1 and forward(top_k=5) == -1
     assert forward(n_experts=0) == -6

@@ -66,6 +66,8 @@ def check_output(Y_gpu, Y_orc, term):
 
 
 CASES = [
+    dict(dtype="f32", n_tokens=300, d_model=100, d_ff=52, n_experts=6),    # float32: no rounding of the hidden activations
+    dict(dtype="f32", n_tokens=129, d_model=64, d_ff=200, n_experts=3, top_k=3),
     dict(),                                                        # several M tiles per expert, ragged N tile
     dict(n_tokens=37, d_model=72, d_ff=40),                        # everything ragged, K tails in both contractions
     dict(n_tokens=1000, d_model=256, d_ff=136, n_experts=5, top_k=3),
@@ -87,14 +89,16 @@ def test_layer_output_matches_oracle_with_and_without_a_mask(cam, case):
     ones = torch.ones(cfg.n_experts * cfg.d_ff, dtype=torch.uint8, device="cuda")
     Y_ones = cam.layer_forward(dev["X"], idx, w, dev["W_gate"], dev["W_up"], dev["W_down"], keep_mask=ones)
     torch.cuda.synchronize()
-    O_full = orc.layer_forward(X64, A, gate, up, down, round_hidden=orc.round_to_bf16)
-    err_full = check_output(Y_full, O_full, largest_term(X64, A, gate, up, down))
+    rounding = orc.round_to_bf16 if cfg.dtype == "bf16" else None
+    flip = 1.0 if cfg.dtype == "bf16" else 0.0                     # float32: only accumulation error is allowed
+    O_full = orc.layer_forward(X64, A, gate, up, down, round_hidden=rounding)
+    err_full = check_output(Y_full, O_full, flip * largest_term(X64, A, gate, up, down))
     assert torch.equal(Y_full, Y_ones)                             # NULL mask == every micro-expert kept, bit for bit
     keep = (torch.rand(cfg.n_experts * cfg.d_ff, generator=torch.Generator().manual_seed(3)) < 0.6).to(torch.uint8)
     Y_kept = cam.layer_forward(dev["X"], idx, w, dev["W_gate"], dev["W_up"], dev["W_down"], keep_mask=keep.cuda())
     torch.cuda.synchronize()
-    O_kept = orc.layer_forward(X64, A, gate, up, down, keep=keep.numpy(), round_hidden=orc.round_to_bf16)
-    err_kept = check_output(Y_kept, O_kept, largest_term(X64, A, gate, up, down, keep.numpy()))
+    O_kept = orc.layer_forward(X64, A, gate, up, down, keep=keep.numpy(), round_hidden=rounding)
+    err_kept = check_output(Y_kept, O_kept, flip * largest_term(X64, A, gate, up, down, keep.numpy()))
     # error measures of the same two outputs
     per_token = cam.output_error(Y_full, Y_kept).cpu().numpy().astype(np.float64)
     want = orc.output_error(Y_full.cpu().numpy(), Y_kept.cpu().numpy())
