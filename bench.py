@@ -50,6 +50,9 @@ def parse_args():
                          "in chunks of the configuration's size through CAMERA_ACCUMULATE (the paper calibrates on "
                          "128 x 2048 = 262144 tokens)")
     ap.add_argument("--chunk-tokens", type=int, default=0, help="chunk size for --calib-tokens (default: the configuration's token count)")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="run consecutive layers on this many HIP streams (one library context each), so that the tail of one "
+                         "layer's kernels overlaps the start of the next layer's; per-kernel timings then overlap as well")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the measured MFMA / HBM ceilings (about 1 s)")
     ap.add_argument("--no-forward", action="store_true",
@@ -284,9 +287,18 @@ def main():
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
+    n_streams = max(1, args.streams)
+    cams = [cam] + [binding.Camera(device=0) for _ in range(n_streams - 1)]
+    streams = [torch.cuda.Stream() for _ in range(n_streams)] if n_streams > 1 else [None]
+
     def step():
-        for lr in layers:
-            lr.run(cam, decisions, binding)
+        if n_streams == 1:
+            for lr in layers:
+                lr.run(cam, decisions, binding)
+            return
+        for i, lr in enumerate(layers):
+            with torch.cuda.stream(streams[i % n_streams]):
+                lr.run(cams[i % n_streams], decisions, binding)
 
     for _ in range(args.warmup):
         step()
