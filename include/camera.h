@@ -69,7 +69,9 @@ enum camera_kernel_id {
   CAMERA_K_GATHER = 6,   /* camera_gather_micro_experts */
   CAMERA_K_DOWN_GEMM = 7, /* camera_layer_forward: hidden activations times W_down^T */
   CAMERA_K_COMBINE = 8,  /* camera_layer_forward: sum over a token's experts; camera_output_error */
-  CAMERA_K_COUNT = 9
+  CAMERA_K_COMPACT_HIDDEN = 9, /* camera_layer_forward_compact: Lambda on the kept gate / up rows */
+  CAMERA_K_COMPACT_DOWN = 10,  /* camera_layer_forward_compact: Lambda times the kept W_down columns */
+  CAMERA_K_COUNT = 11
 };
 
 /* Create / destroy a context bound to HIP device `device`.  Creation touches no
@@ -264,6 +266,34 @@ int camera_layer_forward(camera_ctx* ctx, void* stream,
                          const void* W_gate, const void* W_up, int64_t stride_gu,
                          const void* W_down, int64_t stride_down,
                          const uint8_t* keep_mask, int flags, float* Y);
+
+/*
+ * The output of a pruned layer from its compacted weights (Algorithm 2, line 14, on the matrices that
+ * lines 10-13 leave: expert e keeps count[e] micro-experts), for the small token batches of decoding
+ * (the decoding-speed comparison of a pruned MoE layer, batch of 64 tokens).  Same result as
+ * camera_layer_forward with the keep mask that the compaction was made from, but only the kept
+ * weights are read, each activated expert's once per 64 of its tokens, and the experts that no token
+ * of the batch selected are not read at all: the call is bound by HBM reads, not by arithmetic.
+ *
+ *   X, n, d_model, ldx, topk_idx, topk_w, top_k, n_experts, flags, Y: as in camera_layer_forward
+ *               (topk_idx = topk_w = NULL: every token goes through every expert with weight 1).
+ *               Any n is accepted; beyond 64 tokens per expert the weights are streamed again for
+ *               every further 64, so large batches belong to camera_layer_forward.
+ *   dtype       CAMERA_BF16 only (CAMERA_EUNSUPPORTED otherwise); Lambda is rounded to bf16 before
+ *               the second contraction, float32 accumulation in both
+ *   count       HOST int32 [n_experts]: kept micro-experts of every expert (>= 0, any value: the
+ *               rows of a W_down block need no alignment)
+ *   W_gate_c, W_up_c   [sum(count)][d_model]: the kept rows, expert after expert
+ *   W_down_c    sum(count) * d_model elements: expert e's block starts at element
+ *               d_model * (count[0] + ... + count[e-1]) and is [d_model][count[e]] row-major
+ *               (the three outputs of camera_gather_micro_experts, unchanged)
+ */
+int camera_layer_forward_compact(camera_ctx* ctx, void* stream,
+                                 const void* X, int dtype, int64_t n, int64_t d_model, int64_t ldx,
+                                 const int32_t* topk_idx, const float* topk_w, int top_k,
+                                 int n_experts, const int32_t* count,
+                                 const void* W_gate_c, const void* W_up_c, const void* W_down_c,
+                                 int flags, float* Y);
 int camera_output_error(camera_ctx* ctx, void* stream, const float* Y, const float* Y_hat,
                         int64_t n, int64_t d_model, float* per_token);
 

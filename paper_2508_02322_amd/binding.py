@@ -18,11 +18,12 @@ LIB_PATH = os.path.join(HERE, "libcamera_hip.so")
 F32, BF16 = 0, 1
 ACCUMULATE, NO_FINALIZE = 1, 2
 K_ROUTE, K_BUCKET, K_GEMM, K_DOWN_NORM, K_FINALIZE, K_RANK, K_GATHER, K_DOWN_GEMM, K_COMBINE = range(9)
-KERNEL_NAMES = ["route", "bucket", "gemm", "down_norm", "finalize", "rank", "gather", "down_gemm", "combine"]
+KERNEL_NAMES = ["route", "bucket", "gemm", "down_norm", "finalize", "rank", "gather", "down_gemm", "combine",
+                "compact_hidden", "compact_down"]
 
 EXPORTS = ["camera_create", "camera_destroy", "camera_last_error", "camera_version", "camera_route_topk",
            "camera_score_layer", "camera_select_prune", "camera_select_prune_multi", "camera_alloc_bits",
-           "camera_gather_micro_experts", "camera_layer_forward", "camera_output_error", "camera_profile_enable",
+           "camera_gather_micro_experts", "camera_layer_forward", "camera_layer_forward_compact", "camera_output_error", "camera_profile_enable",
            "camera_profile_read", "camera_probe_mfma_bf16", "camera_probe_hbm_read"]
 
 _c = ctypes
@@ -57,6 +58,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
                                                 _i64, _vp, _vp, _vp, _vp]
     lib.camera_layer_forward.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _vp, _i, _i, _i64, _vp, _vp, _i64,
                                          _vp, _i64, _vp, _i, _vp]
+    lib.camera_layer_forward_compact.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _vp, _i, _i,
+                                                 _c.POINTER(_c.c_int32), _vp, _vp, _vp, _i, _vp]
     lib.camera_output_error.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _vp]
     lib.camera_profile_enable.argtypes = [_vp, _i]
     lib.camera_profile_read.argtypes = [_vp, _i, _c.POINTER(_d), _c.POINTER(_i64)]
@@ -211,6 +214,20 @@ class Camera:
             self._ctx, _stream_handle(self.device), _ptr(X), _dtype_code(X), n, d, X.stride(0), _ptr(topk_idx),
             _ptr(topk_w), top_k, n_experts, d_ff, _ptr(W_gate), _ptr(W_up), W_gate.stride(0), _ptr(W_down),
             W_down.stride(0), _ptr(keep_mask), ACCUMULATE if accumulate else 0, _ptr(Y)))
+        return Y
+
+    def layer_forward_compact(self, X, topk_idx, topk_w, count, W_gate_c, W_up_c, W_down_c, Y=None, accumulate=False):
+        """Layer output from compacted weights (the outputs of gather_micro_experts); count: per-expert kept
+        micro-experts as a sequence of Python ints.  Y float32 [n, d_model]."""
+        n, d = X.shape
+        counts = [int(c) for c in count]
+        top_k = 0 if topk_idx is None else topk_idx.shape[1]
+        if Y is None:
+            Y = torch.empty((n, d), dtype=torch.float32, device=self.device)
+        self._check(self.lib.camera_layer_forward_compact(
+            self._ctx, _stream_handle(self.device), _ptr(X), _dtype_code(X), n, d, X.stride(0), _ptr(topk_idx),
+            _ptr(topk_w), top_k, len(counts), (_c.c_int32 * len(counts))(*counts), _ptr(W_gate_c), _ptr(W_up_c),
+            _ptr(W_down_c), ACCUMULATE if accumulate else 0, _ptr(Y)))
         return Y
 
     def output_error(self, Y, Y_hat):

@@ -16,7 +16,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcamera_hip.so")
-SOURCES = ["api.hip", "route.hip", "bucket.hip", "gemm.hip", "norm.hip", "rank.hip", "probe.hip", "gather.hip", "forward.hip"]
+SOURCES = ["api.hip", "route.hip", "bucket.hip", "gemm.hip", "norm.hip", "rank.hip", "probe.hip", "gather.hip", "forward.hip",
+           "compact.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # keep packed-fp32 instruction selection off for every device function
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

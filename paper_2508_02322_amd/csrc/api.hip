@@ -1,6 +1,7 @@
 // C ABI of libcamera_hip: argument checks on the host, workspace carving and
 // the launch sequence of each entry point.  Declarations and the meaning of
 // every argument are in include/camera.h.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -579,6 +580,117 @@ int camera_layer_forward(camera_ctx* ctx, void* stream_, const void* X, int dtyp
     CAMERA_HIP(camera::launch_grouped_gemm(stream, dtype, hidden, d_ff, d_ff, half, n_experts, wd,
                                            wd + es * half * d_ff, stride_down, max_tiles, t, ep),
                "down gemm launch");
+  }
+  {
+    Bracket b(ctx, stream, CAMERA_K_COMBINE);
+    CAMERA_HIP(camera::launch_combine(stream, product, t.slot_of, n, top_k, n_experts, d_model,
+                                      (flags & CAMERA_ACCUMULATE) ? 1 : 0, Y),
+               "combine launch");
+  }
+  return CAMERA_OK;
+}
+
+int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, int dtype, int64_t n, int64_t d_model,
+                                 int64_t ldx, const int32_t* topk_idx, const float* topk_w, int top_k, int n_experts,
+                                 const int32_t* count, const void* W_gate_c, const void* W_up_c, const void* W_down_c,
+                                 int flags, float* Y) {
+  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
+  if (int rc = check_common(ctx, X, dtype, n, d_model, ldx)) return rc;
+  if (dtype != CAMERA_BF16) return fail(ctx, CAMERA_EUNSUPPORTED, "dtype: the compacted layer is built for CAMERA_BF16 only");
+  const bool dense = topk_idx == nullptr && topk_w == nullptr;
+  if (!dense && (topk_idx == nullptr || topk_w == nullptr))
+    return fail(ctx, CAMERA_EINVAL, "topk_idx / topk_w: give both or neither");
+  if (n_experts < 1 || n_experts > CAMERA_MAX_EXPERTS)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "n_experts: must be in [1, %d]", CAMERA_MAX_EXPERTS);
+  if (!dense && (top_k < 1 || top_k > n_experts)) return fail(ctx, CAMERA_EINVAL, "top_k: must be in [1, n_experts]");
+  if (flags & ~CAMERA_ACCUMULATE) return fail(ctx, CAMERA_EINVAL, "flags: only CAMERA_ACCUMULATE is accepted");
+  if (count == nullptr) return fail(ctx, CAMERA_EINVAL, "count: NULL");
+  camera::CompactTable tab;
+  tab.n_experts = n_experts;
+  int64_t rows = 0, tiles = 0, widest = 0;
+  for (int e = 0; e < n_experts; ++e) {
+    if (count[e] < 0) return fail(ctx, CAMERA_EINVAL, "count[%d]: negative", e);
+    tab.row_off[e] = (int32_t)rows;
+    tab.tile_off[e] = (int32_t)tiles;
+    rows += count[e];
+    tiles += (count[e] + 31) / 32;
+    widest = std::max<int64_t>(widest, count[e]);
+    if (rows >= (int64_t(1) << 31) - 1024) return fail(ctx, CAMERA_ESHAPE, "sum of count: too large");
+  }
+  for (int e = n_experts; e <= CAMERA_MAX_EXPERTS; ++e) {
+    tab.row_off[e] = (int32_t)rows;
+    tab.tile_off[e] = (int32_t)tiles;
+  }
+  if (rows > 0 && (W_gate_c == nullptr || W_up_c == nullptr || W_down_c == nullptr))
+    return fail(ctx, CAMERA_EINVAL, "W_gate_c / W_up_c / W_down_c: NULL");
+  if (n > 0 && Y == nullptr) return fail(ctx, CAMERA_EINVAL, "Y: NULL");
+  if (!aligned16(W_gate_c) || !aligned16(W_up_c) || !aligned16(W_down_c) || !aligned16(Y))
+    return fail(ctx, CAMERA_ESHAPE, "W_gate_c / W_up_c / W_down_c / Y: not 16-byte aligned");
+  const int64_t n_pairs = dense ? n * n_experts : n * (int64_t)top_k;
+  if (n_pairs >= (int64_t(1) << 31) - 1024) return fail(ctx, CAMERA_ESHAPE, "routed pairs: must be below 2^31");
+  const int64_t ldh = (widest + 7) / 8 * 8;
+  if (n_pairs * std::max<int64_t>(ldh, d_model) >= (int64_t(1) << 40))
+    return fail(ctx, CAMERA_EUNSUPPORTED, "batch too large for the compacted layer: use camera_layer_forward");
+  if ((int64_t)n_experts * ((d_model + 31) / 32) >= (int64_t(1) << 31) - 1024)
+    return fail(ctx, CAMERA_ESHAPE, "n_experts * d_model: too large");
+  if (n == 0) return CAMERA_OK;
+
+  // tokens per expert to be expected: above 32 the kernels take them 64 at a time
+  const bool wide = (dense ? n : n * (int64_t)top_k / n_experts) > 32;
+  const int tile_m = 256;  // only the bucket order is used here; the M-tile tables are a by-product
+  const int64_t max_tiles64 = dense ? n_experts * ((n + tile_m - 1) / tile_m) : n_pairs / tile_m + n_experts;
+  if (max_tiles64 > 65535)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "batch too large for the compacted layer: use camera_layer_forward");
+  const int max_tiles = (int)max_tiles64;
+  const int64_t n_blocks = dense ? 0 : camera::bucket_blocks(n_pairs);
+
+  Carver cv;
+  const size_t o_counts = cv.take(sizeof(int32_t) * n_experts);
+  const size_t o_offsets = cv.take(sizeof(int32_t) * (n_experts + 1));
+  const size_t o_tile_off = cv.take(sizeof(int32_t) * (n_experts + 1));
+  const size_t o_tile_exp = cv.take(sizeof(int32_t) * (max_tiles + 1));
+  const size_t o_perm = cv.take(dense ? 0 : sizeof(int32_t) * n_pairs);
+  const size_t o_wperm = cv.take(dense ? 0 : sizeof(float) * n_pairs);
+  const size_t o_slot = cv.take(dense ? 0 : sizeof(int32_t) * n_pairs);
+  const size_t o_hist = cv.take(sizeof(int32_t) * n_blocks * n_experts);
+  const size_t o_hidden = cv.take(2 * (size_t)n_pairs * ldh);
+  const size_t o_product = cv.take(sizeof(float) * (size_t)n_pairs * d_model);
+
+  DeviceGuard guard;
+  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
+  if (int rc = ensure_workspace(ctx, cv.used)) return rc;
+  char* ws = static_cast<char*>(ctx->ws);
+  camera::BucketTables t;
+  t.counts = reinterpret_cast<int32_t*>(ws + o_counts);
+  t.offsets = reinterpret_cast<int32_t*>(ws + o_offsets);
+  t.tile_offset = reinterpret_cast<int32_t*>(ws + o_tile_off);
+  t.tile_expert = reinterpret_cast<int32_t*>(ws + o_tile_exp);
+  t.perm = dense ? nullptr : reinterpret_cast<int32_t*>(ws + o_perm);
+  t.w_perm = dense ? nullptr : reinterpret_cast<float*>(ws + o_wperm);
+  t.slot_of = dense ? nullptr : reinterpret_cast<int32_t*>(ws + o_slot);
+  t.block_hist = reinterpret_cast<int32_t*>(ws + o_hist);
+  t.zeros = ctx->zeros;
+  void* hidden = ws + o_hidden;
+  float* product = reinterpret_cast<float*>(ws + o_product);
+
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  {
+    Bracket b(ctx, stream, CAMERA_K_BUCKET);
+    if (dense)
+      CAMERA_HIP(camera::launch_dense_tables(stream, n, n_experts, tile_m, max_tiles, t), "dense tables launch");
+    else
+      CAMERA_HIP(camera::launch_bucket(stream, topk_idx, topk_w, n, top_k, n_experts, tile_m, max_tiles, t),
+                 "bucket launch");
+  }
+  {
+    Bracket b(ctx, stream, CAMERA_K_COMPACT_HIDDEN);
+    CAMERA_HIP(camera::launch_compact_hidden(stream, X, ldx, d_model, W_gate_c, W_up_c, tab, t, hidden, (int)ldh, wide),
+               "compact hidden launch");
+  }
+  {
+    Bracket b(ctx, stream, CAMERA_K_COMPACT_DOWN);
+    CAMERA_HIP(camera::launch_compact_down(stream, hidden, (int)ldh, W_down_c, d_model, tab, t, product, wide),
+               "compact down launch");
   }
   {
     Bracket b(ctx, stream, CAMERA_K_COMBINE);

@@ -117,6 +117,23 @@ hipError_t launch_combine(hipStream_t stream, const float* product, const int32_
 hipError_t launch_output_error(hipStream_t stream, const float* Y, const float* Y_hat, int64_t n, int64_t d_model,
                                int64_t ldy, int64_t ldh, float* per_token);
 
+// ---- compact.hip ------------------------------------------------------------
+// Where each expert's kept micro-experts sit in the compacted matrices, passed to the kernels by value.
+struct CompactTable {
+  int n_experts;
+  int32_t row_off[CAMERA_MAX_EXPERTS + 1];   // first compact row of each expert (prefix of the kept counts)
+  int32_t tile_off[CAMERA_MAX_EXPERTS + 1];  // first 32-row tile of each expert
+};
+// wide: an expert's tokens are taken 64 at a time instead of 32 (more registers, half the weight reads when an
+// expert has more than 32 tokens).
+// hidden [pairs][ldh] bf16 <- a silu(x w_gate) (x w_up) on the kept rows; columns [count, round8(count)) zero.
+hipError_t launch_compact_hidden(hipStream_t stream, const void* X, int64_t ldx, int64_t d_model, const void* W_gate,
+                                 const void* W_up, const CompactTable& tab, const BucketTables& t, void* hidden,
+                                 int ldh, bool wide);
+// product [pairs][d_model] float32 <- hidden times the expert's compacted W_down block, transposed.
+hipError_t launch_compact_down(hipStream_t stream, const void* hidden, int ldh, const void* W_down, int64_t d_model,
+                               const CompactTable& tab, const BucketTables& t, float* product, bool wide);
+
 // Gather of kept micro-experts (gather.hip).  off: [n_experts + 1] exclusive prefix of the per-expert
 // entry counts (count == nullptr: d_ff each), written by launch_gather_offsets.
 hipError_t launch_gather_offsets(hipStream_t stream, const int32_t* count, int n_experts, int64_t d_ff, int32_t* off);
