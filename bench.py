@@ -57,6 +57,8 @@ def parse_args():
     ap.add_argument("--no-probes", action="store_true", help="skip the measured MFMA / HBM ceilings (about 1 s)")
     ap.add_argument("--no-forward", action="store_true",
                     help="skip the measurement of the pruned layer's output and its decoding error")
+    ap.add_argument("--no-decode", action="store_true",
+                    help="skip the measurement of a pruned layer's output from compacted weights on a 64-token batch")
     ap.add_argument("--no-apply", action="store_true",
                     help="skip the measurement of applying a 40 %% mask (gather of the kept micro-experts)")
     return ap.parse_args()
@@ -217,6 +219,80 @@ def measure_forward(cam, cfg, layers, torch, binding, ratio=0.4, reps=3):
             "synthetic_layers": stats}
 
 
+def measure_decode(cam, cfg, layers, torch, binding, ratios=(0.0, 0.2, 0.4, 0.6), batch=64, reps=30):
+    """Output of one pruned layer from its compacted weights for a decoding batch of 64 tokens, at several pruning
+    ratios (the setting of the paper's decoding-speed comparison of a pruned MoE layer), outside the timed step.
+    The call is bound by reading the kept weights of the experts the batch activates: algorithmic bytes =
+    3 * d_model * (kept micro-experts of the activated experts) * 2."""
+    if cfg.dtype != "bf16":
+        return None
+    lr = layers[0]
+    t, d = lr.t, cfg.d_model
+    X = t["X"][:batch]
+    idx, w = cam.route_topk(X, t["W_r"], t["bias"], cfg.top_k)
+    active = torch.bincount(idx.flatten().long(), minlength=cfg.n_experts).cpu() > 0
+    groups = [("W", cfg.n_experts, 0, 0)]
+    if cfg.n_shared:
+        groups.append(("Ws", cfg.n_shared, cfg.n_experts, cfg.n_micro_routed))
+    Y = torch.empty((batch, d), dtype=torch.float32, device="cuda")
+    rows = []
+    names = ("bucket", "compact_hidden", "compact_down", "combine")
+    dt = t["W_gate"].dtype
+    for ratio in ratios:
+        _, per, kept_idx, _ = cam.select_prune(lr.out["energy"], lr.seg, ratio, want_idx=True)
+        per_h = per.cpu()
+        kept = int(per_h.sum())
+        # routed and shared experts compacted into one set of buffers: one call then runs the whole layer
+        gate_c = torch.empty((kept, d), dtype=dt, device="cuda")
+        up_c = torch.empty_like(gate_c)
+        down_c = torch.empty(kept * d, dtype=dt, device="cuda")
+        pos, kept_bytes = 0, 0.0
+        for prefix, n_e, seg0, base in groups:
+            counts = per_h[seg0:seg0 + n_e]
+            n_idx = int(counts.sum())
+            cam.gather_micro_experts(t[prefix + "_gate"], t[prefix + "_up"], t[prefix + "_down"], kept_idx[pos:pos + n_idx],
+                                     per[seg0:seg0 + n_e], base,
+                                     out=(gate_c[pos:pos + n_idx], up_c[pos:pos + n_idx], down_c[pos * d:(pos + n_idx) * d]))
+            read = counts[active] if prefix == "W" else counts
+            kept_bytes += 3.0 * d * float(read.sum()) * 2.0
+            pos += n_idx
+        counts_all = per_h.tolist()
+
+        def run():
+            cam.layer_forward_compact(X, idx, w, counts_all, gate_c, up_c, down_c, n_shared=cfg.n_shared, Y=Y)
+
+        for _ in range(3):
+            run()
+        torch.cuda.synchronize()
+        for name in names:
+            cam.profile_read(binding.KERNEL_NAMES.index(name))
+        cam.profile_enable(True)
+        for _ in range(reps):
+            run()
+        torch.cuda.synchronize()
+        cam.profile_enable(False)
+        ms = {name: cam.profile_read(binding.KERNEL_NAMES.index(name))[0] / reps for name in names}
+        begin, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        begin.record()
+        for _ in range(reps):
+            run()
+        end.record()
+        torch.cuda.synchronize()
+        stream_ms = begin.elapsed_time(end) / reps
+        kernel_ms = ms["compact_hidden"] + ms["compact_down"]
+        rows.append({"ratio": ratio, "ms_per_layer": round(stream_ms, 4), "kernel_ms": {k: round(v, 4) for k, v in ms.items()},
+                     "kept_weight_bytes_read": kept_bytes, "gb_per_s": round(kept_bytes / (kernel_ms * 1e-3) / 1e9, 1)})
+        del gate_c, up_c, down_c
+    base = rows[0]
+    for row in rows:
+        row["speedup_vs_unpruned"] = round(base["ms_per_layer"] / row["ms_per_layer"], 3)
+    return {"what": f"output of layer 0 from compacted weights, {batch} tokens, per pruning ratio (decoding-speed setting)",
+            "batch_tokens": batch, "activated_routed_experts": int(active.sum()), "per_ratio": rows,
+            "roofline": {"kernel": "compact_hidden + compact_down, unpruned layer", "bound": "hbm", "achieved": base["gb_per_s"],
+                         "peak": 8000.0, "unit": "GB/s", "frac": round(base["gb_per_s"] / 8000.0, 4),
+                         "algorithmic_bytes": base["kept_weight_bytes_read"]}}
+
+
 def cpu_baseline(cfg, inputs):
     """The fp64 oracle, as it stands, on a bounded sample of the same workload: layer 0 with
     every expert cut down to a slice of its micro-experts (they are scored independently, so
@@ -345,6 +421,8 @@ def main():
     apply_mask = None if args.no_apply else measure_apply(cam, cfg, layers, torch, binding)
     forward = None if (args.no_forward or calib_tokens != cfg.n_tokens) else measure_forward(cam, cfg, layers, torch, binding)
 
+    decode = None if (args.no_decode or calib_tokens != cfg.n_tokens) else measure_decode(cam, cfg, layers, torch, binding)
+
     ms_per_step = elapsed / args.steps * 1e3
     value = calib_tokens * n_layers * args.steps / elapsed
     result = {
@@ -366,6 +444,8 @@ def main():
         result["apply_mask"] = apply_mask
     if forward is not None:
         result["pruned_layer_output"] = forward
+    if decode is not None:
+        result["pruned_layer_decode"] = decode
     if not args.no_cpu_baseline:
         del layers
         torch.cuda.empty_cache()

@@ -277,21 +277,27 @@ int camera_layer_forward(camera_ctx* ctx, void* stream,
  *
  *   X, n, d_model, ldx, topk_idx, topk_w, top_k, n_experts, flags, Y: as in camera_layer_forward
  *               (topk_idx = topk_w = NULL: every token goes through every expert with weight 1).
- *               Any n is accepted; beyond 64 tokens per expert the weights are streamed again for
- *               every further 64, so large batches belong to camera_layer_forward.
+ *               Any n is accepted; an expert's weights are streamed once per 32 of its tokens (once
+ *               per 64 when the batch brings more than 32 tokens per expert on average), so large
+ *               batches belong to camera_layer_forward.
+ *   n_shared    experts n_experts .. n_experts + n_shared - 1 are shared experts: every token goes
+ *               through them with weight 1, in the same launches as the routed ones (a decoding
+ *               batch is too small to fill the chip with the shared experts alone).  0 without routing.
  *   dtype       CAMERA_BF16 only (CAMERA_EUNSUPPORTED otherwise); Lambda is rounded to bf16 before
  *               the second contraction, float32 accumulation in both
- *   count       HOST int32 [n_experts]: kept micro-experts of every expert (>= 0, any value: the
- *               rows of a W_down block need no alignment)
+ *   count       HOST int32 [n_experts + n_shared]: kept micro-experts of every expert (>= 0, any
+ *               value: the rows of a W_down block need no alignment)
  *   W_gate_c, W_up_c   [sum(count)][d_model]: the kept rows, expert after expert
  *   W_down_c    sum(count) * d_model elements: expert e's block starts at element
  *               d_model * (count[0] + ... + count[e-1]) and is [d_model][count[e]] row-major
- *               (the three outputs of camera_gather_micro_experts, unchanged)
+ *               (the three outputs of camera_gather_micro_experts, unchanged; with shared experts:
+ *               the outputs of the call for the shared group written behind those of the routed group)
+ *   n_experts + n_shared <= CAMERA_MAX_EXPERTS.
  */
 int camera_layer_forward_compact(camera_ctx* ctx, void* stream,
                                  const void* X, int dtype, int64_t n, int64_t d_model, int64_t ldx,
                                  const int32_t* topk_idx, const float* topk_w, int top_k,
-                                 int n_experts, const int32_t* count,
+                                 int n_experts, int n_shared, const int32_t* count,
                                  const void* W_gate_c, const void* W_up_c, const void* W_down_c,
                                  int flags, float* Y);
 int camera_output_error(camera_ctx* ctx, void* stream, const float* Y, const float* Y_hat,

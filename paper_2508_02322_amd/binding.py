@@ -58,7 +58,7 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
                                                 _i64, _vp, _vp, _vp, _vp]
     lib.camera_layer_forward.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _vp, _i, _i, _i64, _vp, _vp, _i64,
                                          _vp, _i64, _vp, _i, _vp]
-    lib.camera_layer_forward_compact.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _vp, _i, _i,
+    lib.camera_layer_forward_compact.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _vp, _i, _i, _i,
                                                  _c.POINTER(_c.c_int32), _vp, _vp, _vp, _i, _vp]
     lib.camera_output_error.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _vp]
     lib.camera_profile_enable.argtypes = [_vp, _i]
@@ -216,9 +216,11 @@ class Camera:
             W_down.stride(0), _ptr(keep_mask), ACCUMULATE if accumulate else 0, _ptr(Y)))
         return Y
 
-    def layer_forward_compact(self, X, topk_idx, topk_w, count, W_gate_c, W_up_c, W_down_c, Y=None, accumulate=False):
+    def layer_forward_compact(self, X, topk_idx, topk_w, count, W_gate_c, W_up_c, W_down_c, n_shared=0, Y=None,
+                              accumulate=False):
         """Layer output from compacted weights (the outputs of gather_micro_experts); count: per-expert kept
-        micro-experts as a sequence of Python ints.  Y float32 [n, d_model]."""
+        micro-experts as a sequence of Python ints, the last n_shared of them shared experts (every token,
+        weight 1).  Y float32 [n, d_model]."""
         n, d = X.shape
         counts = [int(c) for c in count]
         top_k = 0 if topk_idx is None else topk_idx.shape[1]
@@ -226,8 +228,8 @@ class Camera:
             Y = torch.empty((n, d), dtype=torch.float32, device=self.device)
         self._check(self.lib.camera_layer_forward_compact(
             self._ctx, _stream_handle(self.device), _ptr(X), _dtype_code(X), n, d, X.stride(0), _ptr(topk_idx),
-            _ptr(topk_w), top_k, len(counts), (_c.c_int32 * len(counts))(*counts), _ptr(W_gate_c), _ptr(W_up_c),
-            _ptr(W_down_c), ACCUMULATE if accumulate else 0, _ptr(Y)))
+            _ptr(topk_w), top_k, len(counts) - int(n_shared), int(n_shared), (_c.c_int32 * len(counts))(*counts),
+            _ptr(W_gate_c), _ptr(W_up_c), _ptr(W_down_c), ACCUMULATE if accumulate else 0, _ptr(Y)))
         return Y
 
     def output_error(self, Y, Y_hat):

@@ -592,69 +592,82 @@ int camera_layer_forward(camera_ctx* ctx, void* stream_, const void* X, int dtyp
 
 int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, int dtype, int64_t n, int64_t d_model,
                                  int64_t ldx, const int32_t* topk_idx, const float* topk_w, int top_k, int n_experts,
-                                 const int32_t* count, const void* W_gate_c, const void* W_up_c, const void* W_down_c,
-                                 int flags, float* Y) {
+                                 int n_shared, const int32_t* count, const void* W_gate_c, const void* W_up_c,
+                                 const void* W_down_c, int flags, float* Y) {
   if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
   if (int rc = check_common(ctx, X, dtype, n, d_model, ldx)) return rc;
   if (dtype != CAMERA_BF16) return fail(ctx, CAMERA_EUNSUPPORTED, "dtype: the compacted layer is built for CAMERA_BF16 only");
   const bool dense = topk_idx == nullptr && topk_w == nullptr;
   if (!dense && (topk_idx == nullptr || topk_w == nullptr))
     return fail(ctx, CAMERA_EINVAL, "topk_idx / topk_w: give both or neither");
-  if (n_experts < 1 || n_experts > CAMERA_MAX_EXPERTS)
-    return fail(ctx, CAMERA_EUNSUPPORTED, "n_experts: must be in [1, %d]", CAMERA_MAX_EXPERTS);
+  if (n_shared < 0 || (dense && n_shared != 0))
+    return fail(ctx, CAMERA_EINVAL, "n_shared: must be >= 0, and 0 without routing (every expert is then dense already)");
+  const int total = n_experts + n_shared;
+  if (n_experts < 1 || total > CAMERA_MAX_EXPERTS)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "n_experts: must be >= 1, n_experts + n_shared at most %d", CAMERA_MAX_EXPERTS);
   if (!dense && (top_k < 1 || top_k > n_experts)) return fail(ctx, CAMERA_EINVAL, "top_k: must be in [1, n_experts]");
   if (flags & ~CAMERA_ACCUMULATE) return fail(ctx, CAMERA_EINVAL, "flags: only CAMERA_ACCUMULATE is accepted");
   if (count == nullptr) return fail(ctx, CAMERA_EINVAL, "count: NULL");
   camera::CompactTable tab;
-  tab.n_experts = n_experts;
-  int64_t rows = 0, tiles = 0, widest = 0;
-  for (int e = 0; e < n_experts; ++e) {
+  tab.n_experts = total;
+  int64_t rows = 0, tiles = 0, widest = 0, chunks = 0;
+  int most_chunks = 1;
+  for (int e = 0; e < total; ++e) {
     if (count[e] < 0) return fail(ctx, CAMERA_EINVAL, "count[%d]: negative", e);
     tab.row_off[e] = (int32_t)rows;
     tab.tile_off[e] = (int32_t)tiles;
+    tab.chunk_off[e] = (int32_t)chunks;
     rows += count[e];
     tiles += (count[e] + 31) / 32;
+    chunks += camera::compact_chunks(count[e]);
+    most_chunks = std::max(most_chunks, camera::compact_chunks(count[e]));
     widest = std::max<int64_t>(widest, count[e]);
     if (rows >= (int64_t(1) << 31) - 1024) return fail(ctx, CAMERA_ESHAPE, "sum of count: too large");
   }
-  for (int e = n_experts; e <= CAMERA_MAX_EXPERTS; ++e) {
+  for (int e = total; e <= CAMERA_MAX_EXPERTS; ++e) {
     tab.row_off[e] = (int32_t)rows;
     tab.tile_off[e] = (int32_t)tiles;
+    tab.chunk_off[e] = (int32_t)chunks;
   }
   if (rows > 0 && (W_gate_c == nullptr || W_up_c == nullptr || W_down_c == nullptr))
     return fail(ctx, CAMERA_EINVAL, "W_gate_c / W_up_c / W_down_c: NULL");
   if (n > 0 && Y == nullptr) return fail(ctx, CAMERA_EINVAL, "Y: NULL");
   if (!aligned16(W_gate_c) || !aligned16(W_up_c) || !aligned16(W_down_c) || !aligned16(Y))
     return fail(ctx, CAMERA_ESHAPE, "W_gate_c / W_up_c / W_down_c / Y: not 16-byte aligned");
-  const int64_t n_pairs = dense ? n * n_experts : n * (int64_t)top_k;
+  const int terms = dense ? n_experts : top_k + n_shared;  // experts that every token goes through
+  const int64_t n_pairs = n * (int64_t)terms;
   if (n_pairs >= (int64_t(1) << 31) - 1024) return fail(ctx, CAMERA_ESHAPE, "routed pairs: must be below 2^31");
   const int64_t ldh = (widest + 7) / 8 * 8;
-  if (n_pairs * std::max<int64_t>(ldh, d_model) >= (int64_t(1) << 40))
+  if (n_pairs * std::max<int64_t>(ldh, d_model * most_chunks) >= (int64_t(1) << 38))
     return fail(ctx, CAMERA_EUNSUPPORTED, "batch too large for the compacted layer: use camera_layer_forward");
-  if ((int64_t)n_experts * ((d_model + 31) / 32) >= (int64_t(1) << 31) - 1024)
+  if (chunks * ((d_model + 31) / 32) >= (int64_t(1) << 31) - 1024)
     return fail(ctx, CAMERA_ESHAPE, "n_experts * d_model: too large");
   if (n == 0) return CAMERA_OK;
 
-  // tokens per expert to be expected: above 32 the kernels take them 64 at a time
-  const bool wide = (dense ? n : n * (int64_t)top_k / n_experts) > 32;
-  const int tile_m = 256;  // only the bucket order is used here; the M-tile tables are a by-product
-  const int64_t max_tiles64 = dense ? n_experts * ((n + tile_m - 1) / tile_m) : n_pairs / tile_m + n_experts;
+  // grid rows of 32 tokens per expert; the last row also takes what lies beyond it
+  const int token_groups = (int)std::min<int64_t>((n + 31) / 32, 64);
+  const bool small = !dense && n_pairs <= camera::kCompactSmallPairs;
+  const int tile_m = 256;  // of the general counting sort: only its bucket order is used, the M-tile tables are a by-product
+  const int64_t max_tiles64 = dense ? n_experts * ((n + tile_m - 1) / tile_m) : n_pairs / tile_m + total;
   if (max_tiles64 > 65535)
     return fail(ctx, CAMERA_EUNSUPPORTED, "batch too large for the compacted layer: use camera_layer_forward");
   const int max_tiles = (int)max_tiles64;
-  const int64_t n_blocks = dense ? 0 : camera::bucket_blocks(n_pairs);
+  const int64_t n_blocks = (dense || small) ? 0 : camera::bucket_blocks(n_pairs);
+  const bool append = !dense && !small && n_shared > 0;
 
   Carver cv;
-  const size_t o_counts = cv.take(sizeof(int32_t) * n_experts);
-  const size_t o_offsets = cv.take(sizeof(int32_t) * (n_experts + 1));
-  const size_t o_tile_off = cv.take(sizeof(int32_t) * (n_experts + 1));
+  const size_t o_counts = cv.take(sizeof(int32_t) * total);
+  const size_t o_offsets = cv.take(sizeof(int32_t) * (total + 1));
+  const size_t o_tile_off = cv.take(sizeof(int32_t) * (total + 1));
   const size_t o_tile_exp = cv.take(sizeof(int32_t) * (max_tiles + 1));
   const size_t o_perm = cv.take(dense ? 0 : sizeof(int32_t) * n_pairs);
   const size_t o_wperm = cv.take(dense ? 0 : sizeof(float) * n_pairs);
   const size_t o_slot = cv.take(dense ? 0 : sizeof(int32_t) * n_pairs);
-  const size_t o_hist = cv.take(sizeof(int32_t) * n_blocks * n_experts);
+  const size_t o_hist = cv.take(sizeof(int32_t) * n_blocks * total);
+  const size_t o_idx_aug = cv.take(append ? sizeof(int32_t) * n_pairs : 0);
+  const size_t o_w_aug = cv.take(append ? sizeof(float) * n_pairs : 0);
   const size_t o_hidden = cv.take(2 * (size_t)n_pairs * ldh);
-  const size_t o_product = cv.take(sizeof(float) * (size_t)n_pairs * d_model);
+  const size_t o_product = cv.take(sizeof(float) * (size_t)most_chunks * n_pairs * d_model);
 
   DeviceGuard guard;
   CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
@@ -676,27 +689,43 @@ int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, 
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   {
     Bracket b(ctx, stream, CAMERA_K_BUCKET);
-    if (dense)
+    if (dense) {
       CAMERA_HIP(camera::launch_dense_tables(stream, n, n_experts, tile_m, max_tiles, t), "dense tables launch");
-    else
-      CAMERA_HIP(camera::launch_bucket(stream, topk_idx, topk_w, n, top_k, n_experts, tile_m, max_tiles, t),
-                 "bucket launch");
+    } else if (small) {
+      CAMERA_HIP(camera::launch_compact_bucket_small(stream, topk_idx, topk_w, n, top_k, n_experts, n_shared, t),
+                 "small bucket launch");
+    } else {
+      const int32_t* idx = topk_idx;
+      const float* wts = topk_w;
+      if (append) {
+        int32_t* idx_aug = reinterpret_cast<int32_t*>(ws + o_idx_aug);
+        float* w_aug = reinterpret_cast<float*>(ws + o_w_aug);
+        CAMERA_HIP(camera::launch_compact_append_shared(stream, topk_idx, topk_w, n, top_k, n_experts, n_shared, idx_aug,
+                                                        w_aug),
+                   "append shared launch");
+        idx = idx_aug;
+        wts = w_aug;
+      }
+      CAMERA_HIP(camera::launch_bucket(stream, idx, wts, n, terms, total, tile_m, max_tiles, t), "bucket launch");
+    }
   }
   {
     Bracket b(ctx, stream, CAMERA_K_COMPACT_HIDDEN);
-    CAMERA_HIP(camera::launch_compact_hidden(stream, X, ldx, d_model, W_gate_c, W_up_c, tab, t, hidden, (int)ldh, wide),
+    CAMERA_HIP(camera::launch_compact_hidden(stream, X, ldx, d_model, W_gate_c, W_up_c, tab, t, token_groups, hidden,
+                                             (int)ldh),
                "compact hidden launch");
   }
   {
     Bracket b(ctx, stream, CAMERA_K_COMPACT_DOWN);
-    CAMERA_HIP(camera::launch_compact_down(stream, hidden, (int)ldh, W_down_c, d_model, tab, t, product, wide),
+    CAMERA_HIP(camera::launch_compact_down(stream, hidden, (int)ldh, W_down_c, d_model, tab, t, token_groups, n_pairs,
+                                           product),
                "compact down launch");
   }
   {
     Bracket b(ctx, stream, CAMERA_K_COMBINE);
-    CAMERA_HIP(camera::launch_combine(stream, product, t.slot_of, n, top_k, n_experts, d_model,
-                                      (flags & CAMERA_ACCUMULATE) ? 1 : 0, Y),
-               "combine launch");
+    CAMERA_HIP(camera::launch_compact_combine(stream, product, tab, t, n, terms, d_model, n_pairs,
+                                              (flags & CAMERA_ACCUMULATE) ? 1 : 0, Y),
+               "compact combine launch");
   }
   return CAMERA_OK;
 }

@@ -121,18 +121,39 @@ hipError_t launch_output_error(hipStream_t stream, const float* Y, const float* 
 // Where each expert's kept micro-experts sit in the compacted matrices, passed to the kernels by value.
 struct CompactTable {
   int n_experts;
-  int32_t row_off[CAMERA_MAX_EXPERTS + 1];   // first compact row of each expert (prefix of the kept counts)
-  int32_t tile_off[CAMERA_MAX_EXPERTS + 1];  // first 32-row tile of each expert
+  int32_t row_off[CAMERA_MAX_EXPERTS + 1];    // first compact row of each expert (prefix of the kept counts)
+  int32_t tile_off[CAMERA_MAX_EXPERTS + 1];   // first 32-row tile of each expert (first contraction)
+  int32_t chunk_off[CAMERA_MAX_EXPERTS + 1];  // first K chunk of each expert (second contraction)
 };
-// wide: an expert's tokens are taken 64 at a time instead of 32 (more registers, half the weight reads when an
-// expert has more than 32 tokens).
-// hidden [pairs][ldh] bf16 <- a silu(x w_gate) (x w_up) on the kept rows; columns [count, round8(count)) zero.
+// K chunks of an expert with `count` kept micro-experts in the second contraction: chunks of at most
+// kCompactChunk elements, at most kCompactMaxChunks of them (0 for an expert that keeps nothing).
+constexpr int kCompactChunk = 3072;
+constexpr int kCompactMaxChunks = 8;
+inline int compact_chunks(int count) {
+  const int c = (count + kCompactChunk - 1) / kCompactChunk;
+  return c > kCompactMaxChunks ? kCompactMaxChunks : c;
+}
+// Bucket tables (counts, offsets, perm, w_perm, slot_of) of the pairs (token, routed choice k < top_k) and
+// (token, appended expert n_experts + s, weight 1), in one launch; n * (top_k + n_shared) <= kCompactSmallPairs.
+constexpr int kCompactSmallPairs = 2048;
+hipError_t launch_compact_bucket_small(hipStream_t stream, const int32_t* topk_idx, const float* topk_w, int64_t n,
+                                       int top_k, int n_experts, int n_shared, const BucketTables& t);
+// idx_aug / w_aug [n][top_k + n_shared]: the routed choices followed by the appended experts with weight 1.
+hipError_t launch_compact_append_shared(hipStream_t stream, const int32_t* topk_idx, const float* topk_w, int64_t n,
+                                        int top_k, int n_experts, int n_shared, int32_t* idx_aug, float* w_aug);
+// token_groups: grid rows of 32 tokens per expert; the last one also takes what lies beyond.
+// hidden [slots][ldh] bf16 <- a silu(x w_gate) (x w_up) on the kept rows; columns [count, round8(count)) zero.
 hipError_t launch_compact_hidden(hipStream_t stream, const void* X, int64_t ldx, int64_t d_model, const void* W_gate,
-                                 const void* W_up, const CompactTable& tab, const BucketTables& t, void* hidden,
-                                 int ldh, bool wide);
-// product [pairs][d_model] float32 <- hidden times the expert's compacted W_down block, transposed.
+                                 const void* W_up, const CompactTable& tab, const BucketTables& t, int token_groups,
+                                 void* hidden, int ldh);
+// partial [chunk within its expert][n_slots][d_model] float32 <- hidden times the chunk of the expert's W_down block.
 hipError_t launch_compact_down(hipStream_t stream, const void* hidden, int ldh, const void* W_down, int64_t d_model,
-                               const CompactTable& tab, const BucketTables& t, float* product, bool wide);
+                               const CompactTable& tab, const BucketTables& t, int token_groups, int64_t n_slots,
+                               float* partial);
+// Y[token] (+)= the partial rows of the token's slots (experts in k order, chunks in chunk order).
+hipError_t launch_compact_combine(hipStream_t stream, const float* partial, const CompactTable& tab,
+                                  const BucketTables& t, int64_t n, int terms, int64_t d_model, int64_t n_slots,
+                                  int accumulate, float* Y);
 
 // Gather of kept micro-experts (gather.hip).  off: [n_experts + 1] exclusive prefix of the per-expert
 // entry counts (count == nullptr: d_ff each), written by launch_gather_offsets.

@@ -4,21 +4,36 @@
 // pruned MoE layer, batch of 64 tokens).
 //
 // With a handful of tokens per expert the layer is bound by reading each
-// activated expert's weights once, so nothing is tiled through LDS: a wave owns
-// 32 weight rows, streams them from HBM straight into MFMA operand registers
-// (v_mfma_f32_32x32x16_bf16: the weight rows are the M side, up to 64 tokens of
-// the expert the N side) and never shares data with another wave.  Inside a
-// 64-element K block lane (row, half) holds the 32 consecutive elements
-// [32*half, 32*half + 32) of its row as four 16-byte loads, so the two lanes of
-// a row read one full 128-byte line; the token operand uses the same K order,
-// which a sum over K does not care about.  Experts that no token of the batch
-// selected are skipped before any weight is read.
+// activated expert's weights once, so no operand is tiled through LDS: a
+// workgroup owns 32 weight rows and up to 32 tokens of one expert, its waves
+// split the K extent between them and stream their share from HBM straight
+// into MFMA operand registers (v_mfma_f32_32x32x16_bf16: the weight rows are
+// the M side, the tokens the N side); the partial sums of the waves meet in
+// LDS, added in wave order.  Work items are kept small and alike, so that a
+// launch has several times more workgroups than the chip holds at once and its
+// last round does not leave most compute units idle:
+//   - the K extent of a workgroup is split between its waves;
+//   - the 32-token groups of an expert go to different workgroups (grid y),
+//     which read the same weights at about the same time (the second read is
+//     served by the caches); the workgroups of groups an expert does not have
+//     leave at once;
+//   - in the second contraction an expert with many kept micro-experts (a
+//     large shared expert) is cut into K chunks that go to different
+//     workgroups, each writing its own partial product rows; the chunks are
+//     added, in chunk order, when the token's experts are summed.
+// Inside a 64-element K block lane (row, half) holds the 32 consecutive
+// elements [32*half, 32*half + 32) of its row as four 16-byte loads, so the two
+// lanes of a row read one full 128-byte line; the token operand uses the same
+// K order, which a sum over K does not care about.  Experts that no token of
+// the batch selected are skipped before any weight is read.
 //
 //   hidden  : Lambda[slot][c] = a silu(x w_gate,c) (x w_up,c), bf16, for the c < count[e] kept micro-experts
-//   down    : product[slot][r] = sum_c Lambda[slot][c] W_down_e[r][c], float32
+//   down    : partial[chunk][slot][r] = sum over the chunk's c of Lambda[slot][c] W_down_e[r][c], float32
+//   combine : y_token (+)= the partial rows of its experts' slots, experts in k order, chunks in chunk order
 // The rows of the compacted W_down block of an expert are count[e] elements
 // long, which need not be a multiple of eight: its 16-byte loads are unaligned
-// (2-byte aligned), and the ragged end of a row is read element by element.
+// (2-byte aligned), and the chunk that straddles the end of a row is taken as
+// the 16 bytes that end there, shifted down.
 #include "camera_internal.h"
 
 namespace camera {
@@ -27,10 +42,17 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) uint64_t u64x2;
+typedef __attribute__((ext_vector_type(8))) int16_t i16x8;
 
-constexpr int kThreads = 256;
-constexpr int kWavesPerBlock = kThreads / kWave;
-constexpr int kRows = 32;    // weight rows per wave (the MFMA's M)
+#ifndef CAMERA_COMPACT_KSPLIT
+#define CAMERA_COMPACT_KSPLIT 4
+#endif
+constexpr int kSplit = CAMERA_COMPACT_KSPLIT;  // waves of a workgroup, each with its share of the K blocks
+static_assert(kSplit == 1 || kSplit == 2 || kSplit == 4, "the four accumulator groups are dealt to 1, 2 or 4 waves");
+constexpr int kThreads = kWave * kSplit;
+constexpr int kRows = 32;    // weight rows per workgroup (the MFMA's M)
+constexpr int kTokens = 32;  // tokens per workgroup (the MFMA's N)
 constexpr int kKBlock = 64;  // K elements per step: 4 MFMAs of K = 16
 
 __device__ __forceinline__ float silu_f32(float g) {
@@ -64,22 +86,49 @@ __device__ __forceinline__ void load_frag(Frag& f, const __bf16* p) {
   for (int j = 0; j < 4; ++j) f.c[j] = ALIGNED ? load8(p + 8 * j) : load8_unaligned(p + 8 * j);
 }
 
-// The last, partial K block.  `k` is the K index of the lane's first element, `k_full` the end of the valid
-// elements, `k_pad` (a multiple of 8, >= k_full) the end of what may be read when PAD_READABLE (an operand whose
-// rows are padded with zeros up to k_pad), else elements at and beyond k_full are never touched.
-template <bool ALIGNED, bool PAD_READABLE>
-__device__ __forceinline__ void load_frag_tail(Frag& f, const __bf16* p, int k, int k_full, int k_pad) {
+// out[i] = w[i + d] for i + d < 8, else 0 (1 <= d <= 7, the same for the whole wave)
+__device__ __forceinline__ bf16x8 shift_down(bf16x8 w, int d) {
+  const u64x2 v = __builtin_bit_cast(u64x2, w);
+  const int s = 16 * d;
+  u64x2 o;
+  if (s < 64) {
+    o[0] = (v[0] >> s) | (v[1] << (64 - s));
+    o[1] = v[1] >> s;
+  } else {
+    o[0] = v[1] >> (s - 64);
+    o[1] = 0;
+  }
+  return __builtin_bit_cast(bf16x8, o);
+}
+
+// The last, partial K block of an operand row.  `k` is the K index (inside the block) of the lane's first element,
+// `k_full` the end of the valid elements.  MODE says what lies behind k_full:
+//   kWhole   k_full is a multiple of 8 (no partial chunk)
+//   kPadded  the row is zero-filled and readable up to the next multiple of 8
+//   kRagged  nothing at or beyond k_full may be touched: the chunk that straddles the end is taken as the 16 bytes
+//            that end at k_full, shifted down (`row_k`, the valid elements of the whole row, must be >= 8 for
+//            that; shorter rows are read element by element)
+enum TailMode { kWhole, kPadded, kRagged };
+template <bool ALIGNED, TailMode MODE>
+__device__ __forceinline__ void load_frag_tail(Frag& f, const __bf16* p, int k, int k_full, int row_k) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int kj = k + 8 * j;
-    if (kj + 8 <= k_full || (PAD_READABLE && kj < k_pad)) {
+    if (kj + 8 <= k_full || (MODE == kPadded && kj < k_full)) {
       f.c[j] = ALIGNED ? load8(p + 8 * j) : load8_unaligned(p + 8 * j);
-    } else if (kj < k_full) {
-      bf16x8 v = zero8();
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-        if (kj + i < k_full) v[i] = p[8 * j + i];
-      f.c[j] = v;
+    } else if (MODE == kRagged && kj < k_full) {
+      const int valid = k_full - kj;  // 1..7, the same for every lane that gets here
+      if (row_k >= 8) {
+        f.c[j] = shift_down(load8_unaligned(p + 8 * j + valid - 8), 8 - valid);
+      } else {
+        u64x2 o = {0, 0};
+#pragma unroll 1
+        for (int i = 0; i < valid; ++i) {
+          const uint64_t x = __builtin_bit_cast(uint16_t, p[8 * j + i]);
+          o[i >> 2] |= x << (16 * (i & 3));
+        }
+        f.c[j] = __builtin_bit_cast(bf16x8, o);
+      }
     } else {
       f.c[j] = zero8();
     }
@@ -91,68 +140,102 @@ __device__ __forceinline__ void mfma4(f32x16& acc, const Frag& a, const Frag& b)
   for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.c[j], b.c[j], acc, 0, 0, 0);
 }
 
+// ---- partial sums of the waves ------------------------------------------------------------------------------
+// red[wave][tile][i][lane]: accumulator element i of `lane`.  With one wave per workgroup nothing goes through LDS.
+template <int TILES>
+struct Reduce {
+  float (*red)[TILES][16][kWave];
+  __device__ __forceinline__ void put(int wave, int tile, const f32x16& acc, int lane) const {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) red[wave][tile][i][lane] = acc[i];
+  }
+  __device__ __forceinline__ float get(int tile, int i, int lane) const {
+    float s = red[0][tile][i][lane];
+#pragma unroll
+    for (int w = 1; w < kSplit; ++w) s += red[w][tile][i][lane];
+    return s;
+  }
+};
+// The groups of four accumulator elements (q = i / 4) that `wave` finishes after the reduction.
+__device__ __forceinline__ bool owns_group(int wave, int q) { return (q * kSplit) / 4 == wave; }
+
+// K blocks [kb0, kb1) of a wave; the wave with `tail` also takes the partial block after the last full one.
+struct KRange {
+  int kb0, kb1;
+  bool tail;
+};
+__device__ __forceinline__ KRange k_range(int full_blocks, bool has_tail, int wave) {
+  KRange k;
+  k.kb0 = full_blocks * wave / kSplit;
+  k.kb1 = full_blocks * (wave + 1) / kSplit;
+  k.tail = has_tail && wave == kSplit - 1;
+  return k;
+}
+
+// Last index e in [0, n) with off[e] <= x, for a rising table with off[0] <= x < off[n].
+__device__ __forceinline__ int find_segment(const int32_t* off, int n, int x) {
+  int lo = 0, hi = n;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (off[mid] <= x) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
 // ---- Lambda = a silu(X W_gate^T) (X W_up^T) on the kept rows ----------------------------------------------
-// One pass over the K extent for up to 64 tokens (TWO) or up to 32 (not TWO) of one expert.
-template <bool TWO>
 __device__ __forceinline__ void hidden_pass(const __bf16* __restrict__ wg, const __bf16* __restrict__ wu,
-                                            const __bf16* __restrict__ x0, const __bf16* __restrict__ x1, int d_model,
-                                            f32x16& g0, f32x16& u0, f32x16& g1, f32x16& u1) {
-  const int full = d_model / kKBlock;
-  Frag ag[2], au[2], b0[2], b1[2];
+                                            const __bf16* __restrict__ x, int d_model, KRange kr, f32x16& g,
+                                            f32x16& u) {
+  Frag ag[2], au[2], b[2];
   auto fetch = [&](int buf, int kb) {
     const int off = kb * kKBlock;
     load_frag<true>(ag[buf], wg + off);
     load_frag<true>(au[buf], wu + off);
-    load_frag<true>(b0[buf], x0 + off);
-    if (TWO) load_frag<true>(b1[buf], x1 + off);
+    load_frag<true>(b[buf], x + off);
   };
   auto multiply = [&](int buf) {
-    mfma4(g0, ag[buf], b0[buf]);
-    mfma4(u0, au[buf], b0[buf]);
-    if (TWO) {
-      mfma4(g1, ag[buf], b1[buf]);
-      mfma4(u1, au[buf], b1[buf]);
-    }
+    mfma4(g, ag[buf], b[buf]);
+    mfma4(u, au[buf], b[buf]);
   };
-  if (full > 0) fetch(0, 0);
-  int kb = 0;
-  for (; kb + 2 <= full; kb += 2) {  // the loads of the next block are in flight while this one multiplies
+  int kb = kr.kb0;
+  if (kb < kr.kb1) fetch(0, kb);
+  for (; kb + 2 <= kr.kb1; kb += 2) {  // the loads of the next block are in flight while this one multiplies
     fetch(1, kb + 1);
     multiply(0);
-    if (kb + 2 < full) fetch(0, kb + 2);
+    if (kb + 2 < kr.kb1) fetch(0, kb + 2);
     multiply(1);
   }
-  if (kb < full) multiply(0);
-  const int rem = d_model - full * kKBlock;  // a multiple of 8
-  if (rem > 0) {
+  if (kb < kr.kb1) multiply(0);
+  if (kr.tail) {
+    const int full = d_model / kKBlock;
+    const int rem = d_model - full * kKBlock;         // a multiple of 8
     const int half_k = (threadIdx.x & 63) >> 5 << 5;  // K index of the lane's first element inside the block
     const int off = full * kKBlock;
-    load_frag_tail<true, false>(ag[0], wg + off, half_k, rem, rem);
-    load_frag_tail<true, false>(au[0], wu + off, half_k, rem, rem);
-    load_frag_tail<true, false>(b0[0], x0 + off, half_k, rem, rem);
-    if (TWO) load_frag_tail<true, false>(b1[0], x1 + off, half_k, rem, rem);
+    load_frag_tail<true, kWhole>(ag[0], wg + off, half_k, rem, d_model);
+    load_frag_tail<true, kWhole>(au[0], wu + off, half_k, rem, d_model);
+    load_frag_tail<true, kWhole>(b[0], x + off, half_k, rem, d_model);
     multiply(0);
   }
 }
 
-// WIDE: the tokens of an expert are taken 64 at a time (two accumulator tiles), else 32 at a time.
-template <bool WIDE>
-__global__ __launch_bounds__(kThreads) void compact_hidden_kernel(
+// grid: x = 32-row tiles of all experts (exactly tab.tile_off[tab.n_experts]), y = 32-token groups.  The
+// workgroups of the last group also take any further groups of their expert (an expert can hold more tokens
+// than the batch has only if a token names it twice).
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void compact_hidden_kernel(
     const __bf16* __restrict__ X, int64_t ldx, int d_model, const __bf16* __restrict__ W_gate,
     const __bf16* __restrict__ W_up, CompactTable tab, const int32_t* __restrict__ counts,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm, const float* __restrict__ w_perm,
     __bf16* __restrict__ H, int ldh) {
+  __shared__ float red_mem[kSplit][2][16][kWave];  // gate and up
+  const Reduce<2> red{red_mem};
   const int lane = threadIdx.x & 63;
-  const int tile = __builtin_amdgcn_readfirstlane((int)blockIdx.x * kWavesPerBlock + (int)(threadIdx.x >> 6));
-  if (tile >= tab.tile_off[tab.n_experts]) return;
-  int lo = 0, hi = tab.n_experts;  // tile_off[lo] <= tile < tile_off[hi]
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (tab.tile_off[mid] <= tile) lo = mid; else hi = mid;
-  }
-  const int e = lo;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int tile = blockIdx.x;
+  const int e = find_segment(tab.tile_off, tab.n_experts, tile);
   const int m = __builtin_amdgcn_readfirstlane(counts[e]);
-  if (m <= 0) return;  // no token of the batch selected this expert: its weights are not read
+  const int t_first = (int)blockIdx.y * kTokens;
+  if (t_first >= m) return;  // no token (of this group) selected the expert: the whole workgroup leaves, nothing is read
+  const bool last_group = blockIdx.y + 1 == gridDim.y;
   const int slot0 = __builtin_amdgcn_readfirstlane(offsets[e]);
   const int cnt = tab.row_off[e + 1] - tab.row_off[e];
   const int cnt8 = (cnt + 7) & ~7;
@@ -162,158 +245,327 @@ __global__ __launch_bounds__(kThreads) void compact_hidden_kernel(
   const int64_t w_off = ((int64_t)tab.row_off[e] + row) * d_model + h * 32;
   const __bf16* wg = W_gate + w_off;
   const __bf16* wu = W_up + w_off;
+  const KRange kr = k_range(d_model / kKBlock, d_model % kKBlock != 0, wave);
 
-  for (int t0 = 0; t0 < m; t0 += WIDE ? 64 : 32) {
-    const bool two = WIDE && m - t0 > 32;
-    const int ta = min(t0 + r, m - 1), tb = min(t0 + 32 + r, m - 1);  // clamped: columns past m are dropped
-    const int64_t tok_a = perm ? perm[slot0 + ta] : ta;
-    const int64_t tok_b = perm ? perm[slot0 + tb] : tb;
-    const __bf16* x0 = X + tok_a * ldx + h * 32;
-    const __bf16* x1 = X + tok_b * ldx + h * 32;
-    f32x16 g0 = {}, u0 = {}, g1 = {}, u1 = {};
-    if constexpr (WIDE) {
-      if (two)
-        hidden_pass<true>(wg, wu, x0, x1, d_model, g0, u0, g1, u1);
-      else
-        hidden_pass<false>(wg, wu, x0, x1, d_model, g0, u0, g1, u1);
-    } else {
-      hidden_pass<false>(wg, wu, x0, x1, d_model, g0, u0, g1, u1);
+  for (int t0 = t_first; t0 < m; t0 += kTokens) {
+    const int t = t0 + r;
+    const int tc = min(t, m - 1);  // clamped: columns past m are dropped
+    const int64_t tok = perm ? perm[slot0 + tc] : tc;
+    const __bf16* x = X + tok * ldx + h * 32;
+    f32x16 g = {}, u = {};
+    hidden_pass(wg, wu, x, d_model, kr, g, u);
+    if constexpr (kSplit > 1) {
+      red.put(wave, 0, g, lane);
+      red.put(wave, 1, u, lane);
+      __syncthreads();
     }
     // accumulator element i of a lane: weight row 8*(i/4) + 4*h + i%4, token column r
-#pragma unroll
-    for (int tile_n = 0; tile_n < 2; ++tile_n) {
-      const int t = t0 + 32 * tile_n + r;
-      if ((tile_n == 1 && !two) || t >= m) continue;
+    if (t < m) {
       const int64_t slot = slot0 + t;
       const float a = w_perm ? w_perm[slot] : 1.0f;
-      const f32x16& g = tile_n ? g1 : g0;
-      const f32x16& u = tile_n ? u1 : u0;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
+        if (!owns_group(wave, q)) continue;
         const int c = c0 + 8 * q + 4 * h;
         if (c >= cnt8) continue;  // columns [cnt, cnt8) are written as zeros: the down kernel reads whole chunks
         bf16x4 out;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float lam = a * silu_f32(g[4 * q + i]) * u[4 * q + i];
+          const float gv = kSplit > 1 ? red.get(0, 4 * q + i, lane) : g[4 * q + i];
+          const float uv = kSplit > 1 ? red.get(1, 4 * q + i, lane) : u[4 * q + i];
+          const float lam = a * silu_f32(gv) * uv;
           out[i] = (__bf16)(c + i < cnt ? lam : 0.0f);
         }
         *reinterpret_cast<bf16x4*>(H + slot * ldh + c) = out;
       }
     }
+    if (!last_group) break;
+    if constexpr (kSplit > 1) __syncthreads();  // the next pass writes the same LDS
   }
 }
 
-// ---- product = Lambda W_down_e^T ---------------------------------------------------------------------------
-template <bool TWO>
-__device__ __forceinline__ void down_pass(const __bf16* __restrict__ wd, const __bf16* __restrict__ h0,
-                                          const __bf16* __restrict__ h1, int cnt, int cnt8, f32x16& p0, f32x16& p1) {
-  const int full = cnt / kKBlock;
-  Frag a[2], b0[2], b1[2];
+// ---- partial = Lambda W_down_e^T over one K chunk ----------------------------------------------------------
+// wd, hrow point at the first element of the chunk; k_len its length; row_k the valid length of the whole row.
+__device__ __forceinline__ void down_pass(const __bf16* __restrict__ wd, const __bf16* __restrict__ hrow, int k_len,
+                                          int row_k, KRange kr, f32x16& p) {
+  Frag a[2], b[2];
   auto fetch = [&](int buf, int kb) {
     const int off = kb * kKBlock;
     load_frag<false>(a[buf], wd + off);
-    load_frag<true>(b0[buf], h0 + off);
-    if (TWO) load_frag<true>(b1[buf], h1 + off);
+    load_frag<true>(b[buf], hrow + off);
   };
-  auto multiply = [&](int buf) {
-    mfma4(p0, a[buf], b0[buf]);
-    if (TWO) mfma4(p1, a[buf], b1[buf]);
-  };
-  if (full > 0) fetch(0, 0);
-  int kb = 0;
-  for (; kb + 2 <= full; kb += 2) {
+  int kb = kr.kb0;
+  if (kb < kr.kb1) fetch(0, kb);
+  for (; kb + 2 <= kr.kb1; kb += 2) {
     fetch(1, kb + 1);
-    multiply(0);
-    if (kb + 2 < full) fetch(0, kb + 2);
-    multiply(1);
+    mfma4(p, a[0], b[0]);
+    if (kb + 2 < kr.kb1) fetch(0, kb + 2);
+    mfma4(p, a[1], b[1]);
   }
-  if (kb < full) multiply(0);
-  const int rem = cnt - full * kKBlock;
-  if (rem > 0) {
+  if (kb < kr.kb1) mfma4(p, a[0], b[0]);
+  if (kr.tail) {
+    const int full = k_len / kKBlock;
+    const int rem = k_len - full * kKBlock;
     const int half_k = (threadIdx.x & 63) >> 5 << 5;
     const int off = full * kKBlock;
-    const int rem8 = cnt8 - off;
-    load_frag_tail<false, false>(a[0], wd + off, half_k, rem, rem8);  // never past the end of the weight row
-    load_frag_tail<true, true>(b0[0], h0 + off, half_k, rem, rem8);   // Lambda rows are zero-filled up to cnt8
-    if (TWO) load_frag_tail<true, true>(b1[0], h1 + off, half_k, rem, rem8);
-    multiply(0);
+    load_frag_tail<false, kRagged>(a[0], wd + off, half_k, rem, row_k);   // never past the end of the weight row
+    load_frag_tail<true, kPadded>(b[0], hrow + off, half_k, rem, row_k);  // Lambda rows are zero-filled up to a multiple of 8
+    mfma4(p, a[0], b[0]);
   }
 }
 
-template <bool WIDE>
-__global__ __launch_bounds__(kThreads) void compact_down_kernel(const __bf16* __restrict__ H, int ldh,
-                                                                const __bf16* __restrict__ W_down, int d_model,
-                                                                CompactTable tab, const int32_t* __restrict__ counts,
-                                                                const int32_t* __restrict__ offsets,
-                                                                float* __restrict__ product) {
+// Length of the K chunks of an expert with cnt kept micro-experts cut into n_chunks (a multiple of 64).
+__device__ __forceinline__ int chunk_length(int cnt, int n_chunks) {
+  return ((cnt + n_chunks - 1) / n_chunks + kKBlock - 1) & ~(kKBlock - 1);
+}
+
+// grid: x = (K chunk of an expert, 32-row tile of d_model): tab.chunk_off[tab.n_experts] * row_tiles workgroups,
+// y = 32-token groups.  partial is [chunk within the expert][n_slots][d_model].
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) void compact_down_kernel(
+    const __bf16* __restrict__ H, int ldh, const __bf16* __restrict__ W_down, int d_model, CompactTable tab,
+    const int32_t* __restrict__ counts, const int32_t* __restrict__ offsets, int64_t n_slots,
+    float* __restrict__ partial) {
+  __shared__ float red_mem[kSplit][1][16][kWave];
+  const Reduce<1> red{red_mem};
   const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int row_tiles = (d_model + kRows - 1) / kRows;
-  const int tile = __builtin_amdgcn_readfirstlane((int)blockIdx.x * kWavesPerBlock + (int)(threadIdx.x >> 6));
-  if (tile >= tab.n_experts * row_tiles) return;
-  const int e = tile / row_tiles;
-  const int r0 = (tile - e * row_tiles) * kRows;
+  const int chunk = blockIdx.x / row_tiles;
+  const int r0 = ((int)blockIdx.x - chunk * row_tiles) * kRows;
+  const int e = find_segment(tab.chunk_off, tab.n_experts, chunk);
   const int m = __builtin_amdgcn_readfirstlane(counts[e]);
-  if (m <= 0) return;
+  const int t_first = (int)blockIdx.y * kTokens;
+  if (t_first >= m) return;
+  const bool last_group = blockIdx.y + 1 == gridDim.y;
   const int slot0 = __builtin_amdgcn_readfirstlane(offsets[e]);
-  const int cnt = tab.row_off[e + 1] - tab.row_off[e];  // 0: the product rows of this expert's tokens are zero
-  const int cnt8 = (cnt + 7) & ~7;
+  const int cnt = tab.row_off[e + 1] - tab.row_off[e];
+  const int chunk_in = chunk - tab.chunk_off[e];
+  const int len = chunk_length(cnt, tab.chunk_off[e + 1] - tab.chunk_off[e]);
+  const int k0 = min(chunk_in * len, cnt);
+  const int k_len = min(len, cnt - k0);
   const int r = lane & 31, h = lane >> 5;
   const int row = min(r0 + r, d_model - 1);
-  const __bf16* wd = W_down + (int64_t)tab.row_off[e] * d_model + (int64_t)row * cnt + h * 32;
+  const __bf16* wd = W_down + (int64_t)tab.row_off[e] * d_model + (int64_t)row * cnt + k0 + h * 32;
+  const KRange kr = k_range(k_len / kKBlock, k_len % kKBlock != 0, wave);
+  float* out_chunk = partial + (int64_t)chunk_in * n_slots * d_model;
 
-  for (int t0 = 0; t0 < m; t0 += WIDE ? 64 : 32) {
-    const bool two = WIDE && m - t0 > 32;
-    const int ta = min(t0 + r, m - 1), tb = min(t0 + 32 + r, m - 1);
-    const __bf16* h0 = H + (int64_t)(slot0 + ta) * ldh + h * 32;
-    const __bf16* h1 = H + (int64_t)(slot0 + tb) * ldh + h * 32;
-    f32x16 p0 = {}, p1 = {};
-    if constexpr (WIDE) {
-      if (two)
-        down_pass<true>(wd, h0, h1, cnt, cnt8, p0, p1);
-      else
-        down_pass<false>(wd, h0, h1, cnt, cnt8, p0, p1);
-    } else {
-      down_pass<false>(wd, h0, h1, cnt, cnt8, p0, p1);
+  for (int t0 = t_first; t0 < m; t0 += kTokens) {
+    const int t = t0 + r;
+    const __bf16* hrow = H + (int64_t)(slot0 + min(t, m - 1)) * ldh + k0 + h * 32;
+    f32x16 p = {};
+    down_pass(wd, hrow, k_len, cnt, kr, p);
+    if constexpr (kSplit > 1) {
+      red.put(wave, 0, p, lane);
+      __syncthreads();
     }
-#pragma unroll
-    for (int tile_n = 0; tile_n < 2; ++tile_n) {
-      const int t = t0 + 32 * tile_n + r;
-      if ((tile_n == 1 && !two) || t >= m) continue;
-      const f32x16& p = tile_n ? p1 : p0;
-      float* out = product + (int64_t)(slot0 + t) * d_model;
+    if (t < m) {
+      float* out = out_chunk + (int64_t)(slot0 + t) * d_model;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
+        if (!owns_group(wave, q)) continue;
         const int rr = r0 + 8 * q + 4 * h;
         if (rr >= d_model) continue;  // d_model is a multiple of 8: a group of four is inside or outside as a whole
-        *reinterpret_cast<float4*>(out + rr) = make_float4(p[4 * q], p[4 * q + 1], p[4 * q + 2], p[4 * q + 3]);
+        float v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = kSplit > 1 ? red.get(0, 4 * q + i, lane) : p[4 * q + i];
+        *reinterpret_cast<float4*>(out + rr) = make_float4(v[0], v[1], v[2], v[3]);
+      }
+    }
+    if (!last_group) break;
+    if constexpr (kSplit > 1) __syncthreads();
+  }
+}
+
+// ---- y_token (+)= its partial rows -------------------------------------------------------------------------
+// One thread per (token, four output columns).  Routed: the token's slots are slot_of[token * terms + k], the
+// expert of a slot is found in `offsets`; dense (slot_of == nullptr): expert k, slot k * n + token.
+__global__ __launch_bounds__(256) void compact_combine_kernel(const float4* __restrict__ partial,
+                                                              const int32_t* __restrict__ slot_of,
+                                                              const int32_t* __restrict__ offsets, CompactTable tab,
+                                                              int64_t n, int terms, int vecs, int64_t n_slots,
+                                                              int accumulate, float4* __restrict__ Y) {
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= n * vecs) return;
+  const int64_t tok = id / vecs;
+  const int v = (int)(id - tok * vecs);
+  float4 s = accumulate ? Y[id] : make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int k = 0; k < terms; ++k) {
+    int64_t slot;
+    int e;
+    if (slot_of) {
+      slot = slot_of[tok * terms + k];
+      if (slot < 0) continue;  // a pair with an expert id outside the group
+      e = find_segment(offsets, tab.n_experts, (int)slot);
+    } else {
+      slot = (int64_t)k * n + tok;
+      e = k;
+    }
+    const int chunks = tab.chunk_off[e + 1] - tab.chunk_off[e];
+    for (int c = 0; c < chunks; ++c) {
+      const float4 p = partial[((int64_t)c * n_slots + slot) * vecs + v];
+      s.x += p.x;
+      s.y += p.y;
+      s.z += p.z;
+      s.w += p.w;
+    }
+  }
+  Y[id] = s;
+}
+
+// ---- bucket order of a decoding batch ----------------------------------------------------------------------
+// Pair p = token * (top_k + n_shared) + k: for k < top_k the routed expert topk_idx[token][k] with weight
+// topk_w[token][k], for k >= top_k the appended expert n_experts + k - top_k with weight 1.
+//
+// One workgroup does what the three launches of the general counting sort do, for at most kCompactSmallPairs
+// pairs.  Four threads per expert, each with a quarter of the pair range: a thread counts the pairs of its
+// expert in its quarter, an exclusive prefix over the threads (expert-major, quarter-minor: the stable order)
+// gives its first slot, and it places its pairs in pair order.
+constexpr int kQuarters = 4;
+constexpr int kSmallThreads = CAMERA_MAX_EXPERTS * kQuarters;
+static_assert(kSmallThreads <= 1024, "one workgroup");
+
+__global__ __launch_bounds__(kSmallThreads) void compact_bucket_small_kernel(
+    const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w, int n, int top_k, int n_experts,
+    int n_shared, int32_t* __restrict__ counts, int32_t* __restrict__ offsets, int32_t* __restrict__ perm,
+    float* __restrict__ w_perm, int32_t* __restrict__ slot_of) {
+  __shared__ __attribute__((aligned(16))) int16_t ids[kCompactSmallPairs];  // expert of every pair, -1: none
+  __shared__ int16_t token[kCompactSmallPairs];                             // its token
+  __shared__ float weight[kCompactSmallPairs];                              // and its weight
+  __shared__ int32_t wave_total[kSmallThreads / kWave];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kk = top_k + n_shared, total = n_experts + n_shared, n_pairs = n * kk;
+  const int padded = (n_pairs + 7) & ~7;
+  for (int p = tid; p < padded; p += kSmallThreads) {
+    int e = -1, j = 0;
+    float a = 1.0f;
+    if (p < n_pairs) {
+      j = p / kk;
+      const int k = p - j * kk;
+      if (k < top_k) {
+        e = topk_idx[j * top_k + k];
+        a = topk_w[j * top_k + k];
+        if (e < 0 || e >= n_experts) e = -1;
+      } else {
+        e = n_experts + k - top_k;
+      }
+      if (e < 0) slot_of[p] = -1;
+    }
+    ids[p] = (int16_t)e;
+    token[p] = (int16_t)j;
+    weight[p] = a;
+  }
+  __syncthreads();
+  const int e = tid / kQuarters, quarter = tid % kQuarters;
+  const int groups = padded / 8;
+  const int p_begin = groups * quarter / kQuarters * 8, p_end = groups * (quarter + 1) / kQuarters * 8;
+  int mine = 0;
+  if (e < total) {
+    for (int p = p_begin; p < p_end; p += 8) {
+      const i16x8 v = *reinterpret_cast<const i16x8*>(&ids[p]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) mine += v[i] == e;
+    }
+  }
+  // exclusive prefix of `mine` over the threads: inside the wave by shuffles, then the totals of the waves before
+  int incl = mine;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    const int up = __shfl_up(incl, d);
+    if (lane >= d) incl += up;
+  }
+  if (lane == kWave - 1) wave_total[wave] = incl;
+  __syncthreads();
+  int first = incl - mine;
+  for (int w = 0; w < wave; ++w) first += wave_total[w];
+  const int first_of_expert = __shfl(first, lane & ~(kQuarters - 1));  // the four threads of an expert are neighbours
+  if (e < total) {
+    if (quarter == 0) offsets[e] = first;
+    if (quarter == kQuarters - 1) {
+      counts[e] = first + mine - first_of_expert;
+      if (e == total - 1) offsets[total] = first + mine;
+    }
+    int slot = first;
+    for (int p = p_begin; p < p_end; p += 8) {
+      const i16x8 v = *reinterpret_cast<const i16x8*>(&ids[p]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (v[i] != e) continue;
+        const int q = p + i;
+        perm[slot] = token[q];
+        w_perm[slot] = weight[q];
+        slot_of[q] = slot;
+        ++slot;
       }
     }
   }
 }
 
+// The same pairs written out, for the general counting sort: idx_aug / w_aug [n][top_k + n_shared].
+__global__ void compact_append_shared_kernel(const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w,
+                                             int64_t n, int top_k, int n_experts, int n_shared,
+                                             int32_t* __restrict__ idx_aug, float* __restrict__ w_aug) {
+  const int kk = top_k + n_shared;
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= n * kk) return;
+  const int64_t j = p / kk;
+  const int k = (int)(p - j * kk);
+  if (k < top_k) {
+    const int e = topk_idx[j * top_k + k];
+    idx_aug[p] = (e < 0 || e >= n_experts) ? -1 : e;  // an id of the appended experts is not a routed choice
+    w_aug[p] = topk_w[j * top_k + k];
+  } else {
+    idx_aug[p] = n_experts + k - top_k;
+    w_aug[p] = 1.0f;
+  }
+}
+
 }  // namespace
 
+hipError_t launch_compact_bucket_small(hipStream_t stream, const int32_t* topk_idx, const float* topk_w, int64_t n,
+                                       int top_k, int n_experts, int n_shared, const BucketTables& t) {
+  compact_bucket_small_kernel<<<1, kSmallThreads, 0, stream>>>(topk_idx, topk_w, (int)n, top_k, n_experts, n_shared,
+                                                               t.counts, t.offsets, t.perm, t.w_perm, t.slot_of);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact_append_shared(hipStream_t stream, const int32_t* topk_idx, const float* topk_w, int64_t n,
+                                        int top_k, int n_experts, int n_shared, int32_t* idx_aug, float* w_aug) {
+  const int64_t pairs = n * (top_k + n_shared);
+  compact_append_shared_kernel<<<(int)((pairs + 255) / 256), 256, 0, stream>>>(topk_idx, topk_w, n, top_k, n_experts,
+                                                                                n_shared, idx_aug, w_aug);
+  return hipGetLastError();
+}
+
 hipError_t launch_compact_hidden(hipStream_t stream, const void* X, int64_t ldx, int64_t d_model, const void* W_gate,
-                                 const void* W_up, const CompactTable& tab, const BucketTables& t, void* hidden,
-                                 int ldh, bool wide) {
+                                 const void* W_up, const CompactTable& tab, const BucketTables& t, int token_groups,
+                                 void* hidden, int ldh) {
   const int tiles = tab.tile_off[tab.n_experts];
   if (tiles <= 0) return hipSuccess;
-  const int blocks = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-  auto kernel = wide ? compact_hidden_kernel<true> : compact_hidden_kernel<false>;
-  kernel<<<blocks, kThreads, 0, stream>>>(static_cast<const __bf16*>(X), ldx, (int)d_model,
-                                          static_cast<const __bf16*>(W_gate), static_cast<const __bf16*>(W_up), tab,
-                                          t.counts, t.offsets, t.perm, t.w_perm, static_cast<__bf16*>(hidden), ldh);
+  compact_hidden_kernel<<<dim3(tiles, token_groups), kThreads, 0, stream>>>(
+      static_cast<const __bf16*>(X), ldx, (int)d_model, static_cast<const __bf16*>(W_gate),
+      static_cast<const __bf16*>(W_up), tab, t.counts, t.offsets, t.perm, t.w_perm, static_cast<__bf16*>(hidden), ldh);
   return hipGetLastError();
 }
 
 hipError_t launch_compact_down(hipStream_t stream, const void* hidden, int ldh, const void* W_down, int64_t d_model,
-                               const CompactTable& tab, const BucketTables& t, float* product, bool wide) {
-  const int64_t tiles = (int64_t)tab.n_experts * ((d_model + kRows - 1) / kRows);
-  const int blocks = (int)((tiles + kWavesPerBlock - 1) / kWavesPerBlock);
-  auto kernel = wide ? compact_down_kernel<true> : compact_down_kernel<false>;
-  kernel<<<blocks, kThreads, 0, stream>>>(static_cast<const __bf16*>(hidden), ldh, static_cast<const __bf16*>(W_down),
-                                          (int)d_model, tab, t.counts, t.offsets, product);
+                               const CompactTable& tab, const BucketTables& t, int token_groups, int64_t n_slots,
+                               float* partial) {
+  const int64_t blocks = (int64_t)tab.chunk_off[tab.n_experts] * ((d_model + kRows - 1) / kRows);
+  if (blocks <= 0) return hipSuccess;
+  compact_down_kernel<<<dim3((unsigned)blocks, token_groups), kThreads, 0, stream>>>(
+      static_cast<const __bf16*>(hidden), ldh, static_cast<const __bf16*>(W_down), (int)d_model, tab, t.counts,
+      t.offsets, n_slots, partial);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact_combine(hipStream_t stream, const float* partial, const CompactTable& tab,
+                                  const BucketTables& t, int64_t n, int terms, int64_t d_model, int64_t n_slots,
+                                  int accumulate, float* Y) {
+  const int vecs = (int)(d_model / 4);
+  const int64_t threads = n * vecs;
+  compact_combine_kernel<<<(unsigned)((threads + 255) / 256), 256, 0, stream>>>(
+      reinterpret_cast<const float4*>(partial), t.slot_of, t.offsets, tab, n, terms, vecs, n_slots, accumulate,
+      reinterpret_cast<float4*>(Y));
   return hipGetLastError();
 }
 

@@ -67,9 +67,33 @@ def test_compacted_layer_output_matches_oracle(cam, case):
         print(f"{case} keep {frac}: rel err {err:.2e}, against the masked layer {err_masked:.2e}, counts {count[:6]}")
 
 
-@pytest.mark.parametrize("n_tokens", [7, 64, 90])
-def test_shared_experts_accumulate_into_the_routed_output(cam, n_tokens):
-    cfg = small(n_tokens=n_tokens, n_shared=2, d_ff_shared=200)
+def compact_layer(cam, dev, cfg, keep_r, keep_s):
+    """Routed and shared experts compacted into one set of buffers: the shared group's rows and blocks behind the routed."""
+    d = cfg.d_model
+    parts = [("W", keep_r, cfg.n_experts, cfg.d_ff), ("Ws", keep_s, cfg.n_shared, cfg.d_ff_shared)]
+    total = int(np.count_nonzero(keep_r)) + int(np.count_nonzero(keep_s))
+    gate_c = torch.empty((total, d), dtype=torch.bfloat16, device="cuda")
+    up_c = torch.empty_like(gate_c)
+    down_c = torch.empty(total * d, dtype=torch.bfloat16, device="cuda")
+    counts, at = [], 0
+    for prefix, keep, n_e, f in parts:
+        keep = np.asarray(keep).astype(bool)
+        index = torch.from_numpy(np.flatnonzero(keep).astype(np.int32)).cuda()
+        count = keep.reshape(n_e, f).sum(axis=1).astype(np.int32)
+        k = int(count.sum())
+        cam.gather_micro_experts(dev[prefix + "_gate"], dev[prefix + "_up"], dev[prefix + "_down"], index,
+                                 torch.from_numpy(count).cuda(), out=(gate_c[at:at + k], up_c[at:at + k], down_c[at * d:(at + k) * d]))
+        counts += [int(c) for c in count]
+        at += k
+    return counts, gate_c, up_c, down_c
+
+
+# 700 tokens: more pairs than the one-workgroup bucket kernel takes; a shared expert of 7000: three K chunks in the
+# second contraction (ragged: 0.6 * 7000 kept)
+@pytest.mark.parametrize("n_tokens,n_shared,d_ff_shared", [(7, 2, 200), (64, 2, 200), (90, 2, 200), (700, 2, 200),
+                                                           (64, 1, 7000), (40, 2, 3500)])
+def test_shared_experts_in_the_same_call_and_accumulated(cam, n_tokens, n_shared, d_ff_shared):
+    cfg = small(n_tokens=n_tokens, n_shared=n_shared, d_ff_shared=d_ff_shared, d_model=64 if d_ff_shared > 1000 else 128)
     layer = inputs.make_layer(cfg, 0, device="cpu")
     dev = H.to_dev(layer)
     idx, w = cam.route_topk(dev["X"], dev["W_r"], dev["bias"], cfg.top_k)
@@ -82,14 +106,24 @@ def test_shared_experts_accumulate_into_the_routed_output(cam, n_tokens):
     Y_routed = Y.clone()
     cam.layer_forward_compact(dev["X"], None, None, cs, gs, us, ds, Y=Y, accumulate=True)
     Y_shared = cam.layer_forward_compact(dev["X"], None, None, cs, gs, us, ds)
+    call, gc, uc, dc = compact_layer(cam, dev, cfg, keep_r, keep_s)
+    Y_one = cam.layer_forward_compact(dev["X"], idx, w, call, gc, uc, dc, n_shared=cfg.n_shared)
     torch.cuda.synchronize()
-    # (routed + shared_0) + shared_1 against routed + (shared_0 + shared_1): equal up to float32 rounding
-    assert (Y - (Y_routed + Y_shared)).abs().max().item() <= 4e-7 * Y.abs().max().item()
+    # the same terms in another order of summation: equal up to float32 rounding
+    scale = Y.abs().max().item()
+    assert (Y - (Y_routed + Y_shared)).abs().max().item() <= 4e-7 * scale
+    assert (Y - Y_one).abs().max().item() <= 1e-6 * scale
     X64 = H.f64(layer["X"])
     gate, up, down = expert_lists(layer, "Ws")
     ones = np.ones((cfg.n_tokens, cfg.n_shared))
-    O = orc.layer_forward(X64, ones, gate, up, down, keep=keep_s, round_hidden=orc.round_to_bf16)
-    check_output(Y_shared, O, largest_term(X64, ones, gate, up, down, keep_s))
+    O_s = orc.layer_forward(X64, ones, gate, up, down, keep=keep_s, round_hidden=orc.round_to_bf16)
+    term_s = largest_term(X64, ones, gate, up, down, keep_s)
+    check_output(Y_shared, O_s, term_s)
+    # the whole layer in one call against the oracle's routed + shared layer
+    A = dense_A(idx.cpu().numpy().astype(np.int64), w.cpu().numpy().astype(np.float64), cfg.n_experts)
+    gate_r, up_r, down_r = expert_lists(layer, "W")
+    O_r = orc.layer_forward(X64, A, gate_r, up_r, down_r, keep=keep_r, round_hidden=orc.round_to_bf16)
+    check_output(Y_one, O_r + O_s, np.maximum(term_s, largest_term(X64, A, gate_r, up_r, down_r, keep_r)))
 
 
 def test_nothing_kept_and_bad_arguments(cam):
@@ -102,5 +136,7 @@ def test_nothing_kept_and_bad_arguments(cam):
     assert torch.count_nonzero(Y).item() == 0
     with pytest.raises(binding.CameraError, match="count"):
         cam.layer_forward_compact(dev["X"], idx, w, [-1] + [0] * (cfg.n_experts - 1), empty, empty, empty.reshape(-1))
+    with pytest.raises(binding.CameraError, match="n_shared"):
+        cam.layer_forward_compact(dev["X"], None, None, [0] * cfg.n_experts, empty, empty, empty.reshape(-1), n_shared=1)
     with pytest.raises(binding.CameraError, match="BF16"):
         cam.layer_forward_compact(dev["X"].float(), idx, w, [0] * cfg.n_experts, empty, empty, empty.reshape(-1))
