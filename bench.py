@@ -238,28 +238,32 @@ def measure_decode(cam, cfg, layers, torch, binding, ratios=(0.0, 0.2, 0.4, 0.6)
     rows = []
     names = ("bucket", "compact_hidden", "compact_down", "combine")
     dt = t["W_gate"].dtype
+    align = 64
     for ratio in ratios:
         _, per, kept_idx, _ = cam.select_prune(lr.out["energy"], lr.seg, ratio, want_idx=True)
         per_h = per.cpu()
         kept = int(per_h.sum())
+        ld = (per_h + (align - 1)) // align * align     # row lengths of the W_down blocks: zero-padded to whole cache lines
         # routed and shared experts compacted into one set of buffers: one call then runs the whole layer
         gate_c = torch.empty((kept, d), dtype=dt, device="cuda")
         up_c = torch.empty_like(gate_c)
-        down_c = torch.empty(kept * d, dtype=dt, device="cuda")
-        pos, kept_bytes = 0, 0.0
+        down_c = torch.empty(int(ld.sum()) * d, dtype=dt, device="cuda")
+        pos, pos_ld, kept_bytes = 0, 0, 0.0
         for prefix, n_e, seg0, base in groups:
             counts = per_h[seg0:seg0 + n_e]
-            n_idx = int(counts.sum())
+            n_idx, n_ld = int(counts.sum()), int(ld[seg0:seg0 + n_e].sum())
             cam.gather_micro_experts(t[prefix + "_gate"], t[prefix + "_up"], t[prefix + "_down"], kept_idx[pos:pos + n_idx],
-                                     per[seg0:seg0 + n_e], base,
-                                     out=(gate_c[pos:pos + n_idx], up_c[pos:pos + n_idx], down_c[pos * d:(pos + n_idx) * d]))
+                                     per[seg0:seg0 + n_e], base, down_row_align=align,
+                                     out=(gate_c[pos:pos + n_idx], up_c[pos:pos + n_idx], down_c[pos_ld * d:(pos_ld + n_ld) * d]))
             read = counts[active] if prefix == "W" else counts
             kept_bytes += 3.0 * d * float(read.sum()) * 2.0
             pos += n_idx
+            pos_ld += n_ld
         counts_all = per_h.tolist()
 
         def run():
-            cam.layer_forward_compact(X, idx, w, counts_all, gate_c, up_c, down_c, n_shared=cfg.n_shared, Y=Y)
+            cam.layer_forward_compact(X, idx, w, counts_all, gate_c, up_c, down_c, n_shared=cfg.n_shared,
+                                      down_row_align=align, Y=Y)
 
         for _ in range(3):
             run()

@@ -57,6 +57,7 @@ enum camera_flags {
 #define CAMERA_MAX_EXPERTS 256   /* routed experts per call */
 #define CAMERA_MAX_SEGMENTS 512  /* expert segments in select / alloc */
 #define CAMERA_MAX_LEVELS 8      /* precision classes in camera_alloc_bits */
+#define CAMERA_MAX_ROW_ALIGN 512 /* largest row alignment (elements) of the compacted W_down blocks */
 
 /* Kernel groups for camera_profile_read. */
 enum camera_kernel_id {
@@ -219,10 +220,14 @@ int camera_alloc_bits(camera_ctx* ctx, void* stream,
  *               index of the group's first micro-expert)
  *   count       int32 [n_experts]: entries of `index` that belong to each expert (camera_select_prune's
  *               kept_per_expert), or NULL: d_ff each
+ *   down_row_align   the rows of every W_down_out block are ld(e) = count[e] rounded up to a multiple of
+ *               this many elements long, the surplus filled with zeros; 1: no padding.  64 (bf16: 128
+ *               bytes) makes every row start on a cache line, which is what camera_layer_forward_compact
+ *               reads fastest.  1 <= down_row_align <= CAMERA_MAX_ROW_ALIGN.
  *   W_gate_out, W_up_out   [n_index][d_model] out, `dtype`: row r is the gate / up row of index[r]
- *   W_down_out  out, `dtype`, n_index * d_model elements: expert e's block starts at element
- *               d_model * (count[0] + ... + count[e-1]) and is [d_model][count[e]] row-major; its column
- *               j is the down column of the expert's j-th entry
+ *   W_down_out  out, `dtype`, d_model * (ld(0) + ... + ld(n_experts-1)) elements: expert e's block starts
+ *               at element d_model * (ld(0) + ... + ld(e-1)) and is [d_model][ld(e)] row-major; its column
+ *               j < count[e] is the down column of the expert's j-th entry
  *   Any of the three outputs may be NULL (skipped); the matching input may then be NULL too.
  * Values are copied bit for bit.  An entry that does not lie inside its expert's range gives a zero
  * row / column; if the counts add up to less than n_index the remaining output rows are left
@@ -233,7 +238,7 @@ int camera_gather_micro_experts(camera_ctx* ctx, void* stream, int dtype,
                                 const void* W_gate, const void* W_up, int64_t stride_gu,
                                 const void* W_down, int64_t stride_down,
                                 const int32_t* index, int64_t n_index, int64_t index_base,
-                                const int32_t* count,
+                                const int32_t* count, int down_row_align,
                                 void* W_gate_out, void* W_up_out, void* W_down_out);
 
 /*
@@ -285,11 +290,13 @@ int camera_layer_forward(camera_ctx* ctx, void* stream,
  *               batch is too small to fill the chip with the shared experts alone).  0 without routing.
  *   dtype       CAMERA_BF16 only (CAMERA_EUNSUPPORTED otherwise); Lambda is rounded to bf16 before
  *               the second contraction, float32 accumulation in both
- *   count       HOST int32 [n_experts + n_shared]: kept micro-experts of every expert (>= 0, any
- *               value: the rows of a W_down block need no alignment)
+ *   count       HOST int32 [n_experts + n_shared]: kept micro-experts of every expert (>= 0, any value)
+ *   down_row_align   the row alignment the W_down blocks were gathered with: ld(e) = count[e] rounded
+ *               up to a multiple of it.  Any value gives the same result; rows that start on 128-byte
+ *               lines (64 for bf16) are read about a third faster than rows of odd lengths.
  *   W_gate_c, W_up_c   [sum(count)][d_model]: the kept rows, expert after expert
- *   W_down_c    sum(count) * d_model elements: expert e's block starts at element
- *               d_model * (count[0] + ... + count[e-1]) and is [d_model][count[e]] row-major
+ *   W_down_c    expert e's block starts at element d_model * (ld(0) + ... + ld(e-1)) and is
+ *               [d_model][ld(e)] row-major, zero beyond column count[e]
  *               (the three outputs of camera_gather_micro_experts, unchanged; with shared experts:
  *               the outputs of the call for the shared group written behind those of the routed group)
  *   n_experts + n_shared <= CAMERA_MAX_EXPERTS.
@@ -297,7 +304,7 @@ int camera_layer_forward(camera_ctx* ctx, void* stream,
 int camera_layer_forward_compact(camera_ctx* ctx, void* stream,
                                  const void* X, int dtype, int64_t n, int64_t d_model, int64_t ldx,
                                  const int32_t* topk_idx, const float* topk_w, int top_k,
-                                 int n_experts, int n_shared, const int32_t* count,
+                                 int n_experts, int n_shared, const int32_t* count, int down_row_align,
                                  const void* W_gate_c, const void* W_up_c, const void* W_down_c,
                                  int flags, float* Y);
 int camera_output_error(camera_ctx* ctx, void* stream, const float* Y, const float* Y_hat,

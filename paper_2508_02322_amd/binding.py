@@ -55,11 +55,11 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.camera_alloc_bits.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _i, _c.POINTER(_i),
                                       _c.POINTER(_d), _vp, _vp, _vp]
     lib.camera_gather_micro_experts.argtypes = [_vp, _vp, _i, _i, _i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, _i64,
-                                                _i64, _vp, _vp, _vp, _vp]
+                                                _i64, _vp, _i, _vp, _vp, _vp]
     lib.camera_layer_forward.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _vp, _i, _i, _i64, _vp, _vp, _i64,
                                          _vp, _i64, _vp, _i, _vp]
     lib.camera_layer_forward_compact.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _vp, _i, _i, _i,
-                                                 _c.POINTER(_c.c_int32), _vp, _vp, _vp, _i, _vp]
+                                                 _c.POINTER(_c.c_int32), _i, _vp, _vp, _vp, _i, _vp]
     lib.camera_output_error.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _vp]
     lib.camera_profile_enable.argtypes = [_vp, _i]
     lib.camera_profile_read.argtypes = [_vp, _i, _c.POINTER(_d), _c.POINTER(_i64)]
@@ -184,11 +184,13 @@ class Camera:
             (_i * n_levels)(*bits), (_d * len(ratios))(*ratios), _ptr(bit_of), _ptr(level_count), _ptr(perm)))
         return bit_of, level_count, perm
 
-    def gather_micro_experts(self, W_gate, W_up, W_down, index, count=None, index_base=0, out=None):
+    def gather_micro_experts(self, W_gate, W_up, W_down, index, count=None, index_base=0, out=None, down_row_align=1):
         """Kept gate / up rows and down columns of one group of experts (Algorithm 2, lines 10-13).
         W_gate, W_up [N_E, d_ff, d_model], W_down [N_E, d_model, d_ff] (any of them may be None: skipped);
-        index int32 [n_index] global indices grouped by expert; count int32 [N_E] or None (d_ff each).
-        Returns (gate_out [n_index, d_model], up_out, down_out flat [n_index * d_model])."""
+        index int32 [n_index] global indices grouped by expert; count int32 [N_E] or None (d_ff each);
+        down_row_align: the rows of every W_down block are padded with zeros to a multiple of it.
+        Returns (gate_out [n_index, d_model], up_out, down_out flat: sized for the longest padding when
+        allocated here, [d_model][ld(e)] blocks one after the other)."""
         ref = W_gate if W_gate is not None else (W_up if W_up is not None else W_down)
         n_experts = ref.shape[0]
         d_ff, d_model = (ref.shape[1], ref.shape[2]) if ref is not W_down else (ref.shape[2], ref.shape[1])
@@ -196,11 +198,12 @@ class Camera:
         stride_gu = (W_gate if W_gate is not None else W_up).stride(0) if (W_gate is not None or W_up is not None) else 0
         if out is None:
             mk = lambda src, shape: None if src is None else torch.empty(shape, dtype=src.dtype, device=self.device)
-            out = (mk(W_gate, (n_index, d_model)), mk(W_up, (n_index, d_model)), mk(W_down, (n_index * d_model,)))
+            padded = n_index + n_experts * (int(down_row_align) - 1)
+            out = (mk(W_gate, (n_index, d_model)), mk(W_up, (n_index, d_model)), mk(W_down, (padded * d_model,)))
         self._check(self.lib.camera_gather_micro_experts(
             self._ctx, _stream_handle(self.device), _dtype_code(ref), n_experts, d_ff, d_model, _ptr(W_gate), _ptr(W_up),
             stride_gu, _ptr(W_down), W_down.stride(0) if W_down is not None else 0, _ptr(index), n_index,
-            int(index_base), _ptr(count), _ptr(out[0]), _ptr(out[1]), _ptr(out[2])))
+            int(index_base), _ptr(count), int(down_row_align), _ptr(out[0]), _ptr(out[1]), _ptr(out[2])))
         return out
 
     def layer_forward(self, X, topk_idx, topk_w, W_gate, W_up, W_down, keep_mask=None, Y=None, accumulate=False):
@@ -216,11 +219,11 @@ class Camera:
             W_down.stride(0), _ptr(keep_mask), ACCUMULATE if accumulate else 0, _ptr(Y)))
         return Y
 
-    def layer_forward_compact(self, X, topk_idx, topk_w, count, W_gate_c, W_up_c, W_down_c, n_shared=0, Y=None,
-                              accumulate=False):
-        """Layer output from compacted weights (the outputs of gather_micro_experts); count: per-expert kept
-        micro-experts as a sequence of Python ints, the last n_shared of them shared experts (every token,
-        weight 1).  Y float32 [n, d_model]."""
+    def layer_forward_compact(self, X, topk_idx, topk_w, count, W_gate_c, W_up_c, W_down_c, n_shared=0,
+                              down_row_align=1, Y=None, accumulate=False):
+        """Layer output from compacted weights (the outputs of gather_micro_experts, with the same
+        down_row_align); count: per-expert kept micro-experts as a sequence of Python ints, the last n_shared
+        of them shared experts (every token, weight 1).  Y float32 [n, d_model]."""
         n, d = X.shape
         counts = [int(c) for c in count]
         top_k = 0 if topk_idx is None else topk_idx.shape[1]
@@ -229,7 +232,7 @@ class Camera:
         self._check(self.lib.camera_layer_forward_compact(
             self._ctx, _stream_handle(self.device), _ptr(X), _dtype_code(X), n, d, X.stride(0), _ptr(topk_idx),
             _ptr(topk_w), top_k, len(counts) - int(n_shared), int(n_shared), (_c.c_int32 * len(counts))(*counts),
-            _ptr(W_gate_c), _ptr(W_up_c), _ptr(W_down_c), ACCUMULATE if accumulate else 0, _ptr(Y)))
+            int(down_row_align), _ptr(W_gate_c), _ptr(W_up_c), _ptr(W_down_c), ACCUMULATE if accumulate else 0, _ptr(Y)))
         return Y
 
     def output_error(self, Y, Y_hat):

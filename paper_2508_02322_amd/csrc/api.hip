@@ -238,10 +238,12 @@ int camera_profile_read(camera_ctx* ctx, int kernel_id, double* total_ms, int64_
 int camera_gather_micro_experts(camera_ctx* ctx, void* stream_, int dtype, int n_experts, int64_t d_ff,
                                 int64_t d_model, const void* W_gate, const void* W_up, int64_t stride_gu,
                                 const void* W_down, int64_t stride_down, const int32_t* index, int64_t n_index,
-                                int64_t index_base, const int32_t* count, void* W_gate_out, void* W_up_out,
-                                void* W_down_out) {
+                                int64_t index_base, const int32_t* count, int down_row_align, void* W_gate_out,
+                                void* W_up_out, void* W_down_out) {
   if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
   if (dtype != CAMERA_F32 && dtype != CAMERA_BF16) return fail(ctx, CAMERA_EDTYPE, "dtype: unknown code %d", dtype);
+  if (down_row_align < 1 || down_row_align > CAMERA_MAX_ROW_ALIGN)
+    return fail(ctx, CAMERA_EINVAL, "down_row_align: must be in [1, %d]", CAMERA_MAX_ROW_ALIGN);
   const int es = dtype == CAMERA_BF16 ? 2 : 4;
   if (n_experts < 1 || n_experts > CAMERA_MAX_EXPERTS)
     return fail(ctx, CAMERA_EUNSUPPORTED, "n_experts: must be in [1, %d]", CAMERA_MAX_EXPERTS);
@@ -252,7 +254,8 @@ int camera_gather_micro_experts(camera_ctx* ctx, void* stream_, int dtype, int n
     return fail(ctx, CAMERA_EINVAL, "n_index: must be in [0, n_experts * d_ff]");
   if (count == nullptr && n_index != (int64_t)n_experts * d_ff)
     return fail(ctx, CAMERA_EINVAL, "count: NULL needs n_index == n_experts * d_ff");
-  if (n_index * d_model >= (int64_t(1) << 40)) return fail(ctx, CAMERA_ESHAPE, "n_index * d_model: too large");
+  if ((n_index + (int64_t)n_experts * down_row_align) * d_model >= (int64_t(1) << 40))
+    return fail(ctx, CAMERA_ESHAPE, "n_index * d_model: too large");
   if (index_base < 0 || index_base > (int64_t(1) << 31) - (int64_t)n_experts * d_ff)
     return fail(ctx, CAMERA_EINVAL, "index_base: indices must fit 32 bits");
   const bool rows = W_gate_out != nullptr || W_up_out != nullptr;
@@ -273,15 +276,18 @@ int camera_gather_micro_experts(camera_ctx* ctx, void* stream_, int dtype, int n
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   Carver cv;
   const size_t o_off = cv.take(sizeof(int32_t) * (CAMERA_MAX_EXPERTS + 1));
+  const size_t o_off_ld = cv.take(sizeof(int32_t) * (CAMERA_MAX_EXPERTS + 1));
   if (int rc = ensure_workspace(ctx, cv.used)) return rc;
   int32_t* off = reinterpret_cast<int32_t*>(static_cast<char*>(ctx->ws) + o_off);
+  int32_t* off_ld = reinterpret_cast<int32_t*>(static_cast<char*>(ctx->ws) + o_off_ld);
   Bracket bracket(ctx, stream, CAMERA_K_GATHER);
-  CAMERA_HIP(camera::launch_gather_offsets(stream, count, n_experts, d_ff, off), "gather offsets");
+  CAMERA_HIP(camera::launch_gather_offsets(stream, count, n_experts, d_ff, down_row_align, off, off_ld),
+             "gather offsets");
   CAMERA_HIP(camera::launch_gather_rows(stream, dtype, W_gate, W_up, stride_gu, n_experts, d_ff, d_model, index, n_index,
                                         index_base, off, W_gate_out, W_up_out),
              "gather rows");
   CAMERA_HIP(camera::launch_gather_cols(stream, dtype, W_down, stride_down, n_experts, d_ff, d_model, index, n_index,
-                                        index_base, off, W_down_out),
+                                        index_base, off, off_ld, W_down_out),
              "gather columns");
   return CAMERA_OK;
 }
@@ -592,8 +598,8 @@ int camera_layer_forward(camera_ctx* ctx, void* stream_, const void* X, int dtyp
 
 int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, int dtype, int64_t n, int64_t d_model,
                                  int64_t ldx, const int32_t* topk_idx, const float* topk_w, int top_k, int n_experts,
-                                 int n_shared, const int32_t* count, const void* W_gate_c, const void* W_up_c,
-                                 const void* W_down_c, int flags, float* Y) {
+                                 int n_shared, const int32_t* count, int down_row_align, const void* W_gate_c,
+                                 const void* W_up_c, const void* W_down_c, int flags, float* Y) {
   if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
   if (int rc = check_common(ctx, X, dtype, n, d_model, ldx)) return rc;
   if (dtype != CAMERA_BF16) return fail(ctx, CAMERA_EUNSUPPORTED, "dtype: the compacted layer is built for CAMERA_BF16 only");
@@ -608,26 +614,34 @@ int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, 
   if (!dense && (top_k < 1 || top_k > n_experts)) return fail(ctx, CAMERA_EINVAL, "top_k: must be in [1, n_experts]");
   if (flags & ~CAMERA_ACCUMULATE) return fail(ctx, CAMERA_EINVAL, "flags: only CAMERA_ACCUMULATE is accepted");
   if (count == nullptr) return fail(ctx, CAMERA_EINVAL, "count: NULL");
-  camera::CompactTable tab;
-  tab.n_experts = total;
-  int64_t rows = 0, tiles = 0, widest = 0, chunks = 0;
+  if (down_row_align < 1 || down_row_align > CAMERA_MAX_ROW_ALIGN)
+    return fail(ctx, CAMERA_EINVAL, "down_row_align: must be in [1, %d]", CAMERA_MAX_ROW_ALIGN);
+  camera::CompactRows tab;
+  camera::CompactDown tab_down;
+  tab.n_experts = tab_down.n_experts = total;
+  int64_t rows = 0, tiles = 0, widest = 0, chunks = 0, ld_rows = 0;
   int most_chunks = 1;
   for (int e = 0; e < total; ++e) {
     if (count[e] < 0) return fail(ctx, CAMERA_EINVAL, "count[%d]: negative", e);
     tab.row_off[e] = (int32_t)rows;
     tab.tile_off[e] = (int32_t)tiles;
-    tab.chunk_off[e] = (int32_t)chunks;
+    tab_down.count[e] = count[e];
+    tab_down.ld_off[e] = (int32_t)ld_rows;
+    tab_down.chunk_off[e] = (int32_t)chunks;
     rows += count[e];
+    ld_rows += ((int64_t)count[e] + down_row_align - 1) / down_row_align * down_row_align;
     tiles += (count[e] + 31) / 32;
     chunks += camera::compact_chunks(count[e]);
     most_chunks = std::max(most_chunks, camera::compact_chunks(count[e]));
     widest = std::max<int64_t>(widest, count[e]);
-    if (rows >= (int64_t(1) << 31) - 1024) return fail(ctx, CAMERA_ESHAPE, "sum of count: too large");
+    if (ld_rows >= (int64_t(1) << 31) - 1024) return fail(ctx, CAMERA_ESHAPE, "sum of count: too large");
   }
   for (int e = total; e <= CAMERA_MAX_EXPERTS; ++e) {
     tab.row_off[e] = (int32_t)rows;
     tab.tile_off[e] = (int32_t)tiles;
-    tab.chunk_off[e] = (int32_t)chunks;
+    tab_down.ld_off[e] = (int32_t)ld_rows;
+    tab_down.chunk_off[e] = (int32_t)chunks;
+    if (e < CAMERA_MAX_EXPERTS) tab_down.count[e] = 0;
   }
   if (rows > 0 && (W_gate_c == nullptr || W_up_c == nullptr || W_down_c == nullptr))
     return fail(ctx, CAMERA_EINVAL, "W_gate_c / W_up_c / W_down_c: NULL");
@@ -717,13 +731,13 @@ int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, 
   }
   {
     Bracket b(ctx, stream, CAMERA_K_COMPACT_DOWN);
-    CAMERA_HIP(camera::launch_compact_down(stream, hidden, (int)ldh, W_down_c, d_model, tab, t, token_groups, n_pairs,
+    CAMERA_HIP(camera::launch_compact_down(stream, hidden, (int)ldh, W_down_c, d_model, tab_down, t, token_groups, n_pairs,
                                            product),
                "compact down launch");
   }
   {
     Bracket b(ctx, stream, CAMERA_K_COMBINE);
-    CAMERA_HIP(camera::launch_compact_combine(stream, product, tab, t, n, terms, d_model, n_pairs,
+    CAMERA_HIP(camera::launch_compact_combine(stream, product, tab_down, t, n, terms, d_model, n_pairs,
                                               (flags & CAMERA_ACCUMULATE) ? 1 : 0, Y),
                "compact combine launch");
   }

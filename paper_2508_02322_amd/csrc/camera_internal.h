@@ -119,11 +119,17 @@ hipError_t launch_output_error(hipStream_t stream, const float* Y, const float* 
 
 // ---- compact.hip ------------------------------------------------------------
 // Where each expert's kept micro-experts sit in the compacted matrices, passed to the kernels by value.
-struct CompactTable {
+struct CompactRows {                          // W_gate_c / W_up_c
   int n_experts;
   int32_t row_off[CAMERA_MAX_EXPERTS + 1];    // first compact row of each expert (prefix of the kept counts)
-  int32_t tile_off[CAMERA_MAX_EXPERTS + 1];   // first 32-row tile of each expert (first contraction)
-  int32_t chunk_off[CAMERA_MAX_EXPERTS + 1];  // first K chunk of each expert (second contraction)
+  int32_t tile_off[CAMERA_MAX_EXPERTS + 1];   // first 32-row tile of each expert
+};
+struct CompactDown {                          // W_down_c
+  int n_experts;
+  int32_t count[CAMERA_MAX_EXPERTS];          // kept micro-experts of each expert
+  int32_t ld_off[CAMERA_MAX_EXPERTS + 1];     // prefix of the row lengths (count rounded up to the row alignment):
+                                              // expert e's block starts at element d_model * ld_off[e]
+  int32_t chunk_off[CAMERA_MAX_EXPERTS + 1];  // first K chunk of each expert
 };
 // K chunks of an expert with `count` kept micro-experts in the second contraction: chunks of at most
 // kCompactChunk elements, at most kCompactMaxChunks of them (0 for an expert that keeps nothing).
@@ -144,26 +150,28 @@ hipError_t launch_compact_append_shared(hipStream_t stream, const int32_t* topk_
 // token_groups: grid rows of 32 tokens per expert; the last one also takes what lies beyond.
 // hidden [slots][ldh] bf16 <- a silu(x w_gate) (x w_up) on the kept rows; columns [count, round8(count)) zero.
 hipError_t launch_compact_hidden(hipStream_t stream, const void* X, int64_t ldx, int64_t d_model, const void* W_gate,
-                                 const void* W_up, const CompactTable& tab, const BucketTables& t, int token_groups,
+                                 const void* W_up, const CompactRows& tab, const BucketTables& t, int token_groups,
                                  void* hidden, int ldh);
 // partial [chunk within its expert][n_slots][d_model] float32 <- hidden times the chunk of the expert's W_down block.
 hipError_t launch_compact_down(hipStream_t stream, const void* hidden, int ldh, const void* W_down, int64_t d_model,
-                               const CompactTable& tab, const BucketTables& t, int token_groups, int64_t n_slots,
+                               const CompactDown& tab, const BucketTables& t, int token_groups, int64_t n_slots,
                                float* partial);
 // Y[token] (+)= the partial rows of the token's slots (experts in k order, chunks in chunk order).
-hipError_t launch_compact_combine(hipStream_t stream, const float* partial, const CompactTable& tab,
+hipError_t launch_compact_combine(hipStream_t stream, const float* partial, const CompactDown& tab,
                                   const BucketTables& t, int64_t n, int terms, int64_t d_model, int64_t n_slots,
                                   int accumulate, float* Y);
 
 // Gather of kept micro-experts (gather.hip).  off: [n_experts + 1] exclusive prefix of the per-expert
-// entry counts (count == nullptr: d_ff each), written by launch_gather_offsets.
-hipError_t launch_gather_offsets(hipStream_t stream, const int32_t* count, int n_experts, int64_t d_ff, int32_t* off);
+// entry counts (count == nullptr: d_ff each), off_ld: the same of the counts rounded up to a multiple of
+// row_align (row lengths of the W_down blocks); both written by launch_gather_offsets.
+hipError_t launch_gather_offsets(hipStream_t stream, const int32_t* count, int n_experts, int64_t d_ff, int row_align,
+                                 int32_t* off, int32_t* off_ld);
 hipError_t launch_gather_rows(hipStream_t stream, int dtype, const void* W_gate, const void* W_up, int64_t stride_gu,
                               int n_experts, int64_t d_ff, int64_t d_model, const int32_t* index, int64_t n_index,
                               int64_t index_base, const int32_t* off, void* gate_out, void* up_out);
 hipError_t launch_gather_cols(hipStream_t stream, int dtype, const void* W_down, int64_t stride_down, int n_experts,
                               int64_t d_ff, int64_t d_model, const int32_t* index, int64_t n_index,
-                              int64_t index_base, const int32_t* off, void* down_out);
+                              int64_t index_base, const int32_t* off, const int32_t* off_ld, void* down_out);
 
 // Machine probes (probe.hip).  The MFMA probe's workspace holds its per-thread sink and, in its last
 // 256 bytes, two 64-bit counters (shader cycles, 100 MHz ticks) that the kernel adds to.

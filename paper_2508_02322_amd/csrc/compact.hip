@@ -30,10 +30,11 @@
 //   hidden  : Lambda[slot][c] = a silu(x w_gate,c) (x w_up,c), bf16, for the c < count[e] kept micro-experts
 //   down    : partial[chunk][slot][r] = sum over the chunk's c of Lambda[slot][c] W_down_e[r][c], float32
 //   combine : y_token (+)= the partial rows of its experts' slots, experts in k order, chunks in chunk order
-// The rows of the compacted W_down block of an expert are count[e] elements
-// long, which need not be a multiple of eight: its 16-byte loads are unaligned
-// (2-byte aligned), and the chunk that straddles the end of a row is taken as
-// the 16 bytes that end there, shifted down.
+// The rows of the compacted W_down block of an expert hold count[e] elements and
+// then zeros up to the caller's row alignment.  Without alignment (rows of any
+// length) its 16-byte loads are unaligned (2-byte aligned) and the chunk that
+// straddles the end of a row is taken as the 16 bytes that end there, shifted
+// down: correct, but a third slower than rows that start on 128-byte lines.
 #include "camera_internal.h"
 
 namespace camera {
@@ -223,7 +224,7 @@ __device__ __forceinline__ void hidden_pass(const __bf16* __restrict__ wg, const
 // than the batch has only if a token names it twice).
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void compact_hidden_kernel(
     const __bf16* __restrict__ X, int64_t ldx, int d_model, const __bf16* __restrict__ W_gate,
-    const __bf16* __restrict__ W_up, CompactTable tab, const int32_t* __restrict__ counts,
+    const __bf16* __restrict__ W_up, CompactRows tab, const int32_t* __restrict__ counts,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm, const float* __restrict__ w_perm,
     __bf16* __restrict__ H, int ldh) {
   __shared__ float red_mem[kSplit][2][16][kWave];  // gate and up
@@ -322,7 +323,7 @@ __device__ __forceinline__ int chunk_length(int cnt, int n_chunks) {
 // grid: x = (K chunk of an expert, 32-row tile of d_model): tab.chunk_off[tab.n_experts] * row_tiles workgroups,
 // y = 32-token groups.  partial is [chunk within the expert][n_slots][d_model].
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) void compact_down_kernel(
-    const __bf16* __restrict__ H, int ldh, const __bf16* __restrict__ W_down, int d_model, CompactTable tab,
+    const __bf16* __restrict__ H, int ldh, const __bf16* __restrict__ W_down, int d_model, CompactDown tab,
     const int32_t* __restrict__ counts, const int32_t* __restrict__ offsets, int64_t n_slots,
     float* __restrict__ partial) {
   __shared__ float red_mem[kSplit][1][16][kWave];
@@ -338,14 +339,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) v
   if (t_first >= m) return;
   const bool last_group = blockIdx.y + 1 == gridDim.y;
   const int slot0 = __builtin_amdgcn_readfirstlane(offsets[e]);
-  const int cnt = tab.row_off[e + 1] - tab.row_off[e];
+  const int cnt = tab.count[e];
+  const int ld = tab.ld_off[e + 1] - tab.ld_off[e];  // row length of the expert's block (cnt and zero padding)
   const int chunk_in = chunk - tab.chunk_off[e];
   const int len = chunk_length(cnt, tab.chunk_off[e + 1] - tab.chunk_off[e]);
   const int k0 = min(chunk_in * len, cnt);
   const int k_len = min(len, cnt - k0);
   const int r = lane & 31, h = lane >> 5;
   const int row = min(r0 + r, d_model - 1);
-  const __bf16* wd = W_down + (int64_t)tab.row_off[e] * d_model + (int64_t)row * cnt + k0 + h * 32;
+  const __bf16* wd = W_down + (int64_t)tab.ld_off[e] * d_model + (int64_t)row * ld + k0 + h * 32;
   const KRange kr = k_range(k_len / kKBlock, k_len % kKBlock != 0, wave);
   float* out_chunk = partial + (int64_t)chunk_in * n_slots * d_model;
 
@@ -381,7 +383,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) v
 // expert of a slot is found in `offsets`; dense (slot_of == nullptr): expert k, slot k * n + token.
 __global__ __launch_bounds__(256) void compact_combine_kernel(const float4* __restrict__ partial,
                                                               const int32_t* __restrict__ slot_of,
-                                                              const int32_t* __restrict__ offsets, CompactTable tab,
+                                                              const int32_t* __restrict__ offsets, CompactDown tab,
                                                               int64_t n, int terms, int vecs, int64_t n_slots,
                                                               int accumulate, float4* __restrict__ Y) {
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -537,7 +539,7 @@ hipError_t launch_compact_append_shared(hipStream_t stream, const int32_t* topk_
 }
 
 hipError_t launch_compact_hidden(hipStream_t stream, const void* X, int64_t ldx, int64_t d_model, const void* W_gate,
-                                 const void* W_up, const CompactTable& tab, const BucketTables& t, int token_groups,
+                                 const void* W_up, const CompactRows& tab, const BucketTables& t, int token_groups,
                                  void* hidden, int ldh) {
   const int tiles = tab.tile_off[tab.n_experts];
   if (tiles <= 0) return hipSuccess;
@@ -548,7 +550,7 @@ hipError_t launch_compact_hidden(hipStream_t stream, const void* X, int64_t ldx,
 }
 
 hipError_t launch_compact_down(hipStream_t stream, const void* hidden, int ldh, const void* W_down, int64_t d_model,
-                               const CompactTable& tab, const BucketTables& t, int token_groups, int64_t n_slots,
+                               const CompactDown& tab, const BucketTables& t, int token_groups, int64_t n_slots,
                                float* partial) {
   const int64_t blocks = (int64_t)tab.chunk_off[tab.n_experts] * ((d_model + kRows - 1) / kRows);
   if (blocks <= 0) return hipSuccess;
@@ -558,7 +560,7 @@ hipError_t launch_compact_down(hipStream_t stream, const void* hidden, int ldh, 
   return hipGetLastError();
 }
 
-hipError_t launch_compact_combine(hipStream_t stream, const float* partial, const CompactTable& tab,
+hipError_t launch_compact_combine(hipStream_t stream, const float* partial, const CompactDown& tab,
                                   const BucketTables& t, int64_t n, int terms, int64_t d_model, int64_t n_slots,
                                   int accumulate, float* Y) {
   const int vecs = (int)(d_model / 4);

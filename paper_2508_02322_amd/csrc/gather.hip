@@ -9,7 +9,9 @@
 //   columns : a workgroup owns one expert and a few rows of its W_down; it
 //             keeps the expert's column list in LDS, streams each row through
 //             LDS with 16-byte loads (the kept columns touch nearly every 64-byte
-//             sector of the row anyway) and writes the kept elements side by side.
+//             sector of the row anyway) and writes the kept elements side by side,
+//             then zeros up to the block's row length (the count rounded up to the
+//             caller's row alignment).
 // Entries that do not lie inside their expert give zero rows / columns: no
 // address is ever formed from an unchecked index.
 #include <hip/hip_bf16.h>
@@ -26,20 +28,26 @@ constexpr int kRowsPerBlock = kThreads / kWave;  // gather_rows: one wave per ou
 constexpr int kDownRows = 8;                     // gather_cols: W_down rows per workgroup
 constexpr uint16_t kNoColumn = 0xffffu;
 
+// off [n_experts + 1]: prefix of the entry counts; off_ld [n_experts + 1]: prefix of the counts rounded up to
+// a multiple of row_align (the row lengths of the W_down blocks).
 __global__ __launch_bounds__(CAMERA_MAX_EXPERTS) void gather_offsets_kernel(const int32_t* __restrict__ count,
-                                                                            int n_experts, int d_ff,
-                                                                            int32_t* __restrict__ off) {
+                                                                            int n_experts, int d_ff, int row_align,
+                                                                            int32_t* __restrict__ off,
+                                                                            int32_t* __restrict__ off_ld) {
   __shared__ int32_t s_cnt[CAMERA_MAX_EXPERTS];
   const int e = threadIdx.x;
   if (e < n_experts) s_cnt[e] = count ? min(max(count[e], 0), d_ff) : d_ff;
   __syncthreads();
   if (e == 0) {
-    int32_t run = 0;
+    int32_t run = 0, run_ld = 0;
     for (int i = 0; i < n_experts; ++i) {
       off[i] = run;
+      off_ld[i] = run_ld;
       run += s_cnt[i];
+      run_ld += (s_cnt[i] + row_align - 1) / row_align * row_align;
     }
     off[n_experts] = run;
+    off_ld[n_experts] = run_ld;
   }
 }
 
@@ -84,6 +92,7 @@ __global__ __launch_bounds__(kThreads) void gather_cols_kernel(const T* __restri
                                                                int d_ff, int d_model,
                                                                const int32_t* __restrict__ index, int64_t n_index,
                                                                int64_t index_base, const int32_t* __restrict__ off,
+                                                               const int32_t* __restrict__ off_ld,
                                                                T* __restrict__ down_out) {
   extern __shared__ __align__(16) unsigned char smem[];
   T* s_row = reinterpret_cast<T*>(smem);
@@ -97,7 +106,8 @@ __global__ __launch_bounds__(kThreads) void gather_cols_kernel(const T* __restri
     s_col[j] = (c >= 0 && c < d_ff) ? (uint16_t)c : kNoColumn;  // d_ff <= 32768 (checked by the caller), so no clash
   }
   const T* src_expert = Wd + (int64_t)e * stride_down;
-  T* dst_expert = down_out + first * (int64_t)d_model;
+  const int ld = off_ld[e + 1] - off_ld[e];  // row length of the block: the count rounded up, the rest zero
+  T* dst_expert = down_out + off_ld[e] * (int64_t)d_model;
   const int r_begin = blockIdx.y * kDownRows, r_end = min(d_model, r_begin + kDownRows);
   for (int r = r_begin; r < r_end; ++r) {
     __syncthreads();  // the column list is complete; the previous row has been read out
@@ -110,9 +120,9 @@ __global__ __launch_bounds__(kThreads) void gather_cols_kernel(const T* __restri
       for (int k = threadIdx.x; k < d_ff; k += kThreads) s_row[k] = src_row[k];
     }
     __syncthreads();
-    T* dst_row = dst_expert + (int64_t)r * cnt;
-    for (int j = threadIdx.x; j < cnt; j += kThreads) {
-      const uint16_t c = s_col[j];
+    T* dst_row = dst_expert + (int64_t)r * ld;
+    for (int j = threadIdx.x; j < ld; j += kThreads) {
+      const uint16_t c = j < cnt ? s_col[j] : kNoColumn;
       dst_row[j] = c == kNoColumn ? T(0) : s_row[c];
     }
   }
@@ -121,9 +131,9 @@ __global__ __launch_bounds__(kThreads) void gather_cols_kernel(const T* __restri
 }  // namespace
 
 hipError_t launch_gather_offsets(hipStream_t stream, const int32_t* count, int n_experts, int64_t d_ff,
-                                 int32_t* off) {
+                                 int row_align, int32_t* off, int32_t* off_ld) {
   hipLaunchKernelGGL(gather_offsets_kernel, dim3(1), dim3(CAMERA_MAX_EXPERTS), 0, stream, count, n_experts, (int)d_ff,
-                     off);
+                     row_align, off, off_ld);
   return hipGetLastError();
 }
 
@@ -143,7 +153,7 @@ hipError_t launch_gather_rows(hipStream_t stream, int dtype, const void* W_gate,
 template <class T>
 static hipError_t launch_cols(hipStream_t stream, const void* W_down, int64_t stride_down, int n_experts, int64_t d_ff,
                               int64_t d_model, const int32_t* index, int64_t n_index, int64_t index_base,
-                              const int32_t* off, void* down_out) {
+                              const int32_t* off, const int32_t* off_ld, void* down_out) {
   const bool vec = (d_ff * sizeof(T)) % 16 == 0 && (stride_down * sizeof(T)) % 16 == 0 &&
                    (reinterpret_cast<uintptr_t>(W_down) & 15u) == 0;
   auto kern = vec ? gather_cols_kernel<T, true> : gather_cols_kernel<T, false>;
@@ -153,19 +163,19 @@ static hipError_t launch_cols(hipStream_t stream, const void* W_down, int64_t st
   if (err != hipSuccess) return err;
   dim3 grid((unsigned)n_experts, (unsigned)((d_model + kDownRows - 1) / kDownRows));
   hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, stream, static_cast<const T*>(W_down), stride_down, (int)d_ff,
-                     (int)d_model, index, n_index, index_base, off, static_cast<T*>(down_out));
+                     (int)d_model, index, n_index, index_base, off, off_ld, static_cast<T*>(down_out));
   return hipGetLastError();
 }
 
 hipError_t launch_gather_cols(hipStream_t stream, int dtype, const void* W_down, int64_t stride_down, int n_experts,
                               int64_t d_ff, int64_t d_model, const int32_t* index, int64_t n_index,
-                              int64_t index_base, const int32_t* off, void* down_out) {
+                              int64_t index_base, const int32_t* off, const int32_t* off_ld, void* down_out) {
   if (n_index <= 0 || down_out == nullptr) return hipSuccess;
   if (dtype == CAMERA_BF16)
     return launch_cols<uint16_t>(stream, W_down, stride_down, n_experts, d_ff, d_model, index, n_index, index_base, off,
-                                 down_out);
+                                 off_ld, down_out);
   return launch_cols<uint32_t>(stream, W_down, stride_down, n_experts, d_ff, d_model, index, n_index, index_base, off,
-                               down_out);
+                               off_ld, down_out);
 }
 
 }  // namespace camera

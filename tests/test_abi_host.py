@@ -161,11 +161,12 @@ def test_gather_argument_checks(lib, ctx):
     vpp = ctypes.c_void_p
     fake = vpp(4096)          # never dereferenced: every check below fails on the host
     def gather(dtype=1, n_experts=2, d_ff=64, d_model=16, wg=fake, wu=fake, stride_gu=64 * 16, wd=fake,
-               stride_down=64 * 16, index=fake, n_index=10, base=0, count=fake, og=fake, ou=fake, od=fake, c=ctx):
+               stride_down=64 * 16, index=fake, n_index=10, base=0, count=fake, align=1, og=fake, ou=fake, od=fake, c=ctx):
         return lib.camera_gather_micro_experts(c, None, dtype, n_experts, d_ff, d_model, wg, wu, stride_gu, wd,
-                                               stride_down, index, n_index, base, count, og, ou, od)
+                                               stride_down, index, n_index, base, count, align, og, ou, od)
     assert gather(c=None) == -1
     assert gather(dtype=7) == -3
+    assert gather(align=0) == -1 and gather(align=513) == -1 and "down_row_align" in err(lib, ctx)
     assert gather(n_experts=0) == -6 and gather(n_experts=257) == -6
     assert gather(d_ff=0) == -2
     assert gather(d_ff=40000, stride_gu=40000 * 16, stride_down=40000 * 16) == -6 and "65536" in err(lib, ctx)

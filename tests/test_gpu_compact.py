@@ -18,13 +18,13 @@ from tests.test_gpu_forward import check_output, dense_A, expert_lists, largest_
 pytestmark = pytest.mark.gpu
 
 
-def compact(cam, dev, prefix, keep, n_experts, d_ff):
+def compact(cam, dev, prefix, keep, n_experts, d_ff, align=1):
     """(count list, gate_c, up_c, down_c) of the experts `prefix` for a 0/1 mask over their micro-experts."""
     keep = np.asarray(keep).astype(bool)
     index = torch.from_numpy(np.flatnonzero(keep).astype(np.int32)).cuda()
     count = keep.reshape(n_experts, d_ff).sum(axis=1).astype(np.int32)
     gate_c, up_c, down_c = cam.gather_micro_experts(dev[prefix + "_gate"], dev[prefix + "_up"], dev[prefix + "_down"],
-                                                    index, torch.from_numpy(count).cuda())
+                                                    index, torch.from_numpy(count).cuda(), down_row_align=align)
     return [int(c) for c in count], gate_c, up_c, down_c
 
 
@@ -56,6 +56,10 @@ def test_compacted_layer_output_matches_oracle(cam, case):
             keep[cfg.d_ff:cfg.d_ff + 3] = 1                                 # and one with at least three
         count, gate_c, up_c, down_c = compact(cam, dev, "W", keep, cfg.n_experts, cfg.d_ff)
         Y = cam.layer_forward_compact(dev["X"], idx, w, count, gate_c, up_c, down_c)
+        for align in (8, 64):   # zero-padded W_down rows: the same sums, bit for bit
+            count_a, gate_a, up_a, down_a = compact(cam, dev, "W", keep, cfg.n_experts, cfg.d_ff, align=align)
+            Y_a = cam.layer_forward_compact(dev["X"], idx, w, count_a, gate_a, up_a, down_a, down_row_align=align)
+            assert torch.equal(Y, Y_a), align
         Y_masked = cam.layer_forward(dev["X"], idx, w, dev["W_gate"], dev["W_up"], dev["W_down"],
                                      keep_mask=torch.from_numpy(keep).cuda())
         torch.cuda.synchronize()
@@ -67,24 +71,27 @@ def test_compacted_layer_output_matches_oracle(cam, case):
         print(f"{case} keep {frac}: rel err {err:.2e}, against the masked layer {err_masked:.2e}, counts {count[:6]}")
 
 
-def compact_layer(cam, dev, cfg, keep_r, keep_s):
+def compact_layer(cam, dev, cfg, keep_r, keep_s, align):
     """Routed and shared experts compacted into one set of buffers: the shared group's rows and blocks behind the routed."""
     d = cfg.d_model
     parts = [("W", keep_r, cfg.n_experts, cfg.d_ff), ("Ws", keep_s, cfg.n_shared, cfg.d_ff_shared)]
-    total = int(np.count_nonzero(keep_r)) + int(np.count_nonzero(keep_s))
+    per_expert = [np.asarray(keep).astype(bool).reshape(n_e, f).sum(axis=1).astype(np.int32) for _, keep, n_e, f in parts]
+    total = int(sum(c.sum() for c in per_expert))
+    total_ld = int(sum((-(-int(c) // align) * align) for cs in per_expert for c in cs))
     gate_c = torch.empty((total, d), dtype=torch.bfloat16, device="cuda")
     up_c = torch.empty_like(gate_c)
-    down_c = torch.empty(total * d, dtype=torch.bfloat16, device="cuda")
-    counts, at = [], 0
-    for prefix, keep, n_e, f in parts:
-        keep = np.asarray(keep).astype(bool)
-        index = torch.from_numpy(np.flatnonzero(keep).astype(np.int32)).cuda()
-        count = keep.reshape(n_e, f).sum(axis=1).astype(np.int32)
+    down_c = torch.empty(total_ld * d, dtype=torch.bfloat16, device="cuda")
+    counts, at, at_ld = [], 0, 0
+    for (prefix, keep, n_e, f), count in zip(parts, per_expert):
+        index = torch.from_numpy(np.flatnonzero(np.asarray(keep)).astype(np.int32)).cuda()
         k = int(count.sum())
+        k_ld = int(sum(-(-int(c) // align) * align for c in count))
         cam.gather_micro_experts(dev[prefix + "_gate"], dev[prefix + "_up"], dev[prefix + "_down"], index,
-                                 torch.from_numpy(count).cuda(), out=(gate_c[at:at + k], up_c[at:at + k], down_c[at * d:(at + k) * d]))
+                                 torch.from_numpy(count).cuda(), down_row_align=align,
+                                 out=(gate_c[at:at + k], up_c[at:at + k], down_c[at_ld * d:(at_ld + k_ld) * d]))
         counts += [int(c) for c in count]
         at += k
+        at_ld += k_ld
     return counts, gate_c, up_c, down_c
 
 
@@ -106,8 +113,9 @@ def test_shared_experts_in_the_same_call_and_accumulated(cam, n_tokens, n_shared
     Y_routed = Y.clone()
     cam.layer_forward_compact(dev["X"], None, None, cs, gs, us, ds, Y=Y, accumulate=True)
     Y_shared = cam.layer_forward_compact(dev["X"], None, None, cs, gs, us, ds)
-    call, gc, uc, dc = compact_layer(cam, dev, cfg, keep_r, keep_s)
-    Y_one = cam.layer_forward_compact(dev["X"], idx, w, call, gc, uc, dc, n_shared=cfg.n_shared)
+    align = 64 if n_tokens % 2 == 0 else 1
+    call, gc, uc, dc = compact_layer(cam, dev, cfg, keep_r, keep_s, align)
+    Y_one = cam.layer_forward_compact(dev["X"], idx, w, call, gc, uc, dc, n_shared=cfg.n_shared, down_row_align=align)
     torch.cuda.synchronize()
     # the same terms in another order of summation: equal up to float32 rounding
     scale = Y.abs().max().item()

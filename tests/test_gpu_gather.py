@@ -26,13 +26,14 @@ def weights(n_experts, d_ff, d_model, dtype, seed, pad=0):
     return one((n_experts, d_ff, d_model)), one((n_experts, d_ff, d_model)), one((n_experts, d_model, d_ff))
 
 
-def check(cam, Wg, Wu, Wd, index, count, index_base=0):
-    """Runs the GPU gather on views of device copies and compares with the oracle, expert by expert."""
+def check(cam, Wg, Wu, Wd, index, count, index_base=0, align=1):
+    """Runs the GPU gather on views of device copies and compares with the oracle, expert by expert; with a row
+    alignment the rows of a W_down block are the oracle's, then zeros up to the next multiple of it."""
     dev = lambda pair: None if pair is None else pair[0].cuda()[:, :pair[1].shape[1] * pair[1].shape[2]].view(pair[1].shape)
     g_d, u_d, d_d = dev(Wg), dev(Wu), dev(Wd)
     idx_d = torch.as_tensor(np.asarray(index), dtype=torch.int32).cuda()
     cnt_d = None if count is None else torch.as_tensor(np.asarray(count), dtype=torch.int32).cuda()
-    gate_out, up_out, down_out = cam.gather_micro_experts(g_d, u_d, d_d, idx_d, cnt_d, index_base)
+    gate_out, up_out, down_out = cam.gather_micro_experts(g_d, u_d, d_d, idx_d, cnt_d, index_base, down_row_align=align)
     torch.cuda.synchronize()
     n_experts, d_ff, d_model = Wg[1].shape
     cnt = np.full(n_experts, d_ff) if count is None else np.asarray(count)
@@ -42,9 +43,11 @@ def check(cam, Wg, Wu, Wd, index, count, index_base=0):
     flat = bits(down_out)
     pos = 0
     for e in range(n_experts):
-        block = flat[pos * d_model:(pos + cnt[e]) * d_model].reshape(d_model, cnt[e])
-        np.testing.assert_array_equal(block, o_down[e])
-        pos += cnt[e]
+        ld = -(-int(cnt[e]) // align) * align
+        block = flat[pos * d_model:(pos + ld) * d_model].reshape(d_model, ld)
+        np.testing.assert_array_equal(block[:, :cnt[e]], o_down[e])
+        assert not block[:, cnt[e]:].any()
+        pos += ld
 
 
 @pytest.mark.parametrize("dtype,n_experts,d_ff,d_model,pad", [
@@ -66,6 +69,7 @@ def test_gather_after_select_matches_oracle(cam, dtype, n_experts, d_ff, d_model
         o_keep, o_per, o_idx, _ = orc.select_prune(E.numpy(), seg, ratio)
         np.testing.assert_array_equal(idx, o_idx)
         check(cam, Wg, Wu, Wd, idx, per.cpu().numpy())
+        check(cam, Wg, Wu, Wd, idx, per.cpu().numpy(), align=64 if ratio < 0.5 else 8)   # zero-padded W_down rows
 
 
 def test_gather_with_the_bit_allocation_permutation(cam):
@@ -83,6 +87,7 @@ def test_gather_degenerate_cases(cam):
     everything = np.arange(n_experts * d_ff)
     check(cam, Wg, Wu, Wd, everything, np.full(n_experts, d_ff))                 # keep all: a copy
     check(cam, Wg, Wu, Wd, [2 * d_ff + 7], [0, 0, 1, 0])                         # one entry, empty experts around it
+    check(cam, Wg, Wu, Wd, [2 * d_ff + 7], [0, 0, 1, 0], align=512)              # the same with the largest row alignment
     check(cam, Wg, Wu, Wd, 500 + everything[::3], [32] * n_experts, index_base=500)   # a group behind another one
     rev = np.concatenate([np.arange(e * d_ff, (e + 1) * d_ff)[::-1] for e in range(n_experts)])
     check(cam, Wg, Wu, Wd, rev, None)                                            # any order inside an expert
