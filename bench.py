@@ -57,6 +57,8 @@ def parse_args():
     ap.add_argument("--no-probes", action="store_true", help="skip the measured MFMA / HBM ceilings (about 1 s)")
     ap.add_argument("--no-forward", action="store_true",
                     help="skip the measurement of the pruned layer's output and its decoding error")
+    ap.add_argument("--decode-ratios", default="0,0.2,0.4,0.6",
+                    help="pruning ratios of the decode measurement (comma separated; the first is the reference of the speed-ups)")
     ap.add_argument("--no-decode", action="store_true",
                     help="skip the measurement of a pruned layer's output from compacted weights on a 64-token batch")
     ap.add_argument("--no-apply", action="store_true",
@@ -425,7 +427,8 @@ def main():
     apply_mask = None if args.no_apply else measure_apply(cam, cfg, layers, torch, binding)
     forward = None if (args.no_forward or calib_tokens != cfg.n_tokens) else measure_forward(cam, cfg, layers, torch, binding)
 
-    decode = None if (args.no_decode or calib_tokens != cfg.n_tokens) else measure_decode(cam, cfg, layers, torch, binding)
+    decode = None if (args.no_decode or calib_tokens != cfg.n_tokens) else measure_decode(cam, cfg, layers, torch, binding,
+                                                                                            ratios=[float(r) for r in args.decode_ratios.split(",")])
 
     ms_per_step = elapsed / args.steps * 1e3
     value = calib_tokens * n_layers * args.steps / elapsed

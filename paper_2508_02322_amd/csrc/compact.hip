@@ -46,12 +46,18 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) uint64_t u64x2;
 typedef __attribute__((ext_vector_type(8))) int16_t i16x8;
 
-#ifndef CAMERA_COMPACT_KSPLIT
-#define CAMERA_COMPACT_KSPLIT 4
+// Waves of a workgroup, each with its share of the K blocks (1, 2 or 4: the four accumulator groups of a lane
+// are dealt to them after the reduction).
+#ifndef CAMERA_COMPACT_KSPLIT_HIDDEN
+#define CAMERA_COMPACT_KSPLIT_HIDDEN 4
 #endif
-constexpr int kSplit = CAMERA_COMPACT_KSPLIT;  // waves of a workgroup, each with its share of the K blocks
-static_assert(kSplit == 1 || kSplit == 2 || kSplit == 4, "the four accumulator groups are dealt to 1, 2 or 4 waves");
-constexpr int kThreads = kWave * kSplit;
+#ifndef CAMERA_COMPACT_KSPLIT_DOWN
+#define CAMERA_COMPACT_KSPLIT_DOWN 4
+#endif
+constexpr int kSplitHidden = CAMERA_COMPACT_KSPLIT_HIDDEN;
+constexpr int kSplitDown = CAMERA_COMPACT_KSPLIT_DOWN;
+static_assert(kSplitHidden == 1 || kSplitHidden == 2 || kSplitHidden == 4, "1, 2 or 4 waves");
+static_assert(kSplitDown == 1 || kSplitDown == 2 || kSplitDown == 4, "1, 2 or 4 waves");
 constexpr int kRows = 32;    // weight rows per workgroup (the MFMA's M)
 constexpr int kTokens = 32;  // tokens per workgroup (the MFMA's N)
 constexpr int kKBlock = 64;  // K elements per step: 4 MFMAs of K = 16
@@ -143,7 +149,7 @@ __device__ __forceinline__ void mfma4(f32x16& acc, const Frag& a, const Frag& b)
 
 // ---- partial sums of the waves ------------------------------------------------------------------------------
 // red[wave][tile][i][lane]: accumulator element i of `lane`.  With one wave per workgroup nothing goes through LDS.
-template <int TILES>
+template <int KS, int TILES>
 struct Reduce {
   float (*red)[TILES][16][kWave];
   __device__ __forceinline__ void put(int wave, int tile, const f32x16& acc, int lane) const {
@@ -153,23 +159,25 @@ struct Reduce {
   __device__ __forceinline__ float get(int tile, int i, int lane) const {
     float s = red[0][tile][i][lane];
 #pragma unroll
-    for (int w = 1; w < kSplit; ++w) s += red[w][tile][i][lane];
+    for (int w = 1; w < KS; ++w) s += red[w][tile][i][lane];
     return s;
   }
 };
 // The groups of four accumulator elements (q = i / 4) that `wave` finishes after the reduction.
-__device__ __forceinline__ bool owns_group(int wave, int q) { return (q * kSplit) / 4 == wave; }
+template <int KS>
+__device__ __forceinline__ bool owns_group(int wave, int q) { return (q * KS) / 4 == wave; }
 
 // K blocks [kb0, kb1) of a wave; the wave with `tail` also takes the partial block after the last full one.
 struct KRange {
   int kb0, kb1;
   bool tail;
 };
+template <int KS>
 __device__ __forceinline__ KRange k_range(int full_blocks, bool has_tail, int wave) {
   KRange k;
-  k.kb0 = full_blocks * wave / kSplit;
-  k.kb1 = full_blocks * (wave + 1) / kSplit;
-  k.tail = has_tail && wave == kSplit - 1;
+  k.kb0 = full_blocks * wave / KS;
+  k.kb1 = full_blocks * (wave + 1) / KS;
+  k.tail = has_tail && wave == KS - 1;
   return k;
 }
 
@@ -222,13 +230,14 @@ __device__ __forceinline__ void hidden_pass(const __bf16* __restrict__ wg, const
 // grid: x = 32-row tiles of all experts (exactly tab.tile_off[tab.n_experts]), y = 32-token groups.  The
 // workgroups of the last group also take any further groups of their expert (an expert can hold more tokens
 // than the batch has only if a token names it twice).
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void compact_hidden_kernel(
+template <int KS>
+__global__ __launch_bounds__(kWave * KS) __attribute__((amdgpu_waves_per_eu(2))) void compact_hidden_kernel(
     const __bf16* __restrict__ X, int64_t ldx, int d_model, const __bf16* __restrict__ W_gate,
     const __bf16* __restrict__ W_up, CompactRows tab, const int32_t* __restrict__ counts,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm, const float* __restrict__ w_perm,
     __bf16* __restrict__ H, int ldh) {
-  __shared__ float red_mem[kSplit][2][16][kWave];  // gate and up
-  const Reduce<2> red{red_mem};
+  __shared__ float red_mem[KS][2][16][kWave];  // gate and up
+  const Reduce<KS, 2> red{red_mem};
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int tile = blockIdx.x;
@@ -246,7 +255,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
   const int64_t w_off = ((int64_t)tab.row_off[e] + row) * d_model + h * 32;
   const __bf16* wg = W_gate + w_off;
   const __bf16* wu = W_up + w_off;
-  const KRange kr = k_range(d_model / kKBlock, d_model % kKBlock != 0, wave);
+  const KRange kr = k_range<KS>(d_model / kKBlock, d_model % kKBlock != 0, wave);
 
   for (int t0 = t_first; t0 < m; t0 += kTokens) {
     const int t = t0 + r;
@@ -255,7 +264,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     const __bf16* x = X + tok * ldx + h * 32;
     f32x16 g = {}, u = {};
     hidden_pass(wg, wu, x, d_model, kr, g, u);
-    if constexpr (kSplit > 1) {
+    if constexpr (KS > 1) {
       red.put(wave, 0, g, lane);
       red.put(wave, 1, u, lane);
       __syncthreads();
@@ -266,14 +275,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
       const float a = w_perm ? w_perm[slot] : 1.0f;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        if (!owns_group(wave, q)) continue;
+        if (!owns_group<KS>(wave, q)) continue;
         const int c = c0 + 8 * q + 4 * h;
         if (c >= cnt8) continue;  // columns [cnt, cnt8) are written as zeros: the down kernel reads whole chunks
         bf16x4 out;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float gv = kSplit > 1 ? red.get(0, 4 * q + i, lane) : g[4 * q + i];
-          const float uv = kSplit > 1 ? red.get(1, 4 * q + i, lane) : u[4 * q + i];
+          const float gv = KS > 1 ? red.get(0, 4 * q + i, lane) : g[4 * q + i];
+          const float uv = KS > 1 ? red.get(1, 4 * q + i, lane) : u[4 * q + i];
           const float lam = a * silu_f32(gv) * uv;
           out[i] = (__bf16)(c + i < cnt ? lam : 0.0f);
         }
@@ -281,7 +290,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
       }
     }
     if (!last_group) break;
-    if constexpr (kSplit > 1) __syncthreads();  // the next pass writes the same LDS
+    if constexpr (KS > 1) __syncthreads();  // the next pass writes the same LDS
   }
 }
 
@@ -322,12 +331,13 @@ __device__ __forceinline__ int chunk_length(int cnt, int n_chunks) {
 
 // grid: x = (K chunk of an expert, 32-row tile of d_model): tab.chunk_off[tab.n_experts] * row_tiles workgroups,
 // y = 32-token groups.  partial is [chunk within the expert][n_slots][d_model].
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) void compact_down_kernel(
+template <int KS>
+__global__ __launch_bounds__(kWave * KS) __attribute__((amdgpu_waves_per_eu(3))) void compact_down_kernel(
     const __bf16* __restrict__ H, int ldh, const __bf16* __restrict__ W_down, int d_model, CompactDown tab,
     const int32_t* __restrict__ counts, const int32_t* __restrict__ offsets, int64_t n_slots,
     float* __restrict__ partial) {
-  __shared__ float red_mem[kSplit][1][16][kWave];
-  const Reduce<1> red{red_mem};
+  __shared__ float red_mem[KS][1][16][kWave];
+  const Reduce<KS, 1> red{red_mem};
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int row_tiles = (d_model + kRows - 1) / kRows;
@@ -348,7 +358,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) v
   const int r = lane & 31, h = lane >> 5;
   const int row = min(r0 + r, d_model - 1);
   const __bf16* wd = W_down + (int64_t)tab.ld_off[e] * d_model + (int64_t)row * ld + k0 + h * 32;
-  const KRange kr = k_range(k_len / kKBlock, k_len % kKBlock != 0, wave);
+  const KRange kr = k_range<KS>(k_len / kKBlock, k_len % kKBlock != 0, wave);
   float* out_chunk = partial + (int64_t)chunk_in * n_slots * d_model;
 
   for (int t0 = t_first; t0 < m; t0 += kTokens) {
@@ -356,7 +366,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) v
     const __bf16* hrow = H + (int64_t)(slot0 + min(t, m - 1)) * ldh + k0 + h * 32;
     f32x16 p = {};
     down_pass(wd, hrow, k_len, cnt, kr, p);
-    if constexpr (kSplit > 1) {
+    if constexpr (KS > 1) {
       red.put(wave, 0, p, lane);
       __syncthreads();
     }
@@ -364,17 +374,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) v
       float* out = out_chunk + (int64_t)(slot0 + t) * d_model;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        if (!owns_group(wave, q)) continue;
+        if (!owns_group<KS>(wave, q)) continue;
         const int rr = r0 + 8 * q + 4 * h;
         if (rr >= d_model) continue;  // d_model is a multiple of 8: a group of four is inside or outside as a whole
         float v[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = kSplit > 1 ? red.get(0, 4 * q + i, lane) : p[4 * q + i];
+        for (int i = 0; i < 4; ++i) v[i] = KS > 1 ? red.get(0, 4 * q + i, lane) : p[4 * q + i];
         *reinterpret_cast<float4*>(out + rr) = make_float4(v[0], v[1], v[2], v[3]);
       }
     }
     if (!last_group) break;
-    if constexpr (kSplit > 1) __syncthreads();
+    if constexpr (KS > 1) __syncthreads();
   }
 }
 
@@ -543,7 +553,7 @@ hipError_t launch_compact_hidden(hipStream_t stream, const void* X, int64_t ldx,
                                  void* hidden, int ldh) {
   const int tiles = tab.tile_off[tab.n_experts];
   if (tiles <= 0) return hipSuccess;
-  compact_hidden_kernel<<<dim3(tiles, token_groups), kThreads, 0, stream>>>(
+  compact_hidden_kernel<kSplitHidden><<<dim3(tiles, token_groups), kWave * kSplitHidden, 0, stream>>>(
       static_cast<const __bf16*>(X), ldx, (int)d_model, static_cast<const __bf16*>(W_gate),
       static_cast<const __bf16*>(W_up), tab, t.counts, t.offsets, t.perm, t.w_perm, static_cast<__bf16*>(hidden), ldh);
   return hipGetLastError();
@@ -554,7 +564,7 @@ hipError_t launch_compact_down(hipStream_t stream, const void* hidden, int ldh, 
                                float* partial) {
   const int64_t blocks = (int64_t)tab.chunk_off[tab.n_experts] * ((d_model + kRows - 1) / kRows);
   if (blocks <= 0) return hipSuccess;
-  compact_down_kernel<<<dim3((unsigned)blocks, token_groups), kThreads, 0, stream>>>(
+  compact_down_kernel<kSplitDown><<<dim3((unsigned)blocks, token_groups), kWave * kSplitDown, 0, stream>>>(
       static_cast<const __bf16*>(hidden), ldh, static_cast<const __bf16*>(W_down), (int)d_model, tab, t.counts,
       t.offsets, n_slots, partial);
   return hipGetLastError();
