@@ -148,3 +148,37 @@ def test_nothing_kept_and_bad_arguments(cam):
         cam.layer_forward_compact(dev["X"], None, None, [0] * cfg.n_experts, empty, empty, empty.reshape(-1), n_shared=1)
     with pytest.raises(binding.CameraError, match="BF16"):
         cam.layer_forward_compact(dev["X"].float(), idx, w, [0] * cfg.n_experts, empty, empty, empty.reshape(-1))
+
+
+@pytest.mark.parametrize("name", ["deepseek-moe-16b", "qwen2-57b-a14b"])
+def test_full_size_layer_decoding_batch(cam, name):
+    """A whole layer of the benchmark shape in the launch configuration bench.py times: 64 tokens, routed and
+    shared experts compacted into one set of buffers with cache-line-aligned W_down rows, one call.  The oracle
+    recomputes every token over the experts the batch uses."""
+    cfg = inputs.CONFIGS[name]
+    layer = inputs.make_layer(cfg, 0, device="cuda")
+    X = layer["X"][:64]
+    idx, w = cam.route_topk(X, layer["W_r"], layer["bias"], cfg.top_k)
+    keep = (torch.rand(cfg.n_micro, generator=torch.Generator().manual_seed(9)) < 0.6).to(torch.uint8).numpy()
+    nr = cfg.n_micro_routed
+    counts, gate_c, up_c, down_c = compact_layer(cam, layer, cfg, keep[:nr], keep[nr:], 64)
+    Y = cam.layer_forward_compact(X, idx, w, counts, gate_c, up_c, down_c, n_shared=cfg.n_shared, down_row_align=64)
+    again = cam.layer_forward_compact(X, idx, w, counts, gate_c, up_c, down_c, n_shared=cfg.n_shared, down_row_align=64)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, again)                                   # no atomics: the same bits every time
+    X64 = H.f64(X)
+    A = dense_A(idx.cpu().numpy().astype(np.int64), w.cpu().numpy().astype(np.float64), cfg.n_experts)
+    used = np.nonzero(A.sum(axis=0))[0]
+    gate = [H.f64(layer["W_gate"][e]) for e in used]
+    up = [H.f64(layer["W_up"][e]) for e in used]
+    down = [H.f64(layer["W_down"][e]) for e in used]
+    keep_used = np.concatenate([keep[e * cfg.d_ff:(e + 1) * cfg.d_ff] for e in used])
+    O = orc.layer_forward(X64, A[:, used], gate, up, down, keep=keep_used, round_hidden=orc.round_to_bf16)
+    term = largest_term(X64, A[:, used], gate, up, down, keep_used)
+    del gate, up, down
+    g2, u2, d2 = expert_lists(layer, "Ws")
+    ones = np.ones((64, cfg.n_shared))
+    O += orc.layer_forward(X64, ones, g2, u2, d2, keep=keep[nr:], round_hidden=orc.round_to_bf16)
+    term = np.maximum(term, largest_term(X64, ones, g2, u2, d2, keep[nr:]))
+    err = check_output(Y, O, term)
+    print(f"{name}: 64-token batch, {len(used)} routed experts used, rel err {err:.2e}")
