@@ -182,3 +182,53 @@ def test_full_size_layer_decoding_batch(cam, name):
     term = np.maximum(term, largest_term(X64, ones, g2, u2, d2, keep[nr:]))
     err = check_output(Y, O, term)
     print(f"{name}: 64-token batch, {len(used)} routed experts used, rel err {err:.2e}")
+
+
+def run_and_check(cam, cfg, keep_frac, align, seed=3):
+    """One merged call (routed + shared, if any) on a small layer against the oracle's masked layer."""
+    layer = inputs.make_layer(cfg, 0, device="cpu")
+    dev = H.to_dev(layer)
+    idx, w = cam.route_topk(dev["X"], dev["W_r"], dev["bias"], cfg.top_k)
+    rng = np.random.default_rng(seed)
+    keep = (rng.random(cfg.n_micro) < keep_frac).astype(np.uint8)
+    nr = cfg.n_micro_routed
+    X64 = H.f64(layer["X"])
+    A = dense_A(idx.cpu().numpy().astype(np.int64), w.cpu().numpy().astype(np.float64), cfg.n_experts)
+    gate, up, down = expert_lists(layer, "W")
+    O = orc.layer_forward(X64, A, gate, up, down, keep=keep[:nr], round_hidden=orc.round_to_bf16)
+    term = largest_term(X64, A, gate, up, down, keep[:nr])
+    if cfg.n_shared:
+        counts, gate_c, up_c, down_c = compact_layer(cam, dev, cfg, keep[:nr], keep[nr:], align)
+        g2, u2, d2 = expert_lists(layer, "Ws")
+        ones = np.ones((cfg.n_tokens, cfg.n_shared))
+        O += orc.layer_forward(X64, ones, g2, u2, d2, keep=keep[nr:], round_hidden=orc.round_to_bf16)
+        term = np.maximum(term, largest_term(X64, ones, g2, u2, d2, keep[nr:]))
+    else:
+        counts, gate_c, up_c, down_c = compact(cam, dev, "W", keep, cfg.n_experts, cfg.d_ff, align=align)
+    Y = cam.layer_forward_compact(dev["X"], idx, w, counts, gate_c, up_c, down_c, n_shared=cfg.n_shared,
+                                  down_row_align=align)
+    torch.cuda.synchronize()
+    return check_output(Y, O, term), counts
+
+
+def test_built_limits_of_the_compacted_layer(cam):
+    # a shared expert that keeps more than 8 chunks' worth: the chunk count is capped and the chunks grow
+    err, counts = run_and_check(cam, small(n_tokens=40, d_model=32, d_ff=64, n_experts=4, n_shared=1, d_ff_shared=32768),
+                                0.93, 64)
+    assert counts[-1] > 8 * 3072
+    # exactly as many pairs as the one-workgroup bucket kernel takes, and one token more (general counting sort)
+    run_and_check(cam, small(n_tokens=512, d_model=32, d_ff=40, n_experts=8, top_k=3, n_shared=1, d_ff_shared=48), 0.7, 1)
+    run_and_check(cam, small(n_tokens=513, d_model=32, d_ff=40, n_experts=8, top_k=3, n_shared=1, d_ff_shared=48), 0.7, 8)
+    # more 32-token groups than the grid has rows (64): the workgroups of the last row walk on
+    run_and_check(cam, small(n_tokens=2100, d_model=32, d_ff=24, n_experts=2, top_k=2, n_shared=1, d_ff_shared=40), 0.8, 64)
+    # the largest row alignment, and the largest number of experts in one call
+    run_and_check(cam, small(n_tokens=9, d_model=32, d_ff=16, n_experts=4, top_k=2), 0.5, 512)
+    run_and_check(cam, small(n_tokens=30, d_model=32, d_ff=8, n_experts=250, top_k=4, n_shared=6, d_ff_shared=8,
+                             router_bias="none"), 0.6, 1)
+    dev = H.to_dev(inputs.make_layer(small(n_tokens=4, d_model=32, d_ff=8, n_experts=250, top_k=4, router_bias="none"), 0))
+    idx, w = cam.route_topk(dev["X"], dev["W_r"], dev["bias"], 4)
+    empty = torch.empty((0, 32), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(binding.CameraError, match="n_shared"):
+        cam.layer_forward_compact(dev["X"], idx, w, [0] * 257, empty, empty, empty.reshape(-1), n_shared=7)
+    with pytest.raises(binding.CameraError, match="down_row_align"):
+        cam.layer_forward_compact(dev["X"], idx, w, [0] * 250, empty, empty, empty.reshape(-1), down_row_align=513)

@@ -47,3 +47,57 @@ def test_layer_step_replays_from_a_graph(cam):
         torch.cuda.synchronize()
         assert torch.equal(got_e, out["energy"]) and torch.equal(got_bits, prune_out[0]) and torch.equal(got_per, prune_out[1])
         assert float(got_e.sum()) > 0
+
+
+def test_compacted_layer_replays_from_a_graph(cam):
+    """The decoding call (routing, bucket order, both streaming contractions, combine) captured once and replayed
+    with new tokens in the same buffer."""
+    cfg = inputs.scaled(inputs.CONFIGS["deepseek-moe-16b"], n_tokens=64, d_model=128, d_ff=200, n_experts=16, top_k=4,
+                        n_shared=1, d_ff_shared=264, n_layers=1)
+    dev = H.to_dev(inputs.make_layer(cfg, 0, device="cpu"))
+    X = dev["X"].clone()
+    rng = np.random.default_rng(2)
+    counts, index = [], []
+    for prefix, n_e, f, base in (("W", cfg.n_experts, cfg.d_ff, 0), ("Ws", cfg.n_shared, cfg.d_ff_shared, 0)):
+        keep = rng.random(n_e * f) < 0.6
+        counts.append(keep.reshape(n_e, f).sum(axis=1).astype(np.int32))
+        index.append(np.flatnonzero(keep).astype(np.int32))
+    align = 64
+    ld = [(-(-c // align) * align) for c in counts]
+    rows = [int(c.sum()) for c in counts]
+    gate_c = torch.empty((sum(rows), cfg.d_model), dtype=torch.bfloat16, device="cuda")
+    up_c = torch.empty_like(gate_c)
+    down_c = torch.empty(int(sum(l.sum() for l in ld)) * cfg.d_model, dtype=torch.bfloat16, device="cuda")
+    at, at_ld = 0, 0
+    for g, prefix in enumerate(("W", "Ws")):
+        k, k_ld = rows[g], int(ld[g].sum())
+        cam.gather_micro_experts(dev[prefix + "_gate"], dev[prefix + "_up"], dev[prefix + "_down"],
+                                 torch.from_numpy(index[g]).cuda(), torch.from_numpy(counts[g]).cuda(), down_row_align=align,
+                                 out=(gate_c[at:at + k], up_c[at:at + k], down_c[at_ld * cfg.d_model:(at_ld + k_ld) * cfg.d_model]))
+        at, at_ld = at + k, at_ld + k_ld
+    count_all = [int(c) for cs in counts for c in cs]
+    Y = torch.empty((cfg.n_tokens, cfg.d_model), dtype=torch.float32, device="cuda")
+
+    def step():
+        idx, w = cam.route_topk(X, dev["W_r"], dev["bias"], cfg.top_k)
+        cam.layer_forward_compact(X, idx, w, count_all, gate_c, up_c, down_c, n_shared=cfg.n_shared, down_row_align=align, Y=Y)
+
+    step()
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            step()
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    for trial in range(4):
+        if trial:
+            X.copy_(torch.randn(X.shape, generator=gen, device="cuda").to(X.dtype))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = Y.clone()
+        Y.zero_()
+        step()
+        torch.cuda.synchronize()
+        assert torch.equal(got, Y) and float(got.abs().sum()) > 0
