@@ -47,17 +47,15 @@ typedef __attribute__((ext_vector_type(2))) uint64_t u64x2;
 typedef __attribute__((ext_vector_type(8))) int16_t i16x8;
 
 // Waves of a workgroup, each with its share of the K blocks (1, 2 or 4: the four accumulator groups of a lane
-// are dealt to them after the reduction).
+// are dealt to them after the reduction).  The first contraction's K extent is d_model.
 #ifndef CAMERA_COMPACT_KSPLIT_HIDDEN
 #define CAMERA_COMPACT_KSPLIT_HIDDEN 4
 #endif
-#ifndef CAMERA_COMPACT_KSPLIT_DOWN
-#define CAMERA_COMPACT_KSPLIT_DOWN 4
-#endif
 constexpr int kSplitHidden = CAMERA_COMPACT_KSPLIT_HIDDEN;
-constexpr int kSplitDown = CAMERA_COMPACT_KSPLIT_DOWN;
 static_assert(kSplitHidden == 1 || kSplitHidden == 2 || kSplitHidden == 4, "1, 2 or 4 waves");
-static_assert(kSplitDown == 1 || kSplitDown == 2 || kSplitDown == 4, "1, 2 or 4 waves");
+// The second contraction's K extent is the expert's kept count, which shrinks with the pruning ratio: four
+// waves while a K chunk gives each of them at least five K blocks, two below that (measured 3-8 % apart).
+constexpr int kDownFourWavesFrom = 1280;
 constexpr int kRows = 32;    // weight rows per workgroup (the MFMA's M)
 constexpr int kTokens = 32;  // tokens per workgroup (the MFMA's N)
 constexpr int kKBlock = 64;  // K elements per step: 4 MFMAs of K = 16
@@ -564,9 +562,17 @@ hipError_t launch_compact_down(hipStream_t stream, const void* hidden, int ldh, 
                                float* partial) {
   const int64_t blocks = (int64_t)tab.chunk_off[tab.n_experts] * ((d_model + kRows - 1) / kRows);
   if (blocks <= 0) return hipSuccess;
-  compact_down_kernel<kSplitDown><<<dim3((unsigned)blocks, token_groups), kWave * kSplitDown, 0, stream>>>(
-      static_cast<const __bf16*>(hidden), ldh, static_cast<const __bf16*>(W_down), (int)d_model, tab, t.counts,
-      t.offsets, n_slots, partial);
+  int64_t kept = 0;
+  for (int e = 0; e < tab.n_experts; ++e) kept += tab.count[e];
+  const dim3 grid((unsigned)blocks, token_groups);
+  if (kept >= (int64_t)kDownFourWavesFrom * tab.chunk_off[tab.n_experts])  // mean chunk length
+    compact_down_kernel<4><<<grid, kWave * 4, 0, stream>>>(static_cast<const __bf16*>(hidden), ldh,
+                                                           static_cast<const __bf16*>(W_down), (int)d_model, tab,
+                                                           t.counts, t.offsets, n_slots, partial);
+  else
+    compact_down_kernel<2><<<grid, kWave * 2, 0, stream>>>(static_cast<const __bf16*>(hidden), ldh,
+                                                           static_cast<const __bf16*>(W_down), (int)d_model, tab,
+                                                           t.counts, t.offsets, n_slots, partial);
   return hipGetLastError();
 }
 
