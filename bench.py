@@ -53,6 +53,9 @@ def parse_args():
     ap.add_argument("--streams", type=int, default=1,
                     help="run consecutive layers on this many HIP streams (one library context each), so that the tail of one "
                          "layer's kernels overlaps the start of the next layer's; per-kernel timings then overlap as well")
+    ap.add_argument("--energy-spread", type=float, default=0.0,
+                    help="scale every W_down column by a log-normal factor of this sigma (per expert and per micro-expert): "
+                         "energies and per-expert kept counts as uneven as on trained models; 0 = the named workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the measured MFMA / HBM ceilings (about 1 s)")
     ap.add_argument("--no-forward", action="store_true",
@@ -287,6 +290,7 @@ def measure_decode(cam, cfg, layers, torch, binding, ratios=(0.0, 0.2, 0.4, 0.6)
         stream_ms = begin.elapsed_time(end) / reps
         kernel_ms = ms["compact_hidden"] + ms["compact_down"]
         rows.append({"ratio": ratio, "ms_per_layer": round(stream_ms, 4), "kernel_ms": {k: round(v, 4) for k, v in ms.items()},
+                     "kept_per_routed_expert_min_max": [int(per_h[:cfg.n_experts].min()), int(per_h[:cfg.n_experts].max())],
                      "kept_weight_bytes_read": kept_bytes, "gb_per_s": round(kept_bytes / (kernel_ms * 1e-3) / 1e9, 1)})
         del gate_c, up_c, down_c
     base = rows[0]
@@ -358,6 +362,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     cfg = inputs.CONFIGS[args.workload]
+    if args.energy_spread > 0:
+        cfg = inputs.scaled(cfg, energy_spread=args.energy_spread)
     n_layers = args.layers if args.layers > 0 else cfg.n_layers
     decisions = DECISIONS[args.workload]
     cam = binding.Camera(device=0)
@@ -438,7 +444,8 @@ def main():
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name + ("" if n_layers == cfg.n_layers else f"[first {n_layers} layers only]")
-                   + ("" if calib_tokens == cfg.n_tokens else f"[{calib_tokens} calibration tokens in chunks of {chunk_tokens}]"),
+                   + ("" if calib_tokens == cfg.n_tokens else f"[{calib_tokens} calibration tokens in chunks of {chunk_tokens}]")
+                   + ("" if cfg.energy_spread == 0 else f"[W_down columns scaled log-normally, sigma {cfg.energy_spread}]"),
                    "layers": n_layers, "tokens": calib_tokens, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
                    "experts": cfg.n_experts, "top_k": cfg.top_k, "shared_experts": cfg.n_shared,
                    "d_ff_shared": cfg.d_ff_shared, "alpha": cfg.alpha, "decisions": decisions,

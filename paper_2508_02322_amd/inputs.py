@@ -46,6 +46,11 @@ class LayerConfig:
     outlier_scale: float = 20.0
     router_bias: str = "none"      # "none" | "normal" | "zipf"
     w_std: float = 0.02
+    # > 0: every down column (e, c) is scaled by exp(energy_spread * (z_e + z_ec)), z ~ N(0, 1) per expert and per
+    # micro-expert: energies spread over orders of magnitude and the experts keep very different numbers of
+    # micro-experts, as the paper reports for trained models ("highly non-uniform" energy distribution; the
+    # per-expert pruning ratios of its figures).  0: i.i.d. weights, all micro-experts statistically alike.
+    energy_spread: float = 0.0
 
     @property
     def torch_dtype(self):
@@ -140,6 +145,14 @@ def make_layer(cfg: LayerConfig, layer: int = 0, device="cpu") -> dict:
         out["Ws_gate"] = _normal((ns, fs, d), cfg.w_std, dt, g, device)
         out["Ws_up"] = _normal((ns, fs, d), cfg.w_std, dt, g, device)
         out["Ws_down"] = _normal((ns, d, fs), cfg.w_std, dt, g, device)
+    if cfg.energy_spread > 0:      # drawn after everything else: the other tensors do not depend on it
+        for key, n_e, width in (("W_down", ne, f), ("Ws_down", cfg.n_shared, cfg.d_ff_shared)):
+            if n_e == 0:
+                continue
+            z = torch.randn((n_e, 1, 1), generator=g, device=device) + torch.randn((n_e, 1, width), generator=g, device=device)
+            scale = torch.exp(cfg.energy_spread * z)
+            for e in range(n_e):   # expert by expert: the float32 temporary stays small
+                out[key][e] = (out[key][e].float() * scale[e]).to(dt)
     return out
 
 

@@ -89,9 +89,10 @@ def check_decisions(cam, cfg, name, energy_gpu, energy_orc=None):
     return report
 
 
-@pytest.mark.parametrize("name", list(SCALED))
-def test_scaled_config_end_to_end(cam, name):
-    cfg = inputs.scaled(inputs.CONFIGS[name], **SCALED[name])
+# spread > 0: down columns with log-normal scales, energies over orders of magnitude as on trained models
+@pytest.mark.parametrize("name,spread", [(n, 0.0) for n in SCALED] + [("deepseek-moe-16b", 1.0), ("qwen2-57b-a14b", 1.0)])
+def test_scaled_config_end_to_end(cam, name, spread):
+    cfg = inputs.scaled(inputs.CONFIGS[name], energy_spread=spread, **SCALED[name])
     for layer_idx in range(min(2, cfg.n_layers)):
         layer = inputs.make_layer(cfg, layer_idx)
         dev = H.to_dev(layer)
@@ -108,7 +109,9 @@ def test_scaled_config_end_to_end(cam, name):
         err = H.rel_err(got, want, want.max() * 1e-9)
         assert err <= TOL, err
         report = check_decisions(cam, cfg, name, out["energy"], want)
-        print(f"{name} layer {layer_idx}: flagged {flagged} differ {differ} energy rel err {err:.2e} {report}")
+        per_expert = cam.select_prune(out["energy"], inputs.segment_offsets(cfg), 0.4)[1].cpu().numpy()
+        print(f"{name} spread {spread} layer {layer_idx}: flagged {flagged} differ {differ} energy rel err {err:.2e} {report} "
+              f"kept per expert at 40 %: min {per_expert.min()} max {per_expert.max()}")
 
 
 FULL = ["mixtral", "deepseek-moe-16b", "qwen2-57b-a14b", "qwen3-30b-a3b"]
