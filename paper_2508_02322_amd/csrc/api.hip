@@ -79,6 +79,39 @@ struct Carver {
   }
 };
 
+// Workspace offsets of the bucket tables of one call, taken from a Carver, and the tables once the workspace exists.
+struct BucketPlan {
+  bool dense = false, slots = false;
+  size_t counts = 0, offsets = 0, tile_off = 0, tile_exp = 0, perm = 0, wperm = 0, slot = 0, hist = 0;
+  // n_experts groups of pairs; dense: no permutation (every expert sees tokens 0..n-1); slots: also the slot of
+  // every pair (the layer output needs it to sum a token's experts)
+  void take(Carver& cv, bool dense_, bool slots_, int n_experts, int64_t n_pairs, int max_tiles, int64_t n_blocks) {
+    dense = dense_;
+    slots = slots_ && !dense_;
+    counts = cv.take(sizeof(int32_t) * n_experts);
+    offsets = cv.take(sizeof(int32_t) * (n_experts + 1));
+    tile_off = cv.take(sizeof(int32_t) * (n_experts + 1));
+    tile_exp = cv.take(sizeof(int32_t) * (max_tiles + 1));
+    perm = cv.take(dense ? 0 : sizeof(int32_t) * n_pairs);
+    wperm = cv.take(dense ? 0 : sizeof(float) * n_pairs);
+    slot = cv.take(slots ? sizeof(int32_t) * n_pairs : 0);
+    hist = cv.take(sizeof(int32_t) * n_blocks * n_experts);
+  }
+  camera::BucketTables bind(char* ws, const void* zeros) const {
+    camera::BucketTables t;
+    t.counts = reinterpret_cast<int32_t*>(ws + counts);
+    t.offsets = reinterpret_cast<int32_t*>(ws + offsets);
+    t.tile_offset = reinterpret_cast<int32_t*>(ws + tile_off);
+    t.tile_expert = reinterpret_cast<int32_t*>(ws + tile_exp);
+    t.perm = dense ? nullptr : reinterpret_cast<int32_t*>(ws + perm);
+    t.w_perm = dense ? nullptr : reinterpret_cast<float*>(ws + wperm);
+    t.slot_of = slots ? reinterpret_cast<int32_t*>(ws + slot) : nullptr;
+    t.block_hist = reinterpret_cast<int32_t*>(ws + hist);
+    t.zeros = zeros;
+    return t;
+  }
+};
+
 int ensure_workspace(camera_ctx* ctx, size_t bytes) {
   if (ctx->zeros == nullptr) {
     hipError_t e = hipMalloc(&ctx->zeros, 256);
@@ -423,13 +456,8 @@ int camera_score_layer(camera_ctx* ctx, void* stream_, const void* X, int dtype,
   const int64_t n_blocks = dense ? 0 : camera::bucket_blocks(n_pairs);
 
   Carver cv;
-  const size_t o_counts = cv.take(sizeof(int32_t) * n_experts);
-  const size_t o_offsets = cv.take(sizeof(int32_t) * (n_experts + 1));
-  const size_t o_tile_off = cv.take(sizeof(int32_t) * (n_experts + 1));
-  const size_t o_tile_exp = cv.take(sizeof(int32_t) * (max_tiles + 1));
-  const size_t o_perm = cv.take(dense ? 0 : sizeof(int32_t) * n_pairs);
-  const size_t o_wperm = cv.take(dense ? 0 : sizeof(float) * n_pairs);
-  const size_t o_hist = cv.take(sizeof(int32_t) * n_blocks * n_experts);
+  BucketPlan plan;
+  plan.take(cv, dense, false, n_experts, n_pairs, max_tiles, n_blocks);
   const size_t o_p2 = cv.take(sizeof(float) * (size_t)max_tiles * d_ff);
   const size_t o_pm = cv.take(sizeof(float) * (size_t)max_tiles * d_ff);
   const size_t o_omega = cv.take(sizeof(float) * (size_t)splits * n_micro);
@@ -438,16 +466,7 @@ int camera_score_layer(camera_ctx* ctx, void* stream_, const void* X, int dtype,
   CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
   if (int rc = ensure_workspace(ctx, cv.used)) return rc;
   char* ws = static_cast<char*>(ctx->ws);
-  camera::BucketTables t;
-  t.counts = reinterpret_cast<int32_t*>(ws + o_counts);
-  t.offsets = reinterpret_cast<int32_t*>(ws + o_offsets);
-  t.tile_offset = reinterpret_cast<int32_t*>(ws + o_tile_off);
-  t.tile_expert = reinterpret_cast<int32_t*>(ws + o_tile_exp);
-  t.perm = dense ? nullptr : reinterpret_cast<int32_t*>(ws + o_perm);
-  t.w_perm = dense ? nullptr : reinterpret_cast<float*>(ws + o_wperm);
-  t.slot_of = nullptr;
-  t.block_hist = reinterpret_cast<int32_t*>(ws + o_hist);
-  t.zeros = ctx->zeros;
+  const camera::BucketTables t = plan.bind(ws, ctx->zeros);
   float* part_phi2 = reinterpret_cast<float*>(ws + o_p2);
   float* part_max = reinterpret_cast<float*>(ws + o_pm);
   float* omega_part = reinterpret_cast<float*>(ws + o_omega);
@@ -524,14 +543,8 @@ int camera_layer_forward(camera_ctx* ctx, void* stream_, const void* X, int dtyp
   const int64_t n_blocks = dense ? 0 : camera::bucket_blocks(n_pairs);
 
   Carver cv;
-  const size_t o_counts = cv.take(sizeof(int32_t) * n_experts);
-  const size_t o_offsets = cv.take(sizeof(int32_t) * (n_experts + 1));
-  const size_t o_tile_off = cv.take(sizeof(int32_t) * (n_experts + 1));
-  const size_t o_tile_exp = cv.take(sizeof(int32_t) * (max_tiles + 1));
-  const size_t o_perm = cv.take(dense ? 0 : sizeof(int32_t) * n_pairs);
-  const size_t o_wperm = cv.take(dense ? 0 : sizeof(float) * n_pairs);
-  const size_t o_slot = cv.take(dense ? 0 : sizeof(int32_t) * n_pairs);
-  const size_t o_hist = cv.take(sizeof(int32_t) * n_blocks * n_experts);
+  BucketPlan plan;
+  plan.take(cv, dense, true, n_experts, n_pairs, max_tiles, n_blocks);
   const size_t es = dtype == CAMERA_BF16 ? 2 : 4;
   const size_t o_hidden = cv.take(es * (size_t)n_pairs * d_ff);
   const size_t o_product = cv.take(sizeof(float) * (size_t)n_pairs * d_model);
@@ -540,16 +553,7 @@ int camera_layer_forward(camera_ctx* ctx, void* stream_, const void* X, int dtyp
   CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
   if (int rc = ensure_workspace(ctx, cv.used)) return rc;
   char* ws = static_cast<char*>(ctx->ws);
-  camera::BucketTables t;
-  t.counts = reinterpret_cast<int32_t*>(ws + o_counts);
-  t.offsets = reinterpret_cast<int32_t*>(ws + o_offsets);
-  t.tile_offset = reinterpret_cast<int32_t*>(ws + o_tile_off);
-  t.tile_expert = reinterpret_cast<int32_t*>(ws + o_tile_exp);
-  t.perm = dense ? nullptr : reinterpret_cast<int32_t*>(ws + o_perm);
-  t.w_perm = dense ? nullptr : reinterpret_cast<float*>(ws + o_wperm);
-  t.slot_of = dense ? nullptr : reinterpret_cast<int32_t*>(ws + o_slot);
-  t.block_hist = reinterpret_cast<int32_t*>(ws + o_hist);
-  t.zeros = ctx->zeros;
+  const camera::BucketTables t = plan.bind(ws, ctx->zeros);
   void* hidden = ws + o_hidden;
   float* product = reinterpret_cast<float*>(ws + o_product);
 
@@ -670,14 +674,8 @@ int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, 
   const bool append = !dense && !small && n_shared > 0;
 
   Carver cv;
-  const size_t o_counts = cv.take(sizeof(int32_t) * total);
-  const size_t o_offsets = cv.take(sizeof(int32_t) * (total + 1));
-  const size_t o_tile_off = cv.take(sizeof(int32_t) * (total + 1));
-  const size_t o_tile_exp = cv.take(sizeof(int32_t) * (max_tiles + 1));
-  const size_t o_perm = cv.take(dense ? 0 : sizeof(int32_t) * n_pairs);
-  const size_t o_wperm = cv.take(dense ? 0 : sizeof(float) * n_pairs);
-  const size_t o_slot = cv.take(dense ? 0 : sizeof(int32_t) * n_pairs);
-  const size_t o_hist = cv.take(sizeof(int32_t) * n_blocks * total);
+  BucketPlan plan;
+  plan.take(cv, dense, true, total, n_pairs, max_tiles, n_blocks);
   const size_t o_idx_aug = cv.take(append ? sizeof(int32_t) * n_pairs : 0);
   const size_t o_w_aug = cv.take(append ? sizeof(float) * n_pairs : 0);
   const size_t o_hidden = cv.take(2 * (size_t)n_pairs * ldh);
@@ -687,16 +685,7 @@ int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, 
   CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
   if (int rc = ensure_workspace(ctx, cv.used)) return rc;
   char* ws = static_cast<char*>(ctx->ws);
-  camera::BucketTables t;
-  t.counts = reinterpret_cast<int32_t*>(ws + o_counts);
-  t.offsets = reinterpret_cast<int32_t*>(ws + o_offsets);
-  t.tile_offset = reinterpret_cast<int32_t*>(ws + o_tile_off);
-  t.tile_expert = reinterpret_cast<int32_t*>(ws + o_tile_exp);
-  t.perm = dense ? nullptr : reinterpret_cast<int32_t*>(ws + o_perm);
-  t.w_perm = dense ? nullptr : reinterpret_cast<float*>(ws + o_wperm);
-  t.slot_of = dense ? nullptr : reinterpret_cast<int32_t*>(ws + o_slot);
-  t.block_hist = reinterpret_cast<int32_t*>(ws + o_hist);
-  t.zeros = ctx->zeros;
+  const camera::BucketTables t = plan.bind(ws, ctx->zeros);
   void* hidden = ws + o_hidden;
   float* product = reinterpret_cast<float*>(ws + o_product);
 
