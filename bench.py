@@ -215,12 +215,60 @@ def measure_forward(cam, cfg, layers, torch, binding, ratio=0.4, reps=3):
     flops_per_launch = (flops_routed + flops_shared) / calls_per_forward
     achieved = flops_per_launch / (down_ms * 1e-3) / 1e12
     forwards = 2 * reps * len(use)
+    # the same pruned layer from its compacted weights: work in proportion to what is kept
+    lr = use[0]
+    align = 64
+    _, per, kept_idx, _ = cam.select_prune(lr.out["energy"], lr.seg, ratio, want_idx=True)
+    per_h = per.cpu()
+    ld = (per_h + (align - 1)) // align * align
+    kept = int(per_h.sum())
+    dt = lr.t["W_gate"].dtype
+    gate_c = torch.empty((kept, d), dtype=dt, device="cuda")
+    up_c = torch.empty_like(gate_c)
+    down_c = torch.empty(int(ld.sum()) * d, dtype=dt, device="cuda")
+    pos, pos_ld = 0, 0
+    groups = [("W", cfg.n_experts, 0, 0)] + ([("Ws", cfg.n_shared, cfg.n_experts, cfg.n_micro_routed)] if cfg.n_shared else [])
+    for prefix, n_e, seg0, base in groups:
+        n_idx, n_ld = int(per_h[seg0:seg0 + n_e].sum()), int(ld[seg0:seg0 + n_e].sum())
+        cam.gather_micro_experts(lr.t[prefix + "_gate"], lr.t[prefix + "_up"], lr.t[prefix + "_down"], kept_idx[pos:pos + n_idx],
+                                 per[seg0:seg0 + n_e], base, down_row_align=align,
+                                 out=(gate_c[pos:pos + n_idx], up_c[pos:pos + n_idx], down_c[pos_ld * d:(pos_ld + n_ld) * d]))
+        pos, pos_ld = pos + n_idx, pos_ld + n_ld
+    X = lr.t["X"][:n]
+    idx, w = cam.route_topk(X, lr.t["W_r"], lr.t["bias"], cfg.top_k)
+    Y_c = torch.empty_like(Y)
+    run_c = lambda: cam.layer_forward_compact(X, idx, w, per_h.tolist(), gate_c, up_c, down_c, n_shared=cfg.n_shared,
+                                              down_row_align=align, Y=Y_c)
+    run_c()
+    begin, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    begin.record()
+    for _ in range(reps):
+        run_c()
+    end.record()
+    torch.cuda.synchronize()
+    compact_ms = begin.elapsed_time(end) / reps
+    for k in range(len(binding.KERNEL_NAMES)):
+        cam.profile_read(k)
+    cam.profile_enable(True)
+    for _ in range(reps):
+        run_c()
+    torch.cuda.synchronize()
+    cam.profile_enable(False)
+    compact_kernels = {name: round(cam.profile_read(k)[0] / reps, 4) for k, name in enumerate(binding.KERNEL_NAMES)
+                       if name in ("bucket", "gemm", "down_gemm", "combine")}
+    keep0 = cam.select_prune(lr.out["energy"], lr.seg, ratio)[0]
+    forward(lr, keep0, Y_hat)
+    torch.cuda.synchronize()
+    compact_diff = float((Y_c - Y_hat).norm() / Y_hat.norm())
+    del gate_c, up_c, down_c
     return {"what": f"layer output of the original and of the pruned layer (lambda = {ratio}) and their distance, {len(use)} layers",
             "ms_per_layer_output": round(sum(ms[k][0] for k in ("route", "bucket", "gemm", "down_gemm", "combine")) / forwards, 3),
             "kernel_ms_per_launch": {k: round(ms[k][0] / max(1, ms[k][1]), 4) for k in ("gemm", "down_gemm", "combine")},
             "roofline": {"kernel": "grouped_gemm_bf16 (Lambda W_down^T)", "bound": "mfma", "achieved": round(achieved, 1),
                          "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                          "flops_per_launch": flops_per_launch, "avg_launch_ms": round(down_ms, 4)},
+            "from_compacted_weights": {"ms_per_layer_output": round(compact_ms, 3), "tokens": n, "kernel_ms": compact_kernels,
+                                       "relative_distance_from_the_masked_layer_output": compact_diff},
             "synthetic_layers": stats}
 
 

@@ -623,6 +623,7 @@ int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, 
   camera::CompactRows tab;
   camera::CompactDown tab_down;
   tab.n_experts = tab_down.n_experts = total;
+  tab_down.k_round = down_row_align % 64 == 0 ? 64 : 8;
   int64_t rows = 0, tiles = 0, widest = 0, chunks = 0, ld_rows = 0;
   int most_chunks = 1;
   for (int e = 0; e < total; ++e) {
@@ -655,7 +656,8 @@ int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, 
   const int terms = dense ? n_experts : top_k + n_shared;  // experts that every token goes through
   const int64_t n_pairs = n * (int64_t)terms;
   if (n_pairs >= (int64_t(1) << 31) - 1024) return fail(ctx, CAMERA_ESHAPE, "routed pairs: must be below 2^31");
-  const int64_t ldh = (widest + 7) / 8 * 8;
+  const int k_round = down_row_align % 64 == 0 ? 64 : 8;  // K granularity of the second contraction on the MFMA path
+  const int64_t ldh = (widest + k_round - 1) / k_round * k_round;
   if (n_pairs * std::max<int64_t>(ldh, d_model * most_chunks) >= (int64_t(1) << 38))
     return fail(ctx, CAMERA_EUNSUPPORTED, "batch too large for the compacted layer: use camera_layer_forward");
   if (chunks * ((d_model + 31) / 32) >= (int64_t(1) << 31) - 1024)
@@ -664,8 +666,12 @@ int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, 
 
   // grid rows of 32 tokens per expert; the last row also takes what lies beyond it
   const int token_groups = (int)std::min<int64_t>((n + 31) / 32, 64);
-  const bool small = !dense && n_pairs <= camera::kCompactSmallPairs;
-  const int tile_m = 256;  // of the general counting sort: only its bucket order is used, the M-tile tables are a by-product
+  // From about 64 tokens per expert on, the tiles of the grouped MFMA kernel are worth filling: the weights are
+  // then read once per 256 tokens of an expert instead of once per 32.  Its 16-byte tile loads need W_down rows
+  // that are a multiple of 8 elements long and the two halves of d_model to be multiples of 8.
+  const bool mfma = n_pairs / total > 64 && down_row_align % 8 == 0 && d_model % 16 == 0;
+  const bool small = !dense && !mfma && n_pairs <= camera::kCompactSmallPairs;  // one-workgroup bucket order, no M-tile tables
+  const int tile_m = camera::gemm_tile_m(dtype, widest);  // M tiles of the MFMA path; otherwise only the bucket order is used
   const int64_t max_tiles64 = dense ? n_experts * ((n + tile_m - 1) / tile_m) : n_pairs / tile_m + total;
   if (max_tiles64 > 65535)
     return fail(ctx, CAMERA_EUNSUPPORTED, "batch too large for the compacted layer: use camera_layer_forward");
@@ -679,7 +685,8 @@ int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, 
   const size_t o_idx_aug = cv.take(append ? sizeof(int32_t) * n_pairs : 0);
   const size_t o_w_aug = cv.take(append ? sizeof(float) * n_pairs : 0);
   const size_t o_hidden = cv.take(2 * (size_t)n_pairs * ldh);
-  const size_t o_product = cv.take(sizeof(float) * (size_t)most_chunks * n_pairs * d_model);
+  const size_t o_product = cv.take(sizeof(float) * (size_t)(mfma ? 1 : most_chunks) * n_pairs * d_model);
+  const size_t o_work = cv.take(sizeof(int32_t) * (total + 1 + 16));  // tile prefix of the experts, then the XCD cuts
 
   DeviceGuard guard;
   CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
@@ -711,6 +718,26 @@ int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, 
       }
       CAMERA_HIP(camera::launch_bucket(stream, idx, wts, n, terms, total, tile_m, max_tiles, t), "bucket launch");
     }
+  }
+  if (mfma) {
+    int32_t* work_off = reinterpret_cast<int32_t*>(ws + o_work);
+    {
+      Bracket b(ctx, stream, CAMERA_K_GEMM);
+      CAMERA_HIP(camera::launch_compact_hidden_gemm(stream, X, ldx, d_model, W_gate_c, W_up_c, tab, (int)widest, max_tiles,
+                                                    t, work_off, hidden, ldh, k_round),
+                 "compact hidden gemm launch");
+    }
+    {
+      Bracket b(ctx, stream, CAMERA_K_DOWN_GEMM);
+      CAMERA_HIP(camera::launch_compact_down_gemm(stream, hidden, ldh, d_model, W_down_c, tab_down, max_tiles, t, work_off,
+                                                  product),
+                 "compact down gemm launch");
+    }
+    Bracket b(ctx, stream, CAMERA_K_COMBINE);
+    CAMERA_HIP(camera::launch_combine(stream, product, t.slot_of, n, terms, n_experts, d_model,
+                                      (flags & CAMERA_ACCUMULATE) ? 1 : 0, Y),
+               "combine launch");
+    return CAMERA_OK;
   }
   {
     Bracket b(ctx, stream, CAMERA_K_COMPACT_HIDDEN);

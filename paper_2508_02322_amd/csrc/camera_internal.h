@@ -126,6 +126,8 @@ struct CompactRows {                          // W_gate_c / W_up_c
 };
 struct CompactDown {                          // W_down_c
   int n_experts;
+  int k_round;                                // MFMA path: the K extent of an expert is its count rounded up to this
+                                              // (8, or 64 when the row alignment is a multiple of 64: no K tail)
   int32_t count[CAMERA_MAX_EXPERTS];          // kept micro-experts of each expert
   int32_t ld_off[CAMERA_MAX_EXPERTS + 1];     // prefix of the row lengths (count rounded up to the row alignment):
                                               // expert e's block starts at element d_model * ld_off[e]
@@ -160,6 +162,19 @@ hipError_t launch_compact_down(hipStream_t stream, const void* hidden, int ldh, 
 hipError_t launch_compact_combine(hipStream_t stream, const float* partial, const CompactDown& tab,
                                   const BucketTables& t, int64_t n, int terms, int64_t d_model, int64_t n_slots,
                                   int accumulate, float* Y);
+
+// The two contractions of the compacted layer in the grouped MFMA kernel (gemm.hip), for batches large enough
+// to fill its 256-row tiles.  work_off: [n_experts + 1 + 9] int32 scratch (tile prefix, then the XCD cuts).  d_model must be a multiple of 16 and the
+// rows of the W_down blocks a multiple of 8 elements long (16-byte tile loads).  pad_to (= tab.k_round of the second
+// contraction): hidden columns from an expert's count up to the next multiple of it are written as zeros; ldh must
+// be a multiple of it.
+hipError_t launch_compact_hidden_gemm(hipStream_t stream, const void* X, int64_t ldx, int64_t d_model,
+                                      const void* W_gate, const void* W_up, const CompactRows& tab, int widest,
+                                      int max_tiles, const BucketTables& t, int32_t* work_off, void* hidden,
+                                      int64_t ldh, int pad_to);
+hipError_t launch_compact_down_gemm(hipStream_t stream, const void* hidden, int64_t ldh, int64_t d_model,
+                                    const void* W_down, const CompactDown& tab, int max_tiles, const BucketTables& t,
+                                    int32_t* work_off, float* product);
 
 // Gather of kept micro-experts (gather.hip).  off: [n_experts + 1] exclusive prefix of the per-expert
 // entry counts (count == nullptr: d_ff each), off_ld: the same of the counts rounded up to a multiple of

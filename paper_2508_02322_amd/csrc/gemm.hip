@@ -77,11 +77,13 @@ enum { kEpiStats = 0, kEpiHidden = 1, kEpiProduct = 2 };
 struct EpiArgs {
   float* part_phi2;
   float* part_max;
-  void* hidden;            // [pairs][d_ff], bf16 (MFMA kernel) or float32 (FMA kernel)
+  void* hidden;            // [pairs][ld_hidden], bf16 (MFMA kernel) or float32 (FMA kernel)
   const uint8_t* keep;     // [n_experts * d_ff] or nullptr (all kept)
   float* product;          // [pairs][ld_product]
   int64_t ld_product;
   int col_gap;
+  int64_t ld_hidden;       // row stride of hidden (d_ff when every expert has the same width)
+  int pad_hidden;          // != 0: columns from d_ff up to the next multiple of it are written as zeros (8 or 64)
 };
 
 template <int WM_, int WN_, int TM_, int TN_, int KT_, int STAGES_>
@@ -319,7 +321,23 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int col = n0 + st.wave_n * TN * 32 + j * 32 + st.frag_row;
-      if (col >= d_ff) continue;
+      if (col >= d_ff) {
+        if constexpr (EPI == kEpiHidden) {
+          if (ep.pad_hidden && col < (d_ff + ep.pad_hidden - 1) / ep.pad_hidden * ep.pad_hidden) {  // K padding of the contraction that reads these rows
+#pragma unroll
+            for (int i = 0; i < ACT; ++i) {
+              const int band = (WM * i + st.wave_m) * 32 + st.frag_half * 4;
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                const int row = band + (r / 4) * 8 + (r % 4);
+                if (row < st.m_len)
+                  static_cast<__hip_bfloat16*>(ep.hidden)[(st.row_first + row) * ep.ld_hidden + col] = __float2bfloat16(0.0f);
+              }
+            }
+          }
+        }
+        continue;
+      }
       float kept = 1.0f;
       if constexpr (EPI == kEpiHidden) kept = (ep.keep == nullptr || ep.keep[(int64_t)st.expert * d_ff + col]) ? 1.0f : 0.0f;
 #pragma unroll
@@ -332,7 +350,7 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
           const int64_t out_row = st.row_first + row;
           if constexpr (EPI == kEpiHidden) {
             const float lam = st.s_a[row] * silu_f32(acc_g[i][j][r]) * acc_u[i][j][r] * kept;
-            static_cast<__hip_bfloat16*>(ep.hidden)[out_row * d_ff + col] = __float2bfloat16(lam);
+            static_cast<__hip_bfloat16*>(ep.hidden)[out_row * ep.ld_hidden + col] = __float2bfloat16(lam);
           } else {
             ep.product[out_row * ep.ld_product + col] = acc_g[i][j][r];
             ep.product[out_row * ep.ld_product + col + ep.col_gap] = acc_u[i][j][r];
@@ -391,9 +409,10 @@ struct TileWork {
 template <class C, bool TAIL, int EPI, int AUX>
 __device__ __forceinline__ void run_tile(const TileWork& w, const __hip_bfloat16* __restrict__ X, int64_t ldx,
                                          int d_model, int d_ff, const __hip_bfloat16* __restrict__ Wg,
-                                         const __hip_bfloat16* __restrict__ Wu, int64_t stride_gu,
+                                         const __hip_bfloat16* __restrict__ Wu, int64_t stride_gu, int64_t ldw,
                                          const int32_t* __restrict__ perm, const float* __restrict__ w_perm,
                                          const __hip_bfloat16* __restrict__ zeros, const EpiArgs& ep) {
+  // d_model: the K extent; ldw: elements between consecutive rows of Wg / Wu (d_model unless the rows are padded)
   constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN, WM = C::WM;
   static_assert(C::kStages * C::kStageBytes <= AUX, "the stages must end before the per-tile arrays");
   const int e = w.e, slot = w.slot, row_first = w.row_first, m_len = w.m_len, n0 = w.n0;
@@ -443,7 +462,7 @@ __device__ __forceinline__ void run_tile(const TileWork& w, const __hip_bfloat16
     const int row = b_row0 + j * C::kDmaRows + lane / C::kChunks;
     const int ck = (lane % C::kChunks) ^ swizzle_key<C>(row);
     const int c = min(n0 + row, d_ff - 1);  // channels past d_ff read the last channel again; never written
-    const int64_t off = (int64_t)e * stride_gu + (int64_t)c * d_model + ck * 8;
+    const int64_t off = (int64_t)e * stride_gu + (int64_t)c * ldw + ck * 8;
     st.b_k[j] = ck * 8;
     st.g_src[j] = Wg + off - (j % 4) * 512;
     st.u_src[j] = Wu + off - (j % 4) * 512;
@@ -527,9 +546,143 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
   // A short last tile of an expert is bound by the latency of its loads, not by the matrix pipe: it runs
   // with the narrow tiling, whose smaller stages leave room for a third one (two K tiles in flight).
   if (CT::kThreads == C::kThreads && m_len <= CT::BM)
-    run_tile<CT, TAIL, EPI, kAux>(w, X, ldx, d_model, d_ff, Wg, Wu, stride_gu, perm, w_perm, zeros, ep);
+    run_tile<CT, TAIL, EPI, kAux>(w, X, ldx, d_model, d_ff, Wg, Wu, stride_gu, d_model, perm, w_perm, zeros, ep);
   else
-    run_tile<C, TAIL, EPI, kAux>(w, X, ldx, d_model, d_ff, Wg, Wu, stride_gu, perm, w_perm, zeros, ep);
+    run_tile<C, TAIL, EPI, kAux>(w, X, ldx, d_model, d_ff, Wg, Wu, stride_gu, d_model, perm, w_perm, zeros, ep);
+}
+
+// ---------------------------------------------------------------------------
+// The same tiles on a compacted layer, where every expert has its own width.
+//   CompactRows  (first contraction): expert e has n_ext = its kept micro-experts as N extent, K = d_model;
+//                its gate / up rows start at row row_off[e] of the packed matrices.
+//   CompactDown  (second contraction): N = d_model / 2 for every expert (the two halves of the block's rows
+//                stand in for gate and up), K = its kept count rounded up to 8 (the hidden rows and the block's
+//                rows are zero there), rows ld(e) elements apart.
+// The logical tile ids of expert e start at work_off[e] = sum over the experts before it of (M tiles x N tiles),
+// written by compact_work_kernel once the bucket tables exist.
+// ---------------------------------------------------------------------------
+struct ExpertGeom {
+  int n_ext, k_ext;
+  int64_t ldw, g_off, u_off;  // row stride and first element of the expert's two B matrices
+};
+__device__ __forceinline__ ExpertGeom expert_geom(const CompactRows& t, int e, int d_model) {
+  const int64_t off = (int64_t)t.row_off[e] * d_model;
+  return {t.row_off[e + 1] - t.row_off[e], d_model, d_model, off, off};
+}
+__device__ __forceinline__ ExpertGeom expert_geom(const CompactDown& t, int e, int d_model) {
+  const int64_t ld = t.ld_off[e + 1] - t.ld_off[e];
+  const int64_t base = (int64_t)t.ld_off[e] * d_model;
+  const int k_ext = (t.count[e] + t.k_round - 1) / t.k_round * t.k_round;  // <= ld: the row alignment is a multiple of k_round
+  return {d_model / 2, k_ext, ld, base, base + (int64_t)(d_model / 2) * ld};
+}
+
+// work_off [n_experts + 1], then xcd_first [kXcds + 1]: XCD x runs the logical ids xcd_first[x] .. xcd_first[x + 1].
+// The cuts are placed by cost (tiles times K tiles of their expert), not by tile count: in the second
+// contraction a shared expert's tiles can be many times longer than a routed expert's.
+template <class TABLE>
+__global__ __launch_bounds__(64) void compact_work_kernel(TABLE tab, int d_model, int bn, int kt,
+                                                          const int32_t* __restrict__ tile_offset,
+                                                          int32_t* __restrict__ work_off) {
+  if (threadIdx.x != 0) return;
+  int32_t* xcd_first = work_off + tab.n_experts + 1;
+  int run = 0;
+  int64_t cost = 0;
+  for (int e = 0; e < tab.n_experts; ++e) {
+    work_off[e] = run;
+    const ExpertGeom g = expert_geom(tab, e, d_model);
+    const int tiles = (tile_offset[e + 1] - tile_offset[e]) * ((g.n_ext + bn - 1) / bn);
+    run += tiles;
+    cost += (int64_t)tiles * max(1, (g.k_ext + kt - 1) / kt);
+  }
+  work_off[tab.n_experts] = run;
+  xcd_first[0] = 0;
+  xcd_first[kXcds] = run;
+  int e = 0;
+  int64_t before = 0;  // cost of the experts before e
+  for (int x = 1; x < kXcds; ++x) {
+    const int64_t target = cost * x / kXcds;
+    int64_t mine = 0;
+    for (; e < tab.n_experts; ++e) {
+      const ExpertGeom g = expert_geom(tab, e, d_model);
+      mine = (int64_t)(work_off[e + 1] - work_off[e]) * max(1, (g.k_ext + kt - 1) / kt);
+      if (before + mine > target) break;
+      before += mine;
+    }
+    if (e >= tab.n_experts) {
+      xcd_first[x] = run;
+    } else {
+      const int64_t per_tile = mine / max(1, work_off[e + 1] - work_off[e]);
+      xcd_first[x] = work_off[e] + (int)((target - before) / max<int64_t>(1, per_tile));
+    }
+  }
+}
+
+template <class C, class CT, bool TAIL, int EPI, class TABLE>
+__global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf16_compact_kernel(
+    const __hip_bfloat16* __restrict__ X, int64_t ldx, int d_model, const __hip_bfloat16* __restrict__ Wg,
+    const __hip_bfloat16* __restrict__ Wu, TABLE tab, const int32_t* __restrict__ offsets,
+    const int32_t* __restrict__ tile_offset, const int32_t* __restrict__ work_off,
+    const int32_t* __restrict__ perm, const float* __restrict__ w_perm, const __hip_bfloat16* __restrict__ zeros,
+    EpiArgs ep) {
+  constexpr int BM = C::BM, BN = C::BN;
+  static_assert(CT::BN == C::BN && CT::kSmemBytes <= C::kSmemBytes, "the narrow tiling shares the workgroup's N extent and LDS");
+  const int n_experts = tab.n_experts;
+  const int32_t* xcd_first = work_off + n_experts + 1;
+  const int xcd = blockIdx.x % kXcds;
+  const int stride = gridDim.x / kXcds;  // workgroups per XCD: a workgroup takes every stride-th tile of its XCD's range
+  const int last = xcd_first[xcd + 1];
+  for (int logical = xcd_first[xcd] + (int)(blockIdx.x / kXcds); logical < last; logical += stride) {
+  __syncthreads();  // the previous tile's per-tile arrays in LDS are no longer read
+  int lo = 0, hi = n_experts;                      // work_off[lo] <= logical < work_off[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (work_off[mid] <= logical) lo = mid; else hi = mid;
+  }
+  const int e = lo;
+  const ExpertGeom g = expert_geom(tab, e, d_model);
+  const int n_tiles_n = (g.n_ext + BN - 1) / BN;  // >= 1: an expert without N tiles owns no logical id
+  const int m_e = tile_offset[e + 1] - tile_offset[e];
+  const int local = logical - work_off[e];
+  // the tile order of grouped_gemm_bf16_kernel inside the expert
+  const int chunk_m = m_e <= kChunkMax ? m_e : kChunkM;
+  const int group_n = max(1, kPatch / chunk_m);
+  const int group = local / (m_e * group_n);
+  const int group_w = min(group_n, n_tiles_n - group * group_n);
+  const int in_group = local - group * m_e * group_n;
+  const int chunk = in_group / (chunk_m * group_w);
+  const int chunk_h = min(chunk_m, m_e - chunk * chunk_m);
+  const int in_chunk = in_group - chunk * chunk_m * group_w;
+  const int tile_n = group * group_n + in_chunk / chunk_h;
+  const int slot = tile_offset[e] + chunk * chunk_m + in_chunk % chunk_h;
+  const int tile_in_expert = slot - tile_offset[e];
+  const int row_first = offsets[e] + tile_in_expert * BM;
+  const int m_len = min(BM, offsets[e + 1] - row_first);  // >= 1
+  const int n0 = tile_n * BN;
+
+  if constexpr (EPI == kEpiProduct) {
+    if (g.k_ext == 0) {  // the expert keeps nothing: its product rows are zero
+      const int width = min(BN, g.n_ext - n0);
+      for (int i = threadIdx.x; i < m_len * width; i += C::kThreads) {
+        float* row = ep.product + (int64_t)(row_first + i / width) * ep.ld_product + n0 + i % width;
+        row[0] = 0.0f;
+        row[ep.col_gap] = 0.0f;
+      }
+      continue;
+    }
+  }
+  TileWork w;
+  w.e = 0;  // the expert's matrices are addressed through g_off / u_off, not through an expert stride
+  w.slot = slot;
+  w.row_first = row_first;
+  w.m_len = m_len;
+  w.n0 = n0;
+  w.tok_first = tile_in_expert * BM;
+  constexpr int kAux = C::kStages * C::kStageBytes;
+  if (CT::kThreads == C::kThreads && m_len <= CT::BM)
+    run_tile<CT, TAIL, EPI, kAux>(w, X, ldx, g.k_ext, g.n_ext, Wg + g.g_off, Wu + g.u_off, 0, g.ldw, perm, w_perm, zeros, ep);
+  else
+    run_tile<C, TAIL, EPI, kAux>(w, X, ldx, g.k_ext, g.n_ext, Wg + g.g_off, Wu + g.u_off, 0, g.ldw, perm, w_perm, zeros, ep);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -626,7 +779,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
         if (row >= m_len) continue;
         const int64_t out_row = row_first + row;
         if constexpr (EPI == kEpiHidden) {
-          static_cast<float*>(ep.hidden)[out_row * d_ff + col] = s_a[row] * silu_f32(acc_g[i][j]) * acc_u[i][j] * kept;
+          static_cast<float*>(ep.hidden)[out_row * ep.ld_hidden + col] = s_a[row] * silu_f32(acc_g[i][j]) * acc_u[i][j] * kept;
         } else {
           ep.product[out_row * ep.ld_product + col] = acc_g[i][j];
           ep.product[out_row * ep.ld_product + col + ep.col_gap] = acc_u[i][j];
@@ -707,7 +860,7 @@ hipError_t launch_grouped_gemm(hipStream_t stream, int dtype, const void* X, int
                                int64_t d_ff, int n_experts, const void* W_gate, const void* W_up,
                                int64_t stride_gu, int max_tiles, const BucketTables& t, const GemmEpilogue& e) {
   if (max_tiles <= 0) return hipSuccess;
-  EpiArgs ep{e.part_phi2, e.part_max, e.hidden, e.keep, e.product, e.ld_product, e.col_gap};
+  EpiArgs ep{e.part_phi2, e.part_max, e.hidden, e.keep, e.product, e.ld_product, e.col_gap, d_ff, 0};
   if (dtype == CAMERA_BF16) {
     switch (e.mode) {
       case GemmEpilogue::kStats:
@@ -729,6 +882,53 @@ hipError_t launch_grouped_gemm(hipStream_t stream, int dtype, const void* X, int
                      static_cast<const float*>(W_gate), static_cast<const float*>(W_up), stride_gu, t.offsets,
                      t.tile_offset, t.tile_expert, t.perm, t.w_perm, n_experts, ep);
   return hipGetLastError();
+}
+
+template <int EPI, class TABLE>
+static hipError_t launch_compact(hipStream_t stream, const void* X, int64_t ldx, int64_t d_model, const void* Wg,
+                                 const void* Wu, const TABLE& tab, bool tail, int64_t n_tiles_n_max, int max_tiles,
+                                 const BucketTables& t, int32_t* work_off, const EpiArgs& ep) {
+  // tail: some K extent is not a multiple of the K tile
+  using C = Bf16Cfg;
+  auto kern = tail ? grouped_gemm_bf16_compact_kernel<C, Bf16TailCfg, true, EPI, TABLE>
+                   : grouped_gemm_bf16_compact_kernel<C, Bf16TailCfg, false, EPI, TABLE>;
+  static bool attr_set[2] = {false, false};
+  if (!attr_set[tail]) {
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, C::kSmemBytes);
+    if (err != hipSuccess) return err;
+    attr_set[tail] = true;
+  }
+  hipLaunchKernelGGL((compact_work_kernel<TABLE>), dim3(1), dim3(64), 0, stream, tab, (int)d_model, C::BN, C::KT,
+                     t.tile_offset, work_off);
+  // an upper bound of the tile count, shared evenly between the XCDs: a workgroup walks on through its XCD's
+  // range where the cuts by cost give that XCD more (cheaper) tiles than that
+  const int64_t n_blocks = (max_tiles * n_tiles_n_max + kXcds - 1) / kXcds * kXcds;
+  if (n_blocks >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+  if (n_blocks == 0) return hipGetLastError();
+  hipLaunchKernelGGL(kern, dim3((unsigned)n_blocks), dim3(C::kThreads), C::kSmemBytes, stream,
+                     static_cast<const __hip_bfloat16*>(X), ldx, (int)d_model, static_cast<const __hip_bfloat16*>(Wg),
+                     static_cast<const __hip_bfloat16*>(Wu), tab, t.offsets, t.tile_offset, work_off, t.perm, t.w_perm,
+                     static_cast<const __hip_bfloat16*>(t.zeros), ep);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact_hidden_gemm(hipStream_t stream, const void* X, int64_t ldx, int64_t d_model,
+                                      const void* W_gate, const void* W_up, const CompactRows& tab, int widest,
+                                      int max_tiles, const BucketTables& t, int32_t* work_off, void* hidden,
+                                      int64_t ldh, int pad_to) {
+  EpiArgs ep{nullptr, nullptr, hidden, nullptr, nullptr, 0, 0, ldh, pad_to};
+  return launch_compact<kEpiHidden>(stream, X, ldx, d_model, W_gate, W_up, tab, d_model % Bf16Cfg::KT != 0,
+                                    (widest + Bf16Cfg::BN - 1) / Bf16Cfg::BN, max_tiles, t, work_off, ep);
+}
+
+hipError_t launch_compact_down_gemm(hipStream_t stream, const void* hidden, int64_t ldh, int64_t d_model,
+                                    const void* W_down, const CompactDown& tab, int max_tiles, const BucketTables& t,
+                                    int32_t* work_off, float* product) {
+  const int64_t half = d_model / 2;
+  EpiArgs ep{nullptr, nullptr, nullptr, nullptr, product, d_model, (int)half, 0, 0};
+  return launch_compact<kEpiProduct>(stream, hidden, ldh, d_model, W_down, W_down, tab, tab.k_round % Bf16Cfg::KT != 0,
+                                     (half + Bf16Cfg::BN - 1) / Bf16Cfg::BN, max_tiles, t, work_off, ep);
 }
 
 }  // namespace camera

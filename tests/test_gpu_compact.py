@@ -35,6 +35,8 @@ CASES = [
     dict(n_tokens=200, d_model=256, d_ff=136, n_experts=4, top_k=3),        # > 64 tokens per expert: several passes, wide tiles
     dict(n_tokens=100, d_model=128, d_ff=96, n_experts=8, top_k=1),         # routed, narrow tiles, some experts above 32 tokens
     dict(n_tokens=1, d_model=32, d_ff=16, n_experts=1, top_k=1),
+    dict(n_tokens=1500, d_model=256, d_ff=200, n_experts=8, top_k=2),       # several 256-row tiles per expert (MFMA path when aligned)
+    dict(n_tokens=900, d_model=80, d_ff=296, n_experts=3, top_k=2),         # K tails in both contractions, three N tiles
 ]
 
 
@@ -56,10 +58,16 @@ def test_compacted_layer_output_matches_oracle(cam, case):
             keep[cfg.d_ff:cfg.d_ff + 3] = 1                                 # and one with at least three
         count, gate_c, up_c, down_c = compact(cam, dev, "W", keep, cfg.n_experts, cfg.d_ff)
         Y = cam.layer_forward_compact(dev["X"], idx, w, count, gate_c, up_c, down_c)
-        for align in (8, 64):   # zero-padded W_down rows: the same sums, bit for bit
+        mfma = cfg.n_tokens * cfg.top_k // cfg.n_experts > 64 and cfg.d_model % 16 == 0
+        for align in (8, 64):   # zero-padded W_down rows
             count_a, gate_a, up_a, down_a = compact(cam, dev, "W", keep, cfg.n_experts, cfg.d_ff, align=align)
             Y_a = cam.layer_forward_compact(dev["X"], idx, w, count_a, gate_a, up_a, down_a, down_row_align=align)
-            assert torch.equal(Y, Y_a), align
+            torch.cuda.synchronize()
+            if mfma:            # large batch and aligned rows: the grouped MFMA kernel takes over
+                O_a = orc.layer_forward(X64, A, gate, up, down, keep=keep, round_hidden=orc.round_to_bf16)
+                check_output(Y_a, O_a, largest_term(X64, A, gate, up, down, keep))
+            else:               # the streaming kernels: the same sums, bit for bit
+                assert torch.equal(Y, Y_a), align
         Y_masked = cam.layer_forward(dev["X"], idx, w, dev["W_gate"], dev["W_up"], dev["W_down"],
                                      keep_mask=torch.from_numpy(keep).cuda())
         torch.cuda.synchronize()
@@ -120,7 +128,9 @@ def test_shared_experts_in_the_same_call_and_accumulated(cam, n_tokens, n_shared
     # the same terms in another order of summation: equal up to float32 rounding
     scale = Y.abs().max().item()
     assert (Y - (Y_routed + Y_shared)).abs().max().item() <= 4e-7 * scale
-    assert (Y - Y_one).abs().max().item() <= 1e-6 * scale
+    one_call_on_mfma = align % 8 == 0 and n_tokens * (cfg.top_k + cfg.n_shared) // (cfg.n_experts + cfg.n_shared) > 64
+    if not one_call_on_mfma:   # otherwise another kernel, whose hidden values may round to the other bf16 neighbour
+        assert (Y - Y_one).abs().max().item() <= 1e-6 * scale
     X64 = H.f64(layer["X"])
     gate, up, down = expert_lists(layer, "Ws")
     ones = np.ones((cfg.n_tokens, cfg.n_shared))
