@@ -282,9 +282,10 @@ int camera_layer_forward(camera_ctx* ctx, void* stream,
  *
  *   X, n, d_model, ldx, topk_idx, topk_w, top_k, n_experts, flags, Y: as in camera_layer_forward
  *               (topk_idx = topk_w = NULL: every token goes through every expert with weight 1).
- *               Any n is accepted; an expert's weights are streamed once per 32 of its tokens (once
- *               per 64 when the batch brings more than 32 tokens per expert on average), so large
- *               batches belong to camera_layer_forward.
+ *               Any n is accepted: small batches stream an expert's weights once per 32 of its
+ *               tokens; from 64 tokens per expert on average the call runs on the tiled MFMA kernel
+ *               of camera_layer_forward with per-expert widths, provided down_row_align is a
+ *               multiple of 8 and d_model a multiple of 16 (else it stays on the streaming kernels).
  *   n_shared    experts n_experts .. n_experts + n_shared - 1 are shared experts: every token goes
  *               through them with weight 1, in the same launches as the routed ones (a decoding
  *               batch is too small to fill the chip with the shared experts alone).  0 without routing.
