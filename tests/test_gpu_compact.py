@@ -242,3 +242,19 @@ def test_built_limits_of_the_compacted_layer(cam):
         cam.layer_forward_compact(dev["X"], idx, w, [0] * 257, empty, empty, empty.reshape(-1), n_shared=7)
     with pytest.raises(binding.CameraError, match="down_row_align"):
         cam.layer_forward_compact(dev["X"], idx, w, [0] * 250, empty, empty, empty.reshape(-1), down_row_align=513)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_seeded_shapes_inside_the_limits(cam, seed):
+    """Shapes drawn from a seed (token count, widths, experts, top-k, shared experts, row alignment, kept fraction):
+    the streaming kernels, the one-workgroup and the general bucket order and the tiled path all get their share."""
+    rng = np.random.default_rng(1000 + seed)
+    n_experts = int(rng.integers(1, 13))
+    cfg = small(n_tokens=int(rng.choice([1, 3, 17, 64, 65, 130, 400, 1100])), d_model=int(rng.choice([32, 40, 64, 72, 128, 144])),
+                d_ff=8 * int(rng.integers(1, 40)), n_experts=n_experts, top_k=int(rng.integers(1, min(n_experts, 6) + 1)),
+                n_shared=int(rng.integers(0, 3)), d_ff_shared=8 * int(rng.integers(1, 60)),
+                router_bias=str(rng.choice(["none", "normal", "zipf"])))
+    align = int(rng.choice([1, 2, 8, 24, 64, 128]))
+    err, counts = run_and_check(cam, cfg, float(rng.uniform(0.05, 1.0)), align, seed=seed)
+    print(f"seed {seed}: {cfg.n_tokens} tokens, d_model {cfg.d_model}, d_ff {cfg.d_ff}, {cfg.n_experts} experts top-{cfg.top_k}, "
+          f"{cfg.n_shared} shared of {cfg.d_ff_shared}, align {align}: rel err {err:.2e}")
