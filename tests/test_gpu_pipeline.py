@@ -56,3 +56,26 @@ def test_score_select_pack_and_run(cam, name, n_tokens, ratio, spread):
     err = check_output(Y, O, term)
     print(f"{name}: {n_tokens} tokens, ratio {ratio}, spread {spread}: kept per expert {min(compact.counts)}..{max(compact.counts)}, "
           f"output rel err {err:.2e}")
+
+
+def test_layer_reordered_by_precision_class_gives_the_same_output(cam):
+    """CAMERA-Q's reordering (micro-experts of equal bit width side by side inside every expert) moves the three
+    vectors of a micro-expert together, so the layer's output does not change: the reordered layer, run through the
+    compacted-layer call with every count equal to d_ff, against the oracle's output of the original layer."""
+    cfg = inputs.scaled(inputs.CONFIGS["qwen3-30b-a3b"], n_tokens=90, d_model=128, d_ff=96, n_experts=8, top_k=2, n_layers=1)
+    layer = inputs.make_layer(cfg, 0, device="cpu")
+    dev = H.to_dev(layer)
+    scores = pipeline.score_layer(cam, dev, cfg.top_k, cfg.alpha)
+    bit_of, level_count, perm = cam.alloc_bits(scores.energy, scores.seg_offsets, [3, 2, 1], [0.2, 0.6, 0.2], want_perm=True)
+    gate_r, up_r, down_r = cam.gather_micro_experts(dev["W_gate"], dev["W_up"], dev["W_down"], perm)
+    Y = cam.layer_forward_compact(dev["X"], scores.topk_idx, scores.topk_w, [cfg.d_ff] * cfg.n_experts, gate_r, up_r, down_r)
+    torch.cuda.synchronize()
+    # inside every expert the classes now sit one after the other, in the order of the bit list
+    b = bit_of.cpu().numpy()[perm.cpu().numpy()].reshape(cfg.n_experts, cfg.d_ff)
+    assert np.all(np.diff(b.astype(np.int64), axis=1) <= 0)
+    assert np.array_equal(np.stack([(b == w).sum(axis=1) for w in (3, 2, 1)], axis=1), level_count.cpu().numpy())
+    X64 = H.f64(layer["X"])
+    A = dense_A(scores.topk_idx.cpu().numpy().astype(np.int64), scores.topk_w.cpu().numpy().astype(np.float64), cfg.n_experts)
+    gate, up, down = expert_lists(layer, "W")
+    O = orc.layer_forward(X64, A, gate, up, down, round_hidden=orc.round_to_bf16)
+    check_output(Y, O, largest_term(X64, A, gate, up, down))
