@@ -225,3 +225,33 @@ def test_select_prune_multi_argument_checks(lib, ctx):
     assert multi(ratios=(0.2, 1.5)) == -1
     assert multi(per=None) == -1 and multi(bits=None) == -1
     assert multi(n_seg=0) == -6
+
+
+def test_layer_forward_compact_argument_checks(lib, ctx):
+    fake = vp(4096)           # never dereferenced: every check below fails on the host
+
+    def forward(x=fake, dtype=1, n=16, d_model=64, ldx=64, idx=fake, w=fake, top_k=2, n_experts=4, n_shared=0,
+                count=(8, 9, 0, 31), align=1, wg=fake, wu=fake, wd=fake, flags=0, y=fake, c=ctx):
+        counts = None if count is None else (ctypes.c_int32 * len(count))(*count)
+        return lib.camera_layer_forward_compact(c, None, x, dtype, n, d_model, ldx, idx, w, top_k, n_experts, n_shared,
+                                                counts, align, wg, wu, wd, flags, y)
+    lib.camera_layer_forward_compact.restype = ctypes.c_int
+    assert forward(c=None) == -1
+    assert forward(dtype=0) == -6 and "BF16" in err(lib, ctx)
+    assert forward(dtype=5) == -3
+    assert forward(d_model=60) == -2
+    assert forward(idx=None) == -1 and "both or neither" in err(lib, ctx)
+    assert forward(idx=None, w=None, n_shared=1, count=(8, 9, 0, 31, 4)) == -1 and "n_shared" in err(lib, ctx)
+    assert forward(n_shared=-1) == -1
+    assert forward(n_experts=0, count=()) == -6
+    assert forward(n_experts=250, n_shared=7, count=(1,) * 257) == -6 and "256" in err(lib, ctx)
+    assert forward(top_k=0) == -1 and forward(top_k=5) == -1
+    assert forward(flags=2) == -1 and "flags" in err(lib, ctx)
+    assert forward(count=None) == -1 and "count" in err(lib, ctx)
+    assert forward(count=(8, -1, 0, 31)) == -1 and "count[1]" in err(lib, ctx)
+    assert forward(align=0) == -1 and forward(align=513) == -1 and "down_row_align" in err(lib, ctx)
+    assert forward(wg=None) == -1 and "W_gate_c" in err(lib, ctx)
+    assert forward(y=None) == -1 and "Y" in err(lib, ctx)
+    assert forward(wd=vp(4100)) == -2 and "16-byte" in err(lib, ctx)
+    assert forward(n=0) == 0                                  # nothing to do: no GPU is touched
+    assert forward(count=(0, 0, 0, 0), wg=None, wu=None, wd=None, n=0) == 0
