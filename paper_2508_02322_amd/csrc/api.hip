@@ -686,7 +686,7 @@ int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, 
   const size_t o_w_aug = cv.take(append ? sizeof(float) * n_pairs : 0);
   const size_t o_hidden = cv.take(2 * (size_t)n_pairs * ldh);
   const size_t o_product = cv.take(sizeof(float) * (size_t)(mfma ? 1 : most_chunks) * n_pairs * d_model);
-  const size_t o_work = cv.take(sizeof(int32_t) * (total + 1 + 16));  // tile prefix of the experts, then the XCD cuts
+  const size_t o_work = cv.take(sizeof(int32_t) * camera::kCompactGemmScratchWords);
 
   DeviceGuard guard;
   CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
@@ -724,12 +724,12 @@ int camera_layer_forward_compact(camera_ctx* ctx, void* stream_, const void* X, 
     {
       Bracket b(ctx, stream, CAMERA_K_GEMM);
       CAMERA_HIP(camera::launch_compact_hidden_gemm(stream, X, ldx, d_model, W_gate_c, W_up_c, tab, (int)widest, max_tiles,
-                                                    t, work_off, hidden, ldh, k_round),
+                                                    t, work_off, hidden, k_round),
                  "compact hidden gemm launch");
     }
     {
       Bracket b(ctx, stream, CAMERA_K_DOWN_GEMM);
-      CAMERA_HIP(camera::launch_compact_down_gemm(stream, hidden, ldh, d_model, W_down_c, tab_down, max_tiles, t, work_off,
+      CAMERA_HIP(camera::launch_compact_down_gemm(stream, hidden, d_model, W_down_c, tab_down, max_tiles, t, work_off,
                                                   product),
                  "compact down gemm launch");
     }

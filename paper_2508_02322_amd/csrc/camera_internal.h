@@ -164,17 +164,19 @@ hipError_t launch_compact_combine(hipStream_t stream, const float* partial, cons
                                   int accumulate, float* Y);
 
 // The two contractions of the compacted layer in the grouped MFMA kernel (gemm.hip), for batches large enough
-// to fill its 256-row tiles.  work_off: [n_experts + 1 + 9] int32 scratch (tile prefix, then the XCD cuts).  d_model must be a multiple of 16 and the
-// rows of the W_down blocks a multiple of 8 elements long (16-byte tile loads).  pad_to (= tab.k_round of the second
-// contraction): hidden columns from an expert's count up to the next multiple of it are written as zeros; ldh must
-// be a multiple of it.
+// to fill its 256-row tiles.  d_model must be a multiple of 16 and the rows of the W_down blocks a multiple of 8
+// elements long (16-byte tile loads).  k_round (8, or 64 when every row length is a multiple of 64): the K extent of
+// an expert in the second contraction is its kept count rounded up to it.  The hidden buffer holds expert e's rows
+// back to back, that many elements each: at most pairs * round_up(widest count, k_round) elements.
+// scratch: kCompactGemmScratchWords int32 words, 8-byte aligned, shared by the two launches of a call.
+constexpr int kCompactGemmScratchWords = (CAMERA_MAX_EXPERTS + 1 + 16) + 2 * CAMERA_MAX_EXPERTS;
 hipError_t launch_compact_hidden_gemm(hipStream_t stream, const void* X, int64_t ldx, int64_t d_model,
                                       const void* W_gate, const void* W_up, const CompactRows& tab, int widest,
-                                      int max_tiles, const BucketTables& t, int32_t* work_off, void* hidden,
-                                      int64_t ldh, int pad_to);
-hipError_t launch_compact_down_gemm(hipStream_t stream, const void* hidden, int64_t ldh, int64_t d_model,
-                                    const void* W_down, const CompactDown& tab, int max_tiles, const BucketTables& t,
-                                    int32_t* work_off, float* product);
+                                      int max_tiles, const BucketTables& t, int32_t* scratch, void* hidden,
+                                      int k_round);
+hipError_t launch_compact_down_gemm(hipStream_t stream, const void* hidden, int64_t d_model, const void* W_down,
+                                    const CompactDown& tab, int max_tiles, const BucketTables& t, int32_t* scratch,
+                                    float* product);
 
 // Gather of kept micro-experts (gather.hip).  off: [n_experts + 1] exclusive prefix of the per-expert
 // entry counts (count == nullptr: d_ff each), off_ld: the same of the counts rounded up to a multiple of

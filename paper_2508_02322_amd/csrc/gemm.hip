@@ -576,27 +576,56 @@ __device__ __forceinline__ ExpertGeom expert_geom(const CompactDown& t, int e, i
   return {d_model / 2, k_ext, ld, base, base + (int64_t)(d_model / 2) * ld};
 }
 
-// work_off [n_experts + 1], then xcd_first [kXcds + 1]: XCD x runs the logical ids xcd_first[x] .. xcd_first[x + 1].
-// The cuts are placed by cost (tiles times K tiles of their expert), not by tile count: in the second
-// contraction a shared expert's tiles can be many times longer than a routed expert's.
+// Scratch of a compacted-layer launch, written by compact_work_kernel:
+//   work_off  [n_experts + 1]  first logical tile id of every expert
+//   xcd_first [kXcds + 1]      XCD x runs the logical ids xcd_first[x] .. xcd_first[x + 1].  The cuts are placed by
+//                              cost (tiles times K tiles of their expert), not by tile count: in the second
+//                              contraction a shared expert's tiles can be many times longer than a routed expert's.
+//   hid_off   [n_experts]      (int64) first element of expert e's rows in the hidden buffer, which holds the rows of
+//                              expert e back to back, hidden_ld(e) elements each: rows as long as the widest expert's
+//                              would spread a routed expert's 3 KB rows over 24 KB strides
+struct CompactScratch {
+  int32_t* work_off;
+  int32_t* xcd_first;
+  int64_t* hid_off;
+};
+__host__ __device__ inline CompactScratch compact_scratch(int32_t* base, int n_experts) {
+  CompactScratch s;
+  s.work_off = base;
+  s.xcd_first = base + n_experts + 1;
+  // 8-byte aligned: the int32 part is padded to an even count
+  s.hid_off = reinterpret_cast<int64_t*>(base + ((n_experts + 1 + kXcds + 1 + 1) & ~1));
+  return s;
+}
+// Length of expert e's hidden rows: its kept count rounded up to k_round (the K extent of the second contraction).
+__device__ __forceinline__ int hidden_ld(const CompactRows& t, int e, int k_round) {
+  return (t.row_off[e + 1] - t.row_off[e] + k_round - 1) / k_round * k_round;
+}
+__device__ __forceinline__ int hidden_ld(const CompactDown& t, int e, int k_round) {
+  return (t.count[e] + k_round - 1) / k_round * k_round;
+}
+
 template <class TABLE>
-__global__ __launch_bounds__(64) void compact_work_kernel(TABLE tab, int d_model, int bn, int kt,
+__global__ __launch_bounds__(64) void compact_work_kernel(TABLE tab, int d_model, int bn, int kt, int k_round,
+                                                          const int32_t* __restrict__ offsets,
                                                           const int32_t* __restrict__ tile_offset,
-                                                          int32_t* __restrict__ work_off) {
+                                                          int32_t* __restrict__ scratch) {
   if (threadIdx.x != 0) return;
-  int32_t* xcd_first = work_off + tab.n_experts + 1;
+  const CompactScratch sc = compact_scratch(scratch, tab.n_experts);
   int run = 0;
-  int64_t cost = 0;
+  int64_t cost = 0, hid = 0;
   for (int e = 0; e < tab.n_experts; ++e) {
-    work_off[e] = run;
+    sc.work_off[e] = run;
+    sc.hid_off[e] = hid;
+    hid += (int64_t)(offsets[e + 1] - offsets[e]) * hidden_ld(tab, e, k_round);
     const ExpertGeom g = expert_geom(tab, e, d_model);
     const int tiles = (tile_offset[e + 1] - tile_offset[e]) * ((g.n_ext + bn - 1) / bn);
     run += tiles;
     cost += (int64_t)tiles * max(1, (g.k_ext + kt - 1) / kt);
   }
-  work_off[tab.n_experts] = run;
-  xcd_first[0] = 0;
-  xcd_first[kXcds] = run;
+  sc.work_off[tab.n_experts] = run;
+  sc.xcd_first[0] = 0;
+  sc.xcd_first[kXcds] = run;
   int e = 0;
   int64_t before = 0;  // cost of the experts before e
   for (int x = 1; x < kXcds; ++x) {
@@ -604,15 +633,15 @@ __global__ __launch_bounds__(64) void compact_work_kernel(TABLE tab, int d_model
     int64_t mine = 0;
     for (; e < tab.n_experts; ++e) {
       const ExpertGeom g = expert_geom(tab, e, d_model);
-      mine = (int64_t)(work_off[e + 1] - work_off[e]) * max(1, (g.k_ext + kt - 1) / kt);
+      mine = (int64_t)(sc.work_off[e + 1] - sc.work_off[e]) * max(1, (g.k_ext + kt - 1) / kt);
       if (before + mine > target) break;
       before += mine;
     }
     if (e >= tab.n_experts) {
-      xcd_first[x] = run;
+      sc.xcd_first[x] = run;
     } else {
-      const int64_t per_tile = mine / max(1, work_off[e + 1] - work_off[e]);
-      xcd_first[x] = work_off[e] + (int)((target - before) / max<int64_t>(1, per_tile));
+      const int64_t per_tile = mine / max(1, sc.work_off[e + 1] - sc.work_off[e]);
+      sc.xcd_first[x] = sc.work_off[e] + (int)((target - before) / max<int64_t>(1, per_tile));
     }
   }
 }
@@ -620,14 +649,17 @@ __global__ __launch_bounds__(64) void compact_work_kernel(TABLE tab, int d_model
 template <class C, class CT, bool TAIL, int EPI, class TABLE>
 __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf16_compact_kernel(
     const __hip_bfloat16* __restrict__ X, int64_t ldx, int d_model, const __hip_bfloat16* __restrict__ Wg,
-    const __hip_bfloat16* __restrict__ Wu, TABLE tab, const int32_t* __restrict__ offsets,
-    const int32_t* __restrict__ tile_offset, const int32_t* __restrict__ work_off,
+    const __hip_bfloat16* __restrict__ Wu, TABLE tab, int k_round, const int32_t* __restrict__ offsets,
+    const int32_t* __restrict__ tile_offset, int32_t* __restrict__ scratch,
     const int32_t* __restrict__ perm, const float* __restrict__ w_perm, const __hip_bfloat16* __restrict__ zeros,
-    EpiArgs ep) {
+    EpiArgs ep_launch) {
+  // X: the tokens (first contraction) or the hidden buffer (second contraction, ldx unused: its rows are ragged)
   constexpr int BM = C::BM, BN = C::BN;
   static_assert(CT::BN == C::BN && CT::kSmemBytes <= C::kSmemBytes, "the narrow tiling shares the workgroup's N extent and LDS");
   const int n_experts = tab.n_experts;
-  const int32_t* xcd_first = work_off + n_experts + 1;
+  const CompactScratch sc = compact_scratch(scratch, n_experts);
+  const int32_t* work_off = sc.work_off;
+  const int32_t* xcd_first = sc.xcd_first;
   const int xcd = blockIdx.x % kXcds;
   const int stride = gridDim.x / kXcds;  // workgroups per XCD: a workgroup takes every stride-th tile of its XCD's range
   const int last = xcd_first[xcd + 1];
@@ -640,6 +672,19 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
   }
   const int e = lo;
   const ExpertGeom g = expert_geom(tab, e, d_model);
+  // the expert's rows of the hidden buffer: row of bucket slot s at hid_e + s * hid_ld
+  const int64_t hid_ld = hidden_ld(tab, e, k_round);
+  const int64_t hid_e = sc.hid_off[e] - (int64_t)offsets[e] * hid_ld;
+  EpiArgs ep = ep_launch;
+  const __hip_bfloat16* A = X;
+  int64_t lda = ldx;
+  if constexpr (EPI == kEpiHidden) {
+    ep.hidden = static_cast<__hip_bfloat16*>(ep_launch.hidden) + hid_e;
+    ep.ld_hidden = hid_ld;
+  } else {
+    A = X + hid_e;
+    lda = hid_ld;
+  }
   const int n_tiles_n = (g.n_ext + BN - 1) / BN;  // >= 1: an expert without N tiles owns no logical id
   const int m_e = tile_offset[e + 1] - tile_offset[e];
   const int local = logical - work_off[e];
@@ -679,9 +724,9 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
   w.tok_first = tile_in_expert * BM;
   constexpr int kAux = C::kStages * C::kStageBytes;
   if (CT::kThreads == C::kThreads && m_len <= CT::BM)
-    run_tile<CT, TAIL, EPI, kAux>(w, X, ldx, g.k_ext, g.n_ext, Wg + g.g_off, Wu + g.u_off, 0, g.ldw, perm, w_perm, zeros, ep);
+    run_tile<CT, TAIL, EPI, kAux>(w, A, lda, g.k_ext, g.n_ext, Wg + g.g_off, Wu + g.u_off, 0, g.ldw, perm, w_perm, zeros, ep);
   else
-    run_tile<C, TAIL, EPI, kAux>(w, X, ldx, g.k_ext, g.n_ext, Wg + g.g_off, Wu + g.u_off, 0, g.ldw, perm, w_perm, zeros, ep);
+    run_tile<C, TAIL, EPI, kAux>(w, A, lda, g.k_ext, g.n_ext, Wg + g.g_off, Wu + g.u_off, 0, g.ldw, perm, w_perm, zeros, ep);
   }
 }
 
@@ -886,8 +931,8 @@ hipError_t launch_grouped_gemm(hipStream_t stream, int dtype, const void* X, int
 
 template <int EPI, class TABLE>
 static hipError_t launch_compact(hipStream_t stream, const void* X, int64_t ldx, int64_t d_model, const void* Wg,
-                                 const void* Wu, const TABLE& tab, bool tail, int64_t n_tiles_n_max, int max_tiles,
-                                 const BucketTables& t, int32_t* work_off, const EpiArgs& ep) {
+                                 const void* Wu, const TABLE& tab, int k_round, bool tail, int64_t n_tiles_n_max,
+                                 int max_tiles, const BucketTables& t, int32_t* scratch, const EpiArgs& ep) {
   // tail: some K extent is not a multiple of the K tile
   using C = Bf16Cfg;
   auto kern = tail ? grouped_gemm_bf16_compact_kernel<C, Bf16TailCfg, true, EPI, TABLE>
@@ -899,8 +944,8 @@ static hipError_t launch_compact(hipStream_t stream, const void* X, int64_t ldx,
     if (err != hipSuccess) return err;
     attr_set[tail] = true;
   }
-  hipLaunchKernelGGL((compact_work_kernel<TABLE>), dim3(1), dim3(64), 0, stream, tab, (int)d_model, C::BN, C::KT,
-                     t.tile_offset, work_off);
+  hipLaunchKernelGGL((compact_work_kernel<TABLE>), dim3(1), dim3(64), 0, stream, tab, (int)d_model, C::BN, C::KT, k_round,
+                     t.offsets, t.tile_offset, scratch);
   // an upper bound of the tile count, shared evenly between the XCDs: a workgroup walks on through its XCD's
   // range where the cuts by cost give that XCD more (cheaper) tiles than that
   const int64_t n_blocks = (max_tiles * n_tiles_n_max + kXcds - 1) / kXcds * kXcds;
@@ -908,27 +953,28 @@ static hipError_t launch_compact(hipStream_t stream, const void* X, int64_t ldx,
   if (n_blocks == 0) return hipGetLastError();
   hipLaunchKernelGGL(kern, dim3((unsigned)n_blocks), dim3(C::kThreads), C::kSmemBytes, stream,
                      static_cast<const __hip_bfloat16*>(X), ldx, (int)d_model, static_cast<const __hip_bfloat16*>(Wg),
-                     static_cast<const __hip_bfloat16*>(Wu), tab, t.offsets, t.tile_offset, work_off, t.perm, t.w_perm,
-                     static_cast<const __hip_bfloat16*>(t.zeros), ep);
+                     static_cast<const __hip_bfloat16*>(Wu), tab, k_round, t.offsets, t.tile_offset, scratch, t.perm,
+                     t.w_perm, static_cast<const __hip_bfloat16*>(t.zeros), ep);
   return hipGetLastError();
 }
 
 hipError_t launch_compact_hidden_gemm(hipStream_t stream, const void* X, int64_t ldx, int64_t d_model,
                                       const void* W_gate, const void* W_up, const CompactRows& tab, int widest,
-                                      int max_tiles, const BucketTables& t, int32_t* work_off, void* hidden,
-                                      int64_t ldh, int pad_to) {
-  EpiArgs ep{nullptr, nullptr, hidden, nullptr, nullptr, 0, 0, ldh, pad_to};
-  return launch_compact<kEpiHidden>(stream, X, ldx, d_model, W_gate, W_up, tab, d_model % Bf16Cfg::KT != 0,
-                                    (widest + Bf16Cfg::BN - 1) / Bf16Cfg::BN, max_tiles, t, work_off, ep);
+                                      int max_tiles, const BucketTables& t, int32_t* scratch, void* hidden,
+                                      int k_round) {
+  EpiArgs ep{nullptr, nullptr, hidden, nullptr, nullptr, 0, 0, 0, k_round};
+  return launch_compact<kEpiHidden>(stream, X, ldx, d_model, W_gate, W_up, tab, k_round, d_model % Bf16Cfg::KT != 0,
+                                    (widest + Bf16Cfg::BN - 1) / Bf16Cfg::BN, max_tiles, t, scratch, ep);
 }
 
-hipError_t launch_compact_down_gemm(hipStream_t stream, const void* hidden, int64_t ldh, int64_t d_model,
-                                    const void* W_down, const CompactDown& tab, int max_tiles, const BucketTables& t,
-                                    int32_t* work_off, float* product) {
+hipError_t launch_compact_down_gemm(hipStream_t stream, const void* hidden, int64_t d_model, const void* W_down,
+                                    const CompactDown& tab, int max_tiles, const BucketTables& t, int32_t* scratch,
+                                    float* product) {
   const int64_t half = d_model / 2;
   EpiArgs ep{nullptr, nullptr, nullptr, nullptr, product, d_model, (int)half, 0, 0};
-  return launch_compact<kEpiProduct>(stream, hidden, ldh, d_model, W_down, W_down, tab, tab.k_round % Bf16Cfg::KT != 0,
-                                     (half + Bf16Cfg::BN - 1) / Bf16Cfg::BN, max_tiles, t, work_off, ep);
+  return launch_compact<kEpiProduct>(stream, hidden, 0, d_model, W_down, W_down, tab, tab.k_round,
+                                     tab.k_round % Bf16Cfg::KT != 0, (half + Bf16Cfg::BN - 1) / Bf16Cfg::BN, max_tiles, t,
+                                     scratch, ep);
 }
 
 }  // namespace camera
