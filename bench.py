@@ -482,11 +482,24 @@ def main():
             "hbm_read_gbs": round(hbm, 1),
             "achieved_over_random_operand_ceiling": round(achieved / tf_rand, 4) if bf16 and tf_rand > 0 else None}
 
-    apply_mask = None if args.no_apply else measure_apply(cam, cfg, layers, torch, binding)
-    forward = None if (args.no_forward or calib_tokens != cfg.n_tokens) else measure_forward(cam, cfg, layers, torch, binding)
+    def stage(name, skip, fn):
+        """A follow-on measurement outside the timed step: its failure is reported in its place and on stderr, and
+        does not take the headline line with it."""
+        if skip:
+            return None
+        try:
+            return fn()
+        except Exception as exc:  # noqa: BLE001 - whatever it was, say so
+            print(f"bench.py: stage {name} failed: {exc!r}", file=sys.stderr)
+            torch.cuda.synchronize()
+            return {"error": repr(exc)}
 
-    decode = None if (args.no_decode or calib_tokens != cfg.n_tokens) else measure_decode(cam, cfg, layers, torch, binding,
-                                                                                            ratios=[float(r) for r in args.decode_ratios.split(",")])
+    apply_mask = stage("apply_mask", args.no_apply, lambda: measure_apply(cam, cfg, layers, torch, binding))
+    forward = stage("pruned_layer_output", args.no_forward or calib_tokens != cfg.n_tokens,
+                    lambda: measure_forward(cam, cfg, layers, torch, binding))
+    decode = stage("pruned_layer_decode", args.no_decode or calib_tokens != cfg.n_tokens,
+                   lambda: measure_decode(cam, cfg, layers, torch, binding,
+                                          ratios=[float(r) for r in args.decode_ratios.split(",")]))
 
     ms_per_step = elapsed / args.steps * 1e3
     value = calib_tokens * n_layers * args.steps / elapsed
@@ -515,7 +528,7 @@ def main():
     if not args.no_cpu_baseline:
         del layers
         torch.cuda.empty_cache()
-        result["cpu_baseline"] = cpu_baseline(cfg, inputs)
+        result["cpu_baseline"] = stage("cpu_baseline", False, lambda: cpu_baseline(cfg, inputs))
     print(json.dumps(result))
 
 
