@@ -137,6 +137,11 @@ def test_shared_experts_in_the_same_call_and_accumulated(cam, n_tokens, n_shared
     O_s = orc.layer_forward(X64, ones, gate, up, down, keep=keep_s, round_hidden=orc.round_to_bf16)
     term_s = largest_term(X64, ones, gate, up, down, keep_s)
     check_output(Y_shared, O_s, term_s)
+    if n_tokens > 64:          # every token through every shared expert on the tiled path (aligned W_down rows)
+        ca, ga, ua, da = compact(cam, dev, "Ws", keep_s, cfg.n_shared, cfg.d_ff_shared, align=8)
+        Y_tiled = cam.layer_forward_compact(dev["X"], None, None, ca, ga, ua, da, down_row_align=8)
+        torch.cuda.synchronize()
+        check_output(Y_tiled, O_s, term_s)
     # the whole layer in one call against the oracle's routed + shared layer
     A = dense_A(idx.cpu().numpy().astype(np.int64), w.cpu().numpy().astype(np.float64), cfg.n_experts)
     gate_r, up_r, down_r = expert_lists(layer, "W")
