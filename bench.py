@@ -482,6 +482,26 @@ def main():
             "hbm_read_gbs": round(hbm, 1),
             "achieved_over_random_operand_ceiling": round(achieved / tf_rand, 4) if bf16 and tf_rand > 0 else None}
 
+    def vendor_reference():
+        """The vendor library's plain bf16 GEMM (torch.matmul) on the dense equivalent of the routed call -- the same
+        flops with no gather, no grouping and no fused epilogue -- as a yardstick for the grouped kernel's rate."""
+        M, K, N = cfg.n_tokens * cfg.top_k, cfg.d_model, 2 * cfg.d_ff
+        g = torch.Generator(device="cuda").manual_seed(1)
+        A = torch.randn((M, K), generator=g, device="cuda").to(torch.bfloat16)
+        B = (torch.randn((N, K), generator=g, device="cuda") * cfg.w_std).to(torch.bfloat16)
+        C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+        for _ in range(10):
+            torch.matmul(A, B.t(), out=C)
+        begin, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        begin.record()
+        for _ in range(40):
+            torch.matmul(A, B.t(), out=C)
+        end.record()
+        torch.cuda.synchronize()
+        ms = begin.elapsed_time(end) / 40
+        return {"what": f"torch.matmul bf16 [{M} x {K}] x [{K} x {N}], random operands", "ms": round(ms, 4),
+                "tflops": round(2.0 * M * K * N / ms / 1e9, 1)}
+
     def stage(name, skip, fn):
         """A follow-on measurement outside the timed step: its failure is reported in its place and on stderr, and
         does not take the headline line with it."""
@@ -494,6 +514,8 @@ def main():
             torch.cuda.synchronize()
             return {"error": repr(exc)}
 
+    if "measured" in roofline and bf16:
+        roofline["measured"]["vendor_gemm_dense_equivalent"] = stage("vendor_gemm", False, vendor_reference)
     apply_mask = stage("apply_mask", args.no_apply, lambda: measure_apply(cam, cfg, layers, torch, binding))
     forward = stage("pruned_layer_output", args.no_forward or calib_tokens != cfg.n_tokens,
                     lambda: measure_forward(cam, cfg, layers, torch, binding))
