@@ -25,11 +25,16 @@
 
 #include "camera_internal.h"
 
+#ifndef CAMERA_GEMM_MI16
+#define CAMERA_GEMM_MI16 1
+#endif
+
 namespace camera {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 // silu(g) = g / (1 + exp(-g)); exp2 and rcp are single hardware instructions (about 1 ulp each)
@@ -398,6 +403,259 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
   }  // statistics epilogue
 }
 
+template <class C, int ACT, bool TAIL, bool DEAD, int EPI>
+__device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int d_ff, int slot, const EpiArgs& ep) {
+  constexpr int BN = C::BN, TN = C::TN, WM = C::WM, KT = C::KT;
+  constexpr int NA = ACT > 0 ? ACT : 1;
+  unsigned char* const smem = st.smem;
+
+  // Lane l of a wave instruction writes LDS bytes [16 l, 16 l + 16) after the wave-uniform base,
+  // i.e. chunk position l % kChunks of row l / kChunks of its row group; to produce the swizzled
+  // image it reads logical chunk (l % kChunks) ^ swizzle_key(row) of that row (set up by the caller).
+  // TAIL (d_model not a multiple of KT): chunks past d_model come from a page of zeros.
+  // The instruction's immediate offset is added to the global and to the LDS address alike, so the
+  // j-th group of a wave uses immediate 1024 j on sources that were moved back by 1024 j bytes at
+  // set-up: one LDS base (M0) per matrix and tile instead of one per instruction.
+  auto dma = [&](const __hip_bfloat16* src, int k, int k0, unsigned char* dst, auto group) {
+    // immediate offsets reach 4095 bytes: groups 0-3 use the base, groups 4-7 the base + 4096
+    constexpr int kOff = (decltype(group)::value % 4) * 1024;
+    constexpr int kBase = (decltype(group)::value / 4) * 4096;
+    const unsigned char* p = reinterpret_cast<const unsigned char*>(src + k0);
+    if constexpr (TAIL) p = (k0 + k < st.d_model) ? p : reinterpret_cast<const unsigned char*>(st.zeros) - kOff;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                     (__attribute__((address_space(3))) void*)(dst + kBase), 16, kOff, 0);
+  };
+  // Load d of a tile's kLoadsPerTile wave instructions: the token groups first, then the gate
+  // groups, then the up groups (loads that share an LDS base follow each other).
+  auto dma_one = [&](int stage, int k0, auto index) {
+    constexpr int d = decltype(index)::value;
+    using std::integral_constant;
+    unsigned char* sA = smem + stage * C::kStageBytes + st.a_lds;
+    unsigned char* sG = smem + stage * C::kStageBytes + C::kATileBytes + st.b_lds;
+    if constexpr (d < C::kADma) {
+      dma(st.a_src[d], st.a_k[d], k0, sA, integral_constant<int, d>{});
+    } else if constexpr (d < C::kADma + C::kBDma) {
+      dma(st.g_src[d - C::kADma], st.b_k[d - C::kADma], k0, sG, integral_constant<int, d - C::kADma>{});
+    } else {
+      constexpr int j = d - C::kADma - C::kBDma;
+      dma(st.u_src[j], st.b_k[j], k0, sG + C::kBTileBytes, integral_constant<int, j>{});
+    }
+  };
+  // loads [C::issue_begin(P), C::issue_begin(P + 1)) of a tile: the share of issue slot P
+  auto dma_slot = [&](int stage, int k0, auto slot_index) {
+    constexpr int P = decltype(slot_index)::value;
+    static_for<C::issue_begin(P), C::issue_begin(P + 1)>([&](auto d) {
+      if constexpr (!(DEAD && decltype(d)::value < C::kADma)) dma_one(stage, k0, d);
+    });
+  };
+
+  // v_mfma_f32_16x16x32_bf16: a 32 x 32 block of the wave's tile is four 16 x 16 sub-blocks (a: rows, b: columns)
+  // and an instruction advances K by 32.  With random operand values this instruction holds a shader clock about
+  // 10 % higher than the 32x32x16 one at the same flops (the chip is power-limited), which is why it is used.
+  f32x4 acc_g[NA][TN][2][2], acc_u[NA][TN][2][2];
+#pragma unroll
+  for (int i = 0; i < NA; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int ab = 0; ab < 4; ++ab)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          acc_g[i][j][ab >> 1][ab & 1][r] = 0.0f;
+          acc_u[i][j][ab >> 1][ab & 1][r] = 0.0f;
+        }
+
+  // Lane l holds row (l % 16) of a sub-block, K elements 8*(l / 16) .. +7 of a 32-wide K step.
+  struct FragA {
+    bf16x8 v[NA][2];  // the token rows of one K step: row block i, sub-block a
+  };
+  struct FragB {
+    bf16x8 g[TN], u[TN];  // 16 channels (sub-block b) of every channel block, one K step
+  };
+  auto read_a = [&](FragA& f, int stage, int ks) {
+    if constexpr (ACT > 0) {
+      const unsigned char* sA = smem + stage * C::kStageBytes + st.k_swz[ks] + st.a_frag_base;
+#pragma unroll
+      for (int i = 0; i < ACT; ++i)
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+          f.v[i][a] = *reinterpret_cast<const bf16x8*>(sA + (i * WM * 32 + a * 16) * C::kRowBytes);
+    }
+  };
+  auto read_b = [&](FragB& f, int stage, int ks, int b) {
+    if constexpr (ACT > 0) {
+      const unsigned char* sG = smem + stage * C::kStageBytes + C::kATileBytes + st.k_swz[ks] + st.b_frag_base +
+                                b * 16 * C::kRowBytes;
+      const unsigned char* sU = sG + C::kBTileBytes;
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        f.g[j] = *reinterpret_cast<const bf16x8*>(sG + j * 32 * C::kRowBytes);
+        f.u[j] = *reinterpret_cast<const bf16x8*>(sU + j * 32 * C::kRowBytes);
+      }
+    }
+  };
+  // MFMAs [LO, HI) of one phase (K step ks, channel sub-block b), numbered (row block i, row sub-block a,
+  // channel block j, gate / up)
+  auto mfma_range = [&](const FragA& fa, const FragB& fb, auto b_index, auto lo, auto hi) {
+    constexpr int b = decltype(b_index)::value;
+    static_for<decltype(lo)::value, decltype(hi)::value>([&](auto m) {
+      constexpr int gu = decltype(m)::value % 2, j = (decltype(m)::value / 2) % TN;
+      constexpr int a = (decltype(m)::value / (2 * TN)) % 2, i = decltype(m)::value / (4 * TN);
+      if constexpr (gu == 0)
+        acc_g[i][j][a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v[i][a], fb.g[j], acc_g[i][j][a][b], 0, 0, 0);
+      else
+        acc_u[i][j][a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v[i][a], fb.u[j], acc_u[i][j][a][b], 0, 0, 0);
+    });
+  };
+
+  // Ring schedule as in the 32x32x16 form; what was a 16-deep K step there is a phase here: K step ks = phase / 2
+  // of 32 elements, channel sub-block b = phase % 2.  A phase has the flops of a 16-deep step, twice as many
+  // MFMAs of half the length, and reads the four B fragments of the next phase and, before a new K step, its
+  // four A fragments: the same LDS traffic per unit of time.
+  static_assert(C::kSteps == 4, "two 32-deep K steps of two phases per K tile");
+  const int n_k = (st.d_model + KT - 1) / KT;
+  const int k_last = (n_k - 1) * KT;
+  constexpr int kMayFly = (C::kStages - 2) * C::kLoadsPerTile;  // loads younger than tile kt + 1
+  constexpr int kFull = 4 * ACT * TN;                           // MFMAs of a phase
+  using std::integral_constant;
+  FragA fa[2];
+  FragB fb[2];
+  int fill_stage = C::kStages - 1, fill_k = min((C::kStages - 1) * KT, k_last);
+  if constexpr (DEAD)
+    static_for<0, C::kADma>([&](auto d) { dma_one(fill_stage, fill_k, d); });
+#pragma unroll
+  for (int t = 0; t + 1 < C::kStages; ++t)
+    static_for<0, C::kLoadsPerTile>([&](auto d) { dma_one(t, min(t * KT, k_last), d); });
+  static_for<0, C::kParts>([&](auto p) { dma_slot(fill_stage, fill_k, p); });
+  constexpr int kFirst = C::issue_begin(C::kParts);
+  constexpr int kSlotsFirst = DEAD ? kFirst - (kFirst < C::kADma ? kFirst : C::kADma) : kFirst;
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly + kSlotsFirst) : "memory");
+  __syncthreads();
+  read_a(fa[0], 0, 0);
+  read_b(fb[0], 0, 0, 0);
+  int stage = 0;  // stage of tile kt
+  for (int kt = 0; kt < n_k; ++kt) {
+    const int next = stage + 1 == C::kStages ? 0 : stage + 1;
+    static_for<0, C::kSteps>([&](auto phase) {
+      constexpr int s = decltype(phase)::value;
+      constexpr bool last = s + 1 == C::kSteps;
+      constexpr int P = last ? 0 : C::kParts * (s + 1);  // issue slot of this phase's first part
+      if constexpr (!last) {
+        constexpr int ks1 = (s + 1) / 2, b1 = (s + 1) % 2;
+        read_b(fb[(s + 1) & 1], stage, ks1, b1);
+        if constexpr (b1 == 0) read_a(fa[ks1 & 1], stage, ks1);
+      } else {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly) : "memory");
+        __syncthreads();
+        fill_stage = stage;
+        fill_k = min((kt + C::kStages) * KT, k_last);
+        read_b(fb[0], next, 0, 0);
+        read_a(fa[0], next, 0);
+      }
+      static_for<0, C::kParts>([&](auto part) {
+        constexpr int q = decltype(part)::value;
+        mfma_range(fa[(s / 2) & 1], fb[s & 1], integral_constant<int, s % 2>{},
+                   integral_constant<int, kFull * q / C::kParts>{}, integral_constant<int, kFull * (q + 1) / C::kParts>{});
+        dma_slot(fill_stage, fill_k, integral_constant<int, P + q>{});
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    });
+    stage = next;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS at exit
+
+  // Epilogue.  Accumulator register r of lane l in sub-block (a, b) of block (i, j) is output row
+  // 32*block + 16a + 4*(l/16) + r, column 32*block + 16b + l % 16: a lane owns two channels per channel block.
+  const int lane_col = st.frag_row, lane_rows = st.frag_half * 4;  // l % 16, 4 * (l / 16)
+  if constexpr (EPI != kEpiStats) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const int col = n0 + st.wave_n * TN * 32 + j * 32 + b * 16 + lane_col;
+        if (col >= d_ff) {
+          if constexpr (EPI == kEpiHidden) {
+            if (ep.pad_hidden && col < (d_ff + ep.pad_hidden - 1) / ep.pad_hidden * ep.pad_hidden) {
+#pragma unroll
+              for (int i = 0; i < ACT; ++i)
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+#pragma unroll
+                  for (int r = 0; r < 4; ++r) {
+                    const int row = (WM * i + st.wave_m) * 32 + a * 16 + lane_rows + r;
+                    if (row < st.m_len)
+                      static_cast<__hip_bfloat16*>(ep.hidden)[(st.row_first + row) * ep.ld_hidden + col] = __float2bfloat16(0.0f);
+                  }
+            }
+          }
+          continue;
+        }
+        float kept = 1.0f;
+        if constexpr (EPI == kEpiHidden) kept = (ep.keep == nullptr || ep.keep[(int64_t)st.expert * d_ff + col]) ? 1.0f : 0.0f;
+#pragma unroll
+        for (int i = 0; i < ACT; ++i)
+#pragma unroll
+          for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int row = (WM * i + st.wave_m) * 32 + a * 16 + lane_rows + r;
+              if (row >= st.m_len) continue;
+              const int64_t out_row = st.row_first + row;
+              if constexpr (EPI == kEpiHidden) {
+                const float lam = st.s_a[row] * silu_f32(acc_g[i][j][a][b][r]) * acc_u[i][j][a][b][r] * kept;
+                static_cast<__hip_bfloat16*>(ep.hidden)[out_row * ep.ld_hidden + col] = __float2bfloat16(lam);
+              } else {
+                ep.product[out_row * ep.ld_product + col] = acc_g[i][j][a][b][r];
+                ep.product[out_row * ep.ld_product + col + ep.col_gap] = acc_u[i][j][a][b][r];
+              }
+            }
+      }
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        float sum = 0.0f, mx = 0.0f;
+#pragma unroll
+        for (int i = 0; i < ACT; ++i)
+#pragma unroll
+          for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int row = (WM * i + st.wave_m) * 32 + a * 16 + lane_rows + r;
+              const float lam = st.s_a[row] * silu_f32(acc_g[i][j][a][b][r]) * acc_u[i][j][a][b][r];
+              const float l2 = lam * lam;
+              sum += l2;
+              mx = fmaxf(mx, l2);
+            }
+        sum += __shfl_xor(sum, 16);
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        sum += __shfl_xor(sum, 32);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        if (st.frag_half == 0) {
+          const int col = st.wave_n * TN * 32 + j * 32 + b * 16 + lane_col;
+          st.s_red[st.wave_m * BN + col] = sum;
+          st.s_red[(WM + st.wave_m) * BN + col] = mx;
+        }
+      }
+    }
+    __syncthreads();
+    for (int col = threadIdx.x; col < BN; col += C::kThreads) {
+      if (n0 + col < d_ff) {
+        float sum = 0.0f, mx = 0.0f;
+#pragma unroll
+        for (int w = 0; w < WM; ++w) {  // fixed order
+          sum += st.s_red[w * BN + col];
+          mx = fmaxf(mx, st.s_red[(WM + w) * BN + col]);
+        }
+        ep.part_phi2[(int64_t)slot * d_ff + n0 + col] = sum;
+        ep.part_max[(int64_t)slot * d_ff + n0 + col] = mx;
+      }
+    }
+  }  // statistics epilogue
+}
+
 // What a workgroup has to do: tile (slot, n0 / BN) of expert e.
 struct TileWork {
   int e, slot, row_first, m_len, n0;
@@ -441,8 +699,13 @@ __device__ __forceinline__ void run_tile(const TileWork& w, const __hip_bfloat16
   st.zeros = zeros;
   st.wave_m = wave % WM;
   st.wave_n = wave / WM;
+#if CAMERA_GEMM_MI16
+  st.frag_row = lane % 16;   // 16x16x32: row of a 16-row sub-block
+  st.frag_half = lane / 16;  // and the lane's quarter of the 32-wide K step
+#else
   st.frag_row = lane % 32;
   st.frag_half = lane / 32;
+#endif
   st.expert = e;
   st.m_len = m_len;
   st.row_first = row_first;
@@ -471,8 +734,14 @@ __device__ __forceinline__ void run_tile(const TileWork& w, const __hip_bfloat16
   // swizzle_key(row) only depends on row % 32 here (32-row blocks), so one key per lane.
   st.a_frag_base = (st.wave_m * 32 + st.frag_row) * C::kRowBytes;       // + i*WM*32 rows: block WM*i + wave_m
   st.b_frag_base = (st.wave_n * TN * 32 + st.frag_row) * C::kRowBytes;  // + j*32 rows
+#if CAMERA_GEMM_MI16
+  // 16x16x32: the key of row (16 a + l % 16) of a block does not depend on a, so one key per lane here too
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) st.k_swz[ks] = ((ks * 4 + st.frag_half) ^ swizzle_key<C>(st.frag_row)) << 4;
+#else
 #pragma unroll
   for (int ks = 0; ks < C::kSteps; ++ks) st.k_swz[ks] = ((ks * 2 + st.frag_half) ^ swizzle_key<C>(st.frag_row)) << 4;
+#endif
 
   // accumulator i of this wave covers row block WM*i + wave_m; blocks past m_len are skipped
   const int n_row_blocks = (m_len + 31) / 32;
@@ -480,17 +749,23 @@ __device__ __forceinline__ void run_tile(const TileWork& w, const __hip_bfloat16
   // With two stages the K loop waits for every outstanding load, so a wave may issue fewer of them.
   const bool dead = C::kStages == 2 && a_row0 >= m_len;
   static_assert(TM == 4 || TM == 2 || TM == 1, "dispatch below covers TM = 1, 2 and 4");
+#if CAMERA_GEMM_MI16
+#define CAMERA_TILE_FN tile_body16
+#else
+#define CAMERA_TILE_FN tile_body
+#endif
 #define CAMERA_TILE_BODY(A)                                                              \
   do {                                                                                   \
-    if (dead) tile_body<C, (A), TAIL, true, EPI>(st, n0, d_ff, slot, ep);                \
-    else tile_body<C, (A), TAIL, false, EPI>(st, n0, d_ff, slot, ep);                    \
+    if (dead) CAMERA_TILE_FN<C, (A), TAIL, true, EPI>(st, n0, d_ff, slot, ep);           \
+    else CAMERA_TILE_FN<C, (A), TAIL, false, EPI>(st, n0, d_ff, slot, ep);               \
   } while (0)
-  if (act >= TM) tile_body<C, TM, TAIL, false, EPI>(st, n0, d_ff, slot, ep);
+  if (act >= TM) CAMERA_TILE_FN<C, TM, TAIL, false, EPI>(st, n0, d_ff, slot, ep);
   else if (act == 3) CAMERA_TILE_BODY((TM > 3 ? 3 : 0));
   else if (act == 2) CAMERA_TILE_BODY((TM > 2 ? 2 : 0));
   else if (act == 1) CAMERA_TILE_BODY((TM > 1 ? 1 : 0));
   else CAMERA_TILE_BODY(0);
 #undef CAMERA_TILE_BODY
+#undef CAMERA_TILE_FN
 }
 
 template <class C, class CT, bool TAIL, int EPI>
