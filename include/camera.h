@@ -327,7 +327,7 @@ int camera_profile_read(camera_ctx* ctx, int kernel_id, double* total_ms, int64_
  * their kernels on `stream`, wait for them and return the rate; they use the context workspace.
  *
  * camera_probe_mfma_bf16: `launches` back-to-back launches (about 4 ms each) of a register-resident
- *   v_mfma_f32_32x32x16_bf16 loop on every CU, no LDS and no memory traffic.  random_operands == 0:
+ *   v_mfma_f32_16x16x32_bf16 loop (the instruction of the grouped contraction) on every CU, no LDS and no memory traffic.  random_operands == 0:
  *   all operand elements 1.0 (reaches the published peak); != 0: random operand values as in a
  *   contraction of real data, for which the chip lowers its clock to hold its power limit.
  *   tflops   HOST out: 10^12 floating-point operations per second over all launches

@@ -336,7 +336,7 @@ int camera_probe_mfma_bf16(camera_ctx* ctx, void* stream_, int random_operands, 
   const size_t bytes = camera::probe_mfma_workspace_bytes();
   if (int rc = ensure_workspace(ctx, bytes)) return rc;
   char* counters = static_cast<char*>(ctx->ws) + bytes - 256;
-  constexpr int kIters = 1000;  // 128 000 MFMAs per wave, about 4 ms per launch
+  constexpr int kIters = 4000;  // 256 000 MFMAs (16x16x32) per wave, about 3.5 ms per launch
   hipEvent_t t0, t1;
   CAMERA_HIP(hipEventCreate(&t0), "hipEventCreate");
   CAMERA_HIP(hipEventCreate(&t1), "hipEventCreate");

@@ -117,7 +117,10 @@ struct GemmCfg {
   // Issue slots: a K step is kParts slots, slot 0 is the first one behind the barrier.  The loads of
   // a tile are dealt evenly over the first half of the slots (extra ones in the middle); the second
   // half stays empty, which is the time the youngest load has to land before the next barrier.
-  static constexpr int kParts = (2 * TM * TN) / 4 > 1 ? (2 * TM * TN) / 4 : 1;  // slots per K step: four MFMAs each
+#ifndef CAMERA_GEMM_SLOT_DIV
+#define CAMERA_GEMM_SLOT_DIV 4
+#endif
+  static constexpr int kParts = (2 * TM * TN) / CAMERA_GEMM_SLOT_DIV > 1 ? (2 * TM * TN) / CAMERA_GEMM_SLOT_DIV : 1;  // slots per K step
   static constexpr int kSlots = kParts * kSteps;
   static constexpr int kBusySlots = kSlots >= 2 ? kSlots / 2 : 1;
   static constexpr int issue_count(int p) {
