@@ -28,6 +28,9 @@
 #ifndef CAMERA_GEMM_MI16
 #define CAMERA_GEMM_MI16 1
 #endif
+#ifndef CAMERA_GEMM_ASM_DMA
+#define CAMERA_GEMM_ASM_DMA 1
+#endif
 
 namespace camera {
 namespace {
@@ -90,6 +93,31 @@ struct EpiArgs {
   int64_t ld_hidden;       // row stride of hidden (d_ff when every expert has the same width)
   int pad_hidden;          // != 0: columns from d_ff up to the next multiple of it are written as zeros (8 or 64)
 };
+
+// One wave instruction of the direct global -> LDS path: lane l's 16 bytes at p (+ IMM) go to LDS bytes
+// [16 l, 16 l + 16) behind the wave-uniform address lds (+ IMM).  Written as assembly on purpose: the compiler's
+// wait-count model takes the builtin for an access to both memory and LDS and from then on turns every wait for
+// fragment reads into lgkmcnt(0) and every wait for loads into vmcnt(0), which stalls a wave on the fragment
+// reads it has just issued for the next phase.  Issued this way the loads are invisible to that model: the
+// waits for them are the explicit vmcnt waits of the K loop, and the fragment waits stay exact.
+// M0 holds the LDS address; a scalar write of M0 needs one wait state before an LDS-DMA instruction reads it.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+template <int IMM>
+__device__ __forceinline__ void lds_dma16(const unsigned char* p, unsigned char* lds) {
+#if !CAMERA_GEMM_ASM_DMA
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                   (__attribute__((address_space(3))) void*)lds, 16, IMM, 0);
+  return;
+#endif
+  const unsigned base = __builtin_amdgcn_readfirstlane(
+      (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off offset:%2"
+               :
+               : "s"(base), "v"(p), "n"(IMM)
+               : "memory", "m0");
+}
+#pragma clang diagnostic pop
 
 template <int WM_, int WN_, int TM_, int TN_, int KT_, int STAGES_>
 struct GemmCfg {
@@ -198,8 +226,7 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
     constexpr int kBase = (decltype(group)::value / 4) * 4096;
     const unsigned char* p = reinterpret_cast<const unsigned char*>(src + k0);
     if constexpr (TAIL) p = (k0 + k < st.d_model) ? p : reinterpret_cast<const unsigned char*>(st.zeros) - kOff;
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
-                                     (__attribute__((address_space(3))) void*)(dst + kBase), 16, kOff, 0);
+    lds_dma16<kOff>(p, dst + kBase);
   };
   // Load d of a tile's kLoadsPerTile wave instructions: the token groups first, then the gate
   // groups, then the up groups (loads that share an LDS base follow each other).
@@ -425,8 +452,7 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
     constexpr int kBase = (decltype(group)::value / 4) * 4096;
     const unsigned char* p = reinterpret_cast<const unsigned char*>(src + k0);
     if constexpr (TAIL) p = (k0 + k < st.d_model) ? p : reinterpret_cast<const unsigned char*>(st.zeros) - kOff;
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
-                                     (__attribute__((address_space(3))) void*)(dst + kBase), 16, kOff, 0);
+    lds_dma16<kOff>(p, dst + kBase);
   };
   // Load d of a tile's kLoadsPerTile wave instructions: the token groups first, then the gate
   // groups, then the up groups (loads that share an LDS base follow each other).
