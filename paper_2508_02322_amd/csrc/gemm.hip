@@ -53,8 +53,11 @@ __device__ __forceinline__ float silu_f32(float g) {
 //   are skipped) by TN*32 channels, for both the gate and the up product.  Block
 //   tile BM = 32*WM*TM tokens by BN = 32*WN*TN channels.
 //
-//   K advances KT elements per LDS stage through a ring of kStages stages (64 and 2 in the
-//   built configuration: 64 KiB per stage).  Tiles go from global memory straight into LDS
+//   K advances KT elements per tile.  Token tiles and weight tiles each run through a ring of their own in
+//   LDS: two stages of 32 KiB for the token rows and three of 32 KiB (gate + up) for the weights in the built
+//   configuration, 160 KiB in all.  The weights stream from HBM exactly once and are loaded two tiles ahead;
+//   the token rows, re-read by every channel tile of an expert and so served by the L2, one tile ahead.
+//   Tiles go from global memory straight into LDS
 //   (global_load_lds_dwordx4, no staging registers, no LDS store instructions).  The loads of a
 //   tile are not issued in one go but one or two at a time between groups of MFMAs: a wave that
 //   issues eight loads back to back sits on the vector-memory queue and stops feeding the matrix
@@ -119,9 +122,11 @@ __device__ __forceinline__ void lds_dma16(const unsigned char* p, unsigned char*
 }
 #pragma clang diagnostic pop
 
-template <int WM_, int WN_, int TM_, int TN_, int KT_, int STAGES_>
+// STAGES_: ring depth of the token (A) tiles; BSTAGES_: ring depth of the weight tiles, the same or one more
+// (weights stream from HBM exactly once and need the longer lead; token rows mostly come from the L2).
+template <int WM_, int WN_, int TM_, int TN_, int KT_, int STAGES_, int BSTAGES_ = STAGES_>
 struct GemmCfg {
-  static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_, KT = KT_, kStages = STAGES_;
+  static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_, KT = KT_, kStages = STAGES_, kBStages = BSTAGES_;
   static constexpr int kWaves = WM * WN;
   static constexpr int kThreads = 64 * kWaves;
   static constexpr int BM = 32 * WM * TM;
@@ -138,7 +143,19 @@ struct GemmCfg {
   static constexpr int kADma = BM / kWaves / kDmaRows;  // instructions per wave per tile, A
   static constexpr int kBDma = BN / kWaves / kDmaRows;  // per weight matrix
   static constexpr int kLoadsPerTile = kADma + 2 * kBDma;
-  static constexpr int kSmemBytes = kStages * kStageBytes + BM * 8 + 2 * WM * BN * 4;
+  // LDS: the A stages, then the B stages (gate and up tile of a stage side by side), then the per-tile arrays
+  // (token ids, routing weights, column reduction).  When the ring alone fills the 160 KiB the per-tile arrays
+  // lie over its first bytes: they are only used before the first tile load and after the last fragment read.
+  static constexpr int kBStageBytes = 2 * kBTileBytes;
+  static constexpr int kRingBytes = kStages * kATileBytes + kBStages * kBStageBytes;
+  static constexpr int kAuxBytes = BM * 8 + 2 * WM * BN * 4;
+  static constexpr bool kAliasAux = kRingBytes + kAuxBytes > 160 * 1024;
+  static constexpr int kSmemBytes = kAliasAux ? kRingBytes : kRingBytes + kAuxBytes;
+  static constexpr int a_off(int stage) { return stage * kATileBytes; }
+  static constexpr int b_off(int stage) { return kStages * kATileBytes + stage * kBStageBytes; }
+  // Loads that may still be in flight when tile kt + 1 must have landed: a tile's loads are issued token rows
+  // first, so these are the whole tiles beyond kt + 1 and, with the deeper weight ring, the weight loads of one more.
+  static constexpr int kMayFly = (kStages - 2) * kLoadsPerTile + (kBStages - kStages) * 2 * kBDma;
   // workgroups that fit one CU by LDS (160 KiB), hence waves per SIMD the registers must allow
   static constexpr int kBlocksPerCu = (160 * 1024) / kSmemBytes >= 2 ? 2 : 1;
   static constexpr int kWavesPerSimd = kBlocksPerCu * kWaves / 4 > 0 ? kBlocksPerCu * kWaves / 4 : 1;
@@ -165,6 +182,7 @@ struct GemmCfg {
   static_assert(issue_begin(kSlots) == kLoadsPerTile, "every load has a slot");
   static_assert(KT == 32 || KT == 64, "K tile");
   static_assert(kStages >= 2, "at least the stage being read and the stage being filled");
+  static_assert(kBStages == kStages || kBStages == kStages + 1, "weight ring: as deep as the token ring or one deeper");
   static_assert(kADma >= 1 && kBDma >= 1 && BM % (kWaves * kDmaRows) == 0 && BN % (kWaves * kDmaRows) == 0,
                 "every wave fills whole 1 KiB groups");
   static_assert(kSmemBytes <= 160 * 1024, "LDS per workgroup");
@@ -209,6 +227,7 @@ struct TileState {
 // the K loop skips their loads.
 template <class C, int ACT, bool TAIL, bool DEAD, int EPI>
 __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_ff, int slot, const EpiArgs& ep) {
+  static_assert(C::kBStages == C::kStages && !C::kAliasAux, "the 32x32x16 form keeps one ring depth and its own per-tile arrays");
   constexpr int BN = C::BN, TN = C::TN, WM = C::WM, KT = C::KT;
   constexpr int NA = ACT > 0 ? ACT : 1;
   unsigned char* const smem = st.smem;
@@ -304,7 +323,7 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
   // body and the outstanding-load count never change.
   const int n_k = (st.d_model + KT - 1) / KT;
   const int k_last = (n_k - 1) * KT;
-  constexpr int kMayFly = (C::kStages - 2) * C::kLoadsPerTile;  // loads younger than tile kt + 1
+  constexpr int kMayFly = C::kMayFly;  // loads younger than tile kt + 1
   constexpr int kFull = 2 * ACT * TN;                           // MFMAs of a K step
   using std::integral_constant;
   Frags f[2];
@@ -456,25 +475,28 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
   };
   // Load d of a tile's kLoadsPerTile wave instructions: the token groups first, then the gate
   // groups, then the up groups (loads that share an LDS base follow each other).
-  auto dma_one = [&](int stage, int k0, auto index) {
+  // A tile and a weight tile have their own ring position: Fill says where the next ones go.
+  struct Fill {
+    int a_stage, a_k, b_stage, b_k;
+  };
+  auto dma_one = [&](const Fill& f, auto index) {
     constexpr int d = decltype(index)::value;
     using std::integral_constant;
-    unsigned char* sA = smem + stage * C::kStageBytes + st.a_lds;
-    unsigned char* sG = smem + stage * C::kStageBytes + C::kATileBytes + st.b_lds;
     if constexpr (d < C::kADma) {
-      dma(st.a_src[d], st.a_k[d], k0, sA, integral_constant<int, d>{});
+      dma(st.a_src[d], st.a_k[d], f.a_k, smem + C::a_off(f.a_stage) + st.a_lds, integral_constant<int, d>{});
     } else if constexpr (d < C::kADma + C::kBDma) {
-      dma(st.g_src[d - C::kADma], st.b_k[d - C::kADma], k0, sG, integral_constant<int, d - C::kADma>{});
+      dma(st.g_src[d - C::kADma], st.b_k[d - C::kADma], f.b_k, smem + C::b_off(f.b_stage) + st.b_lds,
+          integral_constant<int, d - C::kADma>{});
     } else {
       constexpr int j = d - C::kADma - C::kBDma;
-      dma(st.u_src[j], st.b_k[j], k0, sG + C::kBTileBytes, integral_constant<int, j>{});
+      dma(st.u_src[j], st.b_k[j], f.b_k, smem + C::b_off(f.b_stage) + C::kBTileBytes + st.b_lds, integral_constant<int, j>{});
     }
   };
   // loads [C::issue_begin(P), C::issue_begin(P + 1)) of a tile: the share of issue slot P
-  auto dma_slot = [&](int stage, int k0, auto slot_index) {
+  auto dma_slot = [&](const Fill& f, auto slot_index) {
     constexpr int P = decltype(slot_index)::value;
     static_for<C::issue_begin(P), C::issue_begin(P + 1)>([&](auto d) {
-      if constexpr (!(DEAD && decltype(d)::value < C::kADma)) dma_one(stage, k0, d);
+      if constexpr (!(DEAD && decltype(d)::value < C::kADma)) dma_one(f, d);
     });
   };
 
@@ -503,7 +525,7 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
   };
   auto read_a = [&](FragA& f, int stage, int ks) {
     if constexpr (ACT > 0) {
-      const unsigned char* sA = smem + stage * C::kStageBytes + st.k_swz[ks] + st.a_frag_base;
+      const unsigned char* sA = smem + C::a_off(stage) + st.k_swz[ks] + st.a_frag_base;
 #pragma unroll
       for (int i = 0; i < ACT; ++i)
 #pragma unroll
@@ -513,8 +535,7 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
   };
   auto read_b = [&](FragB& f, int stage, int ks, int b) {
     if constexpr (ACT > 0) {
-      const unsigned char* sG = smem + stage * C::kStageBytes + C::kATileBytes + st.k_swz[ks] + st.b_frag_base +
-                                b * 16 * C::kRowBytes;
+      const unsigned char* sG = smem + C::b_off(stage) + st.k_swz[ks] + st.b_frag_base + b * 16 * C::kRowBytes;
       const unsigned char* sU = sG + C::kBTileBytes;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
@@ -544,54 +565,76 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
   static_assert(C::kSteps == 4, "two 32-deep K steps of two phases per K tile");
   const int n_k = (st.d_model + KT - 1) / KT;
   const int k_last = (n_k - 1) * KT;
-  constexpr int kMayFly = (C::kStages - 2) * C::kLoadsPerTile;  // loads younger than tile kt + 1
+  constexpr int kMayFly = C::kMayFly;  // loads younger than tile kt + 1
   constexpr int kFull = 4 * ACT * TN;                           // MFMAs of a phase
   using std::integral_constant;
   FragA fa[2];
   FragB fb[2];
-  int fill_stage = C::kStages - 1, fill_k = min((C::kStages - 1) * KT, k_last);
-  if constexpr (DEAD)
-    static_for<0, C::kADma>([&](auto d) { dma_one(fill_stage, fill_k, d); });
+  // Routing weight of the lane's output rows.  They stay in registers when the per-tile arrays lie over the ring:
+  // the first tile load may overwrite them, so every wave must have taken its copy (and finished with the token
+  // ids) before any load is issued.
+  float a_rows[NA][2][4];
+  if constexpr (C::kAliasAux) {
 #pragma unroll
-  for (int t = 0; t + 1 < C::kStages; ++t)
-    static_for<0, C::kLoadsPerTile>([&](auto d) { dma_one(t, min(t * KT, k_last), d); });
-  static_for<0, C::kParts>([&](auto p) { dma_slot(fill_stage, fill_k, p); });
+    for (int i = 0; i < NA; ++i)
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          a_rows[i][a][r] = st.s_a[(WM * i + st.wave_m) * 32 + a * 16 + st.frag_half * 4 + r];
+    __syncthreads();
+  }
+  auto a_of = [&](int i, int a, int r, int row) { return C::kAliasAux ? a_rows[i][a][r] : st.s_a[row]; };
+  constexpr int SA = C::kStages, SB = C::kBStages;
+  Fill fill = {SA - 1, min((SA - 1) * KT, k_last), SB - 1, min((SB - 1) * KT, k_last)};
+  if constexpr (DEAD)
+    static_for<0, C::kADma>([&](auto d) { dma_one(fill, d); });
+#pragma unroll
+  for (int t = 0; t + 1 < SB; ++t) {
+    const Fill whole = {t, min(t * KT, k_last), t, min(t * KT, k_last)};
+    static_for<0, C::kLoadsPerTile>([&](auto d) {
+      if (decltype(d)::value >= C::kADma || t + 1 < SA) dma_one(whole, d);  // the token ring ends one tile earlier
+    });
+  }
+  static_for<0, C::kParts>([&](auto p) { dma_slot(fill, p); });
   constexpr int kFirst = C::issue_begin(C::kParts);
   constexpr int kSlotsFirst = DEAD ? kFirst - (kFirst < C::kADma ? kFirst : C::kADma) : kFirst;
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly + kSlotsFirst) : "memory");
   __syncthreads();
   read_a(fa[0], 0, 0);
   read_b(fb[0], 0, 0, 0);
-  int stage = 0;  // stage of tile kt
+  int stage = 0, b_stage = 0;  // ring positions of tile kt's token rows and weights
   for (int kt = 0; kt < n_k; ++kt) {
-    const int next = stage + 1 == C::kStages ? 0 : stage + 1;
+    const int next = stage + 1 == SA ? 0 : stage + 1;
+    const int b_next = b_stage + 1 == SB ? 0 : b_stage + 1;
     static_for<0, C::kSteps>([&](auto phase) {
       constexpr int s = decltype(phase)::value;
       constexpr bool last = s + 1 == C::kSteps;
       constexpr int P = last ? 0 : C::kParts * (s + 1);  // issue slot of this phase's first part
       if constexpr (!last) {
         constexpr int ks1 = (s + 1) / 2, b1 = (s + 1) % 2;
-        read_b(fb[(s + 1) & 1], stage, ks1, b1);
+        read_b(fb[(s + 1) & 1], b_stage, ks1, b1);
         if constexpr (b1 == 0) read_a(fa[ks1 & 1], stage, ks1);
       } else {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly) : "memory");
         __syncthreads();
-        fill_stage = stage;
-        fill_k = min((kt + C::kStages) * KT, k_last);
-        read_b(fb[0], next, 0, 0);
+        fill = {stage, min((kt + SA) * KT, k_last), b_stage, min((kt + SB) * KT, k_last)};
+        read_b(fb[0], b_next, 0, 0);
         read_a(fa[0], next, 0);
       }
       static_for<0, C::kParts>([&](auto part) {
         constexpr int q = decltype(part)::value;
         mfma_range(fa[(s / 2) & 1], fb[s & 1], integral_constant<int, s % 2>{},
                    integral_constant<int, kFull * q / C::kParts>{}, integral_constant<int, kFull * (q + 1) / C::kParts>{});
-        dma_slot(fill_stage, fill_k, integral_constant<int, P + q>{});
+        dma_slot(fill, integral_constant<int, P + q>{});
         __builtin_amdgcn_sched_barrier(0);
       });
     });
     stage = next;
+    b_stage = b_next;
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS at exit
+  if constexpr (C::kAliasAux && EPI == kEpiStats) __syncthreads();  // the column reduction lies over the ring: every wave has read its last fragments
 
   // Epilogue.  Accumulator register r of lane l in sub-block (a, b) of block (i, j) is output row
   // 32*block + 16a + 4*(l/16) + r, column 32*block + 16b + l % 16: a lane owns two channels per channel block.
@@ -631,7 +674,7 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
               if (row >= st.m_len) continue;
               const int64_t out_row = st.row_first + row;
               if constexpr (EPI == kEpiHidden) {
-                const float lam = st.s_a[row] * silu_f32(acc_g[i][j][a][b][r]) * acc_u[i][j][a][b][r] * kept;
+                const float lam = a_of(i, a, r, row) * silu_f32(acc_g[i][j][a][b][r]) * acc_u[i][j][a][b][r] * kept;
                 static_cast<__hip_bfloat16*>(ep.hidden)[out_row * ep.ld_hidden + col] = __float2bfloat16(lam);
               } else {
                 ep.product[out_row * ep.ld_product + col] = acc_g[i][j][a][b][r];
@@ -653,7 +696,7 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
               const int row = (WM * i + st.wave_m) * 32 + a * 16 + lane_rows + r;
-              const float lam = st.s_a[row] * silu_f32(acc_g[i][j][a][b][r]) * acc_u[i][j][a][b][r];
+              const float lam = a_of(i, a, r, row) * silu_f32(acc_g[i][j][a][b][r]) * acc_u[i][j][a][b][r];
               const float l2 = lam * lam;
               sum += l2;
               mx = fmaxf(mx, l2);
@@ -701,7 +744,7 @@ __device__ __forceinline__ void run_tile(const TileWork& w, const __hip_bfloat16
                                          const __hip_bfloat16* __restrict__ zeros, const EpiArgs& ep) {
   // d_model: the K extent; ldw: elements between consecutive rows of Wg / Wu (d_model unless the rows are padded)
   constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN, WM = C::WM;
-  static_assert(C::kStages * C::kStageBytes <= AUX, "the stages must end before the per-tile arrays");
+  static_assert(C::kAliasAux ? AUX == 0 : C::kRingBytes <= AUX, "the per-tile arrays lie behind the ring, or over its start");
   const int e = w.e, slot = w.slot, row_first = w.row_first, m_len = w.m_len, n0 = w.n0;
   extern __shared__ __align__(16) unsigned char smem[];
   int32_t* s_tok = reinterpret_cast<int32_t*>(smem + AUX);  // [BM] token id
@@ -776,7 +819,7 @@ __device__ __forceinline__ void run_tile(const TileWork& w, const __hip_bfloat16
   const int n_row_blocks = (m_len + 31) / 32;
   const int act = max(0, (n_row_blocks - st.wave_m + WM - 1) / WM);  // wave-uniform, 0 .. TM
   // With two stages the K loop waits for every outstanding load, so a wave may issue fewer of them.
-  const bool dead = C::kStages == 2 && a_row0 >= m_len;
+  const bool dead = C::kStages == 2 && a_row0 >= m_len;  // (the ring of the token rows)
   static_assert(TM == 4 || TM == 2 || TM == 1, "dispatch below covers TM = 1, 2 and 4");
 #if CAMERA_GEMM_MI16
 #define CAMERA_TILE_FN tile_body16
@@ -846,11 +889,13 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
   w.m_len = m_len;
   w.n0 = n0;
   w.tok_first = tile_in_expert * BM;
-  constexpr int kAux = C::kStages * C::kStageBytes;
+  constexpr int kAux = C::kAliasAux ? 0 : C::kRingBytes;           // per-tile arrays of the main tiling
+  constexpr int kAuxTail = C::kAliasAux ? CT::kRingBytes : kAux;  // and of the narrow one (never over its ring)
+  static_assert(kAuxTail + CT::kAuxBytes <= C::kSmemBytes && !CT::kAliasAux, "the narrow tiling fits the workgroup's LDS");
   // A short last tile of an expert is bound by the latency of its loads, not by the matrix pipe: it runs
   // with the narrow tiling, whose smaller stages leave room for a third one (two K tiles in flight).
   if (CT::kThreads == C::kThreads && m_len <= CT::BM)
-    run_tile<CT, TAIL, EPI, kAux>(w, X, ldx, d_model, d_ff, Wg, Wu, stride_gu, d_model, perm, w_perm, zeros, ep);
+    run_tile<CT, TAIL, EPI, kAuxTail>(w, X, ldx, d_model, d_ff, Wg, Wu, stride_gu, d_model, perm, w_perm, zeros, ep);
   else
     run_tile<C, TAIL, EPI, kAux>(w, X, ldx, d_model, d_ff, Wg, Wu, stride_gu, d_model, perm, w_perm, zeros, ep);
 }
@@ -1026,9 +1071,11 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
   w.m_len = m_len;
   w.n0 = n0;
   w.tok_first = tile_in_expert * BM;
-  constexpr int kAux = C::kStages * C::kStageBytes;
+  constexpr int kAux = C::kAliasAux ? 0 : C::kRingBytes;           // per-tile arrays of the main tiling
+  constexpr int kAuxTail = C::kAliasAux ? CT::kRingBytes : kAux;  // and of the narrow one (never over its ring)
+  static_assert(kAuxTail + CT::kAuxBytes <= C::kSmemBytes && !CT::kAliasAux, "the narrow tiling fits the workgroup's LDS");
   if (CT::kThreads == C::kThreads && m_len <= CT::BM)
-    run_tile<CT, TAIL, EPI, kAux>(w, A, lda, g.k_ext, g.n_ext, Wg + g.g_off, Wu + g.u_off, 0, g.ldw, perm, w_perm, zeros, ep);
+    run_tile<CT, TAIL, EPI, kAuxTail>(w, A, lda, g.k_ext, g.n_ext, Wg + g.g_off, Wu + g.u_off, 0, g.ldw, perm, w_perm, zeros, ep);
   else
     run_tile<C, TAIL, EPI, kAux>(w, A, lda, g.k_ext, g.n_ext, Wg + g.g_off, Wu + g.u_off, 0, g.ldw, perm, w_perm, zeros, ep);
   }
@@ -1161,9 +1208,10 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
   }  // statistics epilogue
 }
 
-// Shape of the bf16 kernel: waves (M x N), 32x32 blocks per wave (M x N), K tile, LDS stages.
+// Shape of the bf16 kernel: waves (M x N), 32x32 blocks per wave (M x N), K tile, stages of the token ring, stages
+// of the weight ring.
 #ifndef CAMERA_GEMM_CFG
-#define CAMERA_GEMM_CFG 4, 2, 2, 2, 64, 2
+#define CAMERA_GEMM_CFG 4, 2, 2, 2, 64, 2, 3
 #endif
 using Bf16Cfg = GemmCfg<CAMERA_GEMM_CFG>;
 // Tiling of an expert's short last tile (at most 64 token rows): same eight waves and N extent, 2 x 4 waves of
