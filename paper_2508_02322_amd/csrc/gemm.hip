@@ -98,23 +98,27 @@ struct EpiArgs {
 };
 
 // One wave instruction of the direct global -> LDS path: lane l's 16 bytes at p (+ IMM) go to LDS bytes
-// [16 l, 16 l + 16) behind the wave-uniform address lds (+ IMM).  Written as assembly on purpose: the compiler's
+// [16 l, 16 l + 16) behind the wave-uniform LDS byte address lds (+ IMM).  Written as assembly on purpose: the compiler's
 // wait-count model takes the builtin for an access to both memory and LDS and from then on turns every wait for
 // fragment reads into lgkmcnt(0) and every wait for loads into vmcnt(0), which stalls a wave on the fragment
 // reads it has just issued for the next phase.  Issued this way the loads are invisible to that model: the
 // waits for them are the explicit vmcnt waits of the K loop, and the fragment waits stay exact.
 // M0 holds the LDS address; a scalar write of M0 needs one wait state before an LDS-DMA instruction reads it.
+// LDS byte address of a pointer into the workgroup's LDS.  Taken once per tile from the named array: a cast of a
+// pointer whose address space the compiler cannot see needs a null check that this compiler version miscompiles.
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+  return (unsigned)(size_t)(__attribute__((address_space(3))) const void*)p;
+}
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"
 template <int IMM>
-__device__ __forceinline__ void lds_dma16(const unsigned char* p, unsigned char* lds) {
+__device__ __forceinline__ void lds_dma16(const unsigned char* p, unsigned lds) {
 #if !CAMERA_GEMM_ASM_DMA
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
-                                   (__attribute__((address_space(3))) void*)lds, 16, IMM, 0);
+                                   (__attribute__((address_space(3))) void*)(size_t)lds, 16, IMM, 0);
   return;
 #endif
-  const unsigned base = __builtin_amdgcn_readfirstlane(
-      (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds);
+  const unsigned base = __builtin_amdgcn_readfirstlane(lds);
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off offset:%2"
                :
                : "s"(base), "v"(p), "n"(IMM)
@@ -230,7 +234,8 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
   static_assert(C::kBStages == C::kStages && !C::kAliasAux, "the 32x32x16 form keeps one ring depth and its own per-tile arrays");
   constexpr int BN = C::BN, TN = C::TN, WM = C::WM, KT = C::KT;
   constexpr int NA = ACT > 0 ? ACT : 1;
-  unsigned char* const smem = st.smem;
+  extern __shared__ __align__(16) unsigned char smem[];  // the workgroup's dynamic LDS, named here so that its address space is known
+  const unsigned lds0 = lds_address(smem);
 
   // Lane l of a wave instruction writes LDS bytes [16 l, 16 l + 16) after the wave-uniform base,
   // i.e. chunk position l % kChunks of row l / kChunks of its row group; to produce the swizzled
@@ -239,7 +244,7 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
   // The instruction's immediate offset is added to the global and to the LDS address alike, so the
   // j-th group of a wave uses immediate 1024 j on sources that were moved back by 1024 j bytes at
   // set-up: one LDS base (M0) per matrix and tile instead of one per instruction.
-  auto dma = [&](const __hip_bfloat16* src, int k, int k0, unsigned char* dst, auto group) {
+  auto dma = [&](const __hip_bfloat16* src, int k, int k0, unsigned dst, auto group) {
     // immediate offsets reach 4095 bytes: groups 0-3 use the base, groups 4-7 the base + 4096
     constexpr int kOff = (decltype(group)::value % 4) * 1024;
     constexpr int kBase = (decltype(group)::value / 4) * 4096;
@@ -252,8 +257,8 @@ __device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_
   auto dma_one = [&](int stage, int k0, auto index) {
     constexpr int d = decltype(index)::value;
     using std::integral_constant;
-    unsigned char* sA = smem + stage * C::kStageBytes + st.a_lds;
-    unsigned char* sG = smem + stage * C::kStageBytes + C::kATileBytes + st.b_lds;
+    const unsigned sA = lds0 + stage * C::kStageBytes + st.a_lds;
+    const unsigned sG = lds0 + stage * C::kStageBytes + C::kATileBytes + st.b_lds;
     if constexpr (d < C::kADma) {
       dma(st.a_src[d], st.a_k[d], k0, sA, integral_constant<int, d>{});
     } else if constexpr (d < C::kADma + C::kBDma) {
@@ -456,7 +461,8 @@ template <class C, int ACT, bool TAIL, bool DEAD, int EPI>
 __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int d_ff, int slot, const EpiArgs& ep) {
   constexpr int BN = C::BN, TN = C::TN, WM = C::WM, KT = C::KT;
   constexpr int NA = ACT > 0 ? ACT : 1;
-  unsigned char* const smem = st.smem;
+  extern __shared__ __align__(16) unsigned char smem[];  // the workgroup's dynamic LDS, named here so that its address space is known
+  const unsigned lds0 = lds_address(smem);
 
   // Lane l of a wave instruction writes LDS bytes [16 l, 16 l + 16) after the wave-uniform base,
   // i.e. chunk position l % kChunks of row l / kChunks of its row group; to produce the swizzled
@@ -465,7 +471,7 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
   // The instruction's immediate offset is added to the global and to the LDS address alike, so the
   // j-th group of a wave uses immediate 1024 j on sources that were moved back by 1024 j bytes at
   // set-up: one LDS base (M0) per matrix and tile instead of one per instruction.
-  auto dma = [&](const __hip_bfloat16* src, int k, int k0, unsigned char* dst, auto group) {
+  auto dma = [&](const __hip_bfloat16* src, int k, int k0, unsigned dst, auto group) {
     // immediate offsets reach 4095 bytes: groups 0-3 use the base, groups 4-7 the base + 4096
     constexpr int kOff = (decltype(group)::value % 4) * 1024;
     constexpr int kBase = (decltype(group)::value / 4) * 4096;
@@ -483,13 +489,13 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
     constexpr int d = decltype(index)::value;
     using std::integral_constant;
     if constexpr (d < C::kADma) {
-      dma(st.a_src[d], st.a_k[d], f.a_k, smem + C::a_off(f.a_stage) + st.a_lds, integral_constant<int, d>{});
+      dma(st.a_src[d], st.a_k[d], f.a_k, lds0 + C::a_off(f.a_stage) + st.a_lds, integral_constant<int, d>{});
     } else if constexpr (d < C::kADma + C::kBDma) {
-      dma(st.g_src[d - C::kADma], st.b_k[d - C::kADma], f.b_k, smem + C::b_off(f.b_stage) + st.b_lds,
+      dma(st.g_src[d - C::kADma], st.b_k[d - C::kADma], f.b_k, lds0 + C::b_off(f.b_stage) + st.b_lds,
           integral_constant<int, d - C::kADma>{});
     } else {
       constexpr int j = d - C::kADma - C::kBDma;
-      dma(st.u_src[j], st.b_k[j], f.b_k, smem + C::b_off(f.b_stage) + C::kBTileBytes + st.b_lds, integral_constant<int, j>{});
+      dma(st.u_src[j], st.b_k[j], f.b_k, lds0 + C::b_off(f.b_stage) + C::kBTileBytes + st.b_lds, integral_constant<int, j>{});
     }
   };
   // loads [C::issue_begin(P), C::issue_begin(P + 1)) of a tile: the share of issue slot P
