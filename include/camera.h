@@ -170,6 +170,23 @@ int camera_select_prune(camera_ctx* ctx, void* stream,
                         int32_t* kept_idx, uint32_t* rank);
 
 /*
+ * camera_select_prune for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, order, counts and outputs as
+ * camera_select_prune without the `rank` output, but the kernels' scratch (class bytes, select histograms,
+ * per-workgroup counts) lies in a static device array of the library instead of the context workspace: the
+ * call makes no hipMalloc / hipFree and no other allocating call.  The array (1.5 MiB) exists once per GPU
+ * for the life of the process and serves n_micro <= CAMERA_NOALLOC_MAX_MICRO; larger inputs are refused with
+ * CAMERA_EUNSUPPORTED before anything is launched.  All calls on one GPU share that array, whatever their
+ * context or stream: calls that overlap in time on one GPU race (order them on one stream or with events).
+ * The first call on a device looks up the array's address (no stream work); make it outside a graph capture.
+ */
+#define CAMERA_NOALLOC_MAX_MICRO (1 << 20)
+int camera_select_prune_noalloc(camera_ctx* ctx, void* stream,
+                                const float* energy, int64_t n_micro,
+                                const int64_t* seg_offsets, int n_seg, double ratio,
+                                uint8_t* keep_mask, int32_t* kept_per_expert, int32_t* kept_idx);
+
+/*
  * TopSelect at several ratios from one pass over the ranking (the masks at 20 / 40 / 60 % of "Main Results"
  * come from one set of scores).  Same order and counts as camera_select_prune.
  *   ratios          HOST [n_ratios], each in [0, 1], not falling; n_ratios <= CAMERA_MAX_LEVELS - 1

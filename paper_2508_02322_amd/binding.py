@@ -22,7 +22,7 @@ KERNEL_NAMES = ["route", "bucket", "gemm", "down_norm", "finalize", "rank", "gat
                 "compact_hidden", "compact_down"]
 
 EXPORTS = ["camera_create", "camera_destroy", "camera_last_error", "camera_version", "camera_route_topk",
-           "camera_score_layer", "camera_select_prune", "camera_select_prune_multi", "camera_alloc_bits",
+           "camera_score_layer", "camera_select_prune", "camera_select_prune_noalloc", "camera_select_prune_multi", "camera_alloc_bits",
            "camera_gather_micro_experts", "camera_layer_forward", "camera_layer_forward_compact", "camera_output_error", "camera_profile_enable",
            "camera_profile_read", "camera_probe_mfma_bf16", "camera_probe_hbm_read"]
 
@@ -51,6 +51,7 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.camera_score_layer.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _vp, _i, _i, _i64, _vp, _vp, _i64,
                                        _vp, _i64, _f, _i, _vp, _vp, _vp, _vp]
     lib.camera_select_prune.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _d, _vp, _vp, _vp, _vp]
+    lib.camera_select_prune_noalloc.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _d, _vp, _vp, _vp]
     lib.camera_select_prune_multi.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _i, _c.POINTER(_d), _vp, _vp]
     lib.camera_alloc_bits.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _i, _c.POINTER(_i),
                                       _c.POINTER(_d), _vp, _vp, _vp]
@@ -155,6 +156,15 @@ class Camera:
             self._ctx, _stream_handle(self.device), _ptr(energy), n_micro, seg, n_seg, float(ratio), _ptr(keep),
             _ptr(per_expert), _ptr(kept_idx), _ptr(rank)))
         return keep, per_expert, kept_idx, rank
+
+    def select_prune_noalloc(self, energy, seg_offsets: Sequence[int], ratio: float, keep, per_expert, kept_idx=None):
+        """camera_select_prune_noalloc: the caller brings every output (keep uint8 [n_micro], per_expert int32
+        [n_seg], kept_idx int32 [>= kept] or None); the call itself allocates nothing on the device."""
+        n_seg = len(seg_offsets) - 1
+        seg = (_i64 * (n_seg + 1))(*seg_offsets)
+        self._check(self.lib.camera_select_prune_noalloc(
+            self._ctx, _stream_handle(self.device), _ptr(energy), energy.numel(), seg, n_seg, float(ratio), _ptr(keep),
+            _ptr(per_expert), _ptr(kept_idx)))
 
     def select_prune_multi(self, energy, seg_offsets, ratios, out=None):
         """Masks at several rising ratios from one ranking pass: (keep_bits uint8 [n_micro] with bit k = kept at

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "camera_internal.h"
@@ -25,7 +26,17 @@ struct camera_ctx {
   std::vector<Span> free_spans;                  // reusable event pairs
 };
 
+// Scratch of camera_select_prune_noalloc: one copy per GPU, held until the process ends.  In host code this
+// name is only a handle for hipGetSymbolAddress; the device address it yields (one per device) is what the
+// kernels and every other HIP call are given.
+constexpr size_t kScratchBytes = 1536 * 1024;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
 
 char g_create_error[256] = {0};
 
@@ -812,6 +823,59 @@ int camera_select_prune(camera_ctx* ctx, void* stream_, const float* energy, int
   if (rank)
     CAMERA_HIP(camera::launch_full_rank(stream, energy, n_micro, rank, reinterpret_cast<int32_t*>(ws + o_rank)),
                "rank launch");
+  return CAMERA_OK;
+}
+
+int camera_select_prune_noalloc(camera_ctx* ctx, void* stream_, const float* energy, int64_t n_micro,
+                                const int64_t* seg_offsets, int n_seg, double ratio, uint8_t* keep_mask,
+                                int32_t* kept_per_expert, int32_t* kept_idx) {
+  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
+  if (int rc = check_energy(ctx, energy, n_micro)) return rc;
+  if (n_micro > CAMERA_NOALLOC_MAX_MICRO)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "n_micro: %lld exceeds the %d micro-experts the static scratch is sized for; use camera_select_prune",
+                (long long)n_micro, CAMERA_NOALLOC_MAX_MICRO);
+  camera::SegTable seg;
+  if (int rc = check_segments(ctx, seg_offsets, n_seg, n_micro, &seg)) return rc;
+  if (!(ratio >= 0.0 && ratio <= 1.0)) return fail(ctx, CAMERA_EINVAL, "ratio: must be in [0, 1]");
+  if (kept_per_expert == nullptr) return fail(ctx, CAMERA_EINVAL, "kept_per_expert: NULL");
+  if (n_micro > 0 && keep_mask == nullptr) return fail(ctx, CAMERA_EINVAL, "keep_mask: NULL");
+  if (ctx->device >= kMaxDevices) return fail(ctx, CAMERA_EUNSUPPORTED, "device: index above %d", kMaxDevices - 1);
+
+  camera::RankCuts cuts;
+  memset(&cuts, 0, sizeof(cuts));
+  cuts.n_cuts = 1;
+  cuts.cut_rank[0] = floor_count(ratio, n_micro);  // n_prune
+  cuts.out_of_below[0] = 1;                        // below no cut: kept
+  cuts.out_of_below[1] = 0;
+
+  Carver cv;
+  const size_t o_class = cv.take((size_t)n_micro + 64);
+  const size_t o_rank = cv.take(sizeof(int32_t) * camera::rank_workspace_words(n_micro, 0));
+  if (cv.used > kScratchBytes)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "n_micro: needs %zu bytes of scratch, the static buffer has %zu", cv.used, kScratchBytes);
+  DeviceGuard guard;
+  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
+  char* ws = nullptr;
+  {
+    // every GPU has its own copy of the array at its own address: looked up once per device, with that device current
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[ctx->device] == nullptr) {
+      void* p = nullptr;
+      CAMERA_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+      if (p == nullptr) return fail(ctx, CAMERA_EHIP, "hipGetSymbolAddress(scratch): null address");
+      g_scratch_ptr[ctx->device] = p;
+    }
+    ws = static_cast<char*>(g_scratch_ptr[ctx->device]);
+  }
+  // The scratch keeps the previous call's contents: the select state (histograms, tickets, prefixes) is cleared by
+  // the first kernel of the classification; class bytes and per-workgroup counts are written before they are read.
+  uint8_t* class_buf = reinterpret_cast<uint8_t*>(ws + o_class);
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  CAMERA_HIP(camera::launch_classify(stream, energy, n_micro, cuts, class_buf, keep_mask, kept_idx,
+                                     reinterpret_cast<int32_t*>(ws + o_rank)),
+             "classify launch");
+  CAMERA_HIP(camera::launch_segment_counts(stream, class_buf, seg, 1, 1, kept_per_expert, nullptr),
+             "segment counts launch");
   return CAMERA_OK;
 }
 

@@ -255,3 +255,17 @@ def test_layer_forward_compact_argument_checks(lib, ctx):
     assert forward(wd=vp(4100)) == -2 and "16-byte" in err(lib, ctx)
     assert forward(n=0) == 0                                  # nothing to do: no GPU is touched
     assert forward(count=(0, 0, 0, 0), wg=None, wu=None, wd=None, n=0) == 0
+
+
+def test_select_prune_noalloc_argument_checks(lib, ctx):
+    """The no-allocation variant refuses what does not fit its static scratch before any GPU call."""
+    def sel(n=100, seg=None, n_seg=2, ratio=0.4, E=FAKE, mask=FAKE, per=FAKE, c=ctx):
+        seg = seg_array([0, 40, n]) if seg is None else seg
+        return lib.camera_select_prune_noalloc(c, None, E, n, seg, n_seg, ratio, mask, per, None)
+    assert sel(c=None) == -1
+    assert sel(n=(1 << 20) + 1) == -6 and "static scratch" in err(lib, ctx)
+    assert sel(n=1 << 24) == -6
+    assert sel(ratio=1.5) == -1 and "ratio" in err(lib, ctx)
+    assert sel(E=None) == -1 and sel(mask=None) == -1 and sel(per=None) == -1
+    assert sel(seg=seg_array([0, 40, 90])) == -1 and "seg_offsets" in err(lib, ctx)
+    assert sel(n_seg=0) == -6
