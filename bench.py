@@ -473,9 +473,10 @@ def main():
     if not args.no_probes:
         # Measured ceilings beside the published peak: the register-resident MFMA loop sustains the published rate
         # only with constant operands; with random operand values the chip lowers its clock to hold its power limit.
-        tf_const, mhz_const = cam.probe_mfma_bf16(False, launches=50)
-        tf_rand, mhz_rand = cam.probe_mfma_bf16(True, launches=50)
-        hbm = cam.probe_hbm_read(2 << 30, launches=10)
+        from paper_2508_02322_amd import bench_probes
+        tf_const, mhz_const = bench_probes.mfma_bf16(False, launches=50)
+        tf_rand, mhz_rand = bench_probes.mfma_bf16(True, launches=50)
+        hbm = bench_probes.hbm_read(2 << 30, launches=10)
         roofline["measured"] = {
             "mfma_bf16_constant_operands": {"tflops": round(tf_const, 1), "shader_mhz": round(mhz_const)},
             "mfma_bf16_random_operands": {"tflops": round(tf_rand, 1), "shader_mhz": round(mhz_rand)},

@@ -338,24 +338,6 @@ int camera_output_error(camera_ctx* ctx, void* stream, const float* Y, const flo
 int camera_profile_enable(camera_ctx* ctx, int on);
 int camera_profile_read(camera_ctx* ctx, int kernel_id, double* total_ms, int64_t* launches);
 
-/*
- * Measured ceilings of the machine, for benchmark reports (the measured peaks that the roofline
- * fractions of the grouped contraction and of the column-norm pass are set beside).  Both calls run
- * their kernels on `stream`, wait for them and return the rate; they use the context workspace.
- *
- * camera_probe_mfma_bf16: `launches` back-to-back launches (about 4 ms each) of a register-resident
- *   v_mfma_f32_16x16x32_bf16 loop (the instruction of the grouped contraction) on every CU, no LDS and no memory traffic.  random_operands == 0:
- *   all operand elements 1.0 (reaches the published peak); != 0: random operand values as in a
- *   contraction of real data, for which the chip lowers its clock to hold its power limit.
- *   tflops   HOST out: 10^12 floating-point operations per second over all launches
- *   shader_mhz HOST out: mean shader clock during the kernels (cycle counter / 100 MHz reference)
- * camera_probe_hbm_read: `launches` streaming reads of a `bytes`-long buffer (choose it much
- *   larger than the 256 MB memory-side cache); gb_per_s HOST out: 10^9 bytes per second.
- */
-int camera_probe_mfma_bf16(camera_ctx* ctx, void* stream, int random_operands, int launches,
-                           double* tflops, double* shader_mhz);
-int camera_probe_hbm_read(camera_ctx* ctx, void* stream, int64_t bytes, int launches, double* gb_per_s);
-
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ KERNEL_NAMES = ["route", "bucket", "gemm", "down_norm", "finalize", "rank", "gat
 EXPORTS = ["camera_create", "camera_destroy", "camera_last_error", "camera_version", "camera_route_topk",
            "camera_score_layer", "camera_select_prune", "camera_select_prune_noalloc", "camera_select_prune_multi", "camera_alloc_bits",
            "camera_gather_micro_experts", "camera_layer_forward", "camera_layer_forward_compact", "camera_output_error", "camera_profile_enable",
-           "camera_profile_read", "camera_probe_mfma_bf16", "camera_probe_hbm_read"]
+           "camera_profile_read"]
 
 _c = ctypes
 _vp, _i, _i64, _f, _d = _c.c_void_p, _c.c_int, _c.c_int64, _c.c_float, _c.c_double
@@ -64,8 +64,6 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.camera_output_error.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _vp]
     lib.camera_profile_enable.argtypes = [_vp, _i]
     lib.camera_profile_read.argtypes = [_vp, _i, _c.POINTER(_d), _c.POINTER(_i64)]
-    lib.camera_probe_mfma_bf16.argtypes = [_vp, _vp, _i, _i, _c.POINTER(_d), _c.POINTER(_d)]
-    lib.camera_probe_hbm_read.argtypes = [_vp, _vp, _i64, _i, _c.POINTER(_d)]
     for name in EXPORTS:
         if name != "camera_last_error":
             getattr(lib, name).restype = _i
@@ -261,18 +259,3 @@ class Camera:
         ms, count = _d(), _i64()
         self._check(self.lib.camera_profile_read(self._ctx, kernel_id, _c.byref(ms), _c.byref(count)))
         return ms.value, count.value
-
-    # ---- machine probes ----------------------------------------------------
-    def probe_mfma_bf16(self, random_operands: bool, launches: int = 50):
-        """(TFLOP/s, shader MHz) of the register-resident MFMA loop."""
-        tf, mhz = _d(), _d()
-        self._check(self.lib.camera_probe_mfma_bf16(self._ctx, _stream_handle(self.device), int(random_operands),
-                                                    int(launches), _c.byref(tf), _c.byref(mhz)))
-        return tf.value, mhz.value
-
-    def probe_hbm_read(self, nbytes: int, launches: int = 10):
-        """GB/s of a streaming read of nbytes."""
-        gbs = _d()
-        self._check(self.lib.camera_probe_hbm_read(self._ctx, _stream_handle(self.device), int(nbytes), int(launches),
-                                                   _c.byref(gbs)))
-        return gbs.value

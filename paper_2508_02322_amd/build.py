@@ -1,4 +1,5 @@
-"""Builds libcamera_hip.so (the C-ABI HIP library) in-tree with hipcc for gfx950.
+"""Builds libcamera_hip.so (the C-ABI HIP library) and libcamera_bench.so (machine probes for benchmark
+reports) in-tree with hipcc for gfx950.
 
     python -m paper_2508_02322_amd.build
 
@@ -16,8 +17,10 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcamera_hip.so")
-SOURCES = ["api.hip", "route.hip", "bucket.hip", "gemm.hip", "norm.hip", "rank.hip", "probe.hip", "gather.hip", "forward.hip",
+BENCH_LIB = os.path.join(HERE, "libcamera_bench.so")
+SOURCES = ["api.hip", "route.hip", "bucket.hip", "gemm.hip", "norm.hip", "rank.hip", "gather.hip", "forward.hip",
            "compact.hip"]
+BENCH_SOURCES = ["probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # keep packed-fp32 instruction selection off for every device function
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -42,15 +45,21 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(verbose: bool = True) -> str:
-    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
-        objs = list(pool.map(_compile, SOURCES))
-    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+def _link(lib: str, objs) -> None:
+    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"{' '.join(cmd)}\n{res.stdout}\n{res.stderr}")
+
+
+def build(verbose: bool = True) -> str:
+    every = SOURCES + BENCH_SOURCES
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(every))) as pool:
+        objs = list(pool.map(_compile, every))
+    _link(LIB, objs[:len(SOURCES)])
+    _link(BENCH_LIB, objs[len(SOURCES):])
     if verbose:
-        print(f"built {LIB}")
+        print(f"built {LIB} and {BENCH_LIB}")
     return LIB
 
 

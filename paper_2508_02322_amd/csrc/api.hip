@@ -336,68 +336,6 @@ int camera_gather_micro_experts(camera_ctx* ctx, void* stream_, int dtype, int n
   return CAMERA_OK;
 }
 
-int camera_probe_mfma_bf16(camera_ctx* ctx, void* stream_, int random_operands, int launches, double* tflops,
-                           double* shader_mhz) {
-  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
-  if (launches < 1 || launches > 1000) return fail(ctx, CAMERA_EINVAL, "launches: must be in [1, 1000]");
-  if (tflops == nullptr || shader_mhz == nullptr) return fail(ctx, CAMERA_EINVAL, "tflops / shader_mhz: NULL");
-  DeviceGuard guard;
-  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
-  const size_t bytes = camera::probe_mfma_workspace_bytes();
-  if (int rc = ensure_workspace(ctx, bytes)) return rc;
-  char* counters = static_cast<char*>(ctx->ws) + bytes - 256;
-  constexpr int kIters = 4000;  // 256 000 MFMAs (16x16x32) per wave, about 3.5 ms per launch
-  hipEvent_t t0, t1;
-  CAMERA_HIP(hipEventCreate(&t0), "hipEventCreate");
-  CAMERA_HIP(hipEventCreate(&t1), "hipEventCreate");
-  hipError_t e = hipMemsetAsync(counters, 0, 256, stream);
-  if (e == hipSuccess) e = hipEventRecord(t0, stream);
-  for (int i = 0; i < launches && e == hipSuccess; ++i)
-    e = camera::launch_probe_mfma(stream, random_operands != 0, kIters, ctx->ws);
-  if (e == hipSuccess) e = hipEventRecord(t1, stream);
-  if (e == hipSuccess) e = hipEventSynchronize(t1);
-  float ms = 0.0f;
-  unsigned long long clocks[2] = {0, 0};
-  if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
-  if (e == hipSuccess) e = hipMemcpy(clocks, counters, sizeof(clocks), hipMemcpyDeviceToHost);
-  (void)hipEventDestroy(t0);
-  (void)hipEventDestroy(t1);
-  if (e != hipSuccess) return fail_hip(ctx, e, "MFMA probe");
-  *tflops = camera::probe_mfma_flops(kIters) * launches / (ms * 1e-3) / 1e12;
-  *shader_mhz = clocks[1] ? 100.0 * (double)clocks[0] / (double)clocks[1] : 0.0;
-  return CAMERA_OK;
-}
-
-int camera_probe_hbm_read(camera_ctx* ctx, void* stream_, int64_t bytes, int launches, double* gb_per_s) {
-  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
-  if (bytes < (int64_t(1) << 20) || bytes > (int64_t(1) << 36) || bytes % 16 != 0)
-    return fail(ctx, CAMERA_EINVAL, "bytes: must be a multiple of 16 in [2^20, 2^36]");
-  if (launches < 1 || launches > 1000) return fail(ctx, CAMERA_EINVAL, "launches: must be in [1, 1000]");
-  if (gb_per_s == nullptr) return fail(ctx, CAMERA_EINVAL, "gb_per_s: NULL");
-  DeviceGuard guard;
-  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
-  if (int rc = ensure_workspace(ctx, (size_t)bytes + 256)) return rc;
-  char* sink = static_cast<char*>(ctx->ws) + bytes;
-  hipEvent_t t0, t1;
-  CAMERA_HIP(hipEventCreate(&t0), "hipEventCreate");
-  CAMERA_HIP(hipEventCreate(&t1), "hipEventCreate");
-  hipError_t e = hipMemsetAsync(ctx->ws, 0x5a, (size_t)bytes + 256, stream);
-  if (e == hipSuccess) e = camera::launch_probe_hbm(stream, ctx->ws, bytes, sink);  // warm-up
-  if (e == hipSuccess) e = hipEventRecord(t0, stream);
-  for (int i = 0; i < launches && e == hipSuccess; ++i) e = camera::launch_probe_hbm(stream, ctx->ws, bytes, sink);
-  if (e == hipSuccess) e = hipEventRecord(t1, stream);
-  if (e == hipSuccess) e = hipEventSynchronize(t1);
-  float ms = 0.0f;
-  if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
-  (void)hipEventDestroy(t0);
-  (void)hipEventDestroy(t1);
-  if (e != hipSuccess) return fail_hip(ctx, e, "HBM probe");
-  *gb_per_s = (double)bytes * launches / (ms * 1e-3) / 1e9;
-  return CAMERA_OK;
-}
-
 int camera_route_topk(camera_ctx* ctx, void* stream_, const void* X, int dtype, int64_t n, int64_t d_model,
                       int64_t ldx, const void* W_r, int64_t ldr, const float* bias, int n_experts, int top_k,
                       int renorm, int32_t* topk_idx, float* topk_w) {

@@ -190,11 +190,4 @@ hipError_t launch_gather_cols(hipStream_t stream, int dtype, const void* W_down,
                               int64_t d_ff, int64_t d_model, const int32_t* index, int64_t n_index,
                               int64_t index_base, const int32_t* off, const int32_t* off_ld, void* down_out);
 
-// Machine probes (probe.hip).  The MFMA probe's workspace holds its per-thread sink and, in its last
-// 256 bytes, two 64-bit counters (shader cycles, 100 MHz ticks) that the kernel adds to.
-size_t probe_mfma_workspace_bytes();
-hipError_t launch_probe_mfma(hipStream_t stream, bool random_operands, int iters, void* workspace);
-double probe_mfma_flops(int iters);
-hipError_t launch_probe_hbm(hipStream_t stream, const void* src, int64_t bytes, void* sink);
-
 }  // namespace camera

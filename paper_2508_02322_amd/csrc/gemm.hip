@@ -11,7 +11,7 @@
 // M-tiles of an expert in slot order, so the result is independent of launch
 // order and uses no floating-point atomics.
 //
-// bf16: v_mfma_f32_32x32x16_bf16 (64-wide wavefront, fp32 accumulate).  Token
+// bf16: v_mfma_f32_16x16x32_bf16 (64-wide wavefront, fp32 accumulate).  Token
 // rows (A operand, gathered through the bucket permutation) and weight rows (B
 // operand) are both K-contiguous, so both fragments are 16-byte LDS reads; the
 // LDS tiles are [row][8 chunks of 8 bf16] with the chunk index XOR-ed by
@@ -24,13 +24,6 @@
 #include <type_traits>
 
 #include "camera_internal.h"
-
-#ifndef CAMERA_GEMM_MI16
-#define CAMERA_GEMM_MI16 1
-#endif
-#ifndef CAMERA_GEMM_ASM_DMA
-#define CAMERA_GEMM_ASM_DMA 1
-#endif
 
 namespace camera {
 namespace {
@@ -113,11 +106,6 @@ __device__ __forceinline__ unsigned lds_address(const void* p) {
 #pragma clang diagnostic ignored "-Winline-asm"
 template <int IMM>
 __device__ __forceinline__ void lds_dma16(const unsigned char* p, unsigned lds) {
-#if !CAMERA_GEMM_ASM_DMA
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
-                                   (__attribute__((address_space(3))) void*)(size_t)lds, 16, IMM, 0);
-  return;
-#endif
   const unsigned base = __builtin_amdgcn_readfirstlane(lds);
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off offset:%2"
                :
@@ -166,10 +154,7 @@ struct GemmCfg {
   // Issue slots: a K step is kParts slots, slot 0 is the first one behind the barrier.  The loads of
   // a tile are dealt evenly over the first half of the slots (extra ones in the middle); the second
   // half stays empty, which is the time the youngest load has to land before the next barrier.
-#ifndef CAMERA_GEMM_SLOT_DIV
-#define CAMERA_GEMM_SLOT_DIV 4
-#endif
-  static constexpr int kParts = (2 * TM * TN) / CAMERA_GEMM_SLOT_DIV > 1 ? (2 * TM * TN) / CAMERA_GEMM_SLOT_DIV : 1;  // slots per K step
+  static constexpr int kParts = (2 * TM * TN) / 4 > 1 ? (2 * TM * TN) / 4 : 1;  // slots per K step
   static constexpr int kSlots = kParts * kSteps;
   static constexpr int kBusySlots = kSlots >= 2 ? kSlots / 2 : 1;
   static constexpr int issue_count(int p) {
@@ -229,234 +214,6 @@ struct TileState {
 // loads lies past the end of the expert's bucket (a short last tile); such rows only have to hold
 // finite values (their routing weight is 0), so they are loaded once, in the prologue, and
 // the K loop skips their loads.
-template <class C, int ACT, bool TAIL, bool DEAD, int EPI>
-__device__ __forceinline__ void tile_body(const TileState<C>& st, int n0, int d_ff, int slot, const EpiArgs& ep) {
-  static_assert(C::kBStages == C::kStages && !C::kAliasAux, "the 32x32x16 form keeps one ring depth and its own per-tile arrays");
-  constexpr int BN = C::BN, TN = C::TN, WM = C::WM, KT = C::KT;
-  constexpr int NA = ACT > 0 ? ACT : 1;
-  extern __shared__ __align__(16) unsigned char smem[];  // the workgroup's dynamic LDS, named here so that its address space is known
-  const unsigned lds0 = lds_address(smem);
-
-  // Lane l of a wave instruction writes LDS bytes [16 l, 16 l + 16) after the wave-uniform base,
-  // i.e. chunk position l % kChunks of row l / kChunks of its row group; to produce the swizzled
-  // image it reads logical chunk (l % kChunks) ^ swizzle_key(row) of that row (set up by the caller).
-  // TAIL (d_model not a multiple of KT): chunks past d_model come from a page of zeros.
-  // The instruction's immediate offset is added to the global and to the LDS address alike, so the
-  // j-th group of a wave uses immediate 1024 j on sources that were moved back by 1024 j bytes at
-  // set-up: one LDS base (M0) per matrix and tile instead of one per instruction.
-  auto dma = [&](const __hip_bfloat16* src, int k, int k0, unsigned dst, auto group) {
-    // immediate offsets reach 4095 bytes: groups 0-3 use the base, groups 4-7 the base + 4096
-    constexpr int kOff = (decltype(group)::value % 4) * 1024;
-    constexpr int kBase = (decltype(group)::value / 4) * 4096;
-    const unsigned char* p = reinterpret_cast<const unsigned char*>(src + k0);
-    if constexpr (TAIL) p = (k0 + k < st.d_model) ? p : reinterpret_cast<const unsigned char*>(st.zeros) - kOff;
-    lds_dma16<kOff>(p, dst + kBase);
-  };
-  // Load d of a tile's kLoadsPerTile wave instructions: the token groups first, then the gate
-  // groups, then the up groups (loads that share an LDS base follow each other).
-  auto dma_one = [&](int stage, int k0, auto index) {
-    constexpr int d = decltype(index)::value;
-    using std::integral_constant;
-    const unsigned sA = lds0 + stage * C::kStageBytes + st.a_lds;
-    const unsigned sG = lds0 + stage * C::kStageBytes + C::kATileBytes + st.b_lds;
-    if constexpr (d < C::kADma) {
-      dma(st.a_src[d], st.a_k[d], k0, sA, integral_constant<int, d>{});
-    } else if constexpr (d < C::kADma + C::kBDma) {
-      dma(st.g_src[d - C::kADma], st.b_k[d - C::kADma], k0, sG, integral_constant<int, d - C::kADma>{});
-    } else {
-      constexpr int j = d - C::kADma - C::kBDma;
-      dma(st.u_src[j], st.b_k[j], k0, sG + C::kBTileBytes, integral_constant<int, j>{});
-    }
-  };
-  // loads [C::issue_begin(P), C::issue_begin(P + 1)) of a tile: the share of issue slot P
-  auto dma_slot = [&](int stage, int k0, auto slot_index) {
-    constexpr int P = decltype(slot_index)::value;
-    static_for<C::issue_begin(P), C::issue_begin(P + 1)>([&](auto d) {
-      if constexpr (!(DEAD && decltype(d)::value < C::kADma)) dma_one(stage, k0, d);
-    });
-  };
-
-  f32x16 acc_g[NA][TN], acc_u[NA][TN];
-#pragma unroll
-  for (int i = 0; i < NA; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        acc_g[i][j][r] = 0.0f;
-        acc_u[i][j][r] = 0.0f;
-      }
-
-  struct Frags {
-    bf16x8 a[NA], g[TN], u[TN];
-  };
-  auto read_frags = [&](Frags& f, int stage, int ks) {
-    if constexpr (ACT > 0) {
-      const unsigned char* sA = smem + stage * C::kStageBytes + st.k_swz[ks];
-      const unsigned char* sG = sA + C::kATileBytes + st.b_frag_base;
-      const unsigned char* sU = sG + C::kBTileBytes;
-#pragma unroll
-      for (int i = 0; i < ACT; ++i)
-        f.a[i] = *reinterpret_cast<const bf16x8*>(sA + st.a_frag_base + i * WM * 32 * C::kRowBytes);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        f.g[j] = *reinterpret_cast<const bf16x8*>(sG + j * 32 * C::kRowBytes);
-        f.u[j] = *reinterpret_cast<const bf16x8*>(sU + j * 32 * C::kRowBytes);
-      }
-    }
-  };
-  // MFMAs [LO, HI) of one K step, numbered (row block i, channel block j, gate / up)
-  auto mfma_range = [&](const Frags& f, auto lo, auto hi) {
-    static_for<decltype(lo)::value, decltype(hi)::value>([&](auto m) {
-      constexpr int i = decltype(m)::value / (2 * TN), j = (decltype(m)::value / 2) % TN;
-      if constexpr (decltype(m)::value % 2 == 0)
-        acc_g[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.g[j], acc_g[i][j], 0, 0, 0);
-      else
-        acc_u[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.u[j], acc_u[i][j], 0, 0, 0);
-    });
-  };
-
-  // Ring schedule.  kStages tiles are in LDS or on their way; the barrier of iteration kt says that
-  // tile kt + 1 has landed and that nobody reads tile kt's stage any more, so tile kt + kStages goes
-  // into that stage.  Its loads are not issued in one go: a K step is kParts issue slots (four of the
-  // step's MFMAs each), the barrier sits before the last K step, and slot P counted from the barrier
-  // issues its share C::issue_begin(P) .. of the loads behind its MFMAs.  The order is pinned with
-  // scheduling barriers.  Back-to-back loads fill the wave's vector-memory queue and stall its
-  // MFMAs behind them; one or two at a time between groups of four MFMAs cost next to nothing.
-  // The last slots before the barrier stay empty, which is the time the youngest load has to land.
-  // Tiles past the end are clamped to the last one (redundant loads, never read) so that the loop
-  // body and the outstanding-load count never change.
-  const int n_k = (st.d_model + KT - 1) / KT;
-  const int k_last = (n_k - 1) * KT;
-  constexpr int kMayFly = C::kMayFly;  // loads younger than tile kt + 1
-  constexpr int kFull = 2 * ACT * TN;                           // MFMAs of a K step
-  using std::integral_constant;
-  Frags f[2];
-  // the tile whose loads are under way after the prologue: the slots of one K step here, the rest in the first iteration
-  int fill_stage = C::kStages - 1, fill_k = min((C::kStages - 1) * KT, k_last);
-  if constexpr (DEAD)  // first of all (oldest): the one-time fill of the token rows that the loop never loads
-    static_for<0, C::kADma>([&](auto d) { dma_one(fill_stage, fill_k, d); });
-#pragma unroll
-  for (int t = 0; t + 1 < C::kStages; ++t)
-    static_for<0, C::kLoadsPerTile>([&](auto d) { dma_one(t, min(t * KT, k_last), d); });
-  static_for<0, C::kParts>([&](auto p) { dma_slot(fill_stage, fill_k, p); });
-  // loads issued by these first slots (they may still fly; loads return in order, so tile 0 has landed)
-  constexpr int kFirst = C::issue_begin(C::kParts);
-  constexpr int kSlotsFirst = DEAD ? kFirst - (kFirst < C::kADma ? kFirst : C::kADma) : kFirst;
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly + kSlotsFirst) : "memory");
-  __syncthreads();
-  read_frags(f[0], 0, 0);
-  int stage = 0;  // stage of tile kt
-  for (int kt = 0; kt < n_k; ++kt) {
-    const int next = stage + 1 == C::kStages ? 0 : stage + 1;
-    static_for<0, C::kSteps>([&](auto step) {
-      constexpr int ks = decltype(step)::value;
-      constexpr bool last = ks + 1 == C::kSteps;
-      constexpr int P = last ? 0 : C::kParts * (ks + 1);  // issue slot of this step's first part
-      if constexpr (!last) {
-        read_frags(f[(ks + 1) & 1], stage, ks + 1);
-      } else {
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly) : "memory");
-        __syncthreads();
-        fill_stage = stage;
-        fill_k = min((kt + C::kStages) * KT, k_last);
-        read_frags(f[(ks + 1) & 1], next, 0);
-      }
-      static_for<0, C::kParts>([&](auto part) {
-        constexpr int q = decltype(part)::value;
-        mfma_range(f[ks & 1], integral_constant<int, kFull * q / C::kParts>{},
-                   integral_constant<int, kFull * (q + 1) / C::kParts>{});
-        dma_slot(fill_stage, fill_k, integral_constant<int, P + q>{});
-        __builtin_amdgcn_sched_barrier(0);
-      });
-    });
-    stage = next;
-  }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS at exit
-
-  // Epilogue.  Accumulator register r of lane l is output row 8*(r/4) + 4*(l/32) + (r%4),
-  // column l % 32 of its 32x32 tile: a lane owns one channel and 16 token rows per tile.
-  if constexpr (EPI != kEpiStats) {
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = n0 + st.wave_n * TN * 32 + j * 32 + st.frag_row;
-      if (col >= d_ff) {
-        if constexpr (EPI == kEpiHidden) {
-          if (ep.pad_hidden && col < (d_ff + ep.pad_hidden - 1) / ep.pad_hidden * ep.pad_hidden) {  // K padding of the contraction that reads these rows
-#pragma unroll
-            for (int i = 0; i < ACT; ++i) {
-              const int band = (WM * i + st.wave_m) * 32 + st.frag_half * 4;
-#pragma unroll
-              for (int r = 0; r < 16; ++r) {
-                const int row = band + (r / 4) * 8 + (r % 4);
-                if (row < st.m_len)
-                  static_cast<__hip_bfloat16*>(ep.hidden)[(st.row_first + row) * ep.ld_hidden + col] = __float2bfloat16(0.0f);
-              }
-            }
-          }
-        }
-        continue;
-      }
-      float kept = 1.0f;
-      if constexpr (EPI == kEpiHidden) kept = (ep.keep == nullptr || ep.keep[(int64_t)st.expert * d_ff + col]) ? 1.0f : 0.0f;
-#pragma unroll
-      for (int i = 0; i < ACT; ++i) {
-        const int band = (WM * i + st.wave_m) * 32 + st.frag_half * 4;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = band + (r / 4) * 8 + (r % 4);
-          if (row >= st.m_len) continue;
-          const int64_t out_row = st.row_first + row;
-          if constexpr (EPI == kEpiHidden) {
-            const float lam = st.s_a[row] * silu_f32(acc_g[i][j][r]) * acc_u[i][j][r] * kept;
-            static_cast<__hip_bfloat16*>(ep.hidden)[out_row * ep.ld_hidden + col] = __float2bfloat16(lam);
-          } else {
-            ep.product[out_row * ep.ld_product + col] = acc_g[i][j][r];
-            ep.product[out_row * ep.ld_product + col + ep.col_gap] = acc_u[i][j][r];
-          }
-        }
-      }
-    }
-  } else {
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    float sum = 0.0f, mx = 0.0f;
-#pragma unroll
-    for (int i = 0; i < ACT; ++i) {
-      const int band = (WM * i + st.wave_m) * 32 + st.frag_half * 4;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = band + (r / 4) * 8 + (r % 4);
-        const float lam = st.s_a[row] * silu_f32(acc_g[i][j][r]) * acc_u[i][j][r];
-        const float l2 = lam * lam;
-        sum += l2;
-        mx = fmaxf(mx, l2);
-      }
-    }
-    sum += __shfl_xor(sum, 32);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    if (st.frag_half == 0) {
-      const int col = st.wave_n * TN * 32 + j * 32 + st.frag_row;
-      st.s_red[st.wave_m * BN + col] = sum;
-      st.s_red[(WM + st.wave_m) * BN + col] = mx;
-    }
-  }
-  __syncthreads();
-  for (int col = threadIdx.x; col < BN; col += C::kThreads) {
-    if (n0 + col < d_ff) {
-      float sum = 0.0f, mx = 0.0f;
-#pragma unroll
-      for (int w = 0; w < WM; ++w) {  // fixed order
-        sum += st.s_red[w * BN + col];
-        mx = fmaxf(mx, st.s_red[(WM + w) * BN + col]);
-      }
-      ep.part_phi2[(int64_t)slot * d_ff + n0 + col] = sum;
-      ep.part_max[(int64_t)slot * d_ff + n0 + col] = mx;
-    }
-  }
-  }  // statistics epilogue
-}
-
 template <class C, int ACT, bool TAIL, bool DEAD, int EPI>
 __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int d_ff, int slot, const EpiArgs& ep) {
   constexpr int BN = C::BN, TN = C::TN, WM = C::WM, KT = C::KT;
@@ -564,10 +321,17 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
     });
   };
 
-  // Ring schedule as in the 32x32x16 form; what was a 16-deep K step there is a phase here: K step ks = phase / 2
-  // of 32 elements, channel sub-block b = phase % 2.  A phase has the flops of a 16-deep step, twice as many
-  // MFMAs of half the length, and reads the four B fragments of the next phase and, before a new K step, its
-  // four A fragments: the same LDS traffic per unit of time.
+  // Ring schedule.  Token tiles and weight tiles each cycle through their own ring of LDS stages; the barrier of
+  // iteration kt says that tile kt + 1 has landed and that nobody reads tile kt's stages any more, so the next
+  // token tile and the next weight tile go into them.  A K tile is four phases: K step ks = phase / 2 of 32
+  // elements, channel sub-block b = phase % 2; a phase reads the four B fragments of the next phase and, before a
+  // new K step, its four A fragments.  The loads of a tile are not issued in one go: a phase is kParts issue
+  // slots, the barrier sits before the last phase, and slot P counted from the barrier issues its share
+  // C::issue_begin(P) .. of the loads behind its MFMAs; the order is pinned with scheduling barriers.
+  // Back-to-back loads fill the wave's vector-memory queue and stall its MFMAs behind them; one or two at a time
+  // between groups of MFMAs cost next to nothing.  The last slots before the barrier stay empty, which is the
+  // time the youngest load has to land.  Tiles past the end are clamped to the last one (redundant loads, never
+  // read) so that the loop body and the outstanding-load count never change.
   static_assert(C::kSteps == 4, "two 32-deep K steps of two phases per K tile");
   const int n_k = (st.d_model + KT - 1) / KT;
   const int k_last = (n_k - 1) * KT;
@@ -777,13 +541,8 @@ __device__ __forceinline__ void run_tile(const TileWork& w, const __hip_bfloat16
   st.zeros = zeros;
   st.wave_m = wave % WM;
   st.wave_n = wave / WM;
-#if CAMERA_GEMM_MI16
   st.frag_row = lane % 16;   // 16x16x32: row of a 16-row sub-block
   st.frag_half = lane / 16;  // and the lane's quarter of the 32-wide K step
-#else
-  st.frag_row = lane % 32;
-  st.frag_half = lane / 32;
-#endif
   st.expert = e;
   st.m_len = m_len;
   st.row_first = row_first;
@@ -808,18 +567,12 @@ __device__ __forceinline__ void run_tile(const TileWork& w, const __hip_bfloat16
     st.g_src[j] = Wg + off - (j % 4) * 512;
     st.u_src[j] = Wu + off - (j % 4) * 512;
   }
-  // Fragments: lane l holds tile row (l % 32), K elements 8*(l / 32) .. +7 of a 16-wide K step.
-  // swizzle_key(row) only depends on row % 32 here (32-row blocks), so one key per lane.
+  // Fragments: lane l holds row (l % 16) of a 16-row sub-block, K elements 8*(l / 16) .. +7 of a 32-wide K step.
   st.a_frag_base = (st.wave_m * 32 + st.frag_row) * C::kRowBytes;       // + i*WM*32 rows: block WM*i + wave_m
   st.b_frag_base = (st.wave_n * TN * 32 + st.frag_row) * C::kRowBytes;  // + j*32 rows
-#if CAMERA_GEMM_MI16
-  // 16x16x32: the key of row (16 a + l % 16) of a block does not depend on a, so one key per lane here too
+  // the key of row (16 a + l % 16) of a block does not depend on a, so one key per lane here too
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) st.k_swz[ks] = ((ks * 4 + st.frag_half) ^ swizzle_key<C>(st.frag_row)) << 4;
-#else
-#pragma unroll
-  for (int ks = 0; ks < C::kSteps; ++ks) st.k_swz[ks] = ((ks * 2 + st.frag_half) ^ swizzle_key<C>(st.frag_row)) << 4;
-#endif
 
   // accumulator i of this wave covers row block WM*i + wave_m; blocks past m_len are skipped
   const int n_row_blocks = (m_len + 31) / 32;
@@ -827,11 +580,7 @@ __device__ __forceinline__ void run_tile(const TileWork& w, const __hip_bfloat16
   // With two stages the K loop waits for every outstanding load, so a wave may issue fewer of them.
   const bool dead = C::kStages == 2 && a_row0 >= m_len;  // (the ring of the token rows)
   static_assert(TM == 4 || TM == 2 || TM == 1, "dispatch below covers TM = 1, 2 and 4");
-#if CAMERA_GEMM_MI16
 #define CAMERA_TILE_FN tile_body16
-#else
-#define CAMERA_TILE_FN tile_body
-#endif
 #define CAMERA_TILE_BODY(A)                                                              \
   do {                                                                                   \
     if (dead) CAMERA_TILE_FN<C, (A), TAIL, true, EPI>(st, n0, d_ff, slot, ep);           \
@@ -1216,16 +965,10 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
 
 // Shape of the bf16 kernel: waves (M x N), 32x32 blocks per wave (M x N), K tile, stages of the token ring, stages
 // of the weight ring.
-#ifndef CAMERA_GEMM_CFG
-#define CAMERA_GEMM_CFG 4, 2, 2, 2, 64, 2, 3
-#endif
-using Bf16Cfg = GemmCfg<CAMERA_GEMM_CFG>;
+using Bf16Cfg = GemmCfg<4, 2, 2, 2, 64, 2, 3>;
 // Tiling of an expert's short last tile (at most 64 token rows): same eight waves and N extent, 2 x 4 waves of
 // one 32 x 32 block each, three stages of 40 KiB.
-#ifndef CAMERA_GEMM_TAIL_CFG
-#define CAMERA_GEMM_TAIL_CFG 2, 4, 1, 1, 64, 3
-#endif
-using Bf16TailCfg = GemmCfg<CAMERA_GEMM_TAIL_CFG>;
+using Bf16TailCfg = GemmCfg<2, 4, 1, 1, 64, 3>;
 
 }  // namespace
 

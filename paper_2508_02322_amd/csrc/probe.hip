@@ -8,10 +8,17 @@
 // is the one the grouped GEMM uses: at equal flops it keeps a clock about 10 % higher on
 // random data than v_mfma_f32_32x32x16_bf16 (measured 1.98 against 1.78 PFLOP/s).
 // probe_hbm: a streaming read of a buffer much larger than the caches.
-#include "camera_internal.h"
+//
+// Built into libcamera_bench.so (C ABI in include/camera_bench.h), apart from the product library: these are
+// measurements of the machine for benchmark reports, not steps of the method.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace camera {
+#include "../../include/camera_bench.h"
+
 namespace {
+
+constexpr int kWave = 64;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -109,29 +116,93 @@ __global__ __launch_bounds__(256) void probe_hbm_kernel(const u32x4* __restrict_
   if (s == 0x9e3779b9u) sink[0] = s;  // practically never: the store only keeps the compiler honest
 }
 
+constexpr int kIters = 4000;  // 256 000 MFMAs (16x16x32) per wave, about 3.5 ms per launch
+
+struct DeviceScope {
+  int prev = -1;
+  hipError_t enter(int device) {
+    hipError_t e = hipGetDevice(&prev);
+    if (e == hipSuccess && prev != device) e = hipSetDevice(device);
+    return e;
+  }
+  ~DeviceScope() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
 }  // namespace
 
-size_t probe_mfma_workspace_bytes() { return sizeof(float) * kProbeBlocks * kProbeThreads + 256; }
+extern "C" {
 
-hipError_t launch_probe_mfma(hipStream_t stream, bool random_operands, int iters, void* workspace) {
-  float* sink = static_cast<float*>(workspace);
-  unsigned long long* clocks =
-      reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + sizeof(float) * kProbeBlocks * kProbeThreads);
-  if (random_operands)
-    hipLaunchKernelGGL(probe_mfma_kernel<true>, dim3(kProbeBlocks), dim3(kProbeThreads), 0, stream, sink, iters, clocks);
-  else
-    hipLaunchKernelGGL(probe_mfma_kernel<false>, dim3(kProbeBlocks), dim3(kProbeThreads), 0, stream, sink, iters, clocks);
-  return hipGetLastError();
+int camera_bench_mfma_bf16(int device, int random_operands, int launches, double* tflops, double* shader_mhz) {
+  if (device < 0 || launches < 1 || launches > 1000 || tflops == nullptr || shader_mhz == nullptr) return -1;
+  DeviceScope scope;
+  if (scope.enter(device) != hipSuccess) return -5;
+  const size_t sink_bytes = sizeof(float) * kProbeBlocks * kProbeThreads;
+  char* buf = nullptr;
+  if (hipMalloc(&buf, sink_bytes + 256) != hipSuccess) return -4;
+  float* sink = reinterpret_cast<float*>(buf);
+  unsigned long long* clocks = reinterpret_cast<unsigned long long*>(buf + sink_bytes);
+  hipEvent_t t0 = nullptr, t1 = nullptr;
+  hipError_t e = hipEventCreate(&t0);
+  if (e == hipSuccess) e = hipEventCreate(&t1);
+  if (e == hipSuccess) e = hipMemset(clocks, 0, 256);
+  if (e == hipSuccess) e = hipEventRecord(t0, nullptr);
+  for (int i = 0; i < launches && e == hipSuccess; ++i) {
+    if (random_operands)
+      hipLaunchKernelGGL(probe_mfma_kernel<true>, dim3(kProbeBlocks), dim3(kProbeThreads), 0, nullptr, sink, kIters, clocks);
+    else
+      hipLaunchKernelGGL(probe_mfma_kernel<false>, dim3(kProbeBlocks), dim3(kProbeThreads), 0, nullptr, sink, kIters, clocks);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipEventRecord(t1, nullptr);
+  if (e == hipSuccess) e = hipEventSynchronize(t1);
+  float ms = 0.0f;
+  unsigned long long host_clocks[2] = {0, 0};
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
+  if (e == hipSuccess) e = hipMemcpy(host_clocks, clocks, sizeof(host_clocks), hipMemcpyDeviceToHost);
+  if (t0) (void)hipEventDestroy(t0);
+  if (t1) (void)hipEventDestroy(t1);
+  (void)hipFree(buf);
+  if (e != hipSuccess) return -5;
+  const double flops = 2.0 * 16 * 16 * 32 * kMfmaPerIter * (double)kIters * (kProbeThreads / kWave) * kProbeBlocks;
+  *tflops = flops * launches / (ms * 1e-3) / 1e12;
+  *shader_mhz = host_clocks[1] ? 100.0 * (double)host_clocks[0] / (double)host_clocks[1] : 0.0;
+  return 0;
 }
 
-double probe_mfma_flops(int iters) {
-  return 2.0 * 16 * 16 * 32 * kMfmaPerIter * (double)iters * (kProbeThreads / kWave) * kProbeBlocks;
+int camera_bench_hbm_read(int device, int64_t bytes, int launches, double* gb_per_s) {
+  if (device < 0 || bytes < (int64_t(1) << 20) || bytes > (int64_t(1) << 36) || bytes % 16 != 0) return -1;
+  if (launches < 1 || launches > 1000 || gb_per_s == nullptr) return -1;
+  DeviceScope scope;
+  if (scope.enter(device) != hipSuccess) return -5;
+  char* buf = nullptr;
+  if (hipMalloc(&buf, (size_t)bytes + 256) != hipSuccess) return -4;
+  uint32_t* sink = reinterpret_cast<uint32_t*>(buf + bytes);
+  const dim3 grid(256 * 16), block(256);
+  hipEvent_t t0 = nullptr, t1 = nullptr;
+  hipError_t e = hipEventCreate(&t0);
+  if (e == hipSuccess) e = hipEventCreate(&t1);
+  if (e == hipSuccess) e = hipMemset(buf, 0x5a, (size_t)bytes + 256);
+  if (e == hipSuccess) {  // warm-up
+    hipLaunchKernelGGL(probe_hbm_kernel, grid, block, 0, nullptr, reinterpret_cast<const u32x4*>(buf), bytes / 16, sink);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipEventRecord(t0, nullptr);
+  for (int i = 0; i < launches && e == hipSuccess; ++i) {
+    hipLaunchKernelGGL(probe_hbm_kernel, grid, block, 0, nullptr, reinterpret_cast<const u32x4*>(buf), bytes / 16, sink);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipEventRecord(t1, nullptr);
+  if (e == hipSuccess) e = hipEventSynchronize(t1);
+  float ms = 0.0f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
+  if (t0) (void)hipEventDestroy(t0);
+  if (t1) (void)hipEventDestroy(t1);
+  (void)hipFree(buf);
+  if (e != hipSuccess) return -5;
+  *gb_per_s = (double)bytes * launches / (ms * 1e-3) / 1e9;
+  return 0;
 }
 
-hipError_t launch_probe_hbm(hipStream_t stream, const void* src, int64_t bytes, void* sink) {
-  hipLaunchKernelGGL(probe_hbm_kernel, dim3(256 * 16), dim3(256), 0, stream, static_cast<const u32x4*>(src), bytes / 16,
-                     static_cast<uint32_t*>(sink));
-  return hipGetLastError();
-}
-
-}  // namespace camera
+}  // extern "C"

@@ -143,13 +143,22 @@ def test_create_and_profile_checks(lib, ctx):
     ms, cnt = ctypes.c_double(), i64()
     assert lib.camera_profile_read(ctx, 99, ctypes.byref(ms), ctypes.byref(cnt)) == -1
     assert lib.camera_profile_read(ctx, 0, None, ctypes.byref(cnt)) == -1
+
+
+def test_bench_library_exports_and_argument_checks():
+    """The machine probes live in a library of their own (include/camera_bench.h), not in the product ABI."""
+    from paper_2508_02322_amd import bench_probes
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "camera_bench.h")).read(), flags=re.S)
+    assert sorted(set(re.findall(r"\b(camera_bench_[a-z0-9_]+)\s*\(", text))) == sorted(bench_probes.EXPORTS)
+    blib = bench_probes.load_library()
     tf, mhz = ctypes.c_double(), ctypes.c_double()
-    assert lib.camera_probe_mfma_bf16(None, None, 1, 1, ctypes.byref(tf), ctypes.byref(mhz)) == -1
-    assert lib.camera_probe_mfma_bf16(ctx, None, 1, 0, ctypes.byref(tf), ctypes.byref(mhz)) == -1
-    assert lib.camera_probe_mfma_bf16(ctx, None, 1, 1, None, ctypes.byref(mhz)) == -1
-    assert lib.camera_probe_hbm_read(ctx, None, 1000, 1, ctypes.byref(tf)) == -1
-    assert lib.camera_probe_hbm_read(ctx, None, 1 << 30, 0, ctypes.byref(tf)) == -1
-    assert lib.camera_probe_hbm_read(ctx, None, 1 << 30, 1, None) == -1
+    assert blib.camera_bench_mfma_bf16(0, 1, 0, ctypes.byref(tf), ctypes.byref(mhz)) == -1
+    assert blib.camera_bench_mfma_bf16(0, 1, 1, None, ctypes.byref(mhz)) == -1
+    assert blib.camera_bench_mfma_bf16(-1, 1, 1, ctypes.byref(tf), ctypes.byref(mhz)) == -1
+    assert blib.camera_bench_hbm_read(0, 1000, 1, ctypes.byref(tf)) == -1
+    assert blib.camera_bench_hbm_read(0, 1 << 30, 0, ctypes.byref(tf)) == -1
+    assert blib.camera_bench_hbm_read(0, 1 << 30, 1, None) == -1
+    assert not any(hasattr(binding.load_library(), n) for n in ("camera_probe_mfma_bf16", "camera_bench_mfma_bf16"))
 
 
 def test_missing_library_fails_loudly(tmp_path):

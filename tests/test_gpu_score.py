@@ -221,11 +221,12 @@ def test_tiny_config_end_to_end(cam):
     np.testing.assert_array_equal(per.cpu().numpy(), o_per)
 
 
-def test_machine_probes_report_plausible_ceilings(cam):
+def test_machine_probes_report_plausible_ceilings():
     """The probes are measurements, not results: check their range and that random operands are not faster."""
-    tf_const, mhz_const = cam.probe_mfma_bf16(False, launches=10)
-    tf_rand, mhz_rand = cam.probe_mfma_bf16(True, launches=10)
+    from paper_2508_02322_amd import bench_probes
+    tf_const, mhz_const = bench_probes.mfma_bf16(False, launches=10)
+    tf_rand, mhz_rand = bench_probes.mfma_bf16(True, launches=10)
     assert 500.0 < tf_rand <= tf_const * 1.05 and tf_const < 2600.0
     assert 800.0 < mhz_rand < 2600.0 and 800.0 < mhz_const < 2600.0
-    gbs = cam.probe_hbm_read(1 << 30, launches=3)
+    gbs = bench_probes.hbm_read(1 << 30, launches=3)
     assert 1000.0 < gbs < 8500.0
