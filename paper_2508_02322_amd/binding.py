@@ -82,6 +82,41 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else _vp(t.data_ptr())
 
 
+def _require(cond: bool, message: str):
+    """Layouts the library cannot see from a pointer and one stride: refuse them here instead of reading wrong bytes."""
+    if not cond:
+        raise CameraError(-2, message)
+
+
+def _check_matrix(t, name: str, like=None):
+    """[rows, cols] with unit inner stride (the row stride is passed on)."""
+    if t is None:
+        return
+    _require(t.dim() == 2 and t.stride(1) == 1, f"{name}: must be 2-D with unit inner stride (got strides {tuple(t.stride())})")
+    if like is not None:
+        _require(t.dtype == like.dtype and t.device == like.device, f"{name}: dtype / device differ from X")
+
+
+def _check_experts(t, name: str, like=None):
+    """[N_E, rows, cols] with contiguous rows exactly cols apart (the expert stride is passed on)."""
+    if t is None:
+        return
+    _require(t.dim() == 3 and t.stride(2) == 1 and t.stride(1) == t.shape[2],
+             f"{name}: must be [experts, rows, cols] with rows contiguous and cols apart (got strides {tuple(t.stride())})")
+    if like is not None:
+        _require(t.dtype == like.dtype and t.device == like.device, f"{name}: dtype / device differ from X")
+
+
+def _check_flat(t, name: str, dtype=None, device=None):
+    if t is None:
+        return
+    _require(t.is_contiguous(), f"{name}: must be contiguous")
+    if dtype is not None:
+        _require(t.dtype == dtype, f"{name}: must be {dtype}")
+    if device is not None:
+        _require(t.device == device, f"{name}: on another device")
+
+
 def _stream_handle(device) -> _vp:
     return _vp(torch.cuda.current_stream(device).cuda_stream)
 
@@ -113,8 +148,27 @@ class Camera:
         if rc != 0:
             raise CameraError(rc, self.lib.camera_last_error(self._ctx).decode())
 
+    @staticmethod
+    def _check_layer(X, topk_idx, topk_w, W_gate, W_up, W_down):
+        _check_matrix(X, "X")
+        _check_experts(W_gate, "W_gate", like=X)
+        _check_experts(W_up, "W_up", like=X)
+        _check_experts(W_down, "W_down", like=X)
+        _check_flat(topk_idx, "topk_idx", torch.int32, X.device)
+        _check_flat(topk_w, "topk_w", torch.float32, X.device)
+        if W_gate is not None and W_up is not None:
+            _require(W_gate.shape == W_up.shape and W_gate.stride(0) == W_up.stride(0), "W_gate / W_up: shapes or expert strides differ")
+        if W_gate is not None:
+            _require(W_gate.shape[2] == X.shape[1], "W_gate: d_model differs from X")
+        if W_gate is not None and W_down is not None:
+            _require(W_down.shape[0] == W_gate.shape[0] and W_down.shape[1] == W_gate.shape[2] and W_down.shape[2] == W_gate.shape[1],
+                     "W_down: must be [experts, d_model, d_ff]")
+
     # ---- entry points ------------------------------------------------------
     def route_topk(self, X, W_r, bias, top_k: int, renorm: bool = True):
+        _check_matrix(X, "X")
+        _check_matrix(W_r, "W_r", like=X)
+        _check_flat(bias, "bias", torch.float32, X.device)
         n, d = X.shape
         n_experts = W_r.shape[0]
         idx = torch.empty((n, top_k), dtype=torch.int32, device=self.device)
@@ -127,9 +181,13 @@ class Camera:
     def score_layer(self, X, topk_idx, topk_w, W_gate, W_up, W_down, alpha: float, flags: int = 0, out=None):
         """W_gate / W_up [N_E, d_ff, d_model], W_down [N_E, d_model, d_ff] (None with NO_FINALIZE).
         Returns dict(phi2, phi_inf, omega2, energy); pass `out` to reuse / accumulate into buffers."""
+        self._check_layer(X, topk_idx, topk_w, W_gate, W_up, W_down)
         n, d = X.shape
         n_experts, d_ff, _ = W_gate.shape
         n_micro = n_experts * d_ff
+        if out is not None:
+            for k, v in out.items():
+                _check_flat(v, k, torch.float32, X.device)
         if out is None:
             out = {k: torch.empty(n_micro, dtype=torch.float32, device=self.device)
                    for k in ("phi2", "phi_inf", "omega2", "energy")}
@@ -142,6 +200,7 @@ class Camera:
         return out
 
     def select_prune(self, energy, seg_offsets: Sequence[int], ratio: float, want_idx=False, want_rank=False):
+        _check_flat(energy, "energy", torch.float32)
         n_micro = energy.numel()
         n_seg = len(seg_offsets) - 1
         seg = (_i64 * (n_seg + 1))(*seg_offsets)
@@ -158,6 +217,10 @@ class Camera:
     def select_prune_noalloc(self, energy, seg_offsets: Sequence[int], ratio: float, keep, per_expert, kept_idx=None):
         """camera_select_prune_noalloc: the caller brings every output (keep uint8 [n_micro], per_expert int32
         [n_seg], kept_idx int32 [>= kept] or None); the call itself allocates nothing on the device."""
+        _check_flat(energy, "energy", torch.float32)
+        _check_flat(keep, "keep", torch.uint8, energy.device)
+        _check_flat(per_expert, "per_expert", torch.int32, energy.device)
+        _check_flat(kept_idx, "kept_idx", torch.int32, energy.device)
         n_seg = len(seg_offsets) - 1
         seg = (_i64 * (n_seg + 1))(*seg_offsets)
         self._check(self.lib.camera_select_prune_noalloc(
@@ -167,6 +230,7 @@ class Camera:
     def select_prune_multi(self, energy, seg_offsets, ratios, out=None):
         """Masks at several rising ratios from one ranking pass: (keep_bits uint8 [n_micro] with bit k = kept at
         ratios[k], kept_per_expert int32 [len(ratios), n_seg])."""
+        _check_flat(energy, "energy", torch.float32)
         n_micro = energy.numel()
         n_seg = len(seg_offsets) - 1
         seg = (_i64 * (n_seg + 1))(*seg_offsets)
@@ -180,6 +244,7 @@ class Camera:
 
     def alloc_bits(self, energy, seg_offsets: Sequence[int], bits: Sequence[int], ratios: Sequence[float],
                    want_perm=False):
+        _check_flat(energy, "energy", torch.float32)
         n_micro = energy.numel()
         n_seg = len(seg_offsets) - 1
         n_levels = len(bits)
@@ -200,6 +265,10 @@ class Camera:
         Returns (gate_out [n_index, d_model], up_out, down_out flat: sized for the longest padding when
         allocated here, [d_model][ld(e)] blocks one after the other)."""
         ref = W_gate if W_gate is not None else (W_up if W_up is not None else W_down)
+        for name, t in (("W_gate", W_gate), ("W_up", W_up), ("W_down", W_down)):
+            _check_experts(t, name)
+        _check_flat(index, "index", torch.int32, ref.device)
+        _check_flat(count, "count", torch.int32, ref.device)
         n_experts = ref.shape[0]
         d_ff, d_model = (ref.shape[1], ref.shape[2]) if ref is not W_down else (ref.shape[2], ref.shape[1])
         n_index = index.numel()
@@ -216,6 +285,9 @@ class Camera:
 
     def layer_forward(self, X, topk_idx, topk_w, W_gate, W_up, W_down, keep_mask=None, Y=None, accumulate=False):
         """Layer output over the kept micro-experts of one group of experts (Eq. 1-2); Y float32 [n, d_model]."""
+        self._check_layer(X, topk_idx, topk_w, W_gate, W_up, W_down)
+        _check_flat(keep_mask, "keep_mask", torch.uint8, X.device)
+        _check_flat(Y, "Y", torch.float32, X.device)
         n, d = X.shape
         n_experts, d_ff, _ = W_gate.shape
         top_k = 0 if topk_idx is None else topk_idx.shape[1]
@@ -232,6 +304,12 @@ class Camera:
         """Layer output from compacted weights (the outputs of gather_micro_experts, with the same
         down_row_align); count: per-expert kept micro-experts as a sequence of Python ints, the last n_shared
         of them shared experts (every token, weight 1).  Y float32 [n, d_model]."""
+        _check_matrix(X, "X")
+        for name, t in (("W_gate_c", W_gate_c), ("W_up_c", W_up_c), ("W_down_c", W_down_c)):
+            _check_flat(t, name, X.dtype, X.device)
+        _check_flat(topk_idx, "topk_idx", torch.int32, X.device)
+        _check_flat(topk_w, "topk_w", torch.float32, X.device)
+        _check_flat(Y, "Y", torch.float32, X.device)
         n, d = X.shape
         counts = [int(c) for c in count]
         top_k = 0 if topk_idx is None else topk_idx.shape[1]
@@ -245,6 +323,8 @@ class Camera:
 
     def output_error(self, Y, Y_hat):
         """Per-token [n, 4]: ||y - y_hat||^2, ||y||^2, ||y_hat||^2, <y, y_hat>."""
+        _check_flat(Y, "Y", torch.float32)
+        _check_flat(Y_hat, "Y_hat", torch.float32, Y.device)
         n, d = Y.shape
         out = torch.empty((n, 4), dtype=torch.float32, device=self.device)
         self._check(self.lib.camera_output_error(self._ctx, _stream_handle(self.device), _ptr(Y), _ptr(Y_hat), n, d,

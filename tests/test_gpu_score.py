@@ -230,3 +230,26 @@ def test_machine_probes_report_plausible_ceilings():
     assert 800.0 < mhz_rand < 2600.0 and 800.0 < mhz_const < 2600.0
     gbs = bench_probes.hbm_read(1 << 30, launches=3)
     assert 1000.0 < gbs < 8500.0
+
+
+def test_non_contiguous_inputs_are_refused_or_honoured(cam):
+    """Views the library can describe (a row stride on X, an expert stride on the weights) give the same scores as
+    packed tensors; views it cannot (transposed, inner stride) raise instead of scoring the wrong bytes."""
+    cfg = small(n_tokens=200, d_model=64, d_ff=48, n_experts=4, top_k=2)
+    dev = H.to_dev(inputs.make_layer(cfg, 5))
+    idx, w = cam.route_topk(dev["X"], dev["W_r"], dev["bias"], 2)
+    want = cam.score_layer(dev["X"], idx, w, dev["W_gate"], dev["W_up"], dev["W_down"], 0.95)
+    wide = torch.zeros((200, 96), dtype=dev["X"].dtype, device="cuda")
+    wide[:, :64] = dev["X"]
+    padded = {k: torch.zeros((7, *dev[k].shape[1:]), dtype=dev[k].dtype, device="cuda") for k in ("W_gate", "W_up", "W_down")}
+    for k in padded:
+        padded[k][::2] = dev[k]                      # experts two slabs apart
+    got = cam.score_layer(wide[:, :64], idx, w, padded["W_gate"][::2], padded["W_up"][::2], padded["W_down"][::2], 0.95)
+    for k in want:
+        assert torch.equal(want[k], got[k]), k
+    with pytest.raises(binding.CameraError):
+        cam.score_layer(dev["X"].t().contiguous().t(), idx, w, dev["W_gate"], dev["W_up"], dev["W_down"], 0.95)
+    with pytest.raises(binding.CameraError):
+        cam.score_layer(dev["X"], idx, w, dev["W_gate"], dev["W_up"], dev["W_down"].transpose(1, 2).contiguous().transpose(1, 2), 0.95)
+    with pytest.raises(binding.CameraError):
+        cam.score_layer(dev["X"], idx.cpu(), w, dev["W_gate"], dev["W_up"], dev["W_down"], 0.95)

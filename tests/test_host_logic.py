@@ -78,3 +78,36 @@ def test_product_path_never_imports_the_oracle():
                 assert "camera_oracle" not in text, name
     oracle_text = open(os.path.join(ROOT, "oracle", "camera_oracle.py")).read()
     assert "paper_2508_02322_amd" not in re.sub(r'""".*?"""', "", oracle_text, flags=re.S)
+
+
+def test_binding_refuses_layouts_the_library_cannot_see():
+    """A transposed or sliced view, a foreign dtype or device: an error, not silently wrong scores.  The checks run
+    before anything touches the GPU, so host tensors serve here."""
+    import pytest
+    from paper_2508_02322_amd import binding
+    cam = binding.Camera(device=0)      # creation touches no GPU
+    bf = torch.bfloat16
+    X = torch.zeros((16, 32), dtype=bf)
+    W_r = torch.zeros((4, 32), dtype=bf)
+    Wg = torch.zeros((4, 8, 32), dtype=bf)
+    Wd = torch.zeros((4, 32, 8), dtype=bf)
+    idx = torch.zeros((16, 2), dtype=torch.int32)
+    w = torch.zeros((16, 2), dtype=torch.float32)
+
+    def refused(fn, *a, **kw):
+        with pytest.raises(binding.CameraError) as exc:
+            fn(*a, **kw)
+        assert exc.value.code == -2, exc.value
+        return exc.value.message
+
+    assert "X" in refused(cam.route_topk, torch.zeros((32, 16), dtype=bf).t(), W_r, None, 2)          # transposed
+    assert "W_r" in refused(cam.route_topk, X, torch.zeros((4, 64), dtype=bf)[:, ::2], None, 2)       # inner stride 2
+    assert "W_r" in refused(cam.route_topk, X, W_r.float(), None, 2)                                  # dtype differs
+    assert "W_gate" in refused(cam.score_layer, X, idx, w, Wg.transpose(1, 2).contiguous().transpose(1, 2), Wg, Wd, 0.5)
+    assert "W_up" in refused(cam.score_layer, X, idx, w, Wg, torch.zeros((4, 8, 64), dtype=bf)[:, :, :32], Wd, 0.5)  # rows too far apart
+    assert "W_down" in refused(cam.score_layer, X, idx, w, Wg, Wg, Wg, 0.5)                            # not [experts, d_model, d_ff]
+    assert "topk_w" in refused(cam.score_layer, X, idx, w.double(), Wg, Wg, Wd, 0.5)
+    assert "energy" in refused(cam.select_prune, torch.zeros(64)[::2], [0, 32], 0.5)
+    assert "energy" in refused(cam.alloc_bits, torch.zeros(32, dtype=torch.float64), [0, 32], [3, 2], [0.5, 0.5])
+    assert "Y" in refused(cam.layer_forward, X, idx, w, Wg, Wg, Wd, Y=torch.zeros((32, 16)).t())
+    cam.close()
