@@ -20,7 +20,8 @@
  *     checks run on the host before any GPU call; camera_last_error() then
  *     names the offending argument.  No exception or abort crosses this ABI.
  *   - The context owns a grow-only device workspace (hipMalloc on first use and
- *     on growth, which synchronises the device).
+ *     on growth, which synchronises the device) and, for the ranking calls, a
+ *     small persistent selection state made on their first use.
  *   - NaN / Inf in the inputs: results unspecified (not checked).
  *   - Device data pointers must be 16-byte aligned; for CAMERA_BF16 d_model and
  *     ldx must be multiples of 8, for CAMERA_F32 multiples of 4.
@@ -222,6 +223,22 @@ int camera_alloc_bits(camera_ctx* ctx, void* stream,
                       const int64_t* seg_offsets, int n_seg,
                       int n_levels, const int* bits, const double* ratios,
                       uint8_t* bit_of, int32_t* level_count, int32_t* perm);
+
+/*
+ * Both decisions of a layer from one pass over its ranking: the CAMERA-P masks at n_ratios pruning ratios
+ * (Algorithm 2, line 9: TopSelect) and one CAMERA-Q bit allocation (Algorithm 3, lines 5-8: ListSplitByRatio and
+ * GetSubIndex).  The pruning thresholds and the class boundaries are all cuts on the same stable ascending order of
+ * (energy, index), so one set of selection passes serves both.  Arguments and outputs as in
+ * camera_select_prune_multi (ratios, keep_bits, kept_per_expert) and camera_alloc_bits (bits, level_ratios, bit_of,
+ * level_count, perm), bit for bit the same results as those two calls.  n_ratios >= 1, n_levels >= 1 and
+ * n_ratios + n_levels - 1 <= CAMERA_MAX_LEVELS - 1 (the cuts one pass carries).
+ */
+int camera_rank_decisions(camera_ctx* ctx, void* stream,
+                          const float* energy, int64_t n_micro,
+                          const int64_t* seg_offsets, int n_seg,
+                          int n_ratios, const double* ratios, uint8_t* keep_bits, int32_t* kept_per_expert,
+                          int n_levels, const int* bits, const double* level_ratios,
+                          uint8_t* bit_of, int32_t* level_count, int32_t* perm);
 
 /*
  * W_up, W_gate, W_down <- W_up[S,:], W_gate[S,:], W_down[:,S]  -- Algorithm 2 (CAMERA-P), lines 10-13: only

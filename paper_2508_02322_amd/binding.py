@@ -22,7 +22,7 @@ KERNEL_NAMES = ["route", "bucket", "gemm", "down_norm", "finalize", "rank", "gat
                 "compact_hidden", "compact_down"]
 
 EXPORTS = ["camera_create", "camera_destroy", "camera_last_error", "camera_version", "camera_route_topk",
-           "camera_score_layer", "camera_select_prune", "camera_select_prune_noalloc", "camera_select_prune_multi", "camera_alloc_bits",
+           "camera_score_layer", "camera_select_prune", "camera_select_prune_noalloc", "camera_select_prune_multi", "camera_alloc_bits", "camera_rank_decisions",
            "camera_gather_micro_experts", "camera_layer_forward", "camera_layer_forward_compact", "camera_output_error", "camera_profile_enable",
            "camera_profile_read"]
 
@@ -55,6 +55,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.camera_select_prune_multi.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _i, _c.POINTER(_d), _vp, _vp]
     lib.camera_alloc_bits.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _i, _c.POINTER(_i),
                                       _c.POINTER(_d), _vp, _vp, _vp]
+    lib.camera_rank_decisions.argtypes = [_vp, _vp, _vp, _i64, _c.POINTER(_i64), _i, _i, _c.POINTER(_d), _vp, _vp, _i,
+                                          _c.POINTER(_i), _c.POINTER(_d), _vp, _vp, _vp]
     lib.camera_gather_micro_experts.argtypes = [_vp, _vp, _i, _i, _i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, _i64,
                                                 _i64, _vp, _i, _vp, _vp, _vp]
     lib.camera_layer_forward.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _vp, _i, _i, _i64, _vp, _vp, _i64,
@@ -256,6 +258,26 @@ class Camera:
             self._ctx, _stream_handle(self.device), _ptr(energy), n_micro, seg, n_seg, n_levels,
             (_i * n_levels)(*bits), (_d * len(ratios))(*ratios), _ptr(bit_of), _ptr(level_count), _ptr(perm)))
         return bit_of, level_count, perm
+
+    def rank_decisions(self, energy, seg_offsets, prune_ratios, bits, level_ratios, want_perm=False, out=None):
+        """The CAMERA-P masks at several rising ratios and one CAMERA-Q bit allocation from one pass over the
+        ranking: (keep_bits, kept_per_expert [len(prune_ratios), n_seg], bit_of, level_count [n_seg, len(bits)], perm)."""
+        _check_flat(energy, "energy", torch.float32)
+        n_micro = energy.numel()
+        n_seg = len(seg_offsets) - 1
+        seg = (_i64 * (n_seg + 1))(*seg_offsets)
+        if out is None:
+            out = (torch.empty(n_micro, dtype=torch.uint8, device=self.device),
+                   torch.empty((len(prune_ratios), n_seg), dtype=torch.int32, device=self.device),
+                   torch.empty(n_micro, dtype=torch.uint8, device=self.device),
+                   torch.empty((n_seg, len(bits)), dtype=torch.int32, device=self.device),
+                   torch.empty(n_micro, dtype=torch.int32, device=self.device) if want_perm else None)
+        self._check(self.lib.camera_rank_decisions(
+            self._ctx, _stream_handle(self.device), _ptr(energy), n_micro, seg, n_seg, len(prune_ratios),
+            (_d * len(prune_ratios))(*[float(r) for r in prune_ratios]), _ptr(out[0]), _ptr(out[1]), len(bits),
+            (_i * len(bits))(*bits), (_d * len(level_ratios))(*[float(r) for r in level_ratios]), _ptr(out[2]), _ptr(out[3]),
+            _ptr(out[4])))
+        return out
 
     def gather_micro_experts(self, W_gate, W_up, W_down, index, count=None, index_base=0, out=None, down_row_align=1):
         """Kept gate / up rows and down columns of one group of experts (Algorithm 2, lines 10-13).

@@ -18,6 +18,8 @@ struct camera_ctx {
   void* ws = nullptr;
   size_t ws_bytes = 0;
   void* zeros = nullptr;                         // 256 zero bytes, made on first use
+  void* rank_state = nullptr;                    // persistent select state of the ranking kernels (zero when made, self-cleaning)
+  bool rank_dirty = false;                       // a ranking call failed between its passes: clear the state before the next
   bool profiling = false;
   struct Span {
     hipEvent_t begin, end;
@@ -37,6 +39,7 @@ namespace {
 constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
 void* g_scratch_ptr[kMaxDevices] = {nullptr};
+bool g_scratch_dirty[kMaxDevices] = {false};
 
 char g_create_error[256] = {0};
 
@@ -153,6 +156,21 @@ int ensure_workspace(camera_ctx* ctx, size_t bytes) {
   return CAMERA_OK;
 }
 
+int ensure_rank_state(camera_ctx* ctx) {
+  if (ctx->rank_state != nullptr) return CAMERA_OK;
+  const size_t bytes = camera::rank_state_bytes();
+  hipError_t e = hipMalloc(&ctx->rank_state, bytes);
+  if (e == hipSuccess) e = hipMemset(ctx->rank_state, 0, bytes);
+  if (e == hipSuccess) e = hipDeviceSynchronize();  // once: visible to every stream from here on
+  if (e != hipSuccess) {
+    if (ctx->rank_state) (void)hipFree(ctx->rank_state);
+    ctx->rank_state = nullptr;
+    (void)hipGetLastError();
+    return fail(ctx, CAMERA_EWORKSPACE, "select state: %s", hipGetErrorString(e));
+  }
+  return CAMERA_OK;
+}
+
 // Event bracket around one launch group when profiling is on.
 struct Bracket {
   camera_ctx* ctx;
@@ -233,7 +251,7 @@ int camera_create(camera_ctx** out, int device) {
 int camera_destroy(camera_ctx* ctx) {
   if (ctx == nullptr) return CAMERA_OK;
   int rc = CAMERA_OK;
-  if (ctx->ws || ctx->zeros || !ctx->free_spans.empty()) {
+  if (ctx->ws || ctx->zeros || ctx->rank_state || !ctx->free_spans.empty()) {
     DeviceGuard guard;
     (void)guard.enter(ctx->device);
     for (auto& v : ctx->spans)
@@ -244,6 +262,7 @@ int camera_destroy(camera_ctx* ctx) {
     }
     if (ctx->ws && hipFree(ctx->ws) != hipSuccess) rc = CAMERA_EHIP;
     if (ctx->zeros && hipFree(ctx->zeros) != hipSuccess) rc = CAMERA_EHIP;
+    if (ctx->rank_state && hipFree(ctx->rank_state) != hipSuccess) rc = CAMERA_EHIP;
   }
   delete ctx;
   return rc;
@@ -725,43 +744,163 @@ int camera_output_error(camera_ctx* ctx, void* stream_, const float* Y, const fl
   return CAMERA_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+// The host side of every ranking entry point: the cuts of the pruning ratios and of the precision-level boundaries
+// on the common order, the tables that turn a class (number of cuts an element is below) into the two output bytes
+// and the per-segment counts, and the launch sequence.
+struct RankRequest {
+  int n_ratios = 0;             // CAMERA-P: pruning ratios, not falling
+  const double* ratios = nullptr;
+  bool single_mask = false;     // camera_select_prune: one ratio, the output byte is 1 (kept) / 0, kept_idx may be asked for
+  uint8_t* keep_out = nullptr;  // keep_mask or keep_bits
+  int32_t* kept = nullptr;      // [n_ratios][n_seg]
+  int32_t* kept_idx = nullptr;
+  int n_levels = 0;             // CAMERA-Q: precision levels, most important first
+  const int* bits = nullptr;
+  const double* level_ratios = nullptr;
+  uint8_t* bit_of = nullptr;
+  int32_t* level_count = nullptr;
+  int32_t* perm = nullptr;
+  uint32_t* rank = nullptr;     // full ascending rank (camera_select_prune only)
+};
+
+int check_ratios(camera_ctx* ctx, const RankRequest& r) {
+  if (r.n_ratios > 0) {
+    if (r.ratios == nullptr) return fail(ctx, CAMERA_EINVAL, "ratios: NULL");
+    for (int k = 0; k < r.n_ratios; ++k) {
+      if (!(r.ratios[k] >= 0.0 && r.ratios[k] <= 1.0))
+        return fail(ctx, CAMERA_EINVAL, r.single_mask ? "ratio: must be in [0, 1]" : "ratios[%d]: must be in [0, 1]", k);
+      if (k > 0 && r.ratios[k] < r.ratios[k - 1]) return fail(ctx, CAMERA_EINVAL, "ratios: must not fall");
+    }
+  }
+  if (r.n_levels > 0) {
+    if (r.bits == nullptr || r.level_ratios == nullptr) return fail(ctx, CAMERA_EINVAL, "bits / ratios: NULL");
+    double total = 0.0;
+    for (int m = 0; m < r.n_levels; ++m) {
+      if (!(r.level_ratios[m] >= 0.0)) return fail(ctx, CAMERA_EINVAL, "ratios[%d]: negative", m);
+      if (r.bits[m] < 0 || r.bits[m] > 255) return fail(ctx, CAMERA_EINVAL, "bits[%d]: must be in [0, 255]", m);
+      total += r.level_ratios[m];
+    }
+    if (std::fabs(total - 1.0) > 1e-9) return fail(ctx, CAMERA_EINVAL, "ratios: must sum to 1");
+  }
+  return CAMERA_OK;
+}
+
+// Cuts and tables of a request on n_micro keys.  An element of ascending rank r is below a cut iff r < its
+// cut rank, so an element below k cuts is below the k cuts of highest rank: sorting the cuts by rank tells, for
+// every class k, how many of them are pruning cuts and how many are level boundaries.
+//   pruning ratio j:      cut rank floor(ratio_j n + 1e-6); below it = pruned at ratio j
+//   level boundary m:     cut rank n - floor((r_1 + .. + r_m) n + 1e-6); below it = not in levels 0 .. m
+void plan_cuts(const RankRequest& r, int64_t n_micro, camera::RankCuts* cuts, camera::SegOutputs* seg_out) {
+  struct Cut {
+    int64_t rank;
+    bool prune;
+  };
+  Cut all[CAMERA_MAX_LEVELS];
+  int n = 0;
+  for (int k = 0; k < r.n_ratios; ++k) all[n++] = {floor_count(r.ratios[k], n_micro), true};
+  double acc = 0.0;
+  for (int m = 0; m + 1 < r.n_levels; ++m) {
+    acc += r.level_ratios[m];
+    all[n++] = {n_micro - floor_count(acc, n_micro), false};
+  }
+  std::stable_sort(all, all + n, [](const Cut& a, const Cut& b) { return a.rank > b.rank; });  // highest rank first
+  memset(cuts, 0, sizeof(*cuts));
+  memset(seg_out, 0, sizeof(*seg_out));
+  cuts->n_cuts = n;
+  for (int q = 0; q < n; ++q) cuts->cut_rank[q] = all[q].rank;
+  seg_out->n_classes = n + 1;
+  seg_out->n_ratios = r.n_ratios;
+  seg_out->n_levels = r.n_levels;
+  int prune_below = 0, level = 0;  // of a member of class k: pruning cuts it is below, boundaries it is below
+  for (int k = 0; k <= n; ++k) {
+    if (k > 0) (all[k - 1].prune ? prune_below : level) += 1;
+    // first byte: the keep mask (one ratio) or the keep bits (bit j set iff kept at ratio j: below p pruning cuts
+    // means pruned at the p largest ratios); second byte, or the first when no ratio is asked for: the bit width
+    const uint8_t keep = r.single_mask ? (prune_below == 0 ? 1 : 0) : (uint8_t)((1u << (r.n_ratios - prune_below)) - 1u);
+    const uint8_t width = r.n_levels > 0 ? (uint8_t)r.bits[level] : 0;
+    cuts->out_of_below[k] = r.n_ratios > 0 ? keep : width;
+    cuts->out2_of_below[k] = width;
+    seg_out->prune_cuts_of_class |= (uint32_t)prune_below << (4 * k);
+    seg_out->level_of_class |= (uint32_t)level << (4 * k);
+  }
+  seg_out->kept = r.kept;
+  seg_out->level_count = r.level_count;
+  seg_out->perm = r.perm;
+}
+
+// state: the persistent select state; ws: class bytes + per-call words (+ the sort buffers when rank is asked for)
+int launch_rank(camera_ctx* ctx, hipStream_t stream, const float* energy, int64_t n_micro, const camera::SegTable& seg,
+                const RankRequest& r, void* state, bool* state_dirty, char* ws) {
+  camera::RankCuts cuts;
+  camera::SegOutputs seg_out;
+  plan_cuts(r, n_micro, &cuts, &seg_out);
+  Carver cv;
+  const size_t o_class = cv.take((size_t)n_micro + 64);
+  const size_t o_words = cv.take(sizeof(int32_t) * camera::rank_workspace_words(n_micro, r.rank ? 1 : 0));
+  uint8_t* class_buf = reinterpret_cast<uint8_t*>(ws + o_class);
+  int32_t* words = reinterpret_cast<int32_t*>(ws + o_words);
+  if (*state_dirty) {  // an earlier call failed between its passes: start from a clean state again
+    CAMERA_HIP(hipMemsetAsync(state, 0, camera::rank_state_bytes(), stream), "hipMemsetAsync(select state)");
+    *state_dirty = false;
+  }
+  uint8_t* first = r.n_ratios > 0 ? r.keep_out : r.bit_of;
+  uint8_t* second = r.n_ratios > 0 && r.n_levels > 0 ? r.bit_of : nullptr;
+  hipError_t e = camera::launch_classify(stream, energy, n_micro, cuts, class_buf, first, second, r.kept_idx, state, words);
+  if (e != hipSuccess) {
+    *state_dirty = true;
+    return fail_hip(ctx, e, "classify launch");
+  }
+  CAMERA_HIP(camera::launch_segment_outputs(stream, class_buf, seg, seg_out), "segment launch");
+  if (r.rank) CAMERA_HIP(camera::launch_full_rank(stream, energy, n_micro, r.rank, words), "rank launch");
+  return CAMERA_OK;
+}
+
+size_t rank_ws_bytes(int64_t n_micro, bool want_rank) {
+  Carver cv;
+  cv.take((size_t)n_micro + 64);
+  cv.take(sizeof(int32_t) * camera::rank_workspace_words(n_micro, want_rank ? 1 : 0));
+  return cv.used;
+}
+
+// Checks shared by the ranking entry points, then the launches on the context's workspace and select state.
+int run_rank(camera_ctx* ctx, void* stream_, const float* energy, int64_t n_micro, const int64_t* seg_offsets, int n_seg,
+             const RankRequest& r) {
+  if (int rc = check_energy(ctx, energy, n_micro)) return rc;
+  camera::SegTable seg;
+  if (int rc = check_segments(ctx, seg_offsets, n_seg, n_micro, &seg)) return rc;
+  if (int rc = check_ratios(ctx, r)) return rc;
+  DeviceGuard guard;
+  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
+  if (int rc = ensure_workspace(ctx, rank_ws_bytes(n_micro, r.rank != nullptr))) return rc;
+  if (int rc = ensure_rank_state(ctx)) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  Bracket b(ctx, stream, CAMERA_K_RANK);
+  return launch_rank(ctx, stream, energy, n_micro, seg, r, ctx->rank_state, &ctx->rank_dirty, static_cast<char*>(ctx->ws));
+}
+
+}  // namespace
+
+extern "C" {
+
 int camera_select_prune(camera_ctx* ctx, void* stream_, const float* energy, int64_t n_micro,
                         const int64_t* seg_offsets, int n_seg, double ratio, uint8_t* keep_mask,
                         int32_t* kept_per_expert, int32_t* kept_idx, uint32_t* rank) {
   if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
-  if (int rc = check_energy(ctx, energy, n_micro)) return rc;
-  camera::SegTable seg;
-  if (int rc = check_segments(ctx, seg_offsets, n_seg, n_micro, &seg)) return rc;
-  if (!(ratio >= 0.0 && ratio <= 1.0)) return fail(ctx, CAMERA_EINVAL, "ratio: must be in [0, 1]");
   if (kept_per_expert == nullptr) return fail(ctx, CAMERA_EINVAL, "kept_per_expert: NULL");
   if (n_micro > 0 && keep_mask == nullptr) return fail(ctx, CAMERA_EINVAL, "keep_mask: NULL");
-
-  camera::RankCuts cuts;
-  memset(&cuts, 0, sizeof(cuts));
-  cuts.n_cuts = 1;
-  cuts.cut_rank[0] = floor_count(ratio, n_micro);  // n_prune
-  cuts.out_of_below[0] = 1;                        // below no cut: kept
-  cuts.out_of_below[1] = 0;
-
-  Carver cv;
-  const size_t o_class = cv.take((size_t)n_micro + 64);
-  const size_t o_rank = cv.take(sizeof(int32_t) * camera::rank_workspace_words(n_micro, rank ? 1 : 0));
-  DeviceGuard guard;
-  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
-  if (int rc = ensure_workspace(ctx, cv.used)) return rc;
-  char* ws = static_cast<char*>(ctx->ws);
-  uint8_t* class_buf = reinterpret_cast<uint8_t*>(ws + o_class);
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
-  Bracket b(ctx, stream, CAMERA_K_RANK);
-  CAMERA_HIP(camera::launch_classify(stream, energy, n_micro, cuts, class_buf, keep_mask, kept_idx,
-                                     reinterpret_cast<int32_t*>(ws + o_rank)),
-             "classify launch");
-  CAMERA_HIP(camera::launch_segment_counts(stream, class_buf, seg, 1, 1, kept_per_expert, nullptr),
-             "segment counts launch");
-  if (rank)
-    CAMERA_HIP(camera::launch_full_rank(stream, energy, n_micro, rank, reinterpret_cast<int32_t*>(ws + o_rank)),
-               "rank launch");
-  return CAMERA_OK;
+  RankRequest r;
+  r.n_ratios = 1;
+  r.ratios = &ratio;
+  r.single_mask = true;
+  r.keep_out = keep_mask;
+  r.kept = kept_per_expert;
+  r.kept_idx = kept_idx;
+  r.rank = rank;
+  return run_rank(ctx, stream_, energy, n_micro, seg_offsets, n_seg, r);
 }
 
 int camera_select_prune_noalloc(camera_ctx* ctx, void* stream_, const float* energy, int64_t n_micro,
@@ -774,26 +913,25 @@ int camera_select_prune_noalloc(camera_ctx* ctx, void* stream_, const float* ene
                 (long long)n_micro, CAMERA_NOALLOC_MAX_MICRO);
   camera::SegTable seg;
   if (int rc = check_segments(ctx, seg_offsets, n_seg, n_micro, &seg)) return rc;
-  if (!(ratio >= 0.0 && ratio <= 1.0)) return fail(ctx, CAMERA_EINVAL, "ratio: must be in [0, 1]");
   if (kept_per_expert == nullptr) return fail(ctx, CAMERA_EINVAL, "kept_per_expert: NULL");
   if (n_micro > 0 && keep_mask == nullptr) return fail(ctx, CAMERA_EINVAL, "keep_mask: NULL");
   if (ctx->device >= kMaxDevices) return fail(ctx, CAMERA_EUNSUPPORTED, "device: index above %d", kMaxDevices - 1);
-
-  camera::RankCuts cuts;
-  memset(&cuts, 0, sizeof(cuts));
-  cuts.n_cuts = 1;
-  cuts.cut_rank[0] = floor_count(ratio, n_micro);  // n_prune
-  cuts.out_of_below[0] = 1;                        // below no cut: kept
-  cuts.out_of_below[1] = 0;
-
-  Carver cv;
-  const size_t o_class = cv.take((size_t)n_micro + 64);
-  const size_t o_rank = cv.take(sizeof(int32_t) * camera::rank_workspace_words(n_micro, 0));
-  if (cv.used > kScratchBytes)
-    return fail(ctx, CAMERA_EUNSUPPORTED, "n_micro: needs %zu bytes of scratch, the static buffer has %zu", cv.used, kScratchBytes);
+  RankRequest r;
+  r.n_ratios = 1;
+  r.ratios = &ratio;
+  r.single_mask = true;
+  r.keep_out = keep_mask;
+  r.kept = kept_per_expert;
+  r.kept_idx = kept_idx;
+  if (int rc = check_ratios(ctx, r)) return rc;
+  // the scratch: the select state first, the per-call buffers behind it
+  const size_t state_bytes = (camera::rank_state_bytes() + 255) & ~size_t(255);
+  const size_t need = state_bytes + rank_ws_bytes(n_micro, false);
+  if (need > kScratchBytes)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "n_micro: needs %zu bytes of scratch, the static buffer has %zu", need, kScratchBytes);
   DeviceGuard guard;
   CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
-  char* ws = nullptr;
+  char* base = nullptr;
   {
     // every GPU has its own copy of the array at its own address: looked up once per device, with that device current
     std::lock_guard<std::mutex> lock(g_scratch_mutex);
@@ -803,114 +941,71 @@ int camera_select_prune_noalloc(camera_ctx* ctx, void* stream_, const float* ene
       if (p == nullptr) return fail(ctx, CAMERA_EHIP, "hipGetSymbolAddress(scratch): null address");
       g_scratch_ptr[ctx->device] = p;
     }
-    ws = static_cast<char*>(g_scratch_ptr[ctx->device]);
+    base = static_cast<char*>(g_scratch_ptr[ctx->device]);
   }
-  // The scratch keeps the previous call's contents: the select state (histograms, tickets, prefixes) is cleared by
-  // the first kernel of the classification; class bytes and per-workgroup counts are written before they are read.
-  uint8_t* class_buf = reinterpret_cast<uint8_t*>(ws + o_class);
+  // The array starts as zeros and keeps the previous call's contents: the select state at its start cleans itself
+  // (every pass leaves its histograms and ticket at zero), class bytes and per-workgroup counts are written before
+  // they are read.
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  CAMERA_HIP(camera::launch_classify(stream, energy, n_micro, cuts, class_buf, keep_mask, kept_idx,
-                                     reinterpret_cast<int32_t*>(ws + o_rank)),
-             "classify launch");
-  CAMERA_HIP(camera::launch_segment_counts(stream, class_buf, seg, 1, 1, kept_per_expert, nullptr),
-             "segment counts launch");
-  return CAMERA_OK;
+  return launch_rank(ctx, stream, energy, n_micro, seg, r, base, &g_scratch_dirty[ctx->device], base + state_bytes);
 }
 
 int camera_select_prune_multi(camera_ctx* ctx, void* stream_, const float* energy, int64_t n_micro,
                               const int64_t* seg_offsets, int n_seg, int n_ratios, const double* ratios,
                               uint8_t* keep_bits, int32_t* kept_per_expert) {
   if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
-  if (int rc = check_energy(ctx, energy, n_micro)) return rc;
-  camera::SegTable seg;
-  if (int rc = check_segments(ctx, seg_offsets, n_seg, n_micro, &seg)) return rc;
   if (n_ratios < 1 || n_ratios > CAMERA_MAX_LEVELS - 1)
     return fail(ctx, CAMERA_EUNSUPPORTED, "n_ratios: must be in [1, %d]", CAMERA_MAX_LEVELS - 1);
-  if (ratios == nullptr) return fail(ctx, CAMERA_EINVAL, "ratios: NULL");
-  for (int k = 0; k < n_ratios; ++k) {
-    if (!(ratios[k] >= 0.0 && ratios[k] <= 1.0)) return fail(ctx, CAMERA_EINVAL, "ratios[%d]: must be in [0, 1]", k);
-    if (k > 0 && ratios[k] < ratios[k - 1]) return fail(ctx, CAMERA_EINVAL, "ratios: must not fall");
-  }
   if (kept_per_expert == nullptr) return fail(ctx, CAMERA_EINVAL, "kept_per_expert: NULL");
   if (n_micro > 0 && keep_bits == nullptr) return fail(ctx, CAMERA_EINVAL, "keep_bits: NULL");
-
-  // One cut per ratio, rising: an element below c of them is pruned at the c largest ratios and kept at the
-  // n_ratios - c smallest, so its byte has the low n_ratios - c bits set.
-  camera::RankCuts cuts;
-  memset(&cuts, 0, sizeof(cuts));
-  cuts.n_cuts = n_ratios;
-  for (int k = 0; k < n_ratios; ++k) cuts.cut_rank[k] = floor_count(ratios[k], n_micro);
-  for (int c = 0; c <= n_ratios; ++c) cuts.out_of_below[c] = (uint8_t)((1u << (n_ratios - c)) - 1u);
-
-  Carver cv;
-  const size_t o_class = cv.take((size_t)n_micro + 64);
-  const size_t o_count = cv.take(sizeof(int32_t) * (size_t)n_seg * (n_ratios + 1));
-  const size_t o_rank = cv.take(sizeof(int32_t) * camera::rank_workspace_words(n_micro, 0));
-  DeviceGuard guard;
-  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
-  if (int rc = ensure_workspace(ctx, cv.used)) return rc;
-  char* ws = static_cast<char*>(ctx->ws);
-  uint8_t* class_buf = reinterpret_cast<uint8_t*>(ws + o_class);
-  int32_t* class_count = reinterpret_cast<int32_t*>(ws + o_count);
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
-  Bracket b(ctx, stream, CAMERA_K_RANK);
-  CAMERA_HIP(camera::launch_classify(stream, energy, n_micro, cuts, class_buf, keep_bits, nullptr,
-                                     reinterpret_cast<int32_t*>(ws + o_rank)),
-             "classify launch");
-  CAMERA_HIP(camera::launch_segment_counts(stream, class_buf, seg, n_ratios + 1, 0, class_count, nullptr),
-             "segment counts launch");
-  CAMERA_HIP(camera::launch_kept_from_classes(stream, class_count, n_seg, n_ratios, kept_per_expert),
-             "kept counts launch");
-  return CAMERA_OK;
+  RankRequest r;
+  r.n_ratios = n_ratios;
+  r.ratios = ratios;
+  r.keep_out = keep_bits;
+  r.kept = kept_per_expert;
+  return run_rank(ctx, stream_, energy, n_micro, seg_offsets, n_seg, r);
 }
 
 int camera_alloc_bits(camera_ctx* ctx, void* stream_, const float* energy, int64_t n_micro,
                       const int64_t* seg_offsets, int n_seg, int n_levels, const int* bits, const double* ratios,
                       uint8_t* bit_of, int32_t* level_count, int32_t* perm) {
   if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
-  if (int rc = check_energy(ctx, energy, n_micro)) return rc;
-  camera::SegTable seg;
-  if (int rc = check_segments(ctx, seg_offsets, n_seg, n_micro, &seg)) return rc;
   if (n_levels < 1 || n_levels > CAMERA_MAX_LEVELS)
     return fail(ctx, CAMERA_EUNSUPPORTED, "n_levels: must be in [1, %d]", CAMERA_MAX_LEVELS);
-  if (bits == nullptr || ratios == nullptr) return fail(ctx, CAMERA_EINVAL, "bits / ratios: NULL");
-  double total = 0.0;
-  for (int m = 0; m < n_levels; ++m) {
-    if (!(ratios[m] >= 0.0)) return fail(ctx, CAMERA_EINVAL, "ratios[%d]: negative", m);
-    if (bits[m] < 0 || bits[m] > 255) return fail(ctx, CAMERA_EINVAL, "bits[%d]: must be in [0, 255]", m);
-    total += ratios[m];
-  }
-  if (std::fabs(total - 1.0) > 1e-9) return fail(ctx, CAMERA_EINVAL, "ratios: must sum to 1");
   if (level_count == nullptr) return fail(ctx, CAMERA_EINVAL, "level_count: NULL");
   if (n_micro > 0 && bit_of == nullptr) return fail(ctx, CAMERA_EINVAL, "bit_of: NULL");
+  RankRequest r;
+  r.n_levels = n_levels;
+  r.bits = bits;
+  r.level_ratios = ratios;
+  r.bit_of = bit_of;
+  r.level_count = level_count;
+  r.perm = perm;
+  return run_rank(ctx, stream_, energy, n_micro, seg_offsets, n_seg, r);
+}
 
-  // Class m ends, counted from the most important end, at cut_m = floor((r_1+..+r_m) n + 1e-6);
-  // an element is below ascending-rank cut n - cut_m iff it is not in classes 0..m.
-  camera::RankCuts cuts;
-  memset(&cuts, 0, sizeof(cuts));
-  cuts.n_cuts = n_levels - 1;
-  double acc = 0.0;
-  for (int m = 0; m + 1 < n_levels; ++m) {
-    acc += ratios[m];
-    cuts.cut_rank[m] = n_micro - floor_count(acc, n_micro);
-  }
-  for (int m = 0; m < n_levels; ++m) cuts.out_of_below[m] = (uint8_t)bits[m];
-
-  Carver cv;
-  const size_t o_class = cv.take((size_t)n_micro + 64);
-  const size_t o_rank = cv.take(sizeof(int32_t) * camera::rank_workspace_words(n_micro, 0));
-  DeviceGuard guard;
-  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
-  if (int rc = ensure_workspace(ctx, cv.used)) return rc;
-  uint8_t* class_buf = reinterpret_cast<uint8_t*>(static_cast<char*>(ctx->ws) + o_class);
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
-  Bracket b(ctx, stream, CAMERA_K_RANK);
-  CAMERA_HIP(camera::launch_classify(stream, energy, n_micro, cuts, class_buf, bit_of, nullptr,
-                                     reinterpret_cast<int32_t*>(static_cast<char*>(ctx->ws) + o_rank)),
-             "classify launch");
-  CAMERA_HIP(camera::launch_segment_counts(stream, class_buf, seg, n_levels, 0, level_count, perm),
-             "segment counts launch");
-  return CAMERA_OK;
+int camera_rank_decisions(camera_ctx* ctx, void* stream_, const float* energy, int64_t n_micro,
+                          const int64_t* seg_offsets, int n_seg, int n_ratios, const double* ratios,
+                          uint8_t* keep_bits, int32_t* kept_per_expert, int n_levels, const int* bits,
+                          const double* level_ratios, uint8_t* bit_of, int32_t* level_count, int32_t* perm) {
+  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
+  if (n_ratios < 1 || n_levels < 1 || n_ratios + n_levels - 1 > CAMERA_MAX_LEVELS - 1)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "n_ratios, n_levels: both >= 1 and n_ratios + n_levels - 1 <= %d cuts in one pass",
+                CAMERA_MAX_LEVELS - 1);
+  if (kept_per_expert == nullptr || level_count == nullptr) return fail(ctx, CAMERA_EINVAL, "kept_per_expert / level_count: NULL");
+  if (n_micro > 0 && (keep_bits == nullptr || bit_of == nullptr)) return fail(ctx, CAMERA_EINVAL, "keep_bits / bit_of: NULL");
+  RankRequest r;
+  r.n_ratios = n_ratios;
+  r.ratios = ratios;
+  r.keep_out = keep_bits;
+  r.kept = kept_per_expert;
+  r.n_levels = n_levels;
+  r.bits = bits;
+  r.level_ratios = level_ratios;
+  r.bit_of = bit_of;
+  r.level_count = level_count;
+  r.perm = perm;
+  return run_rank(ctx, stream_, energy, n_micro, seg_offsets, n_seg, r);
 }
 
 }  // extern "C"

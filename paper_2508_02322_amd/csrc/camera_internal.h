@@ -85,25 +85,36 @@ hipError_t launch_finalize(hipStream_t stream, int n_experts, int64_t d_ff, cons
 struct RankCuts {
   int n_cuts;                          // <= CAMERA_MAX_LEVELS - 1
   int64_t cut_rank[CAMERA_MAX_LEVELS]; // element is "below cut q" iff its ascending rank < cut_rank[q]
-  uint8_t out_of_below[CAMERA_MAX_LEVELS + 1];  // output byte for "below k cuts"
+  uint8_t out_of_below[CAMERA_MAX_LEVELS + 1];   // first output byte for "below k cuts"
+  uint8_t out2_of_below[CAMERA_MAX_LEVELS + 1];  // second output byte for "below k cuts" (optional output)
 };
 struct SegTable {
   int n_seg;
   int32_t off[CAMERA_MAX_SEGMENTS + 1];
 };
-// Workspace (int32 words) the rank kernels need for n_micro keys.
+// What the per-segment kernel derives from the class bytes (class = number of cuts an element is below; an
+// element below k cuts is below the k cuts of highest rank, so the class fixes which cuts those are).
+struct SegOutputs {
+  int n_classes;                 // n_cuts + 1, <= CAMERA_MAX_LEVELS
+  int n_ratios;                  // pruning ratios (0: no kept counts)
+  int n_levels;                  // precision levels (0: no level counts)
+  uint32_t prune_cuts_of_class;  // 4 bits per class: how many of the pruning cuts its members are below
+  uint32_t level_of_class;       // 4 bits per class: precision level of its members
+  int32_t* kept;                 // [n_ratios][n_seg]: kept at ratio k = members of the classes below <= n_ratios-1-k pruning cuts
+  int32_t* level_count;          // [n_seg][n_levels]
+  int32_t* perm;                 // optional: inside every segment level 0 first, then level 1, ..., ascending index inside a level
+};
+// Bytes of the persistent select state (zero when made, self-cleaning afterwards) and the int32 words of
+// per-call workspace the rank kernels need for n_micro keys.
+size_t rank_state_bytes();
 int64_t rank_workspace_words(int64_t n_micro, int want_rank);
-// class_out[i] = number of cuts element i is below; byte_out[i] = out_of_below[class_out[i]].
-// kept_idx (optional): ascending indices of the elements below no cut.
+// class_out[i] = number of cuts element i is below; byte_out[i] = out_of_below[class_out[i]], byte_out2
+// (optional) likewise from out2_of_below.  kept_idx (optional): ascending indices of the elements below no cut.
 hipError_t launch_classify(hipStream_t stream, const float* energy, int64_t n_micro, const RankCuts& cuts,
-                           uint8_t* class_out, uint8_t* byte_out, int32_t* kept_idx, int32_t* ws);
-// Per segment: count[s][c] for c in [0, n_classes) of class_out (or, when
-// `kept_only`, the single count of class 0), and the optional stable partition.
-hipError_t launch_segment_counts(hipStream_t stream, const uint8_t* class_out, const SegTable& seg,
-                                 int n_classes, int kept_only, int32_t* counts, int32_t* perm);
-// kept [n_ratios][n_seg] from class_count [n_seg][n_ratios + 1] of a classification with n_ratios ascending cuts.
-hipError_t launch_kept_from_classes(hipStream_t stream, const int32_t* class_count, int n_seg, int n_ratios,
-                                    int32_t* kept);
+                           uint8_t* class_out, uint8_t* byte_out, uint8_t* byte_out2, int32_t* kept_idx, void* state,
+                           int32_t* ws);
+hipError_t launch_segment_outputs(hipStream_t stream, const uint8_t* class_out, const SegTable& seg,
+                                  const SegOutputs& out);
 // Full stable ascending rank by LSD radix sort.
 hipError_t launch_full_rank(hipStream_t stream, const float* energy, int64_t n_micro, uint32_t* rank,
                             int32_t* ws);

@@ -11,11 +11,14 @@
 // walk: every wave owns a contiguous index range, ballots + popcounts give the
 // order inside 256-element steps.
 //
-// rank_* kernels: the select passes and the walk for all cuts at once, one
+// rank_* kernels: the select passes and the walk for all cuts at once (the
+// CAMERA-P cuts of several ratios and the CAMERA-Q class boundaries of a layer
+// are cuts on the same order, so one set of passes serves both decisions), one
 // workgroup per 4096 keys (<= 184 320 keys per layer in the paper's models:
 // latency- and launch-bound, not bandwidth-bound).
-// segment_kernel: one workgroup per expert: class sizes and the stable
-// partition of its micro-experts by class.
+// segment_kernel: one workgroup per expert: class sizes, from them the kept
+// counts per ratio and the level sizes, and the stable partition of its
+// micro-experts by precision level.
 // full rank: LSD radix sort (4 x 8 bits) of (key, index) built from a stable
 // counting sort whose in-wave order again comes from ballots.
 #include "camera_internal.h"
@@ -63,11 +66,14 @@ __device__ __forceinline__ Keys4 load_keys4(const float* __restrict__ E, int64_t
 // once) and chained as short kernels on the stream.  After each histogram pass the workgroup
 // that finishes last (a ticket from an atomic counter after a __threadfence; nobody waits for
 // anybody) picks, for every cut, the bin that holds the cut element and publishes prefix / rest.
-//   zero      clears histograms and tickets, seeds (mode, rest) per cut
 //   hist<P>   P = 0, 1, 2: 11 + 11 + 10 key bits; keys that share the cut's prefix so far
-//   ties      equal-key counts per workgroup, only if a cut runs through a group of equal keys
-//   label     ordered walk: class byte, output byte, kept counts per workgroup
+//   label     ordered walk: class byte, up to two output bytes, kept counts per workgroup
 //   compact   (optional) ascending list of the kept indices
+// The select state is self-cleaning: it starts as zeros (the library clears it when it makes it), pass 0
+// seeds the per-cut fields from the call's cuts, and the last workgroup of every pass clears the histograms
+// and the ticket it has just used.  A call therefore needs no clearing launch and leaves the state as it
+// found it.  Equal keys that a cut runs through (rare: energies of experts without tokens) are ordered by
+// index inside the label kernel, each workgroup counting the equal keys that precede it.
 // ---------------------------------------------------------------------------
 constexpr int kRankThreads = 256;
 constexpr int kRankWaves = kRankThreads / kWave;
@@ -75,7 +81,7 @@ constexpr int kKeysPerBlock = kRankThreads * 16;  // 4096
 constexpr int kKeysPerWave = kKeysPerBlock / kRankWaves;  // 1024 consecutive keys
 constexpr int kBins = 2048;
 
-struct RankState {  // lives in the workspace
+struct RankState {  // persistent, see above
   uint32_t hist[3][kMaxCuts][kBins];
   uint32_t ticket[4];
   uint32_t prefix[kMaxCuts];  // key bits fixed so far (right-aligned); after pass 2 the key K of the cut element
@@ -136,31 +142,20 @@ __device__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s_wave) {
   return base + inc - v;
 }
 
-__global__ __launch_bounds__(kRankThreads) void rank_zero_kernel(RankState* __restrict__ st, RankCuts cuts,
-                                                                int64_t n) {
-  const int n_words = 3 * kMaxCuts * kBins;
-  for (int i = blockIdx.x * kRankThreads + threadIdx.x; i < n_words; i += gridDim.x * kRankThreads)
-    (&st->hist[0][0][0])[i] = 0u;
-  if (blockIdx.x == 0 && threadIdx.x < kMaxCuts) {
-    const int q = threadIdx.x;
-    int mode = 1;
-    uint32_t rest = 0;
-    if (q < cuts.n_cuts) {
-      const int64_t t = cuts.cut_rank[q];
-      mode = t <= 0 ? 1 : (t >= n ? 2 : 0);
-      rest = mode == 0 ? (uint32_t)t : 0u;
-    }
-    st->mode[q] = mode;
-    st->rest[q] = rest;
-    st->prefix[q] = 0u;
-    if (q < 4) st->ticket[q] = 0u;
-    if (q == 0) st->ties_split = 0u;
-  }
+// What another workgroup wrote before it took its ticket: read past this CU's vector cache.
+__device__ __forceinline__ uint32_t load_agent(const uint32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ int cut_mode(const RankCuts& cuts, int q, int64_t n) {
+  if (q >= cuts.n_cuts) return 1;
+  const int64_t t = cuts.cut_rank[q];
+  return t <= 0 ? 1 : (t >= n ? 2 : 0);
 }
 
 // Histogram pass P over the keys that share each cut's prefix, then (last workgroup) the pick.
 template <int P>
-__global__ __launch_bounds__(kRankThreads) void rank_hist_kernel(const float* __restrict__ E, int64_t n, int n_cuts,
+__global__ __launch_bounds__(kRankThreads) void rank_hist_kernel(const float* __restrict__ E, int64_t n, RankCuts cuts,
                                                                 RankState* __restrict__ st) {
   constexpr int kShift = P == 0 ? 21 : (P == 1 ? 10 : 0);
   constexpr int kBits = P == 2 ? 10 : 11;
@@ -171,14 +166,25 @@ __global__ __launch_bounds__(kRankThreads) void rank_hist_kernel(const float* __
   __shared__ uint32_t s_wave[kRankWaves];
   __shared__ uint32_t s_last;
   const int tid = threadIdx.x;
+  const int n_cuts = cuts.n_cuts;
 
   uint32_t want[kMaxCuts];
   bool any = false;
 #pragma unroll
   for (int q = 0; q < kMaxCuts; ++q) {
-    const bool on = q < n_cuts && st->mode[q] == 0;
-    want[q] = on ? st->prefix[q] : 0xffffffffu;  // a real prefix has at most 22 bits
+    const bool on = P == 0 ? cut_mode(cuts, q, n) == 0 : (q < n_cuts && st->mode[q] == 0);
+    want[q] = on ? (P == 0 ? 0u : st->prefix[q]) : 0xffffffffu;  // a real prefix has at most 22 bits
     any |= on;
+  }
+  if (P == 0 && blockIdx.x == 0 && tid < kMaxCuts) {
+    // The per-cut fields of this call.  Nobody else reads them during pass 0 (the pick below takes the cut
+    // ranks from the kernel argument) and only the pick of this pass writes prefix / rest after them.
+    st->mode[tid] = cut_mode(cuts, tid, n);
+    if (cut_mode(cuts, tid, n) != 0) {
+      st->prefix[tid] = 0u;
+      st->rest[tid] = 0u;
+    }
+    if (tid == 0) st->ties_split = 0u;
   }
   if (!any) return;  // block-uniform: no cut needs a select
   const int n_hists = P == 0 ? 1 : n_cuts;
@@ -218,11 +224,11 @@ __global__ __launch_bounds__(kRankThreads) void rank_hist_kernel(const float* __
     uint32_t c[kBins / kRankThreads], mine = 0;
 #pragma unroll
     for (int i = 0; i < kBins / kRankThreads; ++i) {
-      c[i] = h[tid * (kBins / kRankThreads) + i];
+      c[i] = load_agent(h + tid * (kBins / kRankThreads) + i);
       mine += c[i];
     }
     uint32_t before = block_exclusive_scan(mine, s_wave);
-    const uint32_t rest = st->rest[q];
+    const uint32_t rest = P == 0 ? (uint32_t)cuts.cut_rank[q] : st->rest[q];
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < kBins / kRankThreads; ++i) {
@@ -235,40 +241,21 @@ __global__ __launch_bounds__(kRankThreads) void rank_hist_kernel(const float* __
     }
     __syncthreads();
   }
-}
-
-// Equal-key counts per workgroup for the cuts that run through a group of equal keys.
-__global__ __launch_bounds__(kRankThreads) void rank_ties_kernel(const float* __restrict__ E, int64_t n, int n_cuts,
-                                                                const RankState* __restrict__ st,
-                                                                uint32_t* __restrict__ tie_cnt /*[kMaxCuts][grid]*/) {
-  if (!st->ties_split) return;  // block-uniform
-  __shared__ uint32_t s_cnt[kMaxCuts];
-  if (threadIdx.x < kMaxCuts) s_cnt[threadIdx.x] = 0u;
-  __syncthreads();
-  const Keys16 keys = load_keys16(E, n);
-  for (int q = 0; q < n_cuts; ++q) {
-    if (st->mode[q] != 0 || st->rest[q] == 0) continue;  // block-uniform
-    const uint32_t K = st->prefix[q];
-    uint32_t c = 0;
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) c += (keys.g[u].valid[j] && keys.g[u].k[j] == K) ? 1u : 0u;
-    if (c) atomicAdd(&s_cnt[q], c);
-  }
-  __syncthreads();
-  if (threadIdx.x < kMaxCuts) tie_cnt[threadIdx.x * gridDim.x + blockIdx.x] = s_cnt[threadIdx.x];
+  // leave the state as the next call needs it: this pass's histograms and ticket back to zero
+  for (int i = tid; i < n_hists * kBins; i += kRankThreads) (&st->hist[P][0][0])[i] = 0u;
+  if (tid == 0) st->ticket[P] = 0u;
 }
 
 // Ordered walk: an element is below cut q iff key < K_q, or key == K_q and fewer than rest_q equal
-// keys precede it (by index).  Writes the class (number of cuts it is below) and the output byte.
+// keys precede it (by index).  Writes the class (number of cuts it is below) and the output bytes.
 __global__ __launch_bounds__(kRankThreads) void rank_label_kernel(const float* __restrict__ E, int64_t n,
                                                                  RankCuts cuts, const RankState* __restrict__ st,
-                                                                 const uint32_t* __restrict__ tie_cnt,
                                                                  uint8_t* __restrict__ class_out,
                                                                  uint8_t* __restrict__ byte_out,
+                                                                 uint8_t* __restrict__ byte_out2 /*or NULL*/,
                                                                  uint32_t* __restrict__ kept_cnt /*[grid] or NULL*/) {
   __shared__ uint32_t s_tie[kMaxCuts][kRankWaves];
+  __shared__ uint32_t s_before[kMaxCuts][kRankWaves];
   __shared__ uint32_t s_kept[kRankWaves];
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const uint64_t lower = (1ull << lane) - 1ull;
@@ -287,11 +274,13 @@ __global__ __launch_bounds__(kRankThreads) void rank_label_kernel(const float* _
 #pragma unroll
   for (int q = 0; q < kMaxCuts; ++q) tie_base[q] = 0u;
   if (ties_split) {  // block-uniform
-    // equal keys before this wave: earlier workgroups (global counts) + earlier waves of this one
-    uint32_t mine[kMaxCuts];
+    // equal keys before this wave: in the workgroups before this one (counted here, by all threads, over
+    // keys [0, first key of this workgroup)) and in the earlier waves of this one
+    uint32_t mine[kMaxCuts], before[kMaxCuts];
 #pragma unroll
     for (int q = 0; q < kMaxCuts; ++q) {
       mine[q] = 0u;
+      before[q] = 0u;
       if (mode[q] == 0 && R[q] > 0) {
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -300,18 +289,34 @@ __global__ __launch_bounds__(kRankThreads) void rank_label_kernel(const float* _
             mine[q] += __popcll(__ballot(keys.g[u].valid[j] && keys.g[u].k[j] == K[q]));
       }
     }
+    const int64_t n_before = (int64_t)blockIdx.x * kKeysPerBlock;  // a multiple of 4, all inside [0, n)
+    for (int64_t i = (int64_t)threadIdx.x * 4; i < n_before; i += kRankThreads * 4) {
+      const Keys4 k = keys_of(*reinterpret_cast<const float4*>(E + i));
+#pragma unroll
+      for (int q = 0; q < kMaxCuts; ++q)
+        if (mode[q] == 0 && R[q] > 0) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) before[q] += k.k[j] == K[q] ? 1u : 0u;
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < kMaxCuts; ++q) {
+#pragma unroll
+      for (int m = 32; m >= 1; m >>= 1) before[q] += __shfl_xor(before[q], m);
+    }
     if (lane == 0) {
 #pragma unroll
-      for (int q = 0; q < kMaxCuts; ++q) s_tie[q][wave] = mine[q];
+      for (int q = 0; q < kMaxCuts; ++q) {
+        s_tie[q][wave] = mine[q];
+        s_before[q][wave] = before[q];
+      }
     }
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < kMaxCuts; ++q) {
       if (mode[q] == 0 && R[q] > 0) {
         uint32_t run = 0;
-        for (int b = lane; b < (int)blockIdx.x; b += kWave) run += tie_cnt[q * gridDim.x + b];
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) run += __shfl_xor(run, m);
+        for (int w = 0; w < kRankWaves; ++w) run += s_before[q][w];
         for (int w = 0; w < wave; ++w) run += s_tie[q][w];
         tie_base[q] = run;
       }
@@ -362,12 +367,19 @@ __global__ __launch_bounds__(kRankThreads) void rank_label_kernel(const float* _
                             ((uint32_t)cuts.out_of_below[below[3]] << 24);
       *reinterpret_cast<uint32_t*>(class_out + i) = cls4;
       *reinterpret_cast<uint32_t*>(byte_out + i) = out4;
+      if (byte_out2) {
+        const uint32_t second4 = (uint32_t)cuts.out2_of_below[below[0]] | ((uint32_t)cuts.out2_of_below[below[1]] << 8) |
+                                 ((uint32_t)cuts.out2_of_below[below[2]] << 16) |
+                                 ((uint32_t)cuts.out2_of_below[below[3]] << 24);
+        *reinterpret_cast<uint32_t*>(byte_out2 + i) = second4;
+      }
     } else {
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         if (k.valid[j]) {
           class_out[i + j] = (uint8_t)below[j];
           byte_out[i + j] = cuts.out_of_below[below[j]];
+          if (byte_out2) byte_out2[i + j] = cuts.out2_of_below[below[j]];
         }
     }
 #pragma unroll
@@ -435,16 +447,18 @@ __global__ __launch_bounds__(kRankThreads) void rank_compact_kernel(const uint8_
 }
 
 // ---------------------------------------------------------------------------
-// per-segment class sizes and stable partition
+// per segment (expert): class sizes, from them the kept counts of every pruning ratio and the sizes of
+// the precision levels, and the stable partition of the segment by level
 // ---------------------------------------------------------------------------
 constexpr int kSegThreads = 1024;  // a shared expert can be a 20 480-element segment: 16 waves walk it
 constexpr int kSegWaves = kSegThreads / kWave;
 
+__device__ __forceinline__ int nibble(uint32_t packed, int c) { return (int)((packed >> (4 * c)) & 15u); }
+
 __global__ __launch_bounds__(kSegThreads) void segment_kernel(const uint8_t* __restrict__ class_in, SegTable seg,
-                                                              int n_classes, int kept_only,
-                                                              int32_t* __restrict__ counts,
-                                                              int32_t* __restrict__ perm) {
-  __shared__ uint32_t s_cnt[kSegWaves][CAMERA_MAX_LEVELS];
+                                                              SegOutputs out) {
+  __shared__ uint32_t s_cnt[kSegWaves][CAMERA_MAX_LEVELS];   // per wave and class
+  __shared__ uint32_t s_lvl[kSegWaves][CAMERA_MAX_LEVELS];   // per wave and level
   const int s = blockIdx.x;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int begin = seg.off[s], end = seg.off[s + 1];
@@ -452,6 +466,7 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(const uint8_t* __r
   const int w_begin = min(end, begin + wave * span);
   const int w_end = min(end, w_begin + span);
   const uint64_t lower = (1ull << lane) - 1ull;
+  const int n_classes = out.n_classes;
 
   uint32_t cnt[CAMERA_MAX_LEVELS];
 #pragma unroll
@@ -474,45 +489,58 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(const uint8_t* __r
     for (int m = 0; m < CAMERA_MAX_LEVELS; ++m) s_cnt[wave][m] = cnt[m];
   }
   __syncthreads();
-  if (threadIdx.x < n_classes) {
+  if (threadIdx.x < kSegWaves * CAMERA_MAX_LEVELS) {  // (wave w, level m): members of level m in wave w's range
+    const int w = threadIdx.x / CAMERA_MAX_LEVELS, m = threadIdx.x % CAMERA_MAX_LEVELS;
     uint32_t total = 0;
-    for (int w = 0; w < kSegWaves; ++w) total += s_cnt[w][threadIdx.x];
-    if (kept_only) {
-      if (threadIdx.x == 0) counts[s] = (int32_t)total;
-    } else {
-      counts[s * n_classes + threadIdx.x] = (int32_t)total;
-    }
+    for (int c = 0; c < n_classes; ++c)
+      if (nibble(out.level_of_class, c) == m) total += s_cnt[w][c];
+    s_lvl[w][m] = total;
   }
-  if (perm == nullptr) return;  // block-uniform
+  if (threadIdx.x >= 512 && threadIdx.x < 512 + out.n_ratios) {
+    // kept at ratio k: the members of the classes that lie below at most n_ratios - 1 - k of the pruning cuts
+    const int k = threadIdx.x - 512;
+    uint32_t total = 0;
+    for (int c = 0; c < n_classes; ++c)
+      if (nibble(out.prune_cuts_of_class, c) <= out.n_ratios - 1 - k)
+        for (int w = 0; w < kSegWaves; ++w) total += s_cnt[w][c];
+    out.kept[k * seg.n_seg + s] = (int32_t)total;
+  }
+  __syncthreads();
+  if (threadIdx.x < out.n_levels) {
+    uint32_t total = 0;
+    for (int w = 0; w < kSegWaves; ++w) total += s_lvl[w][threadIdx.x];
+    out.level_count[s * out.n_levels + threadIdx.x] = (int32_t)total;
+  }
+  if (out.perm == nullptr) return;  // block-uniform
 
-  // first slot of class m for this wave: segment start + all earlier classes + earlier waves
+  // first slot of level m for this wave: segment start + all earlier levels + earlier waves
   uint32_t slot[CAMERA_MAX_LEVELS];
   uint32_t run = (uint32_t)begin;
 #pragma unroll
   for (int m = 0; m < CAMERA_MAX_LEVELS; ++m) {
     slot[m] = 0;
-    if (m < n_classes) {
+    if (m < out.n_levels) {
       for (int w = 0; w < kSegWaves; ++w) {
         if (w == wave) slot[m] = run;
-        run += s_cnt[w][m];
+        run += s_lvl[w][m];
       }
     }
   }
   for (int i0 = w_begin; i0 < w_end; i0 += 4 * kWave) {
-    int c[4];
+    int lv[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int i = i0 + u * kWave + lane;
-      c[u] = i < w_end ? (int)class_in[i] : -1;
+      lv[u] = i < w_end ? nibble(out.level_of_class, (int)class_in[i] & 7) : -1;
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int i = i0 + u * kWave + lane;
 #pragma unroll
       for (int m = 0; m < CAMERA_MAX_LEVELS; ++m) {
-        if (m < n_classes) {
-          const uint64_t b = __ballot(c[u] == m);
-          if (c[u] == m) perm[slot[m] + __popcll(b & lower)] = i;
+        if (m < out.n_levels) {
+          const uint64_t b = __ballot(lv[u] == m);
+          if (lv[u] == m) out.perm[slot[m] + __popcll(b & lower)] = i;
           slot[m] += __popcll(b);
         }
       }
@@ -638,26 +666,15 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(const uint32
 
 static_assert(kSortThreads == kDigits, "one thread per digit in the scatter prologue");
 
-// Several ratios from one classification: class c = "below c of the m ascending cuts", so an element is kept at
-// ratio k iff c <= m - 1 - k.  kept[k][s] = sum of class_count[s][0 .. m - 1 - k].
-__global__ void kept_from_classes_kernel(const int32_t* __restrict__ class_count, int n_seg, int m,
-                                         int32_t* __restrict__ kept) {
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= n_seg) return;
-  int32_t run = 0;
-  for (int c = 0; c < m; ++c) {  // after adding class c the sum covers classes 0..c: ratio k = m - 1 - c
-    run += class_count[s * (m + 1) + c];
-    kept[(m - 1 - c) * n_seg + s] = run;
-  }
-}
-
 }  // namespace
 
 int64_t rank_blocks(int64_t n_micro) { return (n_micro + kKeysPerBlock - 1) / kKeysPerBlock; }
 
+size_t rank_state_bytes() { return sizeof(RankState); }
+
 int64_t rank_workspace_words(int64_t n_micro, int want_rank) {
   const int64_t g = rank_blocks(n_micro);
-  int64_t words = (int64_t)(sizeof(RankState) / 4) + 64 + (kMaxCuts + 1) * g + 64;
+  int64_t words = g + 64;  // kept counts per workgroup
   if (want_rank) {
     const int64_t n_blocks = (n_micro + kSortChunk - 1) / kSortChunk;
     words += 4 * (n_micro + 64) + n_blocks * kDigits;
@@ -666,39 +683,27 @@ int64_t rank_workspace_words(int64_t n_micro, int want_rank) {
 }
 
 hipError_t launch_classify(hipStream_t stream, const float* energy, int64_t n_micro, const RankCuts& cuts,
-                           uint8_t* class_out, uint8_t* byte_out, int32_t* kept_idx, int32_t* ws) {
+                           uint8_t* class_out, uint8_t* byte_out, uint8_t* byte_out2, int32_t* kept_idx, void* state,
+                           int32_t* ws) {
   if (n_micro <= 0) return hipSuccess;
   const unsigned g = (unsigned)rank_blocks(n_micro);
-  RankState* st = reinterpret_cast<RankState*>(ws);
-  uint32_t* tie_cnt = reinterpret_cast<uint32_t*>(ws) + sizeof(RankState) / 4 + 64;
-  uint32_t* kept_cnt = tie_cnt + (size_t)kMaxCuts * g;
-  hipLaunchKernelGGL(rank_zero_kernel, dim3(32), dim3(kRankThreads), 0, stream, st, cuts, n_micro);
-  hipLaunchKernelGGL(rank_hist_kernel<0>, dim3(g), dim3(kRankThreads), 0, stream, energy, n_micro, cuts.n_cuts, st);
-  hipLaunchKernelGGL(rank_hist_kernel<1>, dim3(g), dim3(kRankThreads), 0, stream, energy, n_micro, cuts.n_cuts, st);
-  hipLaunchKernelGGL(rank_hist_kernel<2>, dim3(g), dim3(kRankThreads), 0, stream, energy, n_micro, cuts.n_cuts, st);
-  hipLaunchKernelGGL(rank_ties_kernel, dim3(g), dim3(kRankThreads), 0, stream, energy, n_micro, cuts.n_cuts, st,
-                     tie_cnt);
-  hipLaunchKernelGGL(rank_label_kernel, dim3(g), dim3(kRankThreads), 0, stream, energy, n_micro, cuts, st, tie_cnt,
-                     class_out, byte_out, kept_idx ? kept_cnt : nullptr);
+  RankState* st = static_cast<RankState*>(state);
+  uint32_t* kept_cnt = reinterpret_cast<uint32_t*>(ws);
+  hipLaunchKernelGGL(rank_hist_kernel<0>, dim3(g), dim3(kRankThreads), 0, stream, energy, n_micro, cuts, st);
+  hipLaunchKernelGGL(rank_hist_kernel<1>, dim3(g), dim3(kRankThreads), 0, stream, energy, n_micro, cuts, st);
+  hipLaunchKernelGGL(rank_hist_kernel<2>, dim3(g), dim3(kRankThreads), 0, stream, energy, n_micro, cuts, st);
+  hipLaunchKernelGGL(rank_label_kernel, dim3(g), dim3(kRankThreads), 0, stream, energy, n_micro, cuts, st, class_out,
+                     byte_out, byte_out2, kept_idx ? kept_cnt : nullptr);
   if (kept_idx)
     hipLaunchKernelGGL(rank_compact_kernel, dim3(g), dim3(kRankThreads), 0, stream, class_out, n_micro, kept_cnt,
                        kept_idx);
   return hipGetLastError();
 }
 
-hipError_t launch_segment_counts(hipStream_t stream, const uint8_t* class_out, const SegTable& seg, int n_classes,
-                                 int kept_only, int32_t* counts, int32_t* perm) {
+hipError_t launch_segment_outputs(hipStream_t stream, const uint8_t* class_out, const SegTable& seg,
+                                  const SegOutputs& out) {
   if (seg.n_seg <= 0) return hipSuccess;
-  hipLaunchKernelGGL(segment_kernel, dim3((unsigned)seg.n_seg), dim3(kSegThreads), 0, stream, class_out, seg,
-                     n_classes, kept_only, counts, perm);
-  return hipGetLastError();
-}
-
-hipError_t launch_kept_from_classes(hipStream_t stream, const int32_t* class_count, int n_seg, int n_ratios,
-                                    int32_t* kept) {
-  if (n_seg <= 0 || n_ratios <= 0) return hipSuccess;
-  hipLaunchKernelGGL(kept_from_classes_kernel, dim3((unsigned)((n_seg + 255) / 256)), dim3(256), 0, stream, class_count,
-                     n_seg, n_ratios, kept);
+  hipLaunchKernelGGL(segment_kernel, dim3((unsigned)seg.n_seg), dim3(kSegThreads), 0, stream, class_out, seg, out);
   return hipGetLastError();
 }
 
@@ -706,7 +711,7 @@ hipError_t launch_full_rank(hipStream_t stream, const float* energy, int64_t n_m
                             int32_t* ws) {
   if (n_micro <= 0) return hipSuccess;
   const int64_t padded = n_micro + 64;
-  ws += rank_workspace_words(n_micro, 0);  // behind the select state
+  ws += rank_workspace_words(n_micro, 0);  // behind the kept counts
   uint32_t* keys_a = reinterpret_cast<uint32_t*>(ws);
   uint32_t* keys_b = keys_a + padded;
   uint32_t* idx_a = keys_b + padded;

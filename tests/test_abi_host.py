@@ -278,3 +278,22 @@ def test_select_prune_noalloc_argument_checks(lib, ctx):
     assert sel(E=None) == -1 and sel(mask=None) == -1 and sel(per=None) == -1
     assert sel(seg=seg_array([0, 40, 90])) == -1 and "seg_offsets" in err(lib, ctx)
     assert sel(n_seg=0) == -6
+
+
+def test_rank_decisions_argument_checks(lib, ctx):
+    seg = seg_array([0, 40, 100])
+
+    def both(ratios=(0.2, 0.4), bits=(3, 2, 1), level_ratios=(0.2, 0.6, 0.2), n_ratios=None, n_levels=None, E=FAKE,
+             keep=FAKE, per=FAKE, bit_of=FAKE, lc=FAKE, c=ctx):
+        return lib.camera_rank_decisions(
+            c, None, E, 100, seg, 2, len(ratios) if n_ratios is None else n_ratios,
+            (ctypes.c_double * len(ratios))(*ratios), keep, per, len(bits) if n_levels is None else n_levels,
+            (ctypes.c_int * len(bits))(*bits), (ctypes.c_double * len(level_ratios))(*level_ratios), bit_of, lc, None)
+    assert both(c=None) == -1
+    assert both(n_ratios=0) == -6 and both(n_levels=0) == -6
+    assert both(ratios=(0.1,) * 6, bits=(3, 2, 1)) == -6 and "cuts" in err(lib, ctx)         # 6 + 2 cuts > 7
+    assert both(ratios=(0.4, 0.2)) == -1 and "fall" in err(lib, ctx)
+    assert both(level_ratios=(0.5, 0.2, 0.2)) == -1 and "sum to 1" in err(lib, ctx)
+    assert both(bits=(300, 2, 1)) == -1
+    assert both(per=None) == -1 and both(lc=None) == -1 and both(keep=None) == -1 and both(bit_of=None) == -1
+    assert both(E=None) == -1 and "energy" in err(lib, ctx)

@@ -115,3 +115,45 @@ def test_select_at_several_ratios_with_ties_and_empty_segments(cam):
     E = inputs.energy_like(5000, seed=2, zero_fraction=0.3, tie_fraction=0.3)
     check_multi(cam, E, [0, 0, 1234, 1234, 4000, 5000], [0.2, 0.29, 0.31, 0.6])
     check_multi(cam, torch.zeros(3000), [0, 1000, 3000], [0.25, 0.5, 0.75])
+
+
+def check_decisions_one_pass(cam, E, seg, ratios, bits, level_ratios):
+    """camera_rank_decisions against the oracle's select at every ratio and its bit allocation."""
+    keep_bits, per, bit_of, level_count, perm = cam.rank_decisions(E.cuda(), seg, ratios, bits, level_ratios, want_perm=True)
+    keep_bits, per = keep_bits.cpu().numpy(), per.cpu().numpy()
+    for k, ratio in enumerate(ratios):
+        o_keep, o_per, _, _ = orc.select_prune(E.numpy(), seg, ratio)
+        np.testing.assert_array_equal((keep_bits >> k) & 1, o_keep)
+        np.testing.assert_array_equal(per[k], o_per)
+    o_bits, o_count, o_perm = orc.alloc_bits(E.numpy(), seg, bits, level_ratios)
+    np.testing.assert_array_equal(bit_of.cpu().numpy(), o_bits)
+    np.testing.assert_array_equal(level_count.cpu().numpy(), o_count)
+    np.testing.assert_array_equal(perm.cpu().numpy(), o_perm)
+
+
+@pytest.mark.parametrize("n", [1, 300, 4097, 98304, 184320])
+def test_masks_and_bits_from_one_pass(cam, n):
+    E = inputs.energy_like(n, seed=n + 17, zero_fraction=0.1, tie_fraction=0.1)
+    seg = even_segments(n, min(n, 9))
+    check_decisions_one_pass(cam, E, seg, [0.2, 0.4, 0.6], [3, 2, 1], [0.2, 0.6, 0.2])      # pruning and class cuts coincide at 0.2
+    check_decisions_one_pass(cam, E, seg, [0.5], [4, 3, 2], [0.1, 0.3, 0.6])
+    check_decisions_one_pass(cam, E, seg, [0.0, 0.35, 1.0], [8, 6, 4, 3, 2], [0.1, 0.2, 0.3, 0.3, 0.1])   # seven cuts
+    check_decisions_one_pass(cam, E, seg, [0.3, 0.3], [5], [1.0])
+
+
+def test_masks_and_bits_with_ties_and_empty_segments(cam):
+    E = inputs.energy_like(5000, seed=4, zero_fraction=0.3, tie_fraction=0.3)      # cuts run through groups of equal keys
+    check_decisions_one_pass(cam, E, [0, 0, 1234, 1234, 4000, 5000], [0.2, 0.29, 0.31], [3, 2, 1], [0.4, 0.31, 0.29])
+    check_decisions_one_pass(cam, torch.zeros(9000), [0, 1000, 9000], [0.25, 0.75], [4, 2], [0.5, 0.5])
+    big = inputs.energy_like(150000, seed=5, zero_fraction=0.5, tie_fraction=0.2)  # ties spread over many workgroups
+    check_decisions_one_pass(cam, big, even_segments(150000, 64), [0.2, 0.4, 0.6], [3, 2, 1], [0.2, 0.6, 0.2])
+
+
+def test_ranking_state_survives_interleaved_calls(cam):
+    """The select state cleans itself: calls of different sizes and cut counts in a row, each checked."""
+    for n, seed in ((184320, 1), (50, 2), (98304, 3), (4096, 4), (184320, 5)):
+        E = inputs.energy_like(n, seed=seed)
+        seg = even_segments(n, min(n, 5))
+        check_multi(cam, E, seg, [0.1, 0.5, 0.9])
+        check_select(cam, E, seg, 0.4, want_rank=False)
+        check_decisions_one_pass(cam, E, seg, [0.2, 0.6], [4, 3, 2], [0.25, 0.5, 0.25])
