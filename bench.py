@@ -101,9 +101,13 @@ class LayerRunner:
                 cam.score_layer(X, None, None, t["Ws_gate"], t["Ws_up"], t["Ws_down"], cfg.alpha, flags=flags,
                                 out=self.out_shared)
         res = []
-        if decisions["prune"]:   # every CAMERA-P mask of the workload from one pass over the ranking
+        alloc = list(decisions["alloc"])
+        if decisions["prune"] and alloc:   # masks and the first bit allocation from one pass over the ranking
+            bits, ratios = alloc.pop(0)
+            res.append(cam.rank_decisions(self.out["energy"], self.seg, decisions["prune"], bits, ratios))
+        elif decisions["prune"]:           # every CAMERA-P mask of the workload from one pass
             res.append(cam.select_prune_multi(self.out["energy"], self.seg, decisions["prune"], out=self.prune_out))
-        for bits, ratios in decisions["alloc"]:
+        for bits, ratios in alloc:
             res.append(cam.alloc_bits(self.out["energy"], self.seg, bits, ratios))
         return res
 

@@ -373,10 +373,11 @@ int camera_route_topk(camera_ctx* ctx, void* stream_, const void* X, int dtype, 
 
   DeviceGuard guard;
   CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
+  if (int rc = ensure_workspace(ctx, 0)) return rc;  // the zero page
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   Bracket b(ctx, stream, CAMERA_K_ROUTE);
   CAMERA_HIP(camera::launch_route_topk(stream, X, dtype, n, d_model, ldx, W_r, ldr, bias, n_experts, top_k, renorm,
-                                       topk_idx, topk_w),
+                                       ctx->zeros, topk_idx, topk_w),
              "route_topk launch");
   return CAMERA_OK;
 }

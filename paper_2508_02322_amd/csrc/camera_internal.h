@@ -29,7 +29,8 @@ struct BucketTables {
 // ---- route.hip --------------------------------------------------------------
 hipError_t launch_route_topk(hipStream_t stream, const void* X, int dtype, int64_t n, int64_t d_model,
                              int64_t ldx, const void* W_r, int64_t ldr, const float* bias, int n_experts,
-                             int top_k, int renorm, int32_t* topk_idx, float* topk_w);
+                             int top_k, int renorm, const void* zeros /* 16 readable zero bytes */, int32_t* topk_idx,
+                             float* topk_w);
 
 // ---- bucket.hip -------------------------------------------------------------
 // Pairs per block of the counting sort.

@@ -77,28 +77,35 @@ __device__ void topk_of_token(const float* s_row, int n_experts, int top_k, int 
   }
 }
 
-// bf16: 32 tokens per block, NT tiles of 32 experts; the four waves split d_model between them
-// (a lone wave per 32 tokens leaves the chip idle and waits for every load in turn) and keep
-// kUnroll K steps of loads in flight; partial logits are added through LDS in wave order.
-template <int NT>
-__global__ __launch_bounds__(256) void route_bf16_kernel(const __hip_bfloat16* __restrict__ X, int64_t n,
-                                                         int d_model, int64_t ldx,
-                                                         const __hip_bfloat16* __restrict__ R, int64_t ldr,
-                                                         const float* __restrict__ bias, int n_experts,
-                                                         int top_k, int renorm, int32_t* __restrict__ topk_idx,
-                                                         float* __restrict__ topk_w) {
+// bf16: 32 tokens per block, NT tiles of 32 experts.  The block's NG * 4 waves split d_model between them (a
+// lone wave per 32 tokens leaves the chip idle and waits for every load in turn) and keep kUnroll K steps of
+// loads in flight.  No load is conditional: a lane whose token, expert or K position lies outside reads a
+// valid address all the same (row 0, or a page of zeros for the K tail), so the compiler can issue a whole
+// batch before the first wait; what such lanes accumulate is never used.  Partial logits are added through
+// LDS in a fixed order: the four waves of a group one after the other, then the groups.
+template <int NT, int NG>
+__global__ __launch_bounds__(256 * NG) void route_bf16_kernel(const __hip_bfloat16* __restrict__ X, int64_t n,
+                                                              int d_model, int64_t ldx,
+                                                              const __hip_bfloat16* __restrict__ R, int64_t ldr,
+                                                              const float* __restrict__ bias, int n_experts,
+                                                              int top_k, int renorm,
+                                                              const __hip_bfloat16* __restrict__ zeros,
+                                                              int32_t* __restrict__ topk_idx,
+                                                              float* __restrict__ topk_w) {
   constexpr int kUnroll = NT <= 2 ? 8 : (NT == 4 ? 4 : 2);
-  __shared__ float s_logit[kTokens][NT * 32 + 1];
+  constexpr int kWaves = 4 * NG;
+  __shared__ float s_logit[NG][kTokens][NT * 32 + 1];
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int group = wave / 4, turn = wave % 4;
   const int frag_row = lane % 32, frag_half = lane / 32;
   const int64_t tok0 = (int64_t)blockIdx.x * kTokens;
   const int64_t tok = tok0 + frag_row;
-  const __hip_bfloat16* x_src = tok < n ? X + tok * ldx + frag_half * 8 : nullptr;
+  const __hip_bfloat16* x_src = X + (tok < n ? tok : 0) * ldx + frag_half * 8;
   const __hip_bfloat16* r_src[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     const int e = t * 32 + frag_row;
-    r_src[t] = e < n_experts ? R + (int64_t)e * ldr + frag_half * 8 : nullptr;
+    r_src[t] = R + (int64_t)(e < n_experts ? e : 0) * ldr + frag_half * 8;
   }
   f32x16 acc[NT];
 #pragma unroll
@@ -108,19 +115,18 @@ __global__ __launch_bounds__(256) void route_bf16_kernel(const __hip_bfloat16* _
 
   // this wave's share of the K steps (16 elements each)
   const int n_steps = (d_model + 15) / 16;
-  const int per_wave = (n_steps + 3) / 4;
-  const int k_begin = wave * per_wave * 16;
+  const int per_wave = (n_steps + kWaves - 1) / kWaves;
+  const int k_begin = min(d_model, wave * per_wave * 16);
   const int k_end = min(d_model, (wave + 1) * per_wave * 16);
-  const u32x4 zero4 = {0u, 0u, 0u, 0u};
   for (int k0 = k_begin; k0 < k_end; k0 += 16 * kUnroll) {
     u32x4 av[kUnroll], bv[kUnroll][NT];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const int k = k0 + 16 * u;
       const bool k_ok = k + frag_half * 8 < k_end;  // d_model and the wave shares are multiples of 8
-      av[u] = (x_src && k_ok) ? *reinterpret_cast<const u32x4*>(x_src + k) : zero4;
+      av[u] = *reinterpret_cast<const u32x4*>(k_ok ? x_src + k : zeros);
 #pragma unroll
-      for (int t = 0; t < NT; ++t) bv[u][t] = (r_src[t] && k_ok) ? *reinterpret_cast<const u32x4*>(r_src[t] + k) : zero4;
+      for (int t = 0; t < NT; ++t) bv[u][t] = *reinterpret_cast<const u32x4*>(k_ok ? r_src[t] + k : zeros);
     }
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u)
@@ -130,24 +136,34 @@ __global__ __launch_bounds__(256) void route_bf16_kernel(const __hip_bfloat16* _
                                                           __builtin_bit_cast(bf16x8, bv[u][t]), acc[t], 0, 0, 0);
   }
   // accumulator register r of lane l: token row 8*(r/4) + 4*(l/32) + (r%4), expert column l % 32
-  for (int w = 0; w < 4; ++w) {  // fixed order: wave 0 stores (with the bias), waves 1..3 add
-    if (wave == w) {
+  for (int w = 0; w < 4; ++w) {  // fixed order inside a group: its first wave stores, the others add
+    if (turn == w) {
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         const int e = t * 32 + frag_row;
-        const float b = (w == 0 && bias && e < n_experts) ? bias[e] : 0.0f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float* dst = &s_logit[(r / 4) * 8 + frag_half * 4 + (r % 4)][e];
-          *dst = (w == 0 ? 0.0f : *dst) + acc[t][r] + b;
+          float* dst = &s_logit[group][(r / 4) * 8 + frag_half * 4 + (r % 4)][e];
+          *dst = (w == 0 ? 0.0f : *dst) + acc[t][r];
         }
       }
     }
     __syncthreads();
   }
-  const int t_local = threadIdx.x / kSub, sub = threadIdx.x % kSub;  // 256 threads = 32 tokens x 8 lanes
+  // groups in order, then the bias
+  for (int i = threadIdx.x; i < kTokens * NT * 32; i += 256 * NG) {
+    const int t_row = i / (NT * 32), e = i % (NT * 32);
+    float v = s_logit[0][t_row][e];
+#pragma unroll
+    for (int g = 1; g < NG; ++g) v += s_logit[g][t_row][e];
+    if (bias && e < n_experts) v += bias[e];
+    s_logit[0][t_row][e] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x >= kTokens * kSub) return;
+  const int t_local = threadIdx.x / kSub, sub = threadIdx.x % kSub;  // 32 tokens x 8 lanes
   if (tok0 + t_local < n)
-    topk_of_token(s_logit[t_local], n_experts, top_k, renorm, sub, topk_idx + (tok0 + t_local) * top_k,
+    topk_of_token(s_logit[0][t_local], n_experts, top_k, renorm, sub, topk_idx + (tok0 + t_local) * top_k,
                   topk_w + (tok0 + t_local) * top_k);
 }
 
@@ -187,32 +203,35 @@ __global__ __launch_bounds__(256) void route_f32_kernel(const float* __restrict_
                   topk_w + (tok0 + t_local) * top_k);
 }
 
-template <int NT>
+template <int NT, int NG>
 void launch_bf16(hipStream_t stream, int64_t n_blocks, const void* X, int64_t n, int64_t d_model, int64_t ldx,
                  const void* W_r, int64_t ldr, const float* bias, int n_experts, int top_k, int renorm,
-                 int32_t* topk_idx, float* topk_w) {
-  hipLaunchKernelGGL(route_bf16_kernel<NT>, dim3((unsigned)n_blocks), dim3(256), 0, stream,
+                 const void* zeros, int32_t* topk_idx, float* topk_w) {
+  hipLaunchKernelGGL((route_bf16_kernel<NT, NG>), dim3((unsigned)n_blocks), dim3(256 * NG), 0, stream,
                      static_cast<const __hip_bfloat16*>(X), n, (int)d_model, ldx,
-                     static_cast<const __hip_bfloat16*>(W_r), ldr, bias, n_experts, top_k, renorm, topk_idx,
-                     topk_w);
+                     static_cast<const __hip_bfloat16*>(W_r), ldr, bias, n_experts, top_k, renorm,
+                     static_cast<const __hip_bfloat16*>(zeros), topk_idx, topk_w);
 }
 
 }  // namespace
 
 hipError_t launch_route_topk(hipStream_t stream, const void* X, int dtype, int64_t n, int64_t d_model,
                              int64_t ldx, const void* W_r, int64_t ldr, const float* bias, int n_experts,
-                             int top_k, int renorm, int32_t* topk_idx, float* topk_w) {
+                             int top_k, int renorm, const void* zeros, int32_t* topk_idx, float* topk_w) {
   if (n <= 0) return hipSuccess;
   const int64_t n_blocks = (n + kTokens - 1) / kTokens;
   if (dtype == CAMERA_BF16) {
     const int nt = (n_experts + 31) / 32;
-#define CAMERA_ROUTE_CASE(NT)                                                                                 \
-  launch_bf16<NT>(stream, n_blocks, X, n, d_model, ldx, W_r, ldr, bias, n_experts, top_k, renorm, topk_idx, \
-                  topk_w)
-    if (nt <= 1) CAMERA_ROUTE_CASE(1);
-    else if (nt <= 2) CAMERA_ROUTE_CASE(2);
-    else if (nt <= 4) CAMERA_ROUTE_CASE(4);
-    else CAMERA_ROUTE_CASE(8);
+    // two groups of four waves where the logits of both fit the 64 KiB of static LDS; a short d_model is not
+    // worth splitting eight ways
+    const bool wide = d_model >= 1024;
+#define CAMERA_ROUTE_CASE(NT, NG)                                                                                     \
+  launch_bf16<NT, NG>(stream, n_blocks, X, n, d_model, ldx, W_r, ldr, bias, n_experts, top_k, renorm, zeros, topk_idx, \
+                      topk_w)
+    if (nt <= 1) { if (wide) CAMERA_ROUTE_CASE(1, 2); else CAMERA_ROUTE_CASE(1, 1); }
+    else if (nt <= 2) { if (wide) CAMERA_ROUTE_CASE(2, 2); else CAMERA_ROUTE_CASE(2, 1); }
+    else if (nt <= 4) { if (wide) CAMERA_ROUTE_CASE(4, 2); else CAMERA_ROUTE_CASE(4, 1); }
+    else CAMERA_ROUTE_CASE(8, 1);
 #undef CAMERA_ROUTE_CASE
   } else {
     hipLaunchKernelGGL(route_f32_kernel, dim3((unsigned)n_blocks), dim3(256), 0, stream,
