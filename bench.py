@@ -22,6 +22,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3       # MI355X fp32 vector
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 # Decisions taken per layer after scoring: CAMERA-P ratios and CAMERA-Q (bits, ratios) settings.
 DECISIONS = {
@@ -34,8 +35,10 @@ DECISIONS = {
 }
 
 # HBM-side bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by what the same
-# counters read for a plain 1 GiB copy (profiles/grouped_gemm_bf16_qwen2-57b-a14b_hbm_traffic.txt); None where not measured.
-PMC_TRAFFIC_BYTES = {"qwen2-57b-a14b": 5.319e9}
+# counters read for a plain 1 GiB copy; not measured by this program: the figure and the file it comes from are
+# reported side by side (None where no such profile exists).
+PMC_TRAFFIC = {"qwen2-57b-a14b": (5.319e9, "profiles/grouped_gemm_bf16_qwen2-57b-a14b_hbm_traffic.txt")}
+PMC_NORM_TRAFFIC = {"qwen2-57b-a14b": (None, "profiles/down_norm_qwen2-57b-a14b_hbm_traffic.txt")}
 # The same for the two streaming kernels of the compacted layer on a 64-token batch, unpruned
 # (profiles/compact_layer_decode_hbm_traffic.txt): read + written bytes per call.
 PMC_DECODE_TRAFFIC_BYTES = {"deepseek-moe-16b": 777.0e6 + 392.5e6 + 5.6e6, "qwen2-57b-a14b": 2976.9e6 + 1522.0e6 + 19.0e6}
@@ -59,6 +62,13 @@ def parse_args():
     ap.add_argument("--energy-spread", type=float, default=0.0,
                     help="scale every W_down column by a log-normal factor of this sigma (per expert and per micro-expert): "
                          "energies and per-expert kept counts as uneven as on trained models; 0 = the named workload")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short timed runs of the other benchmark configurations after the main one")
+    ap.add_argument("--other-steps", type=int, default=5, help="timed steps of each of the other configurations")
+    ap.add_argument("--no-streamed", action="store_true",
+                    help="skip the streamed calibration of the paper's size (128 x 2048 tokens in chunks) after the main run")
+    ap.add_argument("--streamed-tokens", type=int, default=262144)
+    ap.add_argument("--streamed-chunk", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the measured MFMA / HBM ceilings (about 1 s)")
     ap.add_argument("--no-forward", action="store_true",
@@ -405,28 +415,78 @@ def cpu_baseline(cfg, inputs):
                       + f", all {cfg.n_tokens} tokens, {dt:.1f} s measured, scaled by {cfg.n_micro / scored:.1f}x to a whole layer"}
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no second device); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-    import torch
-    from paper_2508_02322_amd import binding, inputs
+def expert_counts(cam, cfg, layers, torch):
+    """Routed (token, expert) pairs per expert and layer, from the library's own routing (outside any timed region)."""
+    counts = []
+    for lr in layers:
+        idx, _ = cam.route_topk(lr.t["X"][:cfg.n_tokens], lr.t["W_r"], lr.t["bias"], cfg.top_k)
+        counts.append(torch.bincount(idx.flatten().long(), minlength=cfg.n_experts).cpu().double())
+    return torch.stack(counts)
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    cfg = inputs.CONFIGS[args.workload]
-    if args.energy_spread > 0:
-        cfg = inputs.scaled(cfg, energy_spread=args.energy_spread)
-    n_layers = args.layers if args.layers > 0 else cfg.n_layers
-    decisions = DECISIONS[args.workload]
+
+def gemm_bound_ms(cfg, counts):
+    """Per layer, the time no kernel can beat on the grouped contraction: every expert needs at least
+    max(its flops / MFMA peak, its gate + up weight bytes / HBM peak) -- an expert with few tokens is bound by
+    streaming its weights, one with many by the matrix pipe (arithmetic intensity ~ tokens of the expert per
+    weight byte against a ridge of 312 flop/B).  Shared experts see every token."""
+    es = 2 if cfg.dtype == "bf16" else 4
+    peak = (PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS) * 1e12
+    w_bytes = 2.0 * cfg.d_model * cfg.d_ff * es
+    t_routed = (counts * 4.0 * cfg.d_model * cfg.d_ff / peak).clamp(min=w_bytes / (PEAK_HBM_GBS * 1e9))
+    t_routed = t_routed * (counts > 0)           # an expert without tokens is not read at all
+    t = t_routed.sum(dim=1)
+    if cfg.n_shared:
+        ws = 2.0 * cfg.d_model * cfg.d_ff_shared * es
+        t = t + cfg.n_shared * max(4.0 * cfg.d_model * cfg.d_ff_shared * cfg.n_tokens / peak, ws / (PEAK_HBM_GBS * 1e9))
+    return float(t.mean() * 1e3)
+
+
+def pass_rooflines(cfg, kernel_ms, n_layers, steps, chunks_per_layer):
+    """HBM-side rooflines of the passes around the contraction, from the same event brackets: algorithmic bytes of a
+    launch group over its average duration.  The small ones are latency-bound and are reported in microseconds too."""
+    es = 2 if cfg.dtype == "bf16" else 4
+    n, d, k = cfg.n_tokens, cfg.d_model, cfg.top_k
+    calls = {  # algorithmic bytes per launch group
+        "down_norm": (cfg.n_micro * d * es + 4.0 * cfg.n_micro) / (2 if cfg.n_shared else 1),   # W_down once, omega2 out
+        "route": n * d * es + cfg.n_experts * d * es + 8.0 * n * k,                              # X and R once, indices and weights out
+        "bucket": 16.0 * n * k / (2 if cfg.n_shared else 1),                                     # 16 B per routed pair; the dense tables are free
+        "finalize": 28.0 * cfg.n_micro / (2 if cfg.n_shared else 1),                             # statistics, omega partials, four outputs
+        "rank": 6.0 * cfg.n_micro,                                                               # the energies once, two output bytes
+    }
+    out = {}
+    for name, bytes_per_call in calls.items():
+        rec = kernel_ms.get(name)
+        if not rec or not rec["launches"]:
+            continue
+        us = rec["ms_total"] / rec["launches"] * 1e3
+        gbs = bytes_per_call / (us * 1e-6) / 1e9
+        out[name] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(gbs / PEAK_HBM_GBS, 4), "us_per_call": round(us, 2),
+                     "algorithmic_bytes_per_call": bytes_per_call, "calls_per_layer": round(rec["launches"] / (n_layers * steps * 1.0), 2),
+                     "ms_per_step": round(rec["ms_total"] / steps, 3)}
+    if "down_norm" in out:
+        traffic = PMC_NORM_TRAFFIC.get(cfg.name)
+        out["down_norm"]["traffic"] = traffic[0] if traffic else None
+        out["down_norm"]["traffic_source"] = traffic[1] if traffic else None
+    for name in ("route", "bucket", "finalize", "rank"):
+        if name in out:
+            out[name]["note"] = "latency- and launch-bound at this size: microseconds per call is the figure that matters"
+    return out
+
+
+def run_workload(name, args, torch, binding, inputs, steps, warmup, calib_tokens=0, chunk_tokens=0, energy_spread=0.0,
+                 n_layers=0, keep_layers=False):
+    """Builds the resident layers of one configuration, times `steps` passes of the whole hot path over them with
+    the per-kernel event brackets on, and returns the figures (and the layers, when asked to keep them)."""
+    cfg = inputs.CONFIGS[name]
+    if energy_spread > 0:
+        cfg = inputs.scaled(cfg, energy_spread=energy_spread)
+    n_layers = n_layers if n_layers > 0 else cfg.n_layers
+    decisions = DECISIONS[name]
     cam = binding.Camera(device=0)
-
     t_gen = time.perf_counter()
-    calib_tokens = args.calib_tokens if args.calib_tokens > 0 else cfg.n_tokens
-    chunk_tokens = args.chunk_tokens if args.chunk_tokens > 0 else cfg.n_tokens
+    calib_tokens = calib_tokens if calib_tokens > 0 else cfg.n_tokens
+    chunk_tokens = chunk_tokens if chunk_tokens > 0 else cfg.n_tokens
     layers = [LayerRunner(cam, cfg, i, torch, inputs, calib_tokens, chunk_tokens) for i in range(n_layers)]
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
@@ -444,35 +504,95 @@ def main():
             with torch.cuda.stream(streams[i % n_streams]):
                 lr.run(cams[i % n_streams], decisions, binding)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     for k in range(len(binding.KERNEL_NAMES)):
         cam.profile_read(k)
     cam.profile_enable(True)
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     cam.profile_enable(False)
 
     kernel_ms = {}
-    for k, name in enumerate(binding.KERNEL_NAMES):
+    for k, kname in enumerate(binding.KERNEL_NAMES):
         ms, count = cam.profile_read(k)
-        kernel_ms[name] = {"ms_total": round(ms, 3), "launches": count}
+        if count:
+            kernel_ms[kname] = {"ms_total": round(ms, 3), "launches": count}
     gemm = kernel_ms["gemm"]
+    chunks_per_layer = len(layers[0].chunks)
     flops_per_step = cfg.gemm_flops_per_layer() * n_layers * (calib_tokens / cfg.n_tokens)
-    gemm_launches_per_step = gemm["launches"] / max(1, args.steps)
-    flops_per_launch = flops_per_step / max(1.0, gemm_launches_per_step)
+    flops_per_launch = flops_per_step / max(1.0, gemm["launches"] / max(1, steps))
     avg_launch_s = gemm["ms_total"] / max(1, gemm["launches"]) * 1e-3
     achieved = flops_per_launch / avg_launch_s / 1e12 if avg_launch_s > 0 else 0.0
     bf16 = cfg.dtype == "bf16"
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_TFLOPS
+    traffic = PMC_TRAFFIC.get(name) if calib_tokens == cfg.n_tokens and energy_spread == 0 else None
     roofline = {"kernel": "grouped_gemm_" + ("bf16" if bf16 else "f32"), "bound": "mfma" if bf16 else "alu",
                 "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                "traffic": PMC_TRAFFIC_BYTES.get(args.workload),
+                "traffic": traffic[0] if traffic else None,
+                "traffic_source": (traffic[1] + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE; not measured in this run)") if traffic else None,
                 "flops_per_launch": flops_per_launch, "avg_launch_ms": round(avg_launch_s * 1e3, 4)}
+    if calib_tokens == cfg.n_tokens:
+        # what the skew of the routing allows at best: every expert bound by its flops or by streaming its weights
+        counts = expert_counts(cam, cfg, layers[:min(4, n_layers)], torch)
+        bound_ms = gemm_bound_ms(cfg, counts)
+        gemm_ms_per_layer = gemm["ms_total"] / (steps * n_layers)
+        roofline["per_expert_bound"] = {
+            "what": "sum over experts of max(flops / MFMA peak, gate + up weight bytes / HBM peak), ms per layer, "
+                    f"from the token counts of the first {counts.shape[0]} layers",
+            "bound_ms_per_layer": round(bound_ms, 4), "gemm_ms_per_layer": round(gemm_ms_per_layer, 4),
+            "frac": round(bound_ms / gemm_ms_per_layer, 4),
+            "tokens_per_expert_min_max": [int(counts.min()), int(counts.max())]}
+    ms_per_step = elapsed / steps * 1e3
+    other = sum(v["ms_total"] for kname, v in kernel_ms.items() if kname != "gemm") / steps
+    result = {
+        "value": round(calib_tokens * n_layers * steps / elapsed, 1), "unit": "tokens*layers/s", "steps": steps,
+        "warmup": warmup, "ms_per_step": round(ms_per_step, 3), "dtype": cfg.dtype,
+        "config": {"workload": cfg.name + ("" if n_layers == cfg.n_layers else f"[first {n_layers} layers only]")
+                   + ("" if calib_tokens == cfg.n_tokens else f"[{calib_tokens} calibration tokens in chunks of {chunk_tokens}]")
+                   + ("" if cfg.energy_spread == 0 else f"[W_down columns scaled log-normally, sigma {cfg.energy_spread}]"),
+                   "layers": n_layers, "tokens": calib_tokens, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
+                   "experts": cfg.n_experts, "top_k": cfg.top_k, "shared_experts": cfg.n_shared,
+                   "d_ff_shared": cfg.d_ff_shared, "alpha": cfg.alpha, "decisions": decisions,
+                   "full_analysis_seconds": round(ms_per_step * 1e-3, 4), "input_generation_s": round(t_gen, 1)},
+        "mfma_util_pct_of_bf16_peak": round(100.0 * achieved / PEAK_BF16_TFLOPS, 2) if bf16 else None,
+        "roofline": roofline,
+        "rooflines": pass_rooflines(cfg, kernel_ms, n_layers, steps, chunks_per_layer),
+        "non_gemm_share_of_step": round(other / ms_per_step, 4),
+        "kernel_ms": kernel_ms,
+    }
+    if keep_layers:
+        return result, cam, cfg, layers
+    del layers, cams
+    cam.close()
+    torch.cuda.empty_cache()
+    return result
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no second device); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2508_02322_amd import binding, inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+
+    main_run, cam, cfg, layers = run_workload(args.workload, args, torch, binding, inputs, args.steps, args.warmup,
+                                              calib_tokens=args.calib_tokens, chunk_tokens=args.chunk_tokens,
+                                              energy_spread=args.energy_spread, n_layers=args.layers, keep_layers=True)
+    calib_tokens = main_run["config"]["tokens"]
+    roofline = main_run["roofline"]
+    achieved = roofline["achieved"]
+    bf16 = cfg.dtype == "bf16"
 
     if not args.no_probes:
         # Measured ceilings beside the published peak: the register-resident MFMA loop sustains the published rate
@@ -521,30 +641,28 @@ def main():
 
     if "measured" in roofline and bf16:
         roofline["measured"]["vendor_gemm_dense_equivalent"] = stage("vendor_gemm", False, vendor_reference)
+    own_size = calib_tokens == cfg.n_tokens
     apply_mask = stage("apply_mask", args.no_apply, lambda: measure_apply(cam, cfg, layers, torch, binding))
-    forward = stage("pruned_layer_output", args.no_forward or calib_tokens != cfg.n_tokens,
+    forward = stage("pruned_layer_output", args.no_forward or not own_size,
                     lambda: measure_forward(cam, cfg, layers, torch, binding))
-    decode = stage("pruned_layer_decode", args.no_decode or calib_tokens != cfg.n_tokens,
+    decode = stage("pruned_layer_decode", args.no_decode or not own_size,
                    lambda: measure_decode(cam, cfg, layers, torch, binding,
                                           ratios=[float(r) for r in args.decode_ratios.split(",")]))
+    del layers
+    cam.close()
+    torch.cuda.empty_cache()
 
-    ms_per_step = elapsed / args.steps * 1e3
-    value = calib_tokens * n_layers * args.steps / elapsed
     result = {
         "metric": "calibration tokens x layers scored/sec; MFMA util % of bf16 peak",
-        "value": round(value, 1), "unit": "tokens*layers/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": main_run["value"], "unit": main_run["unit"], "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_run["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": cfg.name + ("" if n_layers == cfg.n_layers else f"[first {n_layers} layers only]")
-                   + ("" if calib_tokens == cfg.n_tokens else f"[{calib_tokens} calibration tokens in chunks of {chunk_tokens}]")
-                   + ("" if cfg.energy_spread == 0 else f"[W_down columns scaled log-normally, sigma {cfg.energy_spread}]"),
-                   "layers": n_layers, "tokens": calib_tokens, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
-                   "experts": cfg.n_experts, "top_k": cfg.top_k, "shared_experts": cfg.n_shared,
-                   "d_ff_shared": cfg.d_ff_shared, "alpha": cfg.alpha, "decisions": decisions,
-                   "full_analysis_seconds": round(ms_per_step * 1e-3, 4), "input_generation_s": round(t_gen, 1)},
-        "mfma_util_pct_of_bf16_peak": round(100.0 * achieved / PEAK_BF16_TFLOPS, 2) if bf16 else None,
+        "config": main_run["config"],
+        "mfma_util_pct_of_bf16_peak": main_run["mfma_util_pct_of_bf16_peak"],
         "roofline": roofline,
-        "kernel_ms": kernel_ms,
+        "rooflines": main_run["rooflines"],
+        "non_gemm_share_of_step": main_run["non_gemm_share_of_step"],
+        "kernel_ms": main_run["kernel_ms"],
     }
     if apply_mask is not None:
         result["apply_mask"] = apply_mask
@@ -552,9 +670,33 @@ def main():
         result["pruned_layer_output"] = forward
     if decode is not None:
         result["pruned_layer_decode"] = decode
+
+    plain = own_size and args.energy_spread == 0 and args.layers == 0
+    if plain and not args.no_streamed and bf16 and args.workload == "qwen2-57b-a14b":
+        # The paper's calibration size (128 sequences of 2048 tokens), streamed in chunks through CAMERA_ACCUMULATE:
+        # the like-for-like token count beside its "under five minutes" (other hardware, whole pipeline: context only).
+        def streamed():
+            r = run_workload(args.workload, args, torch, binding, inputs, steps=1, warmup=1,
+                             calib_tokens=args.streamed_tokens, chunk_tokens=args.streamed_chunk)
+            return {"tokens": args.streamed_tokens, "chunk": args.streamed_chunk, "layers": r["config"]["layers"],
+                    "seconds": round(r["ms_per_step"] * 1e-3, 4), "tokens_layers_per_s": r["value"],
+                    "frac": r["roofline"]["frac"], "gemm_tflops": r["roofline"]["achieved"],
+                    "non_gemm_share_of_step": r["non_gemm_share_of_step"],
+                    "what": "whole analysis of the configuration on this many calibration tokens per layer, one warm-up pass, one timed pass"}
+        result["streamed_calibration"] = stage("streamed_calibration", False, streamed)
+    if plain and not args.no_other_workloads:
+        others = {}
+        for name in ("tiny", "mixtral", "deepseek-moe-16b", "qwen2-57b-a14b", "qwen3-30b-a3b"):
+            if name == args.workload:
+                continue
+            r = stage(name, False, lambda name=name: run_workload(name, args, torch, binding, inputs,
+                                                                   steps=max(1, args.other_steps), warmup=2))
+            if r is not None and "error" not in r:
+                r = {k: r[k] for k in ("value", "unit", "steps", "ms_per_step", "dtype", "mfma_util_pct_of_bf16_peak", "roofline",
+                                       "rooflines", "non_gemm_share_of_step", "config")}
+            others[name] = r
+        result["workloads"] = others
     if not args.no_cpu_baseline:
-        del layers
-        torch.cuda.empty_cache()
         result["cpu_baseline"] = stage("cpu_baseline", False, lambda: cpu_baseline(cfg, inputs))
     print(json.dumps(result))
 
