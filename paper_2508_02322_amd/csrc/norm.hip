@@ -122,10 +122,25 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(int n_experts, int d
   if (c >= d_ff) return;
   const int64_t i = (int64_t)e * d_ff + c;
   const int64_t n_micro = (int64_t)n_experts * d_ff;
+  // M-tiles of this expert, added in tile order.  Eight loads are in flight at a time (a thread that waits for
+  // each tile in turn spends the kernel waiting); tiles past the end re-read the last one and contribute nothing.
   float sum = 0.0f, mx = 0.0f;
-  for (int t = tile_offset[e]; t < tile_offset[e + 1]; ++t) {  // M-tiles of this expert, in order
-    sum += part_phi2[(int64_t)t * d_ff + c];
-    mx = fmaxf(mx, part_max[(int64_t)t * d_ff + c]);
+  const int t_begin = tile_offset[e], t_end = tile_offset[e + 1];
+  for (int t0 = t_begin; t0 < t_end; t0 += 8) {
+    float p2[8], pm[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int t = min(t0 + u, t_end - 1);
+      p2[u] = part_phi2[(int64_t)t * d_ff + c];
+      pm[u] = part_max[(int64_t)t * d_ff + c];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (t0 + u < t_end) {
+        sum += p2[u];
+        mx = fmaxf(mx, pm[u]);
+      }
+    }
   }
   if (accumulate) {
     sum += phi2[i];
@@ -135,7 +150,14 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(int n_experts, int d
   phi_inf[i] = mx;
   if (finalize) {
     float w2 = 0.0f;
-    for (int s = 0; s < splits; ++s) w2 += omega_part[(int64_t)s * n_micro + i];
+    for (int s0 = 0; s0 < splits; s0 += 8) {  // row splits of omega^2, in split order, eight loads at a time
+      float part[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) part[u] = omega_part[(int64_t)min(s0 + u, splits - 1) * n_micro + i];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (s0 + u < splits) w2 += part[u];
+    }
     omega2[i] = w2;
     energy[i] = ((1.0f - alpha) * sum + alpha * mx) * w2;
   }
