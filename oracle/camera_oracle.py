@@ -23,6 +23,9 @@ Analysis"):
   GetSubIndex (Algorithm 3).
 * Applying a selection (Algorithm 2, lines 10-13): the kept gate / up rows and
   down columns of every expert, gathered in index order.
+* The comparison variant CAMERA-Q-dagger, which slices all three matrices along
+  their input dimension: the input-channel statistic diag(X_e^T X_e) that such
+  schemes rank by, and the column gather W[:, s_k].
 * The layer output with a subset of the micro-experts (Eq. 1-2; the recomputed
   output of Algorithm 2, line 14) and its distance from the original output:
   the Lemma's decoding error, L2 and cosine.
@@ -42,7 +45,9 @@ Parity pins: every function here is pinned by tests/test_oracle_*.py
 library softmax / SiLU, symmetries, brute-force sorting; for the gather, the
 layer rebuilt from the compacted weights against the layer with the pruned
 vectors zeroed; for the layer output, a loop-written forward pass, the
-one-removed-index equality of the Lemma and the library's bfloat16 rounding).  The absolute score
+one-removed-index equality of the Lemma and the library's bfloat16 rounding; for the
+dagger variant, the library's column norms and the invariance of the projections under
+one permutation of the input channels of X and of the matrix columns).  The absolute score
 values on the model-shaped configs are not printed anywhere in the paper:
 for those, parity is pinned only through this oracle.
 """
@@ -335,6 +340,47 @@ def gather_micro_experts(W_gate, W_up, W_down, index, count, index_base=0):
         down_out.append(W_down[e][:, mine].copy())
         pos += int(count[e])
     return gate_out, up_out, down_out
+
+
+# --------------------------------------------------------------------------
+# CAMERA-Q-dagger: the comparison variant that slices every matrix along its
+# input dimension (Section "Experimental Setup", mixed-precision paragraph;
+# Section "Micro-Expert Integrity")
+# --------------------------------------------------------------------------
+def input_channel_energy(X, A):
+    """h[e, c] = sum over the tokens j routed to expert e of X[j, c]^2: the diagonal of
+    H_e = X_e^T X_e, the input-side statistic by which column-wise mixed-precision schemes
+    rank the input channels of a matrix.  X [n, d_model]; A [n, N_E] routing weights (only
+    whether A[j, e] is zero matters: H depends on the inputs alone).  Returns [N_E, d_model]."""
+    X, A = _f64(X), _f64(A)
+    h = np.zeros((A.shape[1], X.shape[1]), dtype=F64)
+    for e in range(A.shape[1]):
+        rows = np.nonzero(A[:, e] != 0.0)[0]
+        h[e] = (X[rows] * X[rows]).sum(axis=0)
+    return h
+
+
+def gather_columns(W, index, count, index_base=0):
+    """W[e][:, S_e] for every expert: the columns listed in ``index`` (global indices
+    index_base + e*cols + c, grouped by expert in expert order, count[e] of them), in that order.
+    W [N_E, rows, cols].  With W = W_up or W_gate ([N_E, d_ff, d_model]: columns are input
+    channels) and the per-expert reordering that ``alloc_bits`` returns for the input-channel
+    energies, this is the column-wise slicing W_{:, s_k} of the dagger variant; with W = W_down it
+    is the W_down half of ``gather_micro_experts``.  Returns a list of [rows, count[e]] matrices."""
+    W = np.asarray(W)
+    n_experts, _, cols = W.shape
+    index = np.asarray(index, dtype=np.int64)
+    count = np.asarray(count, dtype=np.int64)
+    if count.shape != (n_experts,) or count.sum() != index.size or np.any(count < 0):
+        raise ValueError("count must give the number of entries of every expert")
+    out, pos = [], 0
+    for e in range(n_experts):
+        mine = index[pos:pos + count[e]] - index_base - e * cols
+        if np.any(mine < 0) or np.any(mine >= cols):
+            raise ValueError("an index lies outside its expert")
+        out.append(W[e][:, mine].copy())
+        pos += int(count[e])
+    return out
 
 
 # --------------------------------------------------------------------------
