@@ -276,6 +276,25 @@ int camera_gather_micro_experts(camera_ctx* ctx, void* stream, int dtype,
                                 void* W_gate_out, void* W_up_out, void* W_down_out);
 
 /*
+ * The comparison variant CAMERA-Q-dagger (Section "Experimental Setup", mixed-precision paragraph; Section
+ * "Micro-Expert Integrity"): mixed precision by slicing every matrix along its input dimension, W_up[:, s_k],
+ * W_gate[:, s_k], W_down[:, s_k], as single-matrix schemes do that rank input channels by H = X X^T.  For W_down the
+ * input dimension is d_ff, so its split is CAMERA-Q's own.  For W_up and W_gate it is d_model; the statistic such
+ * schemes rank by is returned here:
+ *   h[e * d_model + c] = sum over the tokens j routed to expert e of X[j, c]^2        (the diagonal of X_e^T X_e)
+ * camera_alloc_bits on h (segments of d_model per expert) then gives the bit width of every input column and the
+ * per-expert reordering, and camera_gather_micro_experts with W_up (or W_gate) in the place of W_down, d_ff and
+ * d_model exchanged, applies it (the columns of equal precision side by side).
+ *   X, dtype, n, d_model, ldx: as in camera_score_layer
+ *   topk_idx  [n x top_k] int32, entries outside [0, n_experts) ignored; NULL: every expert sees every token
+ *   h         float32 [n_experts * d_model] out
+ * float32 accumulation in a fixed order (bit-reproducible).  n == 0 gives zeros.
+ */
+int camera_input_channel_energy(camera_ctx* ctx, void* stream,
+                                const void* X, int dtype, int64_t n, int64_t d_model, int64_t ldx,
+                                const int32_t* topk_idx, int top_k, int n_experts, float* h);
+
+/*
  * The layer output over a subset of the micro-experts (Eq. 1-2; the output recomputed after pruning in
  * Algorithm 2, line 14):
  *   Y[j, :] = sum over experts e and kept channels c of  Lambda_e[j, c] * W_down,e[:, c],

@@ -23,7 +23,7 @@ KERNEL_NAMES = ["route", "bucket", "gemm", "down_norm", "finalize", "rank", "gat
 
 EXPORTS = ["camera_create", "camera_destroy", "camera_last_error", "camera_version", "camera_route_topk",
            "camera_score_layer", "camera_select_prune", "camera_select_prune_noalloc", "camera_select_prune_multi", "camera_alloc_bits", "camera_rank_decisions",
-           "camera_gather_micro_experts", "camera_layer_forward", "camera_layer_forward_compact", "camera_output_error", "camera_profile_enable",
+           "camera_gather_micro_experts", "camera_input_channel_energy", "camera_layer_forward", "camera_layer_forward_compact", "camera_output_error", "camera_profile_enable",
            "camera_profile_read"]
 
 _c = ctypes
@@ -59,6 +59,7 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
                                           _c.POINTER(_i), _c.POINTER(_d), _vp, _vp, _vp]
     lib.camera_gather_micro_experts.argtypes = [_vp, _vp, _i, _i, _i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, _i64,
                                                 _i64, _vp, _i, _vp, _vp, _vp]
+    lib.camera_input_channel_energy.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _i, _i, _vp]
     lib.camera_layer_forward.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _vp, _i, _i, _i64, _vp, _vp, _i64,
                                          _vp, _i64, _vp, _i, _vp]
     lib.camera_layer_forward_compact.argtypes = [_vp, _vp, _vp, _i, _i64, _i64, _i64, _vp, _vp, _i, _i, _i,
@@ -303,6 +304,20 @@ class Camera:
             self._ctx, _stream_handle(self.device), _dtype_code(ref), n_experts, d_ff, d_model, _ptr(W_gate), _ptr(W_up),
             stride_gu, _ptr(W_down), W_down.stride(0) if W_down is not None else 0, _ptr(index), n_index,
             int(index_base), _ptr(count), int(down_row_align), _ptr(out[0]), _ptr(out[1]), _ptr(out[2])))
+        return out
+
+    def input_channel_energy(self, X, topk_idx, n_experts: int, out=None):
+        """h [n_experts, d_model] float32: per expert, the sum over its routed tokens of X[j, c]^2 (the statistic the
+        column-wise comparison variant CAMERA-Q-dagger ranks the input channels of W_up / W_gate by)."""
+        _check_matrix(X, "X")
+        _check_flat(topk_idx, "topk_idx", torch.int32, X.device)
+        n, d = X.shape
+        if out is None:
+            out = torch.empty((n_experts, d), dtype=torch.float32, device=self.device)
+        _check_flat(out, "h", torch.float32, X.device)
+        self._check(self.lib.camera_input_channel_energy(
+            self._ctx, _stream_handle(self.device), _ptr(X), _dtype_code(X), n, d, X.stride(0), _ptr(topk_idx),
+            0 if topk_idx is None else topk_idx.shape[1], int(n_experts), _ptr(out)))
         return out
 
     def layer_forward(self, X, topk_idx, topk_w, W_gate, W_up, W_down, keep_mask=None, Y=None, accumulate=False):

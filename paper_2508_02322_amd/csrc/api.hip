@@ -473,6 +473,49 @@ int camera_score_layer(camera_ctx* ctx, void* stream_, const void* X, int dtype,
   return CAMERA_OK;
 }
 
+int camera_input_channel_energy(camera_ctx* ctx, void* stream_, const void* X, int dtype, int64_t n, int64_t d_model,
+                                int64_t ldx, const int32_t* topk_idx, int top_k, int n_experts, float* h) {
+  if (ctx == nullptr) return fail(nullptr, CAMERA_EINVAL, "ctx: NULL");
+  if (int rc = check_common(ctx, X, dtype, n, d_model, ldx)) return rc;
+  const bool dense = topk_idx == nullptr;
+  if (n_experts < 1 || n_experts > CAMERA_MAX_EXPERTS)
+    return fail(ctx, CAMERA_EUNSUPPORTED, "n_experts: must be in [1, %d]", CAMERA_MAX_EXPERTS);
+  if (!dense && (top_k < 1 || top_k > n_experts)) return fail(ctx, CAMERA_EINVAL, "top_k: must be in [1, n_experts]");
+  if (h == nullptr) return fail(ctx, CAMERA_EINVAL, "h: NULL");
+  const int64_t n_pairs = dense ? n * n_experts : n * (int64_t)top_k;
+  if (n_pairs >= (int64_t(1) << 31) - 1024) return fail(ctx, CAMERA_ESHAPE, "routed pairs: must be below 2^31");
+  const int64_t n_cols = (int64_t)n_experts * d_model;
+  if (n_cols >= (int64_t(1) << 31) - 1024) return fail(ctx, CAMERA_ESHAPE, "n_experts * d_model: too large");
+  const int splits = camera::input_energy_splits(n_experts, d_model, dtype);
+  const int64_t n_blocks = dense ? 0 : camera::bucket_blocks(n_pairs);
+  const int tile_m = 256;                         // the M-tile tables are made but not used here
+  const int max_tiles = (int)std::min<int64_t>(65535, n == 0 ? 0 : (dense ? n_experts * ((n + tile_m - 1) / tile_m)
+                                                                          : n_pairs / tile_m + n_experts));
+  Carver cv;
+  BucketPlan plan;
+  plan.take(cv, dense, false, n_experts, n_pairs, max_tiles, n_blocks);
+  const size_t o_part = cv.take(sizeof(float) * (size_t)splits * n_cols);
+  DeviceGuard guard;
+  CAMERA_HIP(guard.enter(ctx->device), "hipSetDevice");
+  if (int rc = ensure_workspace(ctx, cv.used)) return rc;
+  char* ws = static_cast<char*>(ctx->ws);
+  const camera::BucketTables t = plan.bind(ws, ctx->zeros);
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  {
+    Bracket b(ctx, stream, CAMERA_K_BUCKET);
+    if (dense || n == 0)
+      CAMERA_HIP(camera::launch_dense_tables(stream, n, n_experts, tile_m, max_tiles, t), "dense tables launch");
+    else
+      CAMERA_HIP(camera::launch_bucket(stream, topk_idx, nullptr, n, top_k, n_experts, tile_m, max_tiles, t),
+                 "bucket launch");
+  }
+  Bracket b(ctx, stream, CAMERA_K_DOWN_NORM);
+  CAMERA_HIP(camera::launch_input_energy(stream, dtype, X, ldx, n_experts, d_model, t, splits,
+                                         reinterpret_cast<float*>(ws + o_part), h),
+             "input energy launch");
+  return CAMERA_OK;
+}
+
 int camera_layer_forward(camera_ctx* ctx, void* stream_, const void* X, int dtype, int64_t n, int64_t d_model,
                          int64_t ldx, const int32_t* topk_idx, const float* topk_w, int top_k, int n_experts,
                          int64_t d_ff, const void* W_gate, const void* W_up, int64_t stride_gu, const void* W_down,

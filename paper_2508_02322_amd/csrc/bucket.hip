@@ -159,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(const int32_t*
     }
     if (e >= 0) {
       perm[slot] = (int32_t)(p / top_k);
-      w_perm[slot] = topk_w[p];
+      if (topk_w) w_perm[slot] = topk_w[p];
     }
     if (slot_of != nullptr && p < n_pairs) slot_of[p] = e >= 0 ? slot : -1;
   }

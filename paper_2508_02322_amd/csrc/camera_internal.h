@@ -39,6 +39,7 @@ inline int64_t bucket_blocks(int64_t n_pairs) { return (n_pairs + kBucketChunk -
 
 // Stable counting sort of the n*top_k pairs by expert, then the M-tile tables
 // for tiles of `tile_m` rows.
+// (topk_w may be NULL: w_perm is then left unwritten.)
 hipError_t launch_bucket(hipStream_t stream, const int32_t* topk_idx, const float* topk_w, int64_t n, int top_k,
                          int n_experts, int tile_m, int max_tiles, const BucketTables& t);
 // Tables for the dense case: every expert sees tokens 0..n-1 with weight 1.
@@ -74,6 +75,12 @@ hipError_t launch_grouped_gemm(hipStream_t stream, int dtype, const void* X, int
 int down_norm_splits(int n_experts, int64_t d_model, int64_t d_ff);
 hipError_t launch_down_norm(hipStream_t stream, int dtype, const void* W_down, int64_t stride_down,
                             int n_experts, int64_t d_model, int64_t d_ff, int splits, float* omega_part);
+
+// Input-channel energies h[e][c] = sum over the tokens in expert e's bucket of X[token][c]^2; part is
+// [splits x n_experts*d_model] scratch, added in split order.
+int input_energy_splits(int n_experts, int64_t d_model, int dtype);
+hipError_t launch_input_energy(hipStream_t stream, int dtype, const void* X, int64_t ldx, int n_experts,
+                               int64_t d_model, const BucketTables& t, int splits, float* part, float* h);
 
 // Reduce the per-tile statistics in tile order, merge with earlier chunks,
 // reduce omega partials in split order and form the energy.

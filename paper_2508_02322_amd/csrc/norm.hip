@@ -109,6 +109,64 @@ __global__ __launch_bounds__(kThreads) void down_norm_generic_kernel(const T* __
   omega_part[(int64_t)blockIdx.y * n_micro + (int64_t)e * d_ff + c] = s;
 }
 
+// Input-channel energies h[e][c] = sum over the tokens routed to expert e of X[token][c]^2 (the diagonal of
+// X_e^T X_e).  Same streaming shape as down_norm, with the rows found through the bucket permutation:
+// grid = (column blocks, row splits, experts); split s of expert e takes an equal share of its bucket.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void input_energy_kernel(const T* __restrict__ X, int64_t ldx, int d_model,
+                                                                const int32_t* __restrict__ offsets,
+                                                                const int32_t* __restrict__ perm, int64_t n_cols,
+                                                                float* __restrict__ part) {
+  constexpr int V = Vec<T>::kPerLane;
+  __shared__ float s_part[kWaves][kWave * V];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int e = blockIdx.z;
+  const int c0 = (blockIdx.x * kWave + lane) * V;
+  const int first = offsets[e], count = offsets[e + 1] - first;
+  const int r_begin = (int)((int64_t)count * blockIdx.y / gridDim.y);
+  const int r_end = (int)((int64_t)count * (blockIdx.y + 1) / gridDim.y);
+  float acc[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) acc[i] = 0.0f;
+  if (c0 < d_model) {  // d_model is a multiple of V, so the whole vector is inside
+    auto row = [&](int r) { return X + (int64_t)(perm ? perm[first + r] : r) * ldx + c0; };
+    int r = r_begin + wave;
+    for (; r + 3 * kWaves < r_end; r += 4 * kWaves) {  // four independent loads in flight
+      const T* p0 = row(r);
+      const T* p1 = row(r + kWaves);
+      const T* p2 = row(r + 2 * kWaves);
+      const T* p3 = row(r + 3 * kWaves);
+      Vec<T>::load_sq(p0, acc);
+      Vec<T>::load_sq(p1, acc);
+      Vec<T>::load_sq(p2, acc);
+      Vec<T>::load_sq(p3, acc);
+    }
+    for (; r < r_end; r += kWaves) Vec<T>::load_sq(row(r), acc);
+  }
+#pragma unroll
+  for (int i = 0; i < V; ++i) s_part[wave][lane * V + i] = acc[i];
+  __syncthreads();
+  for (int i = threadIdx.x; i < kWave * V; i += kThreads) {
+    const int c = blockIdx.x * kWave * V + i;
+    if (c < d_model) {
+      float s = 0.0f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) s += s_part[w][i];  // fixed order
+      part[(int64_t)blockIdx.y * n_cols + (int64_t)e * d_model + c] = s;
+    }
+  }
+}
+
+// out[i] = part[0][i] + part[1][i] + ... in split order
+__global__ __launch_bounds__(kThreads) void sum_splits_kernel(const float* __restrict__ part, int splits, int64_t n_cols,
+                                                              float* __restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= n_cols) return;
+  float s = 0.0f;
+  for (int k = 0; k < splits; ++k) s += part[(int64_t)k * n_cols + i];
+  out[i] = s;
+}
+
 __global__ __launch_bounds__(kThreads) void finalize_kernel(int n_experts, int d_ff,
                                                             const int32_t* __restrict__ tile_offset,
                                                             const float* __restrict__ part_phi2,
@@ -203,6 +261,30 @@ hipError_t launch_down_norm(hipStream_t stream, int dtype, const void* W_down, i
                          static_cast<const float*>(W_down), stride_down, (int)d_model, (int)d_ff, rows_per_split,
                          n_micro, omega_part);
   }
+  return hipGetLastError();
+}
+
+int input_energy_splits(int n_experts, int64_t d_model, int dtype) {
+  // aim at >= 1024 blocks, at most 16 splits
+  const int v = dtype == CAMERA_BF16 ? 8 : 4;
+  const int64_t col_blocks = (d_model + kWave * v - 1) / (kWave * v);
+  int64_t want = (1024 + n_experts * col_blocks - 1) / (n_experts * col_blocks);
+  return (int)(want < 1 ? 1 : (want > 16 ? 16 : want));
+}
+
+hipError_t launch_input_energy(hipStream_t stream, int dtype, const void* X, int64_t ldx, int n_experts,
+                               int64_t d_model, const BucketTables& t, int splits, float* part, float* h) {
+  const int v = dtype == CAMERA_BF16 ? 8 : 4;
+  const int64_t n_cols = (int64_t)n_experts * d_model;
+  dim3 grid((unsigned)((d_model + kWave * v - 1) / (kWave * v)), (unsigned)splits, (unsigned)n_experts);
+  if (dtype == CAMERA_BF16)
+    hipLaunchKernelGGL(input_energy_kernel<__hip_bfloat16>, grid, dim3(kThreads), 0, stream,
+                       static_cast<const __hip_bfloat16*>(X), ldx, (int)d_model, t.offsets, t.perm, n_cols, part);
+  else
+    hipLaunchKernelGGL(input_energy_kernel<float>, grid, dim3(kThreads), 0, stream, static_cast<const float*>(X), ldx,
+                       (int)d_model, t.offsets, t.perm, n_cols, part);
+  hipLaunchKernelGGL(sum_splits_kernel, dim3((unsigned)((n_cols + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
+                     part, splits, n_cols, h);
   return hipGetLastError();
 }
 

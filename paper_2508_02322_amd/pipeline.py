@@ -8,6 +8,10 @@ the tensors of ``inputs.make_layer`` (``X, W_r, bias, W_gate, W_up, W_down`` and
                 then the shared ones, which every token visits with weight 1)
   prune_layer   Algorithm 2, lines 9-13: the kept micro-experts at a ratio, packed per expert
   CompactLayer  the pruned layer: ``forward`` is Algorithm 2, line 14 (the output recomputed after pruning)
+  cameraq_layer / cameraq_dagger_layer   Algorithm 3, lines 5-8 and the colocation of equal precision: the routed
+                experts' matrices reordered by precision class, row-wise for W_up / W_gate (CAMERA-Q: a micro-expert
+                keeps one precision) or column-wise (the comparison variant CAMERA-Q-dagger: every matrix sliced along
+                its input dimension)
 """
 from __future__ import annotations
 
@@ -92,3 +96,45 @@ def prune_layer(cam, layer: dict, scores: LayerScores, ratio: float, row_align: 
                                  out=(gate_c[pos:pos + n_idx], up_c[pos:pos + n_idx], down_c[pos_ld * d:(pos_ld + n_ld) * d]))
         pos, pos_ld = pos + n_idx, pos_ld + n_ld
     return CompactLayer(counts.tolist(), scores.n_shared, row_align, gate_c, up_c, down_c, keep, kept_idx[:kept])
+
+
+@dataclasses.dataclass
+class MixedPrecisionLayer:
+    """The routed experts' matrices with the members of every precision class side by side inside each expert."""
+    bits_down: torch.Tensor     # uint8 [N_E * d_ff]: bit width of every W_down column (= micro-expert)
+    count_down: torch.Tensor    # int32 [N_E, L]: class sizes per expert
+    W_down: torch.Tensor        # flat [N_E][d_model][d_ff]: columns in class order
+    bits_in: torch.Tensor       # uint8: bit width of every W_up / W_gate slice (rows = micro-experts, or input columns)
+    count_in: torch.Tensor      # int32 [N_E, L]
+    W_gate: torch.Tensor        # CAMERA-Q: [N_E * d_ff, d_model] rows in class order; dagger: flat [N_E][d_ff][d_model], columns in class order
+    W_up: torch.Tensor
+    column_wise: bool
+
+
+def cameraq_layer(cam, layer: dict, scores: LayerScores, bits, ratios) -> MixedPrecisionLayer:
+    """CAMERA-Q on the routed experts: one ranking of the micro-experts, one precision per micro-expert across its
+    gate row, up row and down column."""
+    nr = scores.n_routed
+    d_ff = layer["W_gate"].shape[1]
+    energy, seg = scores.energy[:nr * d_ff], scores.seg_offsets[:nr + 1]
+    bit_of, count, perm = cam.alloc_bits(energy, seg, bits, ratios, want_perm=True)
+    gate, up, down = cam.gather_micro_experts(layer["W_gate"], layer["W_up"], layer["W_down"], perm)
+    return MixedPrecisionLayer(bit_of, count, down, bit_of, count, gate, up, False)
+
+
+def cameraq_dagger_layer(cam, layer: dict, scores: LayerScores, bits, ratios) -> MixedPrecisionLayer:
+    """The comparison variant: W_down split by the micro-expert ranking as above, W_up and W_gate sliced along their
+    input dimension by the ranking of the input channels diag(X_e^T X_e) (every micro-expert then mixes precisions)."""
+    nr = scores.n_routed
+    Wg, Wu = layer["W_gate"], layer["W_up"]
+    d_ff, d_model = Wg.shape[1], Wg.shape[2]
+    energy, seg = scores.energy[:nr * d_ff], scores.seg_offsets[:nr + 1]
+    bits_down, count_down, perm_down = cam.alloc_bits(energy, seg, bits, ratios, want_perm=True)
+    _, _, down = cam.gather_micro_experts(None, None, layer["W_down"], perm_down)
+    h = cam.input_channel_energy(layer["X"], scores.topk_idx, nr)
+    seg_in = [e * d_model for e in range(nr + 1)]
+    bits_in, count_in, perm_in = cam.alloc_bits(h.view(-1), seg_in, bits, ratios, want_perm=True)
+    # columns of W_gate / W_up: the gather's column path, with the matrix in the place of W_down
+    _, _, gate = cam.gather_micro_experts(None, None, Wg, perm_in)
+    _, _, up = cam.gather_micro_experts(None, None, Wu, perm_in)
+    return MixedPrecisionLayer(bits_down, count_down, down, bits_in, count_in, gate, up, True)

@@ -297,3 +297,15 @@ def test_rank_decisions_argument_checks(lib, ctx):
     assert both(bits=(300, 2, 1)) == -1
     assert both(per=None) == -1 and both(lc=None) == -1 and both(keep=None) == -1 and both(bit_of=None) == -1
     assert both(E=None) == -1 and "energy" in err(lib, ctx)
+
+
+def test_input_channel_energy_argument_checks(lib, ctx):
+    def energy(x=FAKE, dtype=1, n=16, d=64, ldx=64, idx=FAKE, k=2, ne=8, h=FAKE, c=ctx):
+        return lib.camera_input_channel_energy(c, None, x, dtype, n, d, ldx, idx, k, ne, h)
+    assert energy(c=None) == -1
+    assert energy(dtype=9) == -3
+    assert energy(d=60) == -2 and "d_model" in err(lib, ctx)
+    assert energy(ne=0) == -6 and energy(ne=300) == -6
+    assert energy(k=0) == -1 and energy(k=9) == -1 and "top_k" in err(lib, ctx)
+    assert energy(h=None) == -1 and "h:" in err(lib, ctx)
+    assert energy(x=None) == -1
