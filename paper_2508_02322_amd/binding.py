@@ -343,7 +343,8 @@ class Camera:
         of them shared experts (every token, weight 1).  Y float32 [n, d_model]."""
         _check_matrix(X, "X")
         for name, t in (("W_gate_c", W_gate_c), ("W_up_c", W_up_c), ("W_down_c", W_down_c)):
-            _check_flat(t, name, X.dtype, X.device)
+            # (a dtype other than bf16 is the library's to refuse: it names what it supports)
+            _check_flat(t, name, X.dtype if X.dtype == torch.bfloat16 else None, X.device)
         _check_flat(topk_idx, "topk_idx", torch.int32, X.device)
         _check_flat(topk_w, "topk_w", torch.float32, X.device)
         _check_flat(Y, "Y", torch.float32, X.device)
