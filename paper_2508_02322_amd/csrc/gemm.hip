@@ -266,6 +266,11 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
   // v_mfma_f32_16x16x32_bf16: a 32 x 32 block of the wave's tile is four 16 x 16 sub-blocks (a: rows, b: columns)
   // and an instruction advances K by 32.  With random operand values this instruction holds a shader clock about
   // 10 % higher than the 32x32x16 one at the same flops (the chip is power-limited), which is why it is used.
+  // Which way round a 16 x 16 sub-block lies in the registers.  Statistics: a lane owns one channel and four
+  // consecutive token rows (the column reduction starts in the lane).  The epilogues that write per token row take
+  // the transposed form, a lane owning one token row and four consecutive channels: its four values are 16
+  // contiguous bytes of the output row (8 for bf16), one store instead of four.
+  constexpr bool kSwap = EPI != kEpiStats;
   f32x4 acc_g[NA][TN][2][2], acc_u[NA][TN][2][2];
 #pragma unroll
   for (int i = 0; i < NA; ++i)
@@ -314,10 +319,13 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
     static_for<decltype(lo)::value, decltype(hi)::value>([&](auto m) {
       constexpr int gu = decltype(m)::value % 2, j = (decltype(m)::value / 2) % TN;
       constexpr int a = (decltype(m)::value / (2 * TN)) % 2, i = decltype(m)::value / (4 * TN);
+      // kSwap: the weight fragment takes the first operand's place, which transposes the accumulator tile
       if constexpr (gu == 0)
-        acc_g[i][j][a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v[i][a], fb.g[j], acc_g[i][j][a][b], 0, 0, 0);
+        acc_g[i][j][a][b] = kSwap ? __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb.g[j], fa.v[i][a], acc_g[i][j][a][b], 0, 0, 0)
+                                  : __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v[i][a], fb.g[j], acc_g[i][j][a][b], 0, 0, 0);
       else
-        acc_u[i][j][a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v[i][a], fb.u[j], acc_u[i][j][a][b], 0, 0, 0);
+        acc_u[i][j][a][b] = kSwap ? __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb.u[j], fa.v[i][a], acc_u[i][j][a][b], 0, 0, 0)
+                                  : __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v[i][a], fb.u[j], acc_u[i][j][a][b], 0, 0, 0);
     });
   };
 
@@ -351,7 +359,7 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
       for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-          a_rows[i][a][r] = st.s_a[(WM * i + st.wave_m) * 32 + a * 16 + st.frag_half * 4 + r];
+          a_rows[i][a][r] = st.s_a[(WM * i + st.wave_m) * 32 + a * 16 + (kSwap ? st.frag_row : st.frag_half * 4 + r)];
     __syncthreads();
   }
   auto a_of = [&](int i, int a, int r, int row) { return C::kAliasAux ? a_rows[i][a][r] : st.s_a[row]; };
@@ -408,49 +416,64 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
 
   // Epilogue.  Accumulator register r of lane l in sub-block (a, b) of block (i, j) is output row
   // 32*block + 16a + 4*(l/16) + r, column 32*block + 16b + l % 16: a lane owns two channels per channel block.
+  // Transposed (kSwap): row 32*block + 16a + l % 16, columns 32*block + 16b + 4*(l/16) + r.
   const int lane_col = st.frag_row, lane_rows = st.frag_half * 4;  // l % 16, 4 * (l / 16)
   if constexpr (EPI != kEpiStats) {
+    const int pad_end = (EPI == kEpiHidden && ep.pad_hidden) ? (d_ff + ep.pad_hidden - 1) / ep.pad_hidden * ep.pad_hidden : d_ff;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
-        const int col = n0 + st.wave_n * TN * 32 + j * 32 + b * 16 + lane_col;
-        if (col >= d_ff) {
-          if constexpr (EPI == kEpiHidden) {
-            if (ep.pad_hidden && col < (d_ff + ep.pad_hidden - 1) / ep.pad_hidden * ep.pad_hidden) {
+        const int col0 = n0 + st.wave_n * TN * 32 + j * 32 + b * 16 + lane_rows;  // this lane's four channels
+        if (col0 >= pad_end) continue;
+        const bool whole = col0 + 3 < d_ff;  // all four inside: one vector store
+        float kept[4] = {1.0f, 1.0f, 1.0f, 1.0f};
+        if constexpr (EPI == kEpiHidden) {
+          if (ep.keep != nullptr) {
 #pragma unroll
-              for (int i = 0; i < ACT; ++i)
-#pragma unroll
-                for (int a = 0; a < 2; ++a)
-#pragma unroll
-                  for (int r = 0; r < 4; ++r) {
-                    const int row = (WM * i + st.wave_m) * 32 + a * 16 + lane_rows + r;
-                    if (row < st.m_len)
-                      static_cast<__hip_bfloat16*>(ep.hidden)[(st.row_first + row) * ep.ld_hidden + col] = __float2bfloat16(0.0f);
-                  }
-            }
+            for (int r = 0; r < 4; ++r)
+              kept[r] = (col0 + r < d_ff && ep.keep[(int64_t)st.expert * d_ff + col0 + r]) ? 1.0f : 0.0f;
           }
-          continue;
         }
-        float kept = 1.0f;
-        if constexpr (EPI == kEpiHidden) kept = (ep.keep == nullptr || ep.keep[(int64_t)st.expert * d_ff + col]) ? 1.0f : 0.0f;
 #pragma unroll
         for (int i = 0; i < ACT; ++i)
 #pragma unroll
-          for (int a = 0; a < 2; ++a)
+          for (int a = 0; a < 2; ++a) {
+            const int row = (WM * i + st.wave_m) * 32 + a * 16 + lane_col;
+            if (row >= st.m_len) continue;
+            const int64_t out_row = st.row_first + row;
+            if constexpr (EPI == kEpiHidden) {
+              __hip_bfloat16* dst = static_cast<__hip_bfloat16*>(ep.hidden) + out_row * ep.ld_hidden + col0;
+              const float a_tok = a_of(i, a, 0, row);
+              __hip_bfloat16 lam[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const int row = (WM * i + st.wave_m) * 32 + a * 16 + lane_rows + r;
-              if (row >= st.m_len) continue;
-              const int64_t out_row = st.row_first + row;
-              if constexpr (EPI == kEpiHidden) {
-                const float lam = a_of(i, a, r, row) * silu_f32(acc_g[i][j][a][b][r]) * acc_u[i][j][a][b][r] * kept;
-                static_cast<__hip_bfloat16*>(ep.hidden)[out_row * ep.ld_hidden + col] = __float2bfloat16(lam);
+              for (int r = 0; r < 4; ++r)
+                lam[r] = __float2bfloat16(a_tok * silu_f32(acc_g[i][j][a][b][r]) * acc_u[i][j][a][b][r] * kept[r]);
+              if (whole) {  // rows of the hidden buffer are multiples of 8 elements long: 8-byte aligned
+                uint2 v;
+                v.x = (uint32_t)__builtin_bit_cast(uint16_t, lam[0]) | ((uint32_t)__builtin_bit_cast(uint16_t, lam[1]) << 16);
+                v.y = (uint32_t)__builtin_bit_cast(uint16_t, lam[2]) | ((uint32_t)__builtin_bit_cast(uint16_t, lam[3]) << 16);
+                *reinterpret_cast<uint2*>(dst) = v;
+              } else {  // the last channels of the expert, then the K padding of the contraction that reads these rows
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                  if (col0 + r < pad_end) dst[r] = col0 + r < d_ff ? lam[r] : __float2bfloat16(0.0f);
+              }
+            } else {
+              float* dst = ep.product + out_row * ep.ld_product + col0;
+              if (whole) {  // output rows and both column halves are multiples of 4 floats: 16-byte aligned
+                *reinterpret_cast<f32x4*>(dst) = acc_g[i][j][a][b];
+                *reinterpret_cast<f32x4*>(dst + ep.col_gap) = acc_u[i][j][a][b];
               } else {
-                ep.product[out_row * ep.ld_product + col] = acc_g[i][j][a][b][r];
-                ep.product[out_row * ep.ld_product + col + ep.col_gap] = acc_u[i][j][a][b][r];
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                  if (col0 + r < d_ff) {
+                    dst[r] = acc_g[i][j][a][b][r];
+                    dst[r + ep.col_gap] = acc_u[i][j][a][b][r];
+                  }
               }
             }
+          }
       }
     }
   } else {
