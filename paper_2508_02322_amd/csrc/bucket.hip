@@ -9,8 +9,9 @@
 //             and builds counts / offsets / the M-tile tables of the GEMM
 //   scatter : every wave walks its 256 consecutive pairs 64 at a time; the
 //             position of a pair inside its expert is found with wavefront
-//             ballots (lanes of equal expert) and popcounts of the lower lanes,
-//             so equal experts keep their pair order (stable, deterministic).
+//             ballots (one per bit of the expert id gives the lanes of equal
+//             expert) and popcounts of the lower lanes, so equal experts keep
+//             their pair order (stable, deterministic).
 #include "camera_internal.h"
 
 namespace camera {
@@ -143,20 +144,21 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(const int32_t*
       e = topk_idx[p];
       if (e < 0 || e >= n_experts) e = -1;
     }
-    // group the lanes by expert: each round serves the expert of the lowest waiting lane
-    uint64_t waiting = __ballot(e >= 0);
-    int slot = -1;
-    while (waiting) {
-      const int leader = __ffsll((unsigned long long)waiting) - 1;
-      const int le = __shfl(e, leader);
-      const uint64_t same = __ballot(e == le);
-      if (e == le) slot = next[wave][le] + __popcll(same & lower_lanes);
-      // every lane of the group has read next[] before its first lane moves it on
-      __builtin_amdgcn_wave_barrier();
-      if (lane == leader) next[wave][le] += __popcll(same);
-      __builtin_amdgcn_wave_barrier();
-      waiting &= ~same;
+    // The lanes that hold the same expert, from one ballot per bit of the id (eight bits: ids are below 256):
+    // a lane keeps the lanes that agree with it on every bit.  Its slot is the expert's next free one plus the
+    // number of such lanes below it; the lowest lane of every group then moves the expert's counter on.
+    uint64_t same = __ballot(e >= 0);
+#pragma unroll
+    for (int bit = 0; bit < 8; ++bit) {
+      const uint64_t ones = __ballot((e >> bit) & 1);
+      same &= ((e >> bit) & 1) ? ones : ~ones;
     }
+    int slot = -1;
+    if (e >= 0) slot = next[wave][e] + __popcll(same & lower_lanes);
+    // every lane has read next[] before the first lane of its group moves it on
+    __builtin_amdgcn_wave_barrier();
+    if (e >= 0 && (same & lower_lanes) == 0) next[wave][e] += __popcll(same);
+    __builtin_amdgcn_wave_barrier();
     if (e >= 0) {
       perm[slot] = (int32_t)(p / top_k);
       if (topk_w) w_perm[slot] = topk_w[p];

@@ -224,12 +224,13 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(int n_experts, int d
 }  // namespace
 
 int down_norm_splits(int n_experts, int64_t d_model, int64_t d_ff) {
-  // aim at >= 2048 blocks, at least 64 rows per split, at most 16 splits
+  // aim at >= 2048 blocks, at least 64 rows per split, at most 64 splits (one wide expert -- a shared expert of
+  // 20480 channels is 40 column blocks -- needs many row splits to fill the chip)
   const int64_t col_blocks = (d_ff + 511) / 512;
   int64_t want = (2048 + n_experts * col_blocks - 1) / (n_experts * col_blocks);
   const int64_t by_rows = d_model / 64 > 0 ? d_model / 64 : 1;
   if (want > by_rows) want = by_rows;
-  if (want > 16) want = 16;
+  if (want > 64) want = 64;
   if (want < 1) want = 1;
   return (int)want;
 }

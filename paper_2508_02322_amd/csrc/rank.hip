@@ -125,23 +125,6 @@ __device__ __forceinline__ Keys16 load_keys16(const float* __restrict__ E, int64
   return out;
 }
 
-// exclusive prefix of v over the block (thread order); s_wave is [kRankWaves] scratch
-__device__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s_wave) {
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  uint32_t inc = v;
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    const uint32_t o = __shfl_up(inc, d);
-    if (lane >= d) inc += o;
-  }
-  if (lane == kWave - 1) s_wave[wave] = inc;
-  __syncthreads();
-  uint32_t base = 0;
-  for (int w = 0; w < wave; ++w) base += s_wave[w];
-  __syncthreads();
-  return base + inc - v;
-}
-
 // What another workgroup wrote before it took its ticket: read past this CU's vector cache.
 __device__ __forceinline__ uint32_t load_agent(const uint32_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -163,7 +146,6 @@ __global__ __launch_bounds__(kRankThreads) void rank_hist_kernel(const float* __
   constexpr uint32_t kMask = (1u << kBits) - 1u;
   constexpr int kHists = P == 0 ? 1 : kMaxCuts;  // pass 0 has no prefix yet: one histogram serves every cut
   __shared__ uint32_t hist[kHists][kBins];
-  __shared__ uint32_t s_wave[kRankWaves];
   __shared__ uint32_t s_last;
   const int tid = threadIdx.x;
   const int n_cuts = cuts.n_cuts;
@@ -218,29 +200,60 @@ __global__ __launch_bounds__(kRankThreads) void rank_hist_kernel(const float* __
   __syncthreads();
   if (!s_last) return;
   __threadfence();
-  for (int q = 0; q < n_cuts; ++q) {
-    if (want[q] == 0xffffffffu) continue;  // block-uniform
-    const uint32_t* h = st->hist[P][P == 0 ? 0 : q];
-    uint32_t c[kBins / kRankThreads], mine = 0;
+  // The pick, for all cuts together (one round of loads, one scan): thread t owns bins kPer t .. kPer t + kPer - 1
+  // of every cut's histogram (pass 0: the one histogram all cuts share).
+  constexpr int kPer = kBins / kRankThreads;
+  uint32_t c[kHists][kPer], before[kHists];
 #pragma unroll
-    for (int i = 0; i < kBins / kRankThreads; ++i) {
-      c[i] = load_agent(h + tid * (kBins / kRankThreads) + i);
-      mine += c[i];
-    }
-    uint32_t before = block_exclusive_scan(mine, s_wave);
-    const uint32_t rest = P == 0 ? (uint32_t)cuts.cut_rank[q] : st->rest[q];
-    __syncthreads();
+  for (int q = 0; q < kHists; ++q) {
+    before[q] = 0u;
+    const bool on = P == 0 || want[q] != 0xffffffffu;
 #pragma unroll
-    for (int i = 0; i < kBins / kRankThreads; ++i) {
-      if (rest >= before && rest < before + c[i]) {
-        st->prefix[q] = (want[q] << kBits) | (uint32_t)(tid * (kBins / kRankThreads) + i);
-        st->rest[q] = rest - before;
-        if (P == 2 && rest - before > 0) st->ties_split = 1u;
-      }
-      before += c[i];
+    for (int i = 0; i < kPer; ++i) {
+      c[q][i] = on ? load_agent(&st->hist[P][q][tid * kPer + i]) : 0u;
+      before[q] += c[q][i];
     }
-    __syncthreads();
   }
+  {  // exclusive prefix over the threads, every histogram at once
+    const int lane = tid % kWave, wave = tid / kWave;
+    __shared__ uint32_t s_tot[kRankWaves][kHists];
+    uint32_t inc[kHists];
+#pragma unroll
+    for (int q = 0; q < kHists; ++q) {
+      inc[q] = before[q];
+#pragma unroll
+      for (int d = 1; d < kWave; d <<= 1) {
+        const uint32_t o = __shfl_up(inc[q], d);
+        if (lane >= d) inc[q] += o;
+      }
+      if (lane == kWave - 1) s_tot[wave][q] = inc[q];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kHists; ++q) {
+      uint32_t base = 0;
+      for (int w = 0; w < wave; ++w) base += s_tot[w][q];
+      before[q] = base + inc[q] - before[q];
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < kMaxCuts; ++q) {
+    if (q >= n_cuts || want[q] == 0xffffffffu) continue;  // block-uniform
+    constexpr int kShared = P == 0 ? 1 : kMaxCuts;
+    const int hq = q % kShared;  // pass 0: histogram 0 serves every cut
+    const uint32_t rest = P == 0 ? (uint32_t)cuts.cut_rank[q] : st->rest[q];
+    uint32_t run = before[hq];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      if (rest >= run && rest < run + c[hq][i]) {
+        st->prefix[q] = (want[q] << kBits) | (uint32_t)(tid * kPer + i);
+        st->rest[q] = rest - run;
+        if (P == 2 && rest - run > 0) st->ties_split = 1u;
+      }
+      run += c[hq][i];
+    }
+  }
+  __syncthreads();
   // leave the state as the next call needs it: this pass's histograms and ticket back to zero
   for (int i = tid; i < n_hists * kBins; i += kRankThreads) (&st->hist[P][0][0])[i] = 0u;
   if (tid == 0) st->ticket[P] = 0u;
