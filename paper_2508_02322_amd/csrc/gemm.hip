@@ -732,43 +732,67 @@ __device__ __forceinline__ int hidden_ld(const CompactDown& t, int e, int k_roun
   return (t.count[e] + k_round - 1) / k_round * k_round;
 }
 
+// One workgroup, thread e owns expert e: its tile count, cost and hidden rows, then exclusive prefixes over the
+// experts (a Hillis-Steele scan in LDS: 256 entries) and, by threads 1 .. kXcds - 1, the cuts.
 template <class TABLE>
-__global__ __launch_bounds__(64) void compact_work_kernel(TABLE tab, int d_model, int bn, int kt, int k_round,
-                                                          const int32_t* __restrict__ offsets,
-                                                          const int32_t* __restrict__ tile_offset,
-                                                          int32_t* __restrict__ scratch) {
-  if (threadIdx.x != 0) return;
+__global__ __launch_bounds__(CAMERA_MAX_EXPERTS) void compact_work_kernel(TABLE tab, int d_model, int bn, int kt,
+                                                                          int k_round,
+                                                                          const int32_t* __restrict__ offsets,
+                                                                          const int32_t* __restrict__ tile_offset,
+                                                                          int32_t* __restrict__ scratch) {
+  __shared__ int32_t s_tiles[2][CAMERA_MAX_EXPERTS];   // inclusive prefixes, double-buffered
+  __shared__ int64_t s_cost[2][CAMERA_MAX_EXPERTS];
+  __shared__ int64_t s_hid[2][CAMERA_MAX_EXPERTS];
   const CompactScratch sc = compact_scratch(scratch, tab.n_experts);
-  int run = 0;
+  const int e = threadIdx.x, n = tab.n_experts;
+  int32_t tiles = 0;
   int64_t cost = 0, hid = 0;
-  for (int e = 0; e < tab.n_experts; ++e) {
-    sc.work_off[e] = run;
-    sc.hid_off[e] = hid;
-    hid += (int64_t)(offsets[e + 1] - offsets[e]) * hidden_ld(tab, e, k_round);
+  if (e < n) {
     const ExpertGeom g = expert_geom(tab, e, d_model);
-    const int tiles = (tile_offset[e + 1] - tile_offset[e]) * ((g.n_ext + bn - 1) / bn);
-    run += tiles;
-    cost += (int64_t)tiles * max(1, (g.k_ext + kt - 1) / kt);
+    tiles = (tile_offset[e + 1] - tile_offset[e]) * ((g.n_ext + bn - 1) / bn);
+    cost = (int64_t)tiles * max(1, (g.k_ext + kt - 1) / kt);
+    hid = (int64_t)(offsets[e + 1] - offsets[e]) * hidden_ld(tab, e, k_round);
   }
-  sc.work_off[tab.n_experts] = run;
-  sc.xcd_first[0] = 0;
-  sc.xcd_first[kXcds] = run;
-  int e = 0;
-  int64_t before = 0;  // cost of the experts before e
-  for (int x = 1; x < kXcds; ++x) {
-    const int64_t target = cost * x / kXcds;
-    int64_t mine = 0;
-    for (; e < tab.n_experts; ++e) {
-      const ExpertGeom g = expert_geom(tab, e, d_model);
-      mine = (int64_t)(sc.work_off[e + 1] - sc.work_off[e]) * max(1, (g.k_ext + kt - 1) / kt);
-      if (before + mine > target) break;
-      before += mine;
+  s_tiles[0][e] = tiles;
+  s_cost[0][e] = cost;
+  s_hid[0][e] = hid;
+  __syncthreads();
+  int cur = 0;
+  for (int d = 1; d < CAMERA_MAX_EXPERTS; d <<= 1) {
+    const int nxt = cur ^ 1;
+    s_tiles[nxt][e] = s_tiles[cur][e] + (e >= d ? s_tiles[cur][e - d] : 0);
+    s_cost[nxt][e] = s_cost[cur][e] + (e >= d ? s_cost[cur][e - d] : (int64_t)0);
+    s_hid[nxt][e] = s_hid[cur][e] + (e >= d ? s_hid[cur][e - d] : (int64_t)0);
+    __syncthreads();
+    cur = nxt;
+  }
+  const int32_t run = s_tiles[cur][CAMERA_MAX_EXPERTS - 1];       // all tiles
+  const int64_t total = s_cost[cur][CAMERA_MAX_EXPERTS - 1];      // all cost
+  if (e < n) {
+    sc.work_off[e] = s_tiles[cur][e] - tiles;
+    sc.hid_off[e] = s_hid[cur][e] - hid;
+  }
+  if (e == 0) {
+    sc.work_off[n] = run;
+    sc.xcd_first[0] = 0;
+    sc.xcd_first[kXcds] = run;
+  }
+  if (e >= 1 && e < kXcds) {
+    // cut x: the first expert whose inclusive cost prefix exceeds total x / kXcds, and inside it the tile that does
+    const int64_t target = total * e / kXcds;
+    int lo = 0, hi = n;  // first expert with inclusive prefix > target
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (s_cost[cur][mid] > target) hi = mid; else lo = mid + 1;
     }
-    if (e >= tab.n_experts) {
-      sc.xcd_first[x] = run;
+    if (lo >= n) {
+      sc.xcd_first[e] = run;
     } else {
-      const int64_t per_tile = mine / max(1, sc.work_off[e + 1] - sc.work_off[e]);
-      sc.xcd_first[x] = sc.work_off[e] + (int)((target - before) / max<int64_t>(1, per_tile));
+      const int32_t first = lo == 0 ? 0 : s_tiles[cur][lo - 1];
+      const int32_t mine_tiles = s_tiles[cur][lo] - first;
+      const int64_t before = lo == 0 ? 0 : s_cost[cur][lo - 1];
+      const int64_t per_tile = (s_cost[cur][lo] - before) / max(1, mine_tiles);
+      sc.xcd_first[e] = first + (int)((target - before) / max<int64_t>(1, per_tile));
     }
   }
 }
@@ -1068,7 +1092,7 @@ static hipError_t launch_compact(hipStream_t stream, const void* X, int64_t ldx,
     if (err != hipSuccess) return err;
     attr_set[tail] = true;
   }
-  hipLaunchKernelGGL((compact_work_kernel<TABLE>), dim3(1), dim3(64), 0, stream, tab, (int)d_model, C::BN, C::KT, k_round,
+  hipLaunchKernelGGL((compact_work_kernel<TABLE>), dim3(1), dim3(CAMERA_MAX_EXPERTS), 0, stream, tab, (int)d_model, C::BN, C::KT, k_round,
                      t.offsets, t.tile_offset, scratch);
   // an upper bound of the tile count, shared evenly between the XCDs: a workgroup walks on through its XCD's
   // range where the cuts by cost give that XCD more (cheaper) tiles than that

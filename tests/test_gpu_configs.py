@@ -75,6 +75,14 @@ def check_decisions(cam, cfg, name, energy_gpu, energy_orc=None):
         np.testing.assert_array_equal(bit_of.cpu().numpy(), o_bits)
         np.testing.assert_array_equal(level_count.cpu().numpy(), o_count)
         np.testing.assert_array_equal(perm.cpu().numpy(), o_perm)
+        if DECISIONS[name]["prune"]:   # the call bench.py makes: every mask and this allocation from one ranking pass
+            prune = DECISIONS[name]["prune"]
+            keep_bits, per, bit_of2, level_count2, perm2 = cam.rank_decisions(energy_gpu, seg, prune, bits, ratios, want_perm=True)
+            for k, ratio in enumerate(prune):
+                o_keep, o_per, _, _ = orc.select_prune(E, seg, ratio)
+                np.testing.assert_array_equal((keep_bits.cpu().numpy() >> k) & 1, o_keep)
+                np.testing.assert_array_equal(per[k].cpu().numpy(), o_per)
+            assert torch.equal(bit_of2, bit_of) and torch.equal(level_count2, level_count) and torch.equal(perm2, perm)
         if energy_orc is not None:
             cuts = orc.class_cuts(ratios, N)
             b = bit_of.cpu().numpy()
