@@ -37,8 +37,8 @@ DECISIONS = {
 # HBM-side bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by what the same
 # counters read for a plain 1 GiB copy; not measured by this program: the figure and the file it comes from are
 # reported side by side (None where no such profile exists).
-PMC_TRAFFIC = {"qwen2-57b-a14b": (5.319e9, "profiles/grouped_gemm_bf16_qwen2-57b-a14b_hbm_traffic.txt")}
-PMC_NORM_TRAFFIC = {"qwen2-57b-a14b": (None, "profiles/down_norm_qwen2-57b-a14b_hbm_traffic.txt")}
+PMC_TRAFFIC = {"qwen2-57b-a14b": (5.379e9, "profiles/grouped_gemm_bf16_qwen2-57b-a14b_hbm_traffic.txt")}
+PMC_NORM_TRAFFIC = {"qwen2-57b-a14b": (6.636e8, "profiles/down_norm_qwen2-57b-a14b_hbm_traffic.txt")}
 # The same for the two streaming kernels of the compacted layer on a 64-token batch, unpruned
 # (profiles/compact_layer_decode_hbm_traffic.txt): read + written bytes per call.
 PMC_DECODE_TRAFFIC_BYTES = {"deepseek-moe-16b": 777.0e6 + 392.5e6 + 5.6e6, "qwen2-57b-a14b": 2976.9e6 + 1522.0e6 + 19.0e6}
