@@ -37,8 +37,8 @@ DECISIONS = {
 # HBM-side bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by what the same
 # counters read for a plain 1 GiB copy; not measured by this program: the figure and the file it comes from are
 # reported side by side (None where no such profile exists).
-PMC_TRAFFIC = {"qwen2-57b-a14b": (5.379e9, "profiles/grouped_gemm_bf16_qwen2-57b-a14b_hbm_traffic.txt")}
-PMC_NORM_TRAFFIC = {"qwen2-57b-a14b": (6.636e8, "profiles/down_norm_qwen2-57b-a14b_hbm_traffic.txt")}
+PMC_TRAFFIC = {"qwen2-57b-a14b": (5.325e9, "profiles/grouped_gemm_bf16_qwen2-57b-a14b_hbm_traffic.txt")}
+PMC_NORM_TRAFFIC = {"qwen2-57b-a14b": (6.651e8, "profiles/down_norm_qwen2-57b-a14b_hbm_traffic.txt")}
 # The same for the two streaming kernels of the compacted layer on a 64-token batch, unpruned
 # (profiles/compact_layer_decode_hbm_traffic.txt): read + written bytes per call.
 PMC_DECODE_TRAFFIC_BYTES = {"deepseek-moe-16b": 777.0e6 + 392.5e6 + 5.6e6, "qwen2-57b-a14b": 2976.9e6 + 1522.0e6 + 19.0e6}
@@ -415,6 +415,43 @@ def cpu_baseline(cfg, inputs):
                       + f", all {cfg.n_tokens} tokens, {dt:.1f} s measured, scaled by {cfg.n_micro / scored:.1f}x to a whole layer"}
 
 
+def constant_operand_rate(cam, cfg, layer, torch, binding, reps=40):
+    """The step's own contractions of one layer (same calls, same routing, same launch shapes) on constant operands
+    (every hidden state 1, every weight 1/64): with nothing toggling in the multipliers the chip holds its full clock,
+    so this is the rate the kernel's schedule sustains when power does not limit it."""
+    t = layer.t
+    idx, w = cam.route_topk(t["X"], t["W_r"], t["bias"], cfg.top_k)
+    X = torch.ones_like(t["X"])
+    def stats(n_micro):   # NO_FINALIZE calls write these two only
+        return {k: torch.empty(n_micro, dtype=torch.float32, device="cuda") for k in ("phi2", "phi_inf")}
+
+    groups = [(idx, w, torch.full_like(t["W_gate"], 2.0 ** -6), torch.full_like(t["W_up"], 2.0 ** -6),
+               stats(cfg.n_micro_routed))]
+    if cfg.n_shared:
+        groups.append((None, None, torch.full_like(t["Ws_gate"], 2.0 ** -6), torch.full_like(t["Ws_up"], 2.0 ** -6),
+                       stats(cfg.n_micro - cfg.n_micro_routed)))
+
+    def run():
+        for gi, gw, Wg, Wu, out in groups:
+            cam.score_layer(X, gi, gw, Wg, Wu, None, cfg.alpha, flags=binding.NO_FINALIZE, out=out)
+
+    for _ in range(10):
+        run()
+    torch.cuda.synchronize()
+    k_gemm = binding.KERNEL_NAMES.index("gemm")
+    cam.profile_read(k_gemm)
+    cam.profile_enable(True)
+    for _ in range(reps):
+        run()
+    torch.cuda.synchronize()
+    cam.profile_enable(False)
+    ms, launches = cam.profile_read(k_gemm)
+    tflops = cfg.gemm_flops_per_layer() * reps / ms / 1e9
+    return {"what": "the contractions of layer 0 with constant operands (hidden states 1, weights 1/64), its own routing",
+            "tflops": round(tflops, 1), "frac_of_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+            "avg_launch_ms": round(ms / max(1, launches), 4)}
+
+
 def expert_counts(cam, cfg, layers, torch):
     """Routed (token, expert) pairs per expert and layer, from the library's own routing (outside any timed region)."""
     counts = []
@@ -641,6 +678,8 @@ def main():
 
     if "measured" in roofline and bf16:
         roofline["measured"]["vendor_gemm_dense_equivalent"] = stage("vendor_gemm", False, vendor_reference)
+        roofline["measured"]["grouped_gemm_constant_operands"] = stage(
+            "constant_operands", calib_tokens != cfg.n_tokens, lambda: constant_operand_rate(cam, cfg, layers[0], torch, binding))
     own_size = calib_tokens == cfg.n_tokens
     apply_mask = stage("apply_mask", args.no_apply, lambda: measure_apply(cam, cfg, layers, torch, binding))
     forward = stage("pruned_layer_output", args.no_forward or not own_size,
