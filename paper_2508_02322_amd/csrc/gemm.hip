@@ -21,6 +21,7 @@
 // fp32: plain FMA tiles (used by the float32 configuration only).
 #include <hip/hip_bf16.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "camera_internal.h"
@@ -33,6 +34,14 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
+// acc += x * y on a 16 x 16 x 32 tile, the accumulator held in accumulation registers.  The compiler sees an
+// opaque instruction: between the last one and the first read of an accumulator the caller waits out the
+// matrix pipe itself (mfma_drain), and no accumulator is used again sooner than eight MFMAs later.
+__device__ __forceinline__ void mfma_pinned(f32x4& acc, const bf16x8& x, const bf16x8& y) {
+  asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(x), "v"(y));
+}
+__device__ __forceinline__ void mfma_drain() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+
 // silu(g) = g / (1 + exp(-g)); exp2 and rcp are single hardware instructions (about 1 ulp each)
 __device__ __forceinline__ float silu_f32(float g) {
   return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g * -1.4426950408889634f));
@@ -40,23 +49,31 @@ __device__ __forceinline__ float silu_f32(float g) {
 
 // ---------------------------------------------------------------------------
 // bf16 MFMA kernel.
-//   A workgroup is WM x WN waves (two per SIMD with the default 4 x 2).  A wave
-//   owns TM 32-row blocks of tokens (blocks wave_m, wave_m + WM, ... of the tile,
-//   so that a short last tile of an expert is shared evenly and its empty blocks
-//   are skipped) by TN*32 channels, for both the gate and the up product.  Block
-//   tile BM = 32*WM*TM tokens by BN = 32*WN*TN channels.
+//   A workgroup is WM x WN waves: 2 x 2 in the built configuration, one wave per SIMD, each with the whole
+//   register file of its SIMD (256 accumulation registers for its outputs, 256 vector registers for the rest).
+//   A wave owns TM 32-row blocks of tokens (blocks wave_m, wave_m + WM, ... of the tile, so that a short last
+//   tile of an expert is shared evenly and its empty blocks are skipped) by TN*32 channels, for both the gate
+//   and the up product: 128 x 64 x {gate, up}.  Block tile BM = 32*WM*TM tokens by BN = 32*WN*TN channels.
+//   The large wave tile is what the kernel is built around: per MFMA it reads a third fewer fragment bytes
+//   from LDS than a 64-row wave tile, and on real-valued operands the chip runs at its power limit, where
+//   throughput is set by the energy per flop and not by how full the matrix pipe is.
 //
 //   K advances KT elements per tile.  Token tiles and weight tiles each run through a ring of their own in
 //   LDS: two stages of 32 KiB for the token rows and three of 32 KiB (gate + up) for the weights in the built
 //   configuration, 160 KiB in all.  The weights stream from HBM exactly once and are loaded two tiles ahead;
 //   the token rows, re-read by every channel tile of an expert and so served by the L2, one tile ahead.
-//   Tiles go from global memory straight into LDS
-//   (global_load_lds_dwordx4, no staging registers, no LDS store instructions).  The loads of a
-//   tile are not issued in one go but one or two at a time between groups of MFMAs: a wave that
-//   issues eight loads back to back sits on the vector-memory queue and stops feeding the matrix
-//   pipe.  One workgroup barrier per K tile publishes the next stage; it sits before the last
-//   16-wide K step so that the first fragments of the next tile are in flight while that step's
+//   Tiles go from global memory straight into LDS (global_load_lds_dwordx4, no staging registers, no LDS
+//   store instructions).  One workgroup barrier per K tile publishes the next stage; it sits before the last
+//   quarter of the K tile so that the first fragments of the next tile are in flight while that quarter's
 //   MFMAs run.
+//
+//   Instruction order.  A wave issues one instruction every fourth cycle at best and, alone on its SIMD, has
+//   nobody to cover for it: an MFMA occupies the matrix pipe for 16 cycles, so at most three other
+//   instructions fit between two MFMAs before the pipe runs dry.  The K loop is therefore written as a
+//   sequence of slots, one MFMA each, followed by at most one fragment read, one tile load or one step of
+//   wave-uniform bookkeeping, and the order is pinned with scheduling barriers.  The MFMAs are written as
+//   assembly with their accumulators constrained to accumulation registers: left to itself the register
+//   allocator moves the 64 accumulator tuples around inside the loop (about 90 copies per 128 MFMAs).
 // ---------------------------------------------------------------------------
 // f(integral_constant<int, LO>), ..., f(integral_constant<int, HI - 1>)
 template <int LO, int HI, class F>
@@ -112,6 +129,16 @@ __device__ __forceinline__ void lds_dma16(const unsigned char* p, unsigned lds) 
                : "s"(base), "v"(p), "n"(IMM)
                : "memory", "m0");
 }
+// The same with the address split into a wave-uniform base and the lane's 32-bit byte offset, and with M0 written
+// apart: the loads of one matrix follow each other in program order (these statements are volatile, the compiler
+// keeps their order and has no use of its own for M0 in these kernels), so one M0 write serves up to four of them.
+__device__ __forceinline__ void lds_dma_base(unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" ::"s"(lds) : "memory", "m0");
+}
+template <int IMM>
+__device__ __forceinline__ void lds_dma16_scalar(unsigned offset, const unsigned char* base) {
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(offset), "s"(base), "n"(IMM) : "memory");
+}
 #pragma clang diagnostic pop
 
 // STAGES_: ring depth of the token (A) tiles; BSTAGES_: ring depth of the weight tiles, the same or one more
@@ -151,24 +178,11 @@ struct GemmCfg {
   // workgroups that fit one CU by LDS (160 KiB), hence waves per SIMD the registers must allow
   static constexpr int kBlocksPerCu = (160 * 1024) / kSmemBytes >= 2 ? 2 : 1;
   static constexpr int kWavesPerSimd = kBlocksPerCu * kWaves / 4 > 0 ? kBlocksPerCu * kWaves / 4 : 1;
-  // Issue slots: a K step is kParts slots, slot 0 is the first one behind the barrier.  The loads of
-  // a tile are dealt evenly over the first half of the slots (extra ones in the middle); the second
-  // half stays empty, which is the time the youngest load has to land before the next barrier.
-  static constexpr int kParts = (2 * TM * TN) / 4 > 1 ? (2 * TM * TN) / 4 : 1;  // slots per K step
-  static constexpr int kSlots = kParts * kSteps;
-  static constexpr int kBusySlots = kSlots >= 2 ? kSlots / 2 : 1;
-  static constexpr int issue_count(int p) {
-    if (p < 0 || p >= kBusySlots) return 0;
-    const int base = kLoadsPerTile / kBusySlots, extra = kLoadsPerTile % kBusySlots;
-    const int first_extra = (kBusySlots - extra) / 2;
-    return base + ((p >= first_extra && p < first_extra + extra) ? 1 : 0);
-  }
-  static constexpr int issue_begin(int p) {  // loads issued by the slots before p
-    int n = 0;
-    for (int q = 0; q < p; ++q) n += issue_count(q);
-    return n;
-  }
-  static_assert(issue_begin(kSlots) == kLoadsPerTile, "every load has a slot");
+  // A tile load is issued behind every kLoadEvery-th MFMA of a full tile, counted from the barrier: densely
+  // issued loads hold the wave on the vector-memory queue (every 2nd MFMA: 9 % slower than every 6th), and the
+  // last third of the K tile stays free of them (the youngest load's time to land; the bookkeeping of the
+  // next fill goes there).
+  static constexpr int kLoadEvery = 6;
   static_assert(KT == 32 || KT == 64, "K tile");
   static_assert(kStages >= 2, "at least the stage being read and the stage being filled");
   static_assert(kBStages == kStages || kBStages == kStages + 1, "weight ring: as deep as the token ring or one deeper");
@@ -194,10 +208,18 @@ struct TileState {
   unsigned char* smem;
   const float* s_a;
   float* s_red;
-  // direct-to-LDS: per-lane source of each of this wave's row groups, wave-uniform LDS offsets
+  // direct-to-LDS sources of this lane's row groups.  Two forms: a 64-bit address per group (TAIL), or a wave-uniform
+  // base per matrix -- its start moved back by kBias bytes so that every offset stays positive -- plus a 32-bit
+  // byte offset per group.  Either way group j's source is moved back by 1024 (j % 4) bytes, which the immediate
+  // offset of its instruction brings back (see dma_one).
+  static constexpr int kBias = 4096;
   const __hip_bfloat16* a_src[C::kADma];
   const __hip_bfloat16* g_src[C::kBDma];
   const __hip_bfloat16* u_src[C::kBDma];
+  unsigned a_off[C::kADma], b_off[C::kBDma];
+  const unsigned char* a_base;
+  const unsigned char* g_base;
+  const unsigned char* u_base;
   const __hip_bfloat16* zeros;  // 16 readable zero bytes (K tail)
   int a_lds, b_lds;             // byte offset of the wave's first A row / weight row in a tile
   int a_k[C::kADma];            // first K element (inside a tile) each A instruction of this lane reads
@@ -213,54 +235,71 @@ struct TileState {
 // ACT: active 32-row blocks of this wave's accumulators.  DEAD: every token row that this wave
 // loads lies past the end of the expert's bucket (a short last tile); such rows only have to hold
 // finite values (their routing weight is 0), so they are loaded once, in the prologue, and
-// the K loop skips their loads.
+// the K loop skips their loads.  TAIL: d_model is not a multiple of the K tile (chunks past it come from a page
+// of zeros), or a matrix is too large for 32-bit offsets: per-lane 64-bit sources.
 template <class C, int ACT, bool TAIL, bool DEAD, int EPI>
 __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int d_ff, int slot, const EpiArgs& ep) {
   constexpr int BN = C::BN, TN = C::TN, WM = C::WM, KT = C::KT;
   constexpr int NA = ACT > 0 ? ACT : 1;
   extern __shared__ __align__(16) unsigned char smem[];  // the workgroup's dynamic LDS, named here so that its address space is known
   const unsigned lds0 = lds_address(smem);
+  using std::integral_constant;
 
   // Lane l of a wave instruction writes LDS bytes [16 l, 16 l + 16) after the wave-uniform base,
   // i.e. chunk position l % kChunks of row l / kChunks of its row group; to produce the swizzled
   // image it reads logical chunk (l % kChunks) ^ swizzle_key(row) of that row (set up by the caller).
-  // TAIL (d_model not a multiple of KT): chunks past d_model come from a page of zeros.
   // The instruction's immediate offset is added to the global and to the LDS address alike, so the
-  // j-th group of a wave uses immediate 1024 j on sources that were moved back by 1024 j bytes at
-  // set-up: one LDS base (M0) per matrix and tile instead of one per instruction.
-  auto dma = [&](const __hip_bfloat16* src, int k, int k0, unsigned dst, auto group) {
-    // immediate offsets reach 4095 bytes: groups 0-3 use the base, groups 4-7 the base + 4096
-    constexpr int kOff = (decltype(group)::value % 4) * 1024;
-    constexpr int kBase = (decltype(group)::value / 4) * 4096;
-    const unsigned char* p = reinterpret_cast<const unsigned char*>(src + k0);
-    if constexpr (TAIL) p = (k0 + k < st.d_model) ? p : reinterpret_cast<const unsigned char*>(st.zeros) - kOff;
-    lds_dma16<kOff>(p, dst + kBase);
-  };
-  // Load d of a tile's kLoadsPerTile wave instructions: the token groups first, then the gate
-  // groups, then the up groups (loads that share an LDS base follow each other).
-  // A tile and a weight tile have their own ring position: Fill says where the next ones go.
+  // j-th group of a wave uses immediate 1024 (j % 4) on a source that was moved back by as much at
+  // set-up: one LDS base (M0) serves four groups of a matrix (immediates reach 4095 bytes).
+  // A fill is what goes into the stages that a barrier has just freed: the next token tile and the next weight
+  // tile, each with its own ring position.  All of its fields are wave-uniform.
   struct Fill {
-    int a_stage, a_k, b_stage, b_k;
+    int a_k, b_k;                                // first K element of either tile
+    unsigned a_lds, b_lds;                       // LDS address of this wave's rows in the target stages
+    const unsigned char *a_ptr, *g_ptr, *u_ptr;  // matrix bases moved on to a_k / b_k (the scalar-base form)
   };
+  auto make_fill = [&](unsigned a_st, int a_k, unsigned b_st, int b_k) {
+    Fill f;
+    f.a_k = a_k;
+    f.b_k = b_k;
+    f.a_lds = lds0 + a_st + st.a_lds;
+    f.b_lds = lds0 + C::kStages * C::kATileBytes + b_st + st.b_lds;
+    f.a_ptr = st.a_base + 2 * (unsigned)a_k;
+    f.g_ptr = st.g_base + 2 * (unsigned)b_k;
+    f.u_ptr = st.u_base + 2 * (unsigned)b_k;
+    return f;
+  };
+  // Load d of a fill's kLoadsPerTile wave instructions: the token groups first, then the gate groups, then the up
+  // groups.  The loads of a fill are issued in this order, everywhere: the scalar-base form writes M0 only with
+  // the first of every four groups of a matrix, and the waits of the K loop count on the token rows being the older.
   auto dma_one = [&](const Fill& f, auto index) {
     constexpr int d = decltype(index)::value;
-    using std::integral_constant;
-    if constexpr (d < C::kADma) {
-      dma(st.a_src[d], st.a_k[d], f.a_k, lds0 + C::a_off(f.a_stage) + st.a_lds, integral_constant<int, d>{});
-    } else if constexpr (d < C::kADma + C::kBDma) {
-      dma(st.g_src[d - C::kADma], st.b_k[d - C::kADma], f.b_k, lds0 + C::b_off(f.b_stage) + st.b_lds,
-          integral_constant<int, d - C::kADma>{});
+    constexpr bool is_a = d < C::kADma, is_g = !is_a && d < C::kADma + C::kBDma;
+    constexpr int j = is_a ? d : (is_g ? d - C::kADma : d - C::kADma - C::kBDma);
+    constexpr int kOff = (j % 4) * 1024, kBase = (j / 4) * 4096;
+    const unsigned dst = (is_a ? f.a_lds : f.b_lds + (is_g ? 0 : C::kBTileBytes)) + kBase;
+    if constexpr (TAIL) {
+      const __hip_bfloat16* src;
+      int k;
+      if constexpr (is_a) {
+        src = st.a_src[j];
+        k = st.a_k[j];
+      } else {
+        src = is_g ? st.g_src[j] : st.u_src[j];
+        k = st.b_k[j];
+      }
+      const int k0 = is_a ? f.a_k : f.b_k;
+      const unsigned char* p = reinterpret_cast<const unsigned char*>(src + k0);
+      p = (k0 + k < st.d_model) ? p : reinterpret_cast<const unsigned char*>(st.zeros) - kOff;
+      lds_dma16<kOff>(p, dst);
     } else {
-      constexpr int j = d - C::kADma - C::kBDma;
-      dma(st.u_src[j], st.b_k[j], f.b_k, lds0 + C::b_off(f.b_stage) + C::kBTileBytes + st.b_lds, integral_constant<int, j>{});
+      if constexpr (j % 4 == 0) lds_dma_base(__builtin_amdgcn_readfirstlane(dst));
+      if constexpr (is_a) lds_dma16_scalar<kOff>(st.a_off[j], f.a_ptr);
+      else lds_dma16_scalar<kOff>(st.b_off[j], is_g ? f.g_ptr : f.u_ptr);
     }
   };
-  // loads [C::issue_begin(P), C::issue_begin(P + 1)) of a tile: the share of issue slot P
-  auto dma_slot = [&](const Fill& f, auto slot_index) {
-    constexpr int P = decltype(slot_index)::value;
-    static_for<C::issue_begin(P), C::issue_begin(P + 1)>([&](auto d) {
-      if constexpr (!(DEAD && decltype(d)::value < C::kADma)) dma_one(f, d);
-    });
+  auto dma_unless_dead = [&](const Fill& f, auto index) {
+    if constexpr (!(DEAD && decltype(index)::value < C::kADma)) dma_one(f, index);
   };
 
   // v_mfma_f32_16x16x32_bf16: a 32 x 32 block of the wave's tile is four 16 x 16 sub-blocks (a: rows, b: columns)
@@ -291,61 +330,67 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
   struct FragB {
     bf16x8 g[TN], u[TN];  // 16 channels (sub-block b) of every channel block, one K step
   };
-  auto read_a = [&](FragA& f, int stage, int ks) {
-    if constexpr (ACT > 0) {
-      const unsigned char* sA = smem + C::a_off(stage) + st.k_swz[ks] + st.a_frag_base;
-#pragma unroll
-      for (int i = 0; i < ACT; ++i)
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-          f.v[i][a] = *reinterpret_cast<const bf16x8*>(sA + (i * WM * 32 + a * 16) * C::kRowBytes);
+  // Per-lane byte offsets of the fragments inside the LDS: token rows of K step ks in the stage at ring offset
+  // a_st; weight rows of (K step ks, channel sub-block b) at b_st.
+  auto frag_a_at = [&](unsigned a_st, int ks) { return a_st + (unsigned)(st.k_swz[ks] + st.a_frag_base); };
+  auto frag_b_at = [&](unsigned b_st, int ks) {
+    return C::kStages * C::kATileBytes + b_st + (unsigned)(st.k_swz[ks] + st.b_frag_base);
+  };
+  // Read r of a phase's fragment reads: the 2 TN weight fragments (gate and up of every channel block) of
+  // channel sub-block b first, then, where a new K step begins, the 2 ACT token fragments.
+  auto read_one = [&](FragA& ra, FragB& rb, unsigned at_a, unsigned at_b, auto b_index, auto r_index) {
+    constexpr int r = decltype(r_index)::value, b = decltype(b_index)::value;
+    if constexpr (r < 2 * TN) {
+      constexpr int j = r / 2;
+      constexpr int off = b * 16 * C::kRowBytes + j * 32 * C::kRowBytes + (r % 2 ? C::kBTileBytes : 0);
+      bf16x8& dst = r % 2 == 0 ? rb.g[j] : rb.u[j];
+      dst = *reinterpret_cast<const bf16x8*>(smem + at_b + off);
+    } else {
+      constexpr int i = (r - 2 * TN) / 2, a = (r - 2 * TN) % 2;
+      ra.v[i][a] = *reinterpret_cast<const bf16x8*>(smem + at_a + (i * WM * 32 + a * 16) * C::kRowBytes);
     }
   };
-  auto read_b = [&](FragB& f, int stage, int ks, int b) {
-    if constexpr (ACT > 0) {
-      const unsigned char* sG = smem + C::b_off(stage) + st.k_swz[ks] + st.b_frag_base + b * 16 * C::kRowBytes;
-      const unsigned char* sU = sG + C::kBTileBytes;
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        f.g[j] = *reinterpret_cast<const bf16x8*>(sG + j * 32 * C::kRowBytes);
-        f.u[j] = *reinterpret_cast<const bf16x8*>(sU + j * 32 * C::kRowBytes);
-      }
-    }
-  };
-  // MFMAs [LO, HI) of one phase (K step ks, channel sub-block b), numbered (row block i, row sub-block a,
+  // MFMA m of one phase (K step ks, channel sub-block b), numbered (row block i, row sub-block a,
   // channel block j, gate / up)
-  auto mfma_range = [&](const FragA& fa, const FragB& fb, auto b_index, auto lo, auto hi) {
-    constexpr int b = decltype(b_index)::value;
-    static_for<decltype(lo)::value, decltype(hi)::value>([&](auto m) {
-      constexpr int gu = decltype(m)::value % 2, j = (decltype(m)::value / 2) % TN;
-      constexpr int a = (decltype(m)::value / (2 * TN)) % 2, i = decltype(m)::value / (4 * TN);
-      // kSwap: the weight fragment takes the first operand's place, which transposes the accumulator tile
-      if constexpr (gu == 0)
-        acc_g[i][j][a][b] = kSwap ? __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb.g[j], fa.v[i][a], acc_g[i][j][a][b], 0, 0, 0)
-                                  : __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v[i][a], fb.g[j], acc_g[i][j][a][b], 0, 0, 0);
-      else
-        acc_u[i][j][a][b] = kSwap ? __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb.u[j], fa.v[i][a], acc_u[i][j][a][b], 0, 0, 0)
-                                  : __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v[i][a], fb.u[j], acc_u[i][j][a][b], 0, 0, 0);
-    });
+  auto mfma_one = [&](const FragA& fa, const FragB& fb, auto b_index, auto m_index) {
+    constexpr int b = decltype(b_index)::value, m = decltype(m_index)::value;
+    constexpr int gu = m % 2, j = (m / 2) % TN, a = (m / (2 * TN)) % 2, i = m / (4 * TN);
+    // kSwap: the weight fragment takes the first operand's place, which transposes the accumulator tile
+    if constexpr (gu == 0) {
+      if constexpr (kSwap) mfma_pinned(acc_g[i][j][a][b], fb.g[j], fa.v[i][a]);
+      else mfma_pinned(acc_g[i][j][a][b], fa.v[i][a], fb.g[j]);
+    } else {
+      if constexpr (kSwap) mfma_pinned(acc_u[i][j][a][b], fb.u[j], fa.v[i][a]);
+      else mfma_pinned(acc_u[i][j][a][b], fa.v[i][a], fb.u[j]);
+    }
   };
 
   // Ring schedule.  Token tiles and weight tiles each cycle through their own ring of LDS stages; the barrier of
   // iteration kt says that tile kt + 1 has landed and that nobody reads tile kt's stages any more, so the next
-  // token tile and the next weight tile go into them.  A K tile is four phases: K step ks = phase / 2 of 32
-  // elements, channel sub-block b = phase % 2; a phase reads the four B fragments of the next phase and, before a
-  // new K step, its four A fragments.  The loads of a tile are not issued in one go: a phase is kParts issue
-  // slots, the barrier sits before the last phase, and slot P counted from the barrier issues its share
-  // C::issue_begin(P) .. of the loads behind its MFMAs; the order is pinned with scheduling barriers.
-  // Back-to-back loads fill the wave's vector-memory queue and stall its MFMAs behind them; one or two at a time
-  // between groups of MFMAs cost next to nothing.  The last slots before the barrier stay empty, which is the
-  // time the youngest load has to land.  Tiles past the end are clamped to the last one (redundant loads, never
+  // fill goes into them.  A K tile is four phases: K step ks = phase / 2 of 32 elements, channel sub-block
+  // b = phase % 2; during a phase the wave reads the weight fragments of the next phase and, before a new K step,
+  // its token fragments.  The barrier sits before the last phase.  A phase is a sequence of slots, one MFMA each
+  // (see the note on instruction order at the top); counted from the barrier, every kEvery-th slot issues the next
+  // load of the fill, token rows first.  Tiles past the end are clamped to the last one (redundant loads, never
   // read) so that the loop body and the outstanding-load count never change.
   static_assert(C::kSteps == 4, "two 32-deep K steps of two phases per K tile");
   const int n_k = (st.d_model + KT - 1) / KT;
   const int k_last = (n_k - 1) * KT;
   constexpr int kMayFly = C::kMayFly;  // loads younger than tile kt + 1
-  constexpr int kFull = 4 * ACT * TN;                           // MFMAs of a phase
-  using std::integral_constant;
+  constexpr int kFull = 4 * ACT * TN;  // MFMAs of a phase
+  constexpr int SA = C::kStages, SB = C::kBStages;
+  constexpr unsigned kARing = SA * C::kATileBytes, kBRing = SB * C::kBStageBytes;
+  // Full tiles spread the wave-uniform bookkeeping of a K tile over the idle slots of its third phase; a short tile
+  // is bound by its loads, not by the matrix pipe, and does that work at the barrier.
+  constexpr bool kSpread = ACT == C::TM && !TAIL && !DEAD && kFull >= 32;
+  constexpr int kEvery = ACT == 0 ? 1
+                         : (kSpread ? C::kLoadEvery
+                                    : ((3 * kFull) / C::kLoadsPerTile < 1 ? 1
+                                       : ((3 * kFull) / C::kLoadsPerTile > C::kLoadEvery ? C::kLoadEvery : (3 * kFull) / C::kLoadsPerTile)));
+  static_assert(!kSpread || kEvery * C::kLoadsPerTile <= 3 * kFull, "the loads of a fill end before the bookkeeping of the next one");
+  // loads of a fill that the phase behind the barrier issues (the prologue does it for the first fill)
+  constexpr int kBehindBarrier = ACT == 0 ? C::kLoadsPerTile
+                                          : (kFull / kEvery < C::kLoadsPerTile ? kFull / kEvery : C::kLoadsPerTile);
   FragA fa[2];
   FragB fb[2];
   // Routing weight of the lane's output rows.  They stay in registers when the per-tile arrays lie over the ring:
@@ -363,55 +408,136 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
     __syncthreads();
   }
   auto a_of = [&](int i, int a, int r, int row) { return C::kAliasAux ? a_rows[i][a][r] : st.s_a[row]; };
-  constexpr int SA = C::kStages, SB = C::kBStages;
-  Fill fill = {SA - 1, min((SA - 1) * KT, k_last), SB - 1, min((SB - 1) * KT, k_last)};
-  if constexpr (DEAD)
-    static_for<0, C::kADma>([&](auto d) { dma_one(fill, d); });
+
+  // Prologue: whole tiles 0 .. SB - 2 (token rows: 0 .. SA - 2), then what the phase behind a barrier would issue
+  // of the first fill (token tile SA - 1, weight tile SB - 1).
+  Fill fill = make_fill((SA - 1) * C::kATileBytes, min((SA - 1) * KT, k_last), (SB - 1) * C::kBStageBytes,
+                        min((SB - 1) * KT, k_last));
+  if constexpr (DEAD) static_for<0, C::kADma>([&](auto d) { dma_one(fill, d); });
 #pragma unroll
   for (int t = 0; t + 1 < SB; ++t) {
-    const Fill whole = {t, min(t * KT, k_last), t, min(t * KT, k_last)};
+    const Fill whole = make_fill(t * C::kATileBytes, min(t * KT, k_last), t * C::kBStageBytes, min(t * KT, k_last));
     static_for<0, C::kLoadsPerTile>([&](auto d) {
       if (decltype(d)::value >= C::kADma || t + 1 < SA) dma_one(whole, d);  // the token ring ends one tile earlier
     });
   }
-  static_for<0, C::kParts>([&](auto p) { dma_slot(fill, p); });
-  constexpr int kFirst = C::issue_begin(C::kParts);
-  constexpr int kSlotsFirst = DEAD ? kFirst - (kFirst < C::kADma ? kFirst : C::kADma) : kFirst;
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly + kSlotsFirst) : "memory");
+  static_for<0, kBehindBarrier>([&](auto d) { dma_unless_dead(fill, d); });
+  constexpr int kFirst = DEAD ? kBehindBarrier - (kBehindBarrier < C::kADma ? kBehindBarrier : C::kADma) : kBehindBarrier;
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly + kFirst) : "memory");
   __syncthreads();
-  read_a(fa[0], 0, 0);
-  read_b(fb[0], 0, 0, 0);
-  int stage = 0, b_stage = 0;  // ring positions of tile kt's token rows and weights
-  for (int kt = 0; kt < n_k; ++kt) {
-    const int next = stage + 1 == SA ? 0 : stage + 1;
-    const int b_next = b_stage + 1 == SB ? 0 : b_stage + 1;
-    static_for<0, C::kSteps>([&](auto phase) {
-      constexpr int s = decltype(phase)::value;
-      constexpr bool last = s + 1 == C::kSteps;
-      constexpr int P = last ? 0 : C::kParts * (s + 1);  // issue slot of this phase's first part
-      if constexpr (!last) {
-        constexpr int ks1 = (s + 1) / 2, b1 = (s + 1) % 2;
-        read_b(fb[(s + 1) & 1], b_stage, ks1, b1);
-        if constexpr (b1 == 0) read_a(fa[ks1 & 1], stage, ks1);
-      } else {
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly) : "memory");
-        __syncthreads();
-        fill = {stage, min((kt + SA) * KT, k_last), b_stage, min((kt + SB) * KT, k_last)};
-        read_b(fb[0], b_next, 0, 0);
-        read_a(fa[0], next, 0);
-      }
-      static_for<0, C::kParts>([&](auto part) {
-        constexpr int q = decltype(part)::value;
-        mfma_range(fa[(s / 2) & 1], fb[s & 1], integral_constant<int, s % 2>{},
-                   integral_constant<int, kFull * q / C::kParts>{}, integral_constant<int, kFull * (q + 1) / C::kParts>{});
-        dma_slot(fill, integral_constant<int, P + q>{});
-        __builtin_amdgcn_sched_barrier(0);
-      });
+  if constexpr (ACT > 0) {
+    static_for<0, 2 * TN + 2 * ACT>([&](auto r) {
+      read_one(fa[0], fb[0], frag_a_at(0, 0), frag_b_at(0, 0), integral_constant<int, 0>{}, r);
     });
-    stage = next;
-    b_stage = b_next;
+  }
+
+  unsigned a_st = 0, b_st = 0;  // ring offsets of the stages that hold tile kt
+  auto next_a = [&](unsigned x) { return x + C::kATileBytes == kARing ? 0u : x + C::kATileBytes; };
+  auto next_b = [&](unsigned x) { return x + C::kBStageBytes == kBRing ? 0u : x + C::kBStageBytes; };
+  if constexpr (ACT == 0) {
+    // nothing to multiply: this wave only brings in its share of every fill, in one go behind the barrier
+    for (int kt = 0; kt < n_k; ++kt) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly) : "memory");
+      __syncthreads();
+      fill = make_fill(a_st, min((kt + SA) * KT, k_last), b_st, min((kt + SB) * KT, k_last));
+      static_for<0, C::kLoadsPerTile>([&](auto d) { dma_unless_dead(fill, d); });
+      a_st = next_a(a_st);
+      b_st = next_b(b_st);
+    }
+  } else if constexpr (!kSpread) {
+    for (int kt = 0; kt < n_k; ++kt) {
+      const unsigned a_nx = next_a(a_st), b_nx = next_b(b_st);
+      static_for<0, C::kSteps>([&](auto phase) {
+        constexpr int s = decltype(phase)::value;
+        constexpr bool last = s + 1 == C::kSteps;
+        constexpr int ks1 = last ? 0 : (s + 1) / 2, b1 = last ? 0 : (s + 1) % 2;  // what this phase reads for the next
+        constexpr int n_reads = 2 * TN + (b1 == 0 ? 2 * ACT : 0);
+        constexpr int stride = 2 * n_reads <= kFull ? 2 : 1;
+        static_assert(n_reads * stride <= kFull + stride - 1, "a read slot for every fragment");
+        if constexpr (last) {
+          asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly) : "memory");
+          __syncthreads();
+          fill = make_fill(a_st, min((kt + SA) * KT, k_last), b_st, min((kt + SB) * KT, k_last));
+        }
+        const unsigned at_a = frag_a_at(last ? a_nx : a_st, ks1), at_b = frag_b_at(last ? b_nx : b_st, ks1);
+        FragA& ra = fa[ks1 & 1];
+        FragB& rb = fb[last ? 0 : (s + 1) & 1];
+        static_for<0, kFull>([&](auto mi) {
+          constexpr int m = decltype(mi)::value;
+          mfma_one(fa[(s / 2) & 1], fb[s & 1], integral_constant<int, s % 2>{}, mi);
+          if constexpr (m % stride == 0 && m / stride < n_reads)
+            read_one(ra, rb, at_a, at_b, integral_constant<int, b1>{}, integral_constant<int, m / stride>{});
+          constexpr int G = (last ? 0 : kFull * (s + 1)) + m;  // slot counted from the barrier
+          if constexpr (G % kEvery == kEvery - 1 && G / kEvery < C::kLoadsPerTile)
+            dma_unless_dead(fill, integral_constant<int, G / kEvery>{});
+          __builtin_amdgcn_sched_barrier(0);
+        });
+      });
+      a_st = a_nx;
+      b_st = b_nx;
+    }
+  } else {
+    // Full tile.  State that the slots of phase 2 bring up to date, one step each, pinned where it is computed:
+    // the fill behind the coming barrier, the ring offsets of tile kt + 1, and the fragment offsets of the reads
+    // of the last phase (from tile kt + 1) and of the next iteration's first three.
+    auto pin_s = [](auto& x) { asm volatile("" : "+s"(x)); };
+    auto pin_v = [](auto& x) { asm volatile("" : "+v"(x)); };
+    int ka = 2 * fill.a_k, kb = 2 * fill.b_k;  // byte offsets along K of the latest fill
+    const unsigned lds_a = __builtin_amdgcn_readfirstlane(lds0 + st.a_lds);
+    const unsigned lds_b = __builtin_amdgcn_readfirstlane(lds0 + kARing + st.b_lds);
+    unsigned a_nx = 0, b_nx = 0;
+    unsigned at_a1 = frag_a_at(0, 1), at_b0 = frag_b_at(0, 0), at_b1 = frag_b_at(0, 1);  // this iteration's reads
+    unsigned at_a0n = 0, at_b0n = 0, nx_a1 = 0, nx_b0 = 0, nx_b1 = 0;
+    for (int kt = 0; kt < n_k; ++kt) {
+      static_for<0, C::kSteps>([&](auto phase) {
+        constexpr int s = decltype(phase)::value;
+        constexpr bool last = s + 1 == C::kSteps;
+        constexpr int ks1 = last ? 0 : (s + 1) / 2, b1 = last ? 0 : (s + 1) % 2;
+        constexpr int n_reads = 2 * TN + (b1 == 0 ? 2 * ACT : 0);
+        static_assert(2 * n_reads <= kFull, "a read behind every other MFMA");
+        if constexpr (last) {
+          asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kMayFly) : "memory");
+          __syncthreads();
+        }
+        const unsigned at_a = last ? at_a0n : at_a1;
+        const unsigned at_b = last ? at_b0n : (s == 0 ? at_b0 : at_b1);
+        FragA& ra = fa[ks1 & 1];
+        FragB& rb = fb[last ? 0 : (s + 1) & 1];
+        static_for<0, kFull>([&](auto mi) {
+          constexpr int m = decltype(mi)::value;
+          mfma_one(fa[(s / 2) & 1], fb[s & 1], integral_constant<int, s % 2>{}, mi);
+          if constexpr (m % 2 == 0 && m / 2 < n_reads)
+            read_one(ra, rb, at_a, at_b, integral_constant<int, b1>{}, integral_constant<int, m / 2>{});
+          constexpr int G = (last ? 0 : kFull * (s + 1)) + m;
+          if constexpr (G % kEvery == kEvery - 1 && G / kEvery < C::kLoadsPerTile) dma_one(fill, integral_constant<int, G / kEvery>{});
+          if constexpr (s == 2 && m % 2 == 1) {  // no load is issued from here to the barrier
+            constexpr int step = m / 2;
+            if constexpr (step == 0) { ka = min(ka + 2 * KT, 2 * k_last); pin_s(ka); }
+            if constexpr (step == 1) { kb = min(kb + 2 * KT, 2 * k_last); pin_s(kb); }
+            if constexpr (step == 2) { fill.a_ptr = st.a_base + (unsigned)ka; pin_s(fill.a_ptr); }
+            if constexpr (step == 3) { fill.g_ptr = st.g_base + (unsigned)kb; pin_s(fill.g_ptr); }
+            if constexpr (step == 4) { fill.u_ptr = st.u_base + (unsigned)kb; pin_s(fill.u_ptr); }
+            if constexpr (step == 5) { fill.a_lds = lds_a + a_st; pin_s(fill.a_lds); }
+            if constexpr (step == 6) { fill.b_lds = lds_b + b_st; pin_s(fill.b_lds); }
+            if constexpr (step == 7) { a_nx = next_a(a_st); pin_s(a_nx); }
+            if constexpr (step == 8) { b_nx = next_b(b_st); pin_s(b_nx); }
+            if constexpr (step == 9) { at_a0n = frag_a_at(a_nx, 0); pin_v(at_a0n); }
+            if constexpr (step == 10) { at_b0n = frag_b_at(b_nx, 0); pin_v(at_b0n); }
+            if constexpr (step == 11) { nx_b0 = at_b0n; nx_a1 = frag_a_at(a_nx, 1); pin_v(nx_a1); }
+            if constexpr (step == 12) { nx_b1 = frag_b_at(b_nx, 1); pin_v(nx_b1); }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        });
+      });
+      a_st = a_nx;
+      b_st = b_nx;
+      at_a1 = nx_a1;
+      at_b0 = nx_b0;
+      at_b1 = nx_b1;
+    }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS at exit
+  mfma_drain();                                      // the last MFMAs have written their accumulators
   if constexpr (C::kAliasAux && EPI == kEpiStats) __syncthreads();  // the column reduction lies over the ring: every wave has read its last fragments
 
   // Epilogue.  Accumulator register r of lane l in sub-block (a, b) of block (i, j) is output row
@@ -578,8 +704,13 @@ __device__ __forceinline__ void run_tile(const TileWork& w, const __hip_bfloat16
     const int row = a_row0 + j * C::kDmaRows + lane / C::kChunks;
     const int ck = (lane % C::kChunks) ^ swizzle_key<C>(row);
     st.a_k[j] = ck * 8;
-    st.a_src[j] = X + (int64_t)s_tok[row] * ldx + ck * 8 - (j % 4) * 512;  // the immediate offset 1024 (j % 4) bytes comes back
+    const int64_t elem = (int64_t)s_tok[row] * ldx + ck * 8;
+    st.a_src[j] = X + elem - (j % 4) * 512;  // the immediate offset 1024 (j % 4) bytes comes back
+    st.a_off[j] = (unsigned)(2 * elem + TileState<C>::kBias - (j % 4) * 1024);
   }
+  st.a_base = reinterpret_cast<const unsigned char*>(X) - TileState<C>::kBias;
+  st.g_base = reinterpret_cast<const unsigned char*>(Wg + (int64_t)e * stride_gu) - TileState<C>::kBias;
+  st.u_base = reinterpret_cast<const unsigned char*>(Wu + (int64_t)e * stride_gu) - TileState<C>::kBias;
 #pragma unroll
   for (int j = 0; j < C::kBDma; ++j) {
     const int row = b_row0 + j * C::kDmaRows + lane / C::kChunks;
@@ -589,6 +720,7 @@ __device__ __forceinline__ void run_tile(const TileWork& w, const __hip_bfloat16
     st.b_k[j] = ck * 8;
     st.g_src[j] = Wg + off - (j % 4) * 512;
     st.u_src[j] = Wu + off - (j % 4) * 512;
+    st.b_off[j] = (unsigned)(2 * ((int64_t)c * ldw + ck * 8) + TileState<C>::kBias - (j % 4) * 1024);
   }
   // Fragments: lane l holds row (l % 16) of a 16-row sub-block, K elements 8*(l / 16) .. +7 of a 32-wide K step.
   st.a_frag_base = (st.wave_m * 32 + st.frag_row) * C::kRowBytes;       // + i*WM*32 rows: block WM*i + wave_m
@@ -618,7 +750,7 @@ __device__ __forceinline__ void run_tile(const TileWork& w, const __hip_bfloat16
 #undef CAMERA_TILE_FN
 }
 
-template <class C, class CT, bool TAIL, int EPI>
+template <class C, bool TAIL, int EPI>
 __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf16_kernel(
     const __hip_bfloat16* __restrict__ X, int64_t ldx, int d_model, int d_ff,
     const __hip_bfloat16* __restrict__ Wg, const __hip_bfloat16* __restrict__ Wu, int64_t stride_gu,
@@ -626,7 +758,6 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
     const int32_t* __restrict__ tile_expert, const int32_t* __restrict__ perm, const float* __restrict__ w_perm,
     int n_experts, const __hip_bfloat16* __restrict__ zeros, EpiArgs ep) {
   constexpr int BM = C::BM, BN = C::BN;
-  static_assert(CT::BN == C::BN && CT::kSmemBytes <= C::kSmemBytes, "the narrow tiling shares the workgroup's N extent and LDS");
   // Workgroup -> tile mapping.  The hardware deals consecutive workgroup ids round-robin to the 8
   // XCDs, each with its own L2 and 32 CUs, and an XCD starts its workgroups in id order.  Every
   // XCD gets an equal, contiguous run of logical ids (sized from the real tile count, which only
@@ -667,15 +798,8 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
   w.m_len = m_len;
   w.n0 = n0;
   w.tok_first = tile_in_expert * BM;
-  constexpr int kAux = C::kAliasAux ? 0 : C::kRingBytes;           // per-tile arrays of the main tiling
-  constexpr int kAuxTail = C::kAliasAux ? CT::kRingBytes : kAux;  // and of the narrow one (never over its ring)
-  static_assert(kAuxTail + CT::kAuxBytes <= C::kSmemBytes && !CT::kAliasAux, "the narrow tiling fits the workgroup's LDS");
-  // A short last tile of an expert is bound by the latency of its loads, not by the matrix pipe: it runs
-  // with the narrow tiling, whose smaller stages leave room for a third one (two K tiles in flight).
-  if (CT::kThreads == C::kThreads && m_len <= CT::BM)
-    run_tile<CT, TAIL, EPI, kAuxTail>(w, X, ldx, d_model, d_ff, Wg, Wu, stride_gu, d_model, perm, w_perm, zeros, ep);
-  else
-    run_tile<C, TAIL, EPI, kAux>(w, X, ldx, d_model, d_ff, Wg, Wu, stride_gu, d_model, perm, w_perm, zeros, ep);
+  constexpr int kAux = C::kAliasAux ? 0 : C::kRingBytes;  // the per-tile arrays
+  run_tile<C, TAIL, EPI, kAux>(w, X, ldx, d_model, d_ff, Wg, Wu, stride_gu, d_model, perm, w_perm, zeros, ep);
 }
 
 // ---------------------------------------------------------------------------
@@ -797,7 +921,7 @@ __global__ __launch_bounds__(CAMERA_MAX_EXPERTS) void compact_work_kernel(TABLE 
   }
 }
 
-template <class C, class CT, bool TAIL, int EPI, class TABLE>
+template <class C, bool TAIL, int EPI, class TABLE>
 __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf16_compact_kernel(
     const __hip_bfloat16* __restrict__ X, int64_t ldx, int d_model, const __hip_bfloat16* __restrict__ Wg,
     const __hip_bfloat16* __restrict__ Wu, TABLE tab, int k_round, const int32_t* __restrict__ offsets,
@@ -806,7 +930,6 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
     EpiArgs ep_launch) {
   // X: the tokens (first contraction) or the hidden buffer (second contraction, ldx unused: its rows are ragged)
   constexpr int BM = C::BM, BN = C::BN;
-  static_assert(CT::BN == C::BN && CT::kSmemBytes <= C::kSmemBytes, "the narrow tiling shares the workgroup's N extent and LDS");
   const int n_experts = tab.n_experts;
   const CompactScratch sc = compact_scratch(scratch, n_experts);
   const int32_t* work_off = sc.work_off;
@@ -873,13 +996,8 @@ __global__ __launch_bounds__(C::kThreads, C::kWavesPerSimd) void grouped_gemm_bf
   w.m_len = m_len;
   w.n0 = n0;
   w.tok_first = tile_in_expert * BM;
-  constexpr int kAux = C::kAliasAux ? 0 : C::kRingBytes;           // per-tile arrays of the main tiling
-  constexpr int kAuxTail = C::kAliasAux ? CT::kRingBytes : kAux;  // and of the narrow one (never over its ring)
-  static_assert(kAuxTail + CT::kAuxBytes <= C::kSmemBytes && !CT::kAliasAux, "the narrow tiling fits the workgroup's LDS");
-  if (CT::kThreads == C::kThreads && m_len <= CT::BM)
-    run_tile<CT, TAIL, EPI, kAuxTail>(w, A, lda, g.k_ext, g.n_ext, Wg + g.g_off, Wu + g.u_off, 0, g.ldw, perm, w_perm, zeros, ep);
-  else
-    run_tile<C, TAIL, EPI, kAux>(w, A, lda, g.k_ext, g.n_ext, Wg + g.g_off, Wu + g.u_off, 0, g.ldw, perm, w_perm, zeros, ep);
+  constexpr int kAux = C::kAliasAux ? 0 : C::kRingBytes;  // the per-tile arrays
+  run_tile<C, TAIL, EPI, kAux>(w, A, lda, g.k_ext, g.n_ext, Wg + g.g_off, Wu + g.u_off, 0, g.ldw, perm, w_perm, zeros, ep);
   }
 }
 
@@ -1011,11 +1129,15 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(
 }
 
 // Shape of the bf16 kernel: waves (M x N), 32x32 blocks per wave (M x N), K tile, stages of the token ring, stages
-// of the weight ring.
-using Bf16Cfg = GemmCfg<4, 2, 2, 2, 64, 2, 3>;
-// Tiling of an expert's short last tile (at most 64 token rows): same eight waves and N extent, 2 x 4 waves of
-// one 32 x 32 block each, three stages of 40 KiB.
-using Bf16TailCfg = GemmCfg<2, 4, 1, 1, 64, 3>;
+// of the weight ring.  Four waves of 128 x 64 x {gate, up}: one per SIMD.
+using Bf16Cfg = GemmCfg<2, 2, 4, 2, 64, 2, 3>;
+
+// Whether the scalar-base form of the tile loads can address the operands: 32-bit byte offsets from the start of
+// the token matrix (a_rows rows of lda elements) and of one expert's weight matrix (b_rows rows of ldw elements).
+bool fits_32bit_offsets(int64_t a_rows, int64_t lda, int64_t b_rows, int64_t ldw) {
+  const int64_t limit = (int64_t(1) << 32) - 2 * TileState<Bf16Cfg>::kBias - 4096;
+  return 2 * a_rows * lda < limit && 2 * b_rows * ldw < limit;
+}
 
 }  // namespace
 
@@ -1029,8 +1151,9 @@ static hipError_t launch_bf16(hipStream_t stream, const void* X, int64_t ldx, in
                               int n_experts, const void* W_gate, const void* W_up, int64_t stride_gu, int max_tiles,
                               const BucketTables& t, const EpiArgs& ep) {
   using C = Bf16Cfg;
-  const bool tail = d_model % C::KT != 0;
-  auto kern = tail ? grouped_gemm_bf16_kernel<C, Bf16TailCfg, true, EPI> : grouped_gemm_bf16_kernel<C, Bf16TailCfg, false, EPI>;
+  // token rows lie below max_tiles * BM (every token, and every bucket slot, belongs to some tile)
+  const bool tail = d_model % C::KT != 0 || !fits_32bit_offsets((int64_t)max_tiles * C::BM, ldx, d_ff, d_model);
+  auto kern = tail ? grouped_gemm_bf16_kernel<C, true, EPI> : grouped_gemm_bf16_kernel<C, false, EPI>;
   static bool attr_set[2] = {false, false};
   if (!attr_set[tail]) {
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1081,10 +1204,22 @@ template <int EPI, class TABLE>
 static hipError_t launch_compact(hipStream_t stream, const void* X, int64_t ldx, int64_t d_model, const void* Wg,
                                  const void* Wu, const TABLE& tab, int k_round, bool tail, int64_t n_tiles_n_max,
                                  int max_tiles, const BucketTables& t, int32_t* scratch, const EpiArgs& ep) {
-  // tail: some K extent is not a multiple of the K tile
+  // tail: some K extent is not a multiple of the K tile, or an operand is too large for 32-bit offsets
   using C = Bf16Cfg;
-  auto kern = tail ? grouped_gemm_bf16_compact_kernel<C, Bf16TailCfg, true, EPI, TABLE>
-                   : grouped_gemm_bf16_compact_kernel<C, Bf16TailCfg, false, EPI, TABLE>;
+  int64_t a_ld = ldx, b_rows = 0, b_ld = d_model;
+  if constexpr (std::is_same<TABLE, CompactRows>::value) {
+    for (int e = 0; e < tab.n_experts; ++e) b_rows = std::max<int64_t>(b_rows, tab.row_off[e + 1] - tab.row_off[e]);
+  } else {
+    b_rows = d_model;
+    b_ld = a_ld = 0;
+    for (int e = 0; e < tab.n_experts; ++e) {
+      b_ld = std::max<int64_t>(b_ld, tab.ld_off[e + 1] - tab.ld_off[e]);
+      a_ld = std::max<int64_t>(a_ld, (tab.count[e] + k_round - 1) / k_round * k_round);
+    }
+  }
+  tail = tail || !fits_32bit_offsets((int64_t)max_tiles * C::BM, a_ld, b_rows, b_ld);
+  auto kern = tail ? grouped_gemm_bf16_compact_kernel<C, true, EPI, TABLE>
+                   : grouped_gemm_bf16_compact_kernel<C, false, EPI, TABLE>;
   static bool attr_set[2] = {false, false};
   if (!attr_set[tail]) {
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
