@@ -322,6 +322,20 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
           acc_g[i][j][ab >> 1][ab & 1][r] = 0.0f;
           acc_u[i][j][ab >> 1][ab & 1][r] = 0.0f;
         }
+  // The accumulators take their registers here, before anything else is loaded: otherwise the allocator parks other
+  // values in accumulation registers and has to move them to scratch when the accumulators arrive.
+  // (The other epilogues hold fewer values through the loop and are better off without.)
+  if constexpr (EPI == kEpiStats) {
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int ab = 0; ab < 4; ++ab) {
+          asm volatile("" : "+a"(acc_g[i][j][ab >> 1][ab & 1]));
+          asm volatile("" : "+a"(acc_u[i][j][ab >> 1][ab & 1]));
+        }
+  }
 
   // Lane l holds row (l % 16) of a sub-block, K elements 8*(l / 16) .. +7 of a 32-wide K step.
   struct FragA {
