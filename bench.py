@@ -37,7 +37,7 @@ DECISIONS = {
 # HBM-side bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by what the same
 # counters read for a plain 1 GiB copy; not measured by this program: the figure and the file it comes from are
 # reported side by side (None where no such profile exists).
-PMC_TRAFFIC = {"qwen2-57b-a14b": (5.325e9, "profiles/grouped_gemm_bf16_qwen2-57b-a14b_hbm_traffic.txt")}
+PMC_TRAFFIC = {"qwen2-57b-a14b": (6.000e9, "profiles/grouped_gemm_bf16_qwen2-57b-a14b_hbm_traffic.txt")}
 PMC_NORM_TRAFFIC = {"qwen2-57b-a14b": (6.651e8, "profiles/down_norm_qwen2-57b-a14b_hbm_traffic.txt")}
 # The same for the two streaming kernels of the compacted layer on a 64-token batch, unpruned
 # (profiles/compact_layer_decode_hbm_traffic.txt): read + written bytes per call.
