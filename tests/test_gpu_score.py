@@ -253,3 +253,21 @@ def test_non_contiguous_inputs_are_refused_or_honoured(cam):
         cam.score_layer(dev["X"], idx, w, dev["W_gate"], dev["W_up"], dev["W_down"].transpose(1, 2).contiguous().transpose(1, 2), 0.95)
     with pytest.raises(binding.CameraError):
         cam.score_layer(dev["X"], idx.cpu(), w, dev["W_gate"], dev["W_up"], dev["W_down"], 0.95)
+
+
+def test_row_stride_beyond_32_bit_offsets(cam):
+    """Token rows so far apart that a 32-bit byte offset from the start of X cannot reach them: the contraction
+    takes its form with a 64-bit address per lane, and scores the same bits."""
+    cfg = small(n_tokens=600, d_model=128, d_ff=96, n_experts=4, top_k=2)
+    dev = H.to_dev(inputs.make_layer(cfg, 6))
+    idx, w = cam.route_topk(dev["X"], dev["W_r"], dev["bias"], 2)
+    want = cam.score_layer(dev["X"], idx, w, dev["W_gate"], dev["W_up"], dev["W_down"], 0.95)
+    ldx = 1 << 21                                    # 600 rows x 4 MiB: 2.5 GB
+    wide = torch.zeros((600, ldx), dtype=dev["X"].dtype, device="cuda")
+    wide[:, :128] = dev["X"]
+    idx2, w2 = cam.route_topk(wide[:, :128], dev["W_r"], dev["bias"], 2)
+    assert torch.equal(idx, idx2) and torch.equal(w, w2)
+    got = cam.score_layer(wide[:, :128], idx, w, dev["W_gate"], dev["W_up"], dev["W_down"], 0.95)
+    for k in want:
+        assert torch.equal(want[k], got[k]), k
+
