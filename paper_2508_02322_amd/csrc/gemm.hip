@@ -1148,8 +1148,9 @@ using Bf16Cfg = GemmCfg<2, 2, 4, 2, 64, 2, 3>;
 
 // Whether the scalar-base form of the tile loads can address the operands: 32-bit byte offsets from the start of
 // the token matrix (a_rows rows of lda elements) and of one expert's weight matrix (b_rows rows of ldw elements).
+// Kept below 2 GiB, where the offset reads the same as a signed and as an unsigned number.
 bool fits_32bit_offsets(int64_t a_rows, int64_t lda, int64_t b_rows, int64_t ldw) {
-  const int64_t limit = (int64_t(1) << 32) - 2 * TileState<Bf16Cfg>::kBias - 4096;
+  const int64_t limit = (int64_t(1) << 31) - 2 * TileState<Bf16Cfg>::kBias - 4096;
   return 2 * a_rows * lda < limit && 2 * b_rows * ldw < limit;
 }
 
