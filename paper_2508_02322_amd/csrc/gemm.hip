@@ -630,10 +630,10 @@ __device__ __forceinline__ void tile_body16(const TileState<C>& st, int n0, int 
             for (int r = 0; r < 4; ++r) {
               const int row = (WM * i + st.wave_m) * 32 + a * 16 + lane_rows + r;
               const float lam = a_of(i, a, r, row) * silu_f32(acc_g[i][j][a][b][r]) * acc_u[i][j][a][b][r];
-              const float l2 = lam * lam;
-              sum += l2;
-              mx = fmaxf(mx, l2);
+              sum = fmaf(lam, lam, sum);
+              mx = fmaxf(mx, fabsf(lam));  // squared once below: rounding keeps order, so max(x^2) = (max |x|)^2 bit for bit
             }
+        mx *= mx;
         sum += __shfl_xor(sum, 16);
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         sum += __shfl_xor(sum, 32);
