@@ -602,6 +602,32 @@ def run_workload(name, args, torch, binding, inputs, steps, warmup, calib_tokens
         "non_gemm_share_of_step": round(other / ms_per_step, 4),
         "kernel_ms": kernel_ms,
     }
+    if name == "tiny" and n_streams == 1:
+        # The one launch-bound configuration: the same step captured once in a HIP graph and replayed (the calls
+        # allocate through torch's capture pool only and never synchronise, so the sequence can be captured).
+        try:
+            side = torch.cuda.Stream()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    step()
+            torch.cuda.synchronize()
+            for _ in range(5):
+                graph.replay()
+            torch.cuda.synchronize()
+            reps = 200
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                graph.replay()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) / reps * 1e3
+            result["graph_replay"] = {"ms_per_step": round(ms, 4), "value": round(calib_tokens * n_layers / (ms * 1e-3), 1),
+                                      "what": f"{reps} replays of one captured step"}
+            del graph
+        except Exception as exc:  # noqa: BLE001 - a side measurement: say so and go on
+            print(f"bench.py: graph replay of {name} failed: {exc!r}", file=sys.stderr)
+            torch.cuda.synchronize()
+            result["graph_replay"] = {"error": repr(exc)}
     if keep_layers:
         return result, cam, cfg, layers
     del layers, cams
@@ -703,6 +729,8 @@ def main():
         "non_gemm_share_of_step": main_run["non_gemm_share_of_step"],
         "kernel_ms": main_run["kernel_ms"],
     }
+    if "graph_replay" in main_run:
+        result["graph_replay"] = main_run["graph_replay"]
     if apply_mask is not None:
         result["apply_mask"] = apply_mask
     if forward is not None:
@@ -732,7 +760,7 @@ def main():
                                                                    steps=max(1, args.other_steps), warmup=2))
             if r is not None and "error" not in r:
                 r = {k: r[k] for k in ("value", "unit", "steps", "ms_per_step", "dtype", "mfma_util_pct_of_bf16_peak", "roofline",
-                                       "rooflines", "non_gemm_share_of_step", "config")}
+                                       "rooflines", "non_gemm_share_of_step", "config", "graph_replay") if k in r}
             others[name] = r
         result["workloads"] = others
     if not args.no_cpu_baseline:
